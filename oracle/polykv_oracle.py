@@ -1,0 +1,312 @@
+"""CPU oracle for the PolyKV shared-pool hot path.  TEST INFRASTRUCTURE ONLY.
+
+This module is the plain, slow, obviously-correct statement of what the GPU
+library computes.  It is imported only by tests, by the smoke check and by the
+benchmark's CPU-baseline leg; the product path never touches it, and it shares
+no code, tables or constants with the HIP sources (it derives its own codebook).
+
+What it follows (PolyKV paper, section "Compression Scheme" unless noted):
+  * Key quantization "q8_0":  s = max|K|/127,  Kq = clip(round(K/s), -128, 127),
+    K_dequant = Kq * s.  The scale is taken per block of 32 consecutive head_dim
+    elements (the block-32 reading of the q8_0 name); ``block=None`` gives the
+    per-tensor form the paper's formula literally states.
+  * Value quantization "TurboQuant MSE, 3-bit": V_rot = FWHT(V)/sqrt(d), then the
+    nearest of the 8 Lloyd-Max centroids of N(0,1) (section "TurboQuant",
+    paragraph "Lloyd-Max quantization"), indices bit-packed at 3 bits.
+  * Dequantization (section "TurboQuant", paragraph "Dequantization"): look the
+    centroids up and undo the rotation using H.H = d.I.  The forward transform is
+    the normalized one, so the true inverse is H.c/sqrt(d); the paper's "divide by
+    d" would return V/sqrt(d) and is read as the un-normalized-forward convention.
+  * Read path: every agent's decode queries attend over the decoded pool (plus the
+    agent's own full-precision continuation), standard scaled-dot-product softmax
+    attention, grouped-query head mapping (section "Experimental Setup": Llama-3-8B
+    uses GQA with 8 KV heads).
+
+Precision: float64 everywhere, except the steps whose float32/float16 rounding is
+part of the stored format (the fp16 block scale and the code decision of q8_0).
+
+Pins (tests/test_oracle_pins.py): H.H = d.I, Parseval and the dense Sylvester
+matrix for the transform; the Lloyd-Max fixed-point conditions by numerical
+integration and the centroid values the paper prints; the distortion bound; the
+q8_0 half-step error bound; exhaustive pack/unpack; brute-force attention; byte
+accounting for the 2.91x ratio.  Quality numbers of the paper (perplexity,
+BERTScore) need model weights and texts and are: parity unpinned.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+Q8_BLOCK = 32          # elements per q8_0 block
+V_BITS = 3             # bits per value code
+V_LEVELS = 1 << V_BITS
+
+
+# --------------------------------------------------------------------------- #
+# Codebook: 8-level Lloyd-Max quantizer of the standard normal
+# --------------------------------------------------------------------------- #
+def _phi(x: float) -> float:
+    return math.exp(-0.5 * x * x) / math.sqrt(2.0 * math.pi) if math.isfinite(x) else 0.0
+
+
+def _Phi(x: float) -> float:
+    if x == math.inf:
+        return 1.0
+    if x == -math.inf:
+        return 0.0
+    return 0.5 * (1.0 + math.erf(x / math.sqrt(2.0)))
+
+
+def lloyd_max_gaussian(levels: int = V_LEVELS, tol: float = 1e-15, max_iter: int = 100000):
+    """Centroids c[0..levels-1] (ascending) and thresholds t[0..levels-2] of the MSE-optimal
+    scalar quantizer of N(0,1), by Lloyd's iteration: thresholds are midpoints of adjacent
+    centroids, centroids are conditional means of their cells.
+    (Section "TurboQuant", paragraph "Lloyd-Max quantization".)"""
+    c = np.linspace(-2.0, 2.0, levels)
+    for _ in range(max_iter):
+        t = 0.5 * (c[:-1] + c[1:])
+        edges = [-math.inf, *t.tolist(), math.inf]
+        new = np.empty(levels)
+        for k in range(levels):
+            a, b = edges[k], edges[k + 1]
+            new[k] = (_phi(a) - _phi(b)) / (_Phi(b) - _Phi(a))
+        done = np.max(np.abs(new - c)) < tol
+        c = new
+        if done:
+            break
+    # enforce the exact odd symmetry the fixed point has
+    c = 0.5 * (c - c[::-1])
+    t = 0.5 * (c[:-1] + c[1:])
+    return c, t
+
+
+_CODEBOOK = None
+
+
+def codebook():
+    global _CODEBOOK
+    if _CODEBOOK is None:
+        _CODEBOOK = lloyd_max_gaussian()
+    return _CODEBOOK
+
+
+def lloyd_max_mse(c, t) -> float:
+    """Per-coordinate MSE of the quantizer (c, t) on N(0,1):  sum_k  int_cell (x-c_k)^2 phi(x) dx,
+    in closed form (second moment, first moment, mass of every cell)."""
+    edges = [-math.inf, *np.asarray(t).tolist(), math.inf]
+    total = 0.0
+    for k, ck in enumerate(c):
+        a, b = edges[k], edges[k + 1]
+        mass = _Phi(b) - _Phi(a)
+        m1 = _phi(a) - _phi(b)
+        ax = a * _phi(a) if math.isfinite(a) else 0.0
+        bx = b * _phi(b) if math.isfinite(b) else 0.0
+        m2 = mass + ax - bx
+        total += m2 - 2.0 * ck * m1 + ck * ck * mass
+    return total
+
+
+def turboquant_mse_bound(bits: int) -> float:
+    """Distortion bound of section "TurboQuant", paragraph "Distortion bound"."""
+    return math.sqrt(3.0) * math.pi / 2.0 / 4.0 ** bits
+
+
+# --------------------------------------------------------------------------- #
+# Walsh-Hadamard transform, natural (Sylvester) order, un-normalized
+# --------------------------------------------------------------------------- #
+def fwht(x):
+    """y = H_d x along the last axis, H[i][j] = (-1)^popcount(i & j), float64 butterflies."""
+    y = np.array(x, dtype=np.float64, copy=True)
+    d = y.shape[-1]
+    if d & (d - 1):
+        raise ValueError("length must be a power of two")
+    h = 1
+    while h < d:
+        z = y.reshape(y.shape[:-1] + (d // (2 * h), 2, h))
+        a = z[..., 0, :].copy()
+        b = z[..., 1, :].copy()
+        z[..., 0, :] = a + b
+        z[..., 1, :] = a - b
+        h *= 2
+    return y
+
+
+# --------------------------------------------------------------------------- #
+# Keys: q8_0
+# --------------------------------------------------------------------------- #
+def k_encode(K, block: int | None = Q8_BLOCK):
+    """K: float16 [..., d].  Returns (codes int8 [..., d], scales float16 [..., d/block],
+    pre float32 [..., d]) where pre = k * (1/s) is the value that was rounded.
+
+    Per block:  amax = max|k|;  s = fp16(fp32(amax) / 127)  (stored);  codes are formed with the
+    STORED scale, inv = fp32(1)/fp32(s), q = clip(rint(fp32(k) * inv), -128, 127), ties to even;
+    an all-zero block stores s = 0 and zero codes.  ``block=None``: one block = the whole tensor.
+    """
+    K = np.asarray(K)
+    if K.dtype != np.float16:
+        raise TypeError("K must be float16")
+    d = K.shape[-1]
+    if block is None:
+        kb = K.reshape(1, -1)
+    else:
+        if d % block:
+            raise ValueError("head_dim must be a multiple of the block size")
+        kb = K.reshape(K.shape[:-1] + (d // block, block))
+    k32 = kb.astype(np.float32)
+    amax = np.max(np.abs(k32), axis=-1)
+    s16 = (amax / np.float32(127.0)).astype(np.float32).astype(np.float16)
+    s32 = s16.astype(np.float32)
+    with np.errstate(divide="ignore"):
+        inv = np.where(s32 > 0, np.float32(1.0) / s32, np.float32(0.0)).astype(np.float32)
+    pre = (k32 * inv[..., None]).astype(np.float32)
+    q = np.clip(np.rint(pre), -128, 127).astype(np.int8)
+    if block is None:
+        return q.reshape(K.shape), s16.reshape(()), pre.reshape(K.shape)
+    return q.reshape(K.shape), s16, pre.reshape(K.shape)
+
+
+def k_decode(codes, scales, block: int | None = Q8_BLOCK):
+    """K_dequant = Kq * s  (float64 holds the fp32 product exactly)."""
+    codes = np.asarray(codes)
+    s = np.asarray(scales).astype(np.float64)
+    if block is None:
+        return codes.astype(np.float64) * s
+    d = codes.shape[-1]
+    q = codes.reshape(codes.shape[:-1] + (d // block, block)).astype(np.float64)
+    return (q * s[..., None]).reshape(codes.shape)
+
+
+# --------------------------------------------------------------------------- #
+# Values: FWHT rotation + 3-bit Lloyd-Max
+# --------------------------------------------------------------------------- #
+def v_rotate(V):
+    """V_rot = FWHT(V)/sqrt(d) along head_dim (step 1 of the value quantizer)."""
+    V = np.asarray(V)
+    d = V.shape[-1]
+    return fwht(V.astype(np.float64)) / math.sqrt(d)
+
+
+def v_quantize(v_rot):
+    """Nearest-centroid index; a tie goes to the lower index, i.e. idx = #{k : v_rot > t_k}
+    (step 2 of the value quantizer)."""
+    _, t = codebook()
+    idx = np.zeros(np.shape(v_rot), dtype=np.uint8)
+    for tk in t:
+        idx += (v_rot > tk).astype(np.uint8)
+    return idx
+
+
+def v_encode(V):
+    """V: float16 [..., d] -> (idx uint8 [..., d] in 0..7, v_rot float64 [..., d])."""
+    V = np.asarray(V)
+    if V.dtype != np.float16:
+        raise TypeError("V must be float16")
+    v_rot = v_rotate(V)
+    return v_quantize(v_rot), v_rot
+
+
+def v_pack(idx):
+    """Canonical bit-packing: code j occupies stream bits 3j..3j+2 (LSB first); stream bit i is
+    bit (i mod 8) of byte floor(i/8).  [..., d] -> uint8 [..., 3d/8]."""
+    idx = np.asarray(idx, dtype=np.uint8)
+    d = idx.shape[-1]
+    if (d * V_BITS) % 8:
+        raise ValueError("3*d must be a multiple of 8")
+    bits = ((idx[..., :, None] >> np.arange(V_BITS, dtype=np.uint8)) & 1).astype(np.uint8)
+    bits = bits.reshape(idx.shape[:-1] + (d * V_BITS,))
+    return np.packbits(bits, axis=-1, bitorder="little")
+
+
+def v_unpack(packed, d: int):
+    packed = np.asarray(packed, dtype=np.uint8)
+    bits = np.unpackbits(packed, axis=-1, bitorder="little")[..., : d * V_BITS]
+    bits = bits.reshape(packed.shape[:-1] + (d, V_BITS)).astype(np.uint8)
+    return (bits << np.arange(V_BITS, dtype=np.uint8)).sum(axis=-1).astype(np.uint8)
+
+
+def v_decode(idx):
+    """V_dequant = H c[idx] / sqrt(d)  (true inverse of the normalized rotation)."""
+    c, _ = codebook()
+    idx = np.asarray(idx)
+    d = idx.shape[-1]
+    return fwht(c[idx]) / math.sqrt(d)
+
+
+# --------------------------------------------------------------------------- #
+# Pool = encode of a whole [L, H, T, d] cache; decode back
+# --------------------------------------------------------------------------- #
+def pool_encode(K, V):
+    """K, V float16 [L, H, T, d] -> dict with the canonical stored arrays and the pre-rounding
+    values a parity test needs to find elements that sit on a decision threshold."""
+    k_codes, k_scales, k_pre = k_encode(K)
+    v_idx, v_rot = v_encode(V)
+    return {
+        "k_codes": k_codes, "k_scales": k_scales, "v_packed": v_pack(v_idx),
+        "v_idx": v_idx, "k_pre": k_pre, "v_rot": v_rot,
+    }
+
+
+def pool_decode(pool):
+    d = pool["k_codes"].shape[-1]
+    return k_decode(pool["k_codes"], pool["k_scales"]), v_decode(v_unpack(pool["v_packed"], d))
+
+
+def stored_bytes(L: int, H: int, T: int, d: int) -> dict:
+    """Byte accounting (section "Compression Scheme", paragraph "Compression ratio")."""
+    n = L * H * T
+    k_codes = n * d
+    k_scales = n * (d // Q8_BLOCK) * 2
+    v_codes = n * d * V_BITS // 8
+    dense16 = 2 * n * d * 2
+    packed = k_codes + k_scales + v_codes
+    return {
+        "k_codes": k_codes, "k_scales": k_scales, "v_codes": v_codes, "packed": packed,
+        "dense16": dense16,
+        "ratio_payload": 16.0 / ((8 + V_BITS) / 2.0),      # the paper's 16/5.5
+        "ratio_stored": dense16 / packed,                   # with the fp16 block scales
+    }
+
+
+# --------------------------------------------------------------------------- #
+# Read path: N agents' decode attention over the shared pool
+# --------------------------------------------------------------------------- #
+def softmax_attend_one(q, Kmat, Vmat, scale):
+    """One query vector against T keys/values, float64: the textbook definition."""
+    s = (Kmat @ q) * scale
+    s = s - np.max(s)
+    p = np.exp(s)
+    p /= np.sum(p)
+    return p @ Vmat
+
+
+def pool_attend(K_hat, V_hat, Q, scale: float | None = None, tails=None):
+    """K_hat, V_hat: decoded pool, float64 [L, H, T, d].
+    Q: [L, A, nq, q_heads, d] (any float dtype); q head h reads kv head h // (q_heads // H).
+    tails: optional list over agents of (tail_K, tail_V) float16 [L, H, t_a, d] (t_a may be 0) or
+    None: the agent's private, uncompressed continuation, attended together with the pool.
+    No mask: each query sees the whole pool and its agent's whole tail.
+    Returns float64 [L, A, nq, q_heads, d]."""
+    K_hat = np.asarray(K_hat, dtype=np.float64)
+    V_hat = np.asarray(V_hat, dtype=np.float64)
+    Q = np.asarray(Q).astype(np.float64)
+    L, H, T, d = K_hat.shape
+    Lq, A, nq, q_heads, dq = Q.shape
+    if (Lq, dq) != (L, d) or q_heads % H:
+        raise ValueError("shape mismatch")
+    G = q_heads // H
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.zeros_like(Q)
+    for l in range(L):
+        for a in range(A):
+            tail = None if tails is None else tails[a]
+            for h in range(q_heads):
+                kv = h // G
+                Km, Vm = K_hat[l, kv], V_hat[l, kv]
+                if tail is not None and tail[0].shape[2] > 0:
+                    Km = np.concatenate([Km, np.asarray(tail[0][l, kv], dtype=np.float64)], axis=0)
+                    Vm = np.concatenate([Vm, np.asarray(tail[1][l, kv], dtype=np.float64)], axis=0)
+                for i in range(nq):
+                    out[l, a, i, h] = softmax_attend_one(Q[l, a, i, h], Km, Vm, scale)
+    return out

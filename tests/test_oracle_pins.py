@@ -1,0 +1,353 @@
+"""Pins for the CPU oracle: each test checks it against something other than itself --
+a closed form, a library routine, a numerical integral, a brute-force search, or a value the
+paper prints (tests/golden/).  All CPU-only."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import scipy.integrate
+import scipy.linalg
+import scipy.stats
+
+from conftest import read_golden_rows
+from oracle import polykv_oracle as O
+
+
+# ------------------------------------------------------------------ FWHT ---
+@pytest.mark.parametrize("d", [2, 8, 64, 128])
+def test_fwht_equals_dense_sylvester_matrix(d):
+    rng = np.random.default_rng(d)
+    x = rng.standard_normal((5, d))
+    H = scipy.linalg.hadamard(d).astype(np.float64)
+    np.testing.assert_allclose(O.fwht(x), x @ H.T, rtol=0, atol=1e-11)
+    # natural order: entry (i, j) is (-1)^popcount(i & j)
+    i, j = 37 % d, 21 % d
+    e = np.zeros(d); e[j] = 1.0
+    assert O.fwht(e)[i] == (-1) ** bin(i & j).count("1")
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_fwht_involution_parseval_special_vectors(d):
+    rng = np.random.default_rng(7)
+    xi = rng.integers(-50, 50, size=(3, d)).astype(np.float64)
+    assert np.array_equal(O.fwht(O.fwht(xi)), d * xi)            # H.H = d.I, exact on integers
+    x = rng.standard_normal((4, d))
+    y = O.fwht(x) / math.sqrt(d)
+    np.testing.assert_allclose((y ** 2).sum(-1), (x ** 2).sum(-1), rtol=1e-13)
+    e0 = np.zeros(d); e0[0] = 1.0
+    assert np.array_equal(O.fwht(e0), np.ones(d))
+    assert np.array_equal(O.fwht(np.ones(d)), d * e0)
+    with pytest.raises(ValueError):
+        O.fwht(np.zeros(48))
+
+
+# -------------------------------------------------------------- codebook ---
+def test_codebook_rounds_to_paper_values():
+    printed = np.array([float(v) for v in read_golden_rows("paper_centroids.txt")[0]])
+    c, _ = O.codebook()
+    assert c.shape == (8,)
+    np.testing.assert_array_equal(np.round(c, 3), printed)
+
+
+def test_codebook_fixed_point_by_numerical_integration():
+    c, t = O.codebook()
+    assert np.all(np.diff(c) > 0)
+    np.testing.assert_allclose(c, -c[::-1], atol=1e-15)           # odd symmetry
+    np.testing.assert_allclose(t, 0.5 * (c[:-1] + c[1:]), atol=1e-15)
+    assert abs(t[3]) < 1e-15
+    pdf = scipy.stats.norm.pdf
+    edges = [-np.inf, *t, np.inf]
+    masses = []
+    for k in range(8):
+        num, _ = scipy.integrate.quad(lambda x: x * pdf(x), edges[k], edges[k + 1], epsabs=1e-13)
+        den, _ = scipy.integrate.quad(pdf, edges[k], edges[k + 1], epsabs=1e-13)
+        assert abs(num / den - c[k]) < 1e-9                        # centroid = conditional mean
+        masses.append(den)
+    assert abs(sum(masses) - 1.0) < 1e-10
+
+
+def test_codebook_distortion_against_integral_and_paper_bound():
+    c, t = O.codebook()
+    pdf = scipy.stats.norm.pdf
+    edges = [-np.inf, *t, np.inf]
+    mse = sum(scipy.integrate.quad(lambda x, ck=c[k]: (x - ck) ** 2 * pdf(x),
+                                   edges[k], edges[k + 1], epsabs=1e-13)[0] for k in range(8))
+    assert abs(mse - O.lloyd_max_mse(c, t)) < 1e-10
+    consts = {r[0]: float(r[1]) for r in read_golden_rows("paper_constants.txt")}
+    assert round(mse, 2) == consts["distortion_b3"]                # "approximately 0.03"
+    bound = O.turboquant_mse_bound(3)
+    assert round(bound * 4 ** 3, 1) == consts["bound_factor"]      # sqrt(3) pi / 2 ~ 2.7
+    assert mse < bound
+    # Lloyd-Max is optimal: any perturbed codebook (with its own midpoints) is worse
+    rng = np.random.default_rng(0)
+    for _ in range(20):
+        c2 = np.sort(c + 1e-3 * rng.standard_normal(8))
+        assert O.lloyd_max_mse(c2, 0.5 * (c2[:-1] + c2[1:])) > mse
+
+
+# ----------------------------------------------------------- value codec ---
+def test_v_quantize_is_bruteforce_nearest_centroid():
+    c, _ = O.codebook()
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(20000) * 1.5
+    want = np.argmin(np.abs(x[:, None] - c[None, :]), axis=1)
+    np.testing.assert_array_equal(O.v_quantize(x), want)
+    # tie exactly on a threshold goes to the lower index (first minimum)
+    assert O.v_quantize(np.array([0.0]))[0] == 3
+    assert O.v_quantize(np.array([1e-12]))[0] == 4
+    assert O.v_quantize(np.array([-10.0, 10.0])).tolist() == [0, 7]
+
+
+def test_v_codec_statistics_on_gaussian_input():
+    c, t = O.codebook()
+    rng = np.random.default_rng(11)
+    d = 128
+    V = rng.standard_normal((8192, d)).astype(np.float16)
+    idx, v_rot = O.v_encode(V)
+    V64 = V.astype(np.float64)
+    # rotation is orthonormal: rotated coordinates are again N(0,1)
+    assert abs(np.mean(v_rot ** 2) / np.mean(V64 ** 2) - 1) < 1e-12
+    # per-coordinate MSE in the rotated domain = the Lloyd-Max MSE, and it carries over unchanged
+    # to the original domain through the inverse rotation (Parseval)
+    mse_rot = np.mean((c[idx] - v_rot) ** 2)
+    mse_orig = np.mean((O.v_decode(idx) - V64) ** 2)
+    expect = O.lloyd_max_mse(c, t)
+    assert abs(mse_rot / expect - 1) < 0.01
+    assert abs(mse_orig / mse_rot - 1) < 1e-9
+    assert mse_orig < O.turboquant_mse_bound(3)
+    # code histogram = cell probabilities of N(0,1)
+    edges = np.array([-np.inf, *t, np.inf])
+    probs = np.diff(scipy.stats.norm.cdf(edges))
+    hist = np.bincount(idx.ravel(), minlength=8) / idx.size
+    np.testing.assert_allclose(hist, probs, atol=2e-3)
+
+
+def test_v_decode_inverts_rotation_exactly_when_no_quantization_error():
+    # a vector whose rotated coordinates ARE centroids must come back exactly:
+    # pins the 1/sqrt(d) (not 1/d) inverse scaling and the transform direction.
+    c, _ = O.codebook()
+    rng = np.random.default_rng(5)
+    for d in (64, 128):
+        idx = rng.integers(0, 8, size=(6, d)).astype(np.uint8)
+        v = scipy.linalg.hadamard(d) @ c[idx].T / math.sqrt(d)     # dense inverse, library matrix
+        np.testing.assert_allclose(O.v_decode(idx), v.T, atol=1e-12)
+        np.testing.assert_allclose(O.v_rotate(v.T), c[idx], atol=1e-12)
+        np.testing.assert_array_equal(O.v_quantize(O.v_rotate(v.T)), idx)
+
+
+def test_v_encode_single_spike_and_constant_vectors():
+    # closed forms: e_j -> row j of H / sqrt(d) (all +-1/sqrt(d)); constant a -> a*sqrt(d) e_0
+    d = 64
+    v = np.zeros((1, d), dtype=np.float16); v[0, 5] = 8.0
+    idx, v_rot = O.v_encode(v)
+    signs = np.array([(-1) ** bin(i & 5).count("1") for i in range(d)])
+    np.testing.assert_allclose(v_rot[0], signs * 1.0)              # 8/sqrt(64) = 1
+    assert set(idx[0].tolist()) == {2, 5}                          # +-1.0 -> centroids +-0.756
+    v = np.full((1, d), 0.25, dtype=np.float16)
+    idx, v_rot = O.v_encode(v)
+    assert v_rot[0, 0] == 2.0 and np.all(v_rot[0, 1:] == 0.0)
+    assert idx[0, 0] == 7 and np.all(idx[0, 1:] == 3)              # 2.0 > 1.748 ; exact 0 -> lower
+
+
+# --------------------------------------------------------------- packing ---
+def test_pack_layout_hand_computed():
+    codes = np.array([[1, 2, 3, 4, 5, 6, 7, 0]], dtype=np.uint8)
+    c = codes[0].tolist()
+    b0 = (c[0] | c[1] << 3 | (c[2] & 3) << 6) & 0xFF
+    b1 = (c[2] >> 2 | c[3] << 1 | c[4] << 4 | (c[5] & 1) << 7) & 0xFF
+    b2 = (c[5] >> 1 | c[6] << 2 | c[7] << 5) & 0xFF
+    assert O.v_pack(codes).tolist() == [[b0, b1, b2]]
+    assert O.v_pack(np.zeros((2, 64), np.uint8)).shape == (2, 24)
+    assert O.v_pack(np.zeros((2, 128), np.uint8)).shape == (2, 48)
+
+
+def test_pack_unpack_exhaustive_one_group():
+    # all 8^8 code patterns of one 3-byte group, in chunks
+    base = np.array(list(itertools.product(range(8), repeat=4)), dtype=np.uint8)   # 4096 x 4
+    seen = set()
+    for hi in range(0, 4096, 512):
+        a = np.repeat(base[hi:hi + 512], 4096, axis=0)
+        b = np.tile(base, (512, 1))
+        codes = np.concatenate([a, b], axis=1)
+        packed = O.v_pack(codes)
+        assert packed.shape == (codes.shape[0], 3)
+        np.testing.assert_array_equal(O.v_unpack(packed, 8), codes)
+        word = packed[:, 0].astype(np.uint32) | packed[:, 1].astype(np.uint32) << 8 \
+            | packed[:, 2].astype(np.uint32) << 16
+        seen.add(int(word.min())); seen.add(int(word.max()))
+        assert np.unique(word).size == codes.shape[0]             # injective
+    assert 0 in seen and (1 << 24) - 1 in seen
+
+
+# ------------------------------------------------------------------ q8_0 ---
+def _rand_k(rng, shape):
+    k = rng.standard_normal(shape) * np.exp(0.7 * rng.standard_normal(shape[:-1] + (1,)))
+    return k.astype(np.float16)
+
+
+def test_q8_error_bound_and_extremes():
+    rng = np.random.default_rng(21)
+    K = _rand_k(rng, (3, 50, 128))
+    q, s, _ = O.k_encode(K)
+    assert q.dtype == np.int8 and s.dtype == np.float16 and s.shape == (3, 50, 4)
+    kh = O.k_decode(q, s)
+    sb = np.repeat(s.astype(np.float64), 32, axis=-1)
+    err = np.abs(kh - K.astype(np.float64))
+    assert np.all(err <= sb / 2 * (1 + 1e-6))                      # half a step
+    # the block maximum maps to +-127 and nothing clips at -128
+    kb = np.abs(K.astype(np.float64)).reshape(3, 50, 4, 32)
+    qb = np.abs(q.astype(np.int32)).reshape(3, 50, 4, 32)
+    assert np.all(qb.max(-1) == 127)
+    assert np.all(np.take_along_axis(qb, kb.argmax(-1)[..., None], -1) == 127)
+    assert q.min() >= -127
+    # stored scale is amax/127 to fp16 accuracy
+    np.testing.assert_allclose(s.astype(np.float64) * 127, kb.max(-1), rtol=2.0 ** -11)
+
+
+def test_q8_codes_are_bruteforce_nearest_multiples_of_stored_scale():
+    rng = np.random.default_rng(22)
+    K = _rand_k(rng, (40, 64))
+    q, s, pre = O.k_encode(K)
+    sb = np.repeat(s.astype(np.float64), 32, axis=-1)
+    cand = np.arange(-128, 128, dtype=np.float64)
+    dist = np.abs(K.astype(np.float64)[..., None] - cand * sb[..., None])
+    best = dist.min(-1)
+    got = np.abs(K.astype(np.float64) - q * sb)
+    # the chosen code is a nearest one, except where fp32 rounding of k/s sits on a .5 tie
+    near_tie = np.abs(np.abs(pre - np.floor(pre)) - 0.5) < 1e-4
+    assert np.all((got <= best * (1 + 1e-9) + 1e-12) | near_tie)
+    assert near_tie.mean() < 0.01
+
+
+def test_q8_special_blocks_and_scale_invariance():
+    z = np.zeros((2, 64), dtype=np.float16)
+    q, s, _ = O.k_encode(z)
+    assert not q.any() and not s.any()
+    assert not O.k_decode(q, s).any()
+    const = np.full((1, 32), -0.375, dtype=np.float16)
+    q, s, _ = O.k_encode(const)
+    assert np.all(q == -127)
+    one = np.zeros((1, 32), dtype=np.float16); one[0, 9] = 3.0
+    q, s, _ = O.k_encode(one)
+    assert q[0, 9] == 127 and np.count_nonzero(q) == 1
+    rng = np.random.default_rng(23)
+    K = rng.standard_normal((16, 128)).astype(np.float16)
+    q1, s1, _ = O.k_encode(K)
+    q2, s2, _ = O.k_encode((K.astype(np.float32) * 4).astype(np.float16))   # exact power-of-two scaling
+    np.testing.assert_array_equal(q1, q2)
+    np.testing.assert_array_equal(s1.astype(np.float32) * 4, s2.astype(np.float32))
+    # ties round to even: with s = 1 (amax = 127) the values 0.5, 1.5, 2.5 are exact ties
+    blk = np.zeros((1, 32), dtype=np.float16)
+    blk[0, :5] = [127.0, 0.5, 1.5, 2.5, -0.5]
+    q, s, _ = O.k_encode(blk)
+    assert float(s[0, 0]) == 1.0 and q[0, :5].tolist() == [127, 0, 2, 2, 0]
+
+
+def test_q8_per_tensor_form_of_the_papers_formula():
+    rng = np.random.default_rng(24)
+    K = rng.standard_normal((2, 3, 10, 64)).astype(np.float16)
+    q, s, _ = O.k_encode(K, block=None)
+    assert s.shape == ()
+    amax = np.abs(K.astype(np.float64)).max()
+    assert abs(float(s) * 127 / amax - 1) < 2.0 ** -11
+    kh = O.k_decode(q, s, block=None)
+    assert np.abs(kh - K.astype(np.float64)).max() <= float(s) / 2 * (1 + 1e-6)
+    assert np.abs(q.astype(np.int32)).max() == 127
+    # one block of 32 is the same thing as the per-tensor form on that block
+    blk = K[0, 0, 0, :32]
+    qa, sa, _ = O.k_encode(blk[None, :])
+    qb, sb_, _ = O.k_encode(blk, block=None)
+    np.testing.assert_array_equal(qa[0], qb)
+    assert sa[0, 0] == sb_
+
+
+# ------------------------------------------------------------ byte counts ---
+def test_compression_accounting_matches_paper():
+    consts = {r[0]: float(r[1]) for r in read_golden_rows("paper_constants.txt")}
+    b = O.stored_bytes(32, 8, 7194, 128)
+    assert round(b["ratio_payload"], 2) == consts["compression_ratio"]
+    assert b["dense16"] == 32 * 8 * 7194 * 128 * 2 * 2
+    assert b["packed"] == 32 * 8 * 7194 * 184                      # 128 + 8 + 48 bytes per token-head
+    assert abs(b["ratio_stored"] - 64 / 23) < 1e-12
+    # payload-only bytes give exactly 16/5.5
+    assert abs(b["dense16"] / (b["k_codes"] + b["v_codes"]) - 16 / 5.5) < 1e-12
+    b64 = O.stored_bytes(1, 4, 600, 64)
+    assert b64["packed"] == 4 * 600 * 92 and b64["dense16"] == 614400
+    # the paper's memory table: N dense caches / one pool = N * (its measured ratio ~ 2.91)
+    for agents, _tok, without, with_ in read_golden_rows("paper_memory_table.txt"):
+        ratio = float(without) / int(agents) / float(with_)
+        assert abs(ratio - consts["compression_ratio"]) < 0.01
+
+
+# -------------------------------------------------------------- attention ---
+def _naive_attention(q, Ks, Vs, scale):
+    T, d = len(Ks), len(q)
+    s = [scale * sum(q[j] * Ks[t][j] for j in range(d)) for t in range(T)]
+    m = max(s)
+    w = [math.exp(x - m) for x in s]
+    z = sum(w)
+    return [sum(w[t] * Vs[t][j] for t in range(T)) / z for j in range(d)]
+
+
+def test_attend_matches_pure_python_bruteforce_with_gqa_and_tails():
+    rng = np.random.default_rng(31)
+    L, H, T, d, A, nq, qh = 2, 2, 9, 8, 3, 2, 4
+    Kh = rng.standard_normal((L, H, T, d))
+    Vh = rng.standard_normal((L, H, T, d))
+    Q = rng.standard_normal((L, A, nq, qh, d))
+    tails = [None,
+             (rng.standard_normal((L, H, 3, d)).astype(np.float16),
+              rng.standard_normal((L, H, 3, d)).astype(np.float16)),
+             (np.zeros((L, H, 0, d), np.float16), np.zeros((L, H, 0, d), np.float16))]
+    out = O.pool_attend(Kh, Vh, Q, tails=tails)
+    assert out.shape == Q.shape
+    for l in range(L):
+        for a in range(A):
+            for i in range(nq):
+                for h in range(qh):
+                    kv = h // 2
+                    Ks = Kh[l, kv].tolist(); Vs = Vh[l, kv].tolist()
+                    if a == 1:
+                        Ks += tails[1][0][l, kv].astype(np.float64).tolist()
+                        Vs += tails[1][1][l, kv].astype(np.float64).tolist()
+                    want = _naive_attention(Q[l, a, i, h].tolist(), Ks, Vs, 1 / math.sqrt(d))
+                    np.testing.assert_allclose(out[l, a, i, h], want, rtol=1e-12, atol=1e-13)
+
+
+def test_attend_special_cases_and_agent_count_invariance():
+    rng = np.random.default_rng(32)
+    L, H, T, d = 1, 2, 40, 16
+    Vh = rng.standard_normal((L, H, T, d))
+    Q = rng.standard_normal((L, 4, 1, 2, d))
+    # zero keys -> uniform weights -> mean of the values
+    out = O.pool_attend(np.zeros((L, H, T, d)), Vh, Q)
+    np.testing.assert_allclose(out[0, 2, 0, 1], Vh[0, 1].mean(0), atol=1e-13)
+    # one dominant key -> its value
+    Kh = np.zeros((L, H, T, d)); Kh[0, 0, 17] = 200.0 * Q[0, 0, 0, 0]
+    out = O.pool_attend(Kh, Vh, Q)
+    np.testing.assert_allclose(out[0, 0, 0, 0], Vh[0, 0, 17], atol=1e-9)
+    # an agent's result does not depend on which other agents are batched with it
+    Kh = rng.standard_normal((L, H, T, d))
+    full = O.pool_attend(Kh, Vh, Q)
+    alone = O.pool_attend(Kh, Vh, Q[:, 2:3])
+    np.testing.assert_array_equal(full[:, 2:3], alone)
+    # explicit scale argument
+    np.testing.assert_allclose(O.pool_attend(Kh, Vh, Q, scale=0.25), O.pool_attend(Kh, Vh, Q))
+
+
+def test_end_to_end_pool_roundtrip_and_linearity_of_rotation():
+    rng = np.random.default_rng(33)
+    L, H, T, d = 1, 2, 33, 64
+    K = rng.standard_normal((L, H, T, d)).astype(np.float16)
+    V = rng.standard_normal((L, H, T, d)).astype(np.float16)
+    pool = O.pool_encode(K, V)
+    assert pool["v_packed"].shape == (L, H, T, 24) and pool["k_scales"].shape == (L, H, T, 2)
+    Kh, Vh = O.pool_decode(pool)
+    assert np.abs(Kh - K.astype(np.float64)).max() < 0.03
+    assert np.mean((Vh - V.astype(np.float64)) ** 2) < O.turboquant_mse_bound(3)
+    # weighting centroids first and rotating once equals rotating every token then weighting
+    c, _ = O.codebook()
+    p = rng.random(T); p /= p.sum()
+    once = O.fwht(p @ c[pool["v_idx"][0, 1]]) / math.sqrt(d)
+    np.testing.assert_allclose(once, p @ Vh[0, 1], atol=1e-13)
