@@ -1,0 +1,151 @@
+#!/usr/bin/env python3
+"""Benchmark of the PolyKV pool hot path on one MI355X.
+
+One step = one pass of the whole path over the Llama-3-8B-shaped pool (32 layers x 8 KV heads x
+head_dim 128, 4096 tokens, 15 agents x 32 query heads): pool_encode -> pool_decode -> pool_attend.
+Inputs are synthetic and already resident in HBM when timing starts.  Prints ONE JSON line:
+`value` is the decode-attention rate in pool GB/s (packed pool + Q + out bytes over the duration of
+the pool_attend call); encode tokens/s and the other phase rates ride along as extra keys;
+`roofline` describes the attention kernel against HBM peak and `cpu_baseline` times the CPU oracle
+on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def cpu_baseline(cfg, W):
+    """The oracle, as it stands, on one layer of the workload (about 10-30 s of CPU work)."""
+    from oracle import polykv_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    one = cfg.scaled(layers=1)
+    K, V = W.kv_pool(one)
+    Q = W.queries(cfg)[:1]
+    t0 = time.perf_counter()
+    ref = O.pool_encode(K, V)
+    t1 = time.perf_counter()
+    Kh, Vh = O.pool_decode(ref)
+    t2 = time.perf_counter()
+    O.pool_attend(Kh, Vh, Q)
+    t3 = time.perf_counter()
+    b = O.stored_bytes(1, one.kv_heads, one.tokens, one.head_dim)
+    attend_bytes = b["packed"] + Q.size * 2 + Q.size * 4
+    return {
+        "value": attend_bytes / (t3 - t2) / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+        "sample": "1 of %d layers of the same workload (8 KV heads x %d tokens, %d agents); "
+                  "encode %.2f s, decode %.2f s, attend %.2f s" % (cfg.layers, one.tokens, cfg.agents,
+                                                                   t1 - t0, t2 - t1, t3 - t2),
+        "encode_tokens_per_s": one.tokens / (t1 - t0) / cfg.layers,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="workload configuration (default: Llama-3-8B shape)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pools", type=int, default=3, help="distinct pool copies rotated between steps")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); the pool path shards by layer / KV head "
+              "with no exchange, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2604_24971_amd import polykv as pk          # fails loudly if the library is not built
+    from paper_2604_24971_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    cfg = W.CONFIGS[args.config]
+    L, H, d, T = cfg.layers, cfg.kv_heads, cfg.head_dim, cfg.tokens
+
+    Kn, Vn = W.kv_pool(cfg)
+    K = torch.from_numpy(Kn).cuda()
+    V = torch.from_numpy(Vn).cuda()
+    del Kn, Vn
+    Q = torch.from_numpy(W.queries(cfg)).cuda()
+    out = torch.empty(Q.shape, dtype=torch.float32, device="cuda")
+    Kd = torch.empty_like(K)
+    Vd = torch.empty_like(V)
+    pools = [pk.Pool(L, H, d, T).bind() for _ in range(max(1, args.pools))]
+    ws = torch.empty(max(pools[0].attend_workspace_bytes(Q), 256), dtype=torch.uint8, device="cuda")
+
+    def step(i, ev=None):
+        p = pools[i % len(pools)]
+        if ev:
+            ev[0].record()
+        p.encode(K, V)
+        if ev:
+            ev[1].record()
+        p.decode(torch.float16, Kd, Vd)
+        if ev:
+            ev[2].record()
+        p.attend(Q, out, workspace=ws)
+        if ev:
+            ev[3].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    enc = np.array([e[0].elapsed_time(e[1]) for e in events]) * 1e-3
+    dec = np.array([e[1].elapsed_time(e[2]) for e in events]) * 1e-3
+    att = np.array([e[2].elapsed_time(e[3]) for e in events]) * 1e-3
+    t_enc, t_dec, t_att = float(enc.mean()), float(dec.mean()), float(att.mean())
+
+    units = L * H
+    packed = units * T * (d + d // 16 + 3 * d // 8)                  # algorithmic pool bytes
+    enc_bytes = units * T * 4 * d + packed
+    dec_bytes = packed + units * T * 4 * d
+    att_bytes = packed + Q.numel() * 2 + out.numel() * 4
+    att_gbps = att_bytes / t_att / 1e9
+
+    result = {
+        "metric": "decode_attention_pool_GB_per_s", "value": att_gbps, "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "layers": L, "kv_heads": H, "q_heads": cfg.q_heads, "head_dim": d,
+                   "tokens": T, "agents": cfg.agents, "q_per_agent": cfg.q_per_agent,
+                   "rows_per_kv_head": cfg.rows_per_kv_head, "pool_bytes": packed, "pool_copies_rotated": len(pools)},
+        "encode_tokens_per_s": T / t_enc, "encode_GB_per_s": enc_bytes / t_enc / 1e9,
+        "encode_frac_hbm_peak": enc_bytes / t_enc / 1e9 / HBM_PEAK_GBPS,
+        "decode_GB_per_s": dec_bytes / t_dec / 1e9,
+        "attend_ms": t_att * 1e3, "encode_ms": t_enc * 1e3, "decode_ms": t_dec * 1e3,
+        "attend_frac_hbm_peak": att_gbps / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "achieved": att_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": att_gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "pool_attend (attention + merge kernels), HIP events on the launch stream"},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, W)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

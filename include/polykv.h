@@ -1,0 +1,138 @@
+/*
+ * polykv.h -- C ABI of the PolyKV shared-pool hot path for AMD MI355X (gfx950).
+ *
+ * One pool holds the KV cache of a shared context, written once and read by any number of
+ * agents (paper: section "PolyKV Architecture", the SharedKVPool abstraction).  Keys are stored
+ * as q8_0 (int8 codes, one fp16 scale = absmax/127 per 32 consecutive head_dim elements; section
+ * "Compression Scheme", key quantization), values as a normalized Walsh-Hadamard rotation
+ * followed by 3-bit Lloyd-Max codes for N(0,1), bit-packed (section "Compression Scheme", value
+ * quantization; codebook of section "TurboQuant").
+ *
+ * Conventions for every call
+ *   - "dev" pointers are device (HBM) addresses on the current HIP device; everything else is
+ *     host memory.  The library allocates no device memory and never synchronizes: work is
+ *     enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - All device buffers are owned by the caller and must stay valid until the enqueued work
+ *     has finished.  A pool handle owns only a small host descriptor.
+ *   - Return value: POLYKV_OK (0) or a negative polykv_status; polykv_last_error() then returns
+ *     a thread-local description.  No call aborts or throws.  NaN/Inf inputs are not checked and
+ *     give unspecified values (never out-of-bounds accesses).
+ *   - Tensor layouts are row-major.  K/V caches: [layers, kv_heads, tokens, head_dim]
+ *     (the paper's [batch=1, heads, seq_len, head_dim] per layer, stacked over layers).
+ */
+#ifndef POLYKV_H
+#define POLYKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct polykv_pool polykv_pool;
+
+typedef enum {
+    POLYKV_OK = 0,
+    POLYKV_EINVAL = -1,  /* NULL pointer, bad enum value                                   */
+    POLYKV_ESHAPE = -2,  /* unsupported or inconsistent dimensions                         */
+    POLYKV_ESTATE = -3,  /* storage not bound, or read before the pool was encoded         */
+    POLYKV_ENOMEM = -4,  /* caller-provided storage / workspace too small                  */
+    POLYKV_EHIP = -5     /* a HIP launch failed                                            */
+} polykv_status;
+
+enum { POLYKV_F16 = 0, POLYKV_F32 = 1 };
+enum { POLYKV_MAX_TAIL_AGENTS = 64 };
+
+/* Attention kernel selection.  AUTO picks by shape: the matrix-core kernel when it supports the
+ * shape, else the vector kernel.  The explicit values exist for tests and profiling. */
+enum { POLYKV_KERNEL_AUTO = 0, POLYKV_KERNEL_VECTOR = 1, POLYKV_KERNEL_MATRIX = 2 };
+
+/* Host descriptor for a pool of `layers` x `kv_heads` x `tokens` vectors of `head_dim` elements.
+ * head_dim must be 64 or 128; all other dimensions >= 1.  (SharedKVPool, section "PolyKV
+ * Architecture".)  *out receives the handle; release it with pool_destroy. */
+int pool_create(int layers, int kv_heads, int head_dim, int tokens, polykv_pool** out);
+void pool_destroy(polykv_pool* pool);
+
+/* Bytes of device storage the packed pool needs (tokens are padded to tiles of 32; per token and
+ * KV head: head_dim code bytes + head_dim/16 scale bytes + 3*head_dim/8 value-code bytes, the
+ * byte counts behind section "Compression Scheme", compression ratio).  0 if pool is NULL. */
+size_t pool_bytes(const polykv_pool* pool);
+
+/* Attach caller-owned device storage (256-byte aligned, >= pool_bytes()).  Re-binding is allowed
+ * and marks the pool as not yet encoded. */
+int pool_bind(polykv_pool* pool, void* dev_storage, size_t bytes);
+
+/* Compress a dense fp16 cache into the bound storage (section "Compression Scheme"):
+ *   keys    per 32-element block: s = fp16(max|k| / 127), code = clip(rint(k / s), -128, 127),
+ *           ties to even, codes formed with the stored (rounded) s; an all-zero block gets s = 0;
+ *   values  v_rot = H_d v / sqrt(d) (natural-order Walsh-Hadamard), code = number of Lloyd-Max
+ *           thresholds strictly below v_rot, 3 bits.
+ * K_dev, V_dev: fp16 [layers, kv_heads, tokens, head_dim], read-only.  May be called again; it
+ * overwrites the pool (the pool is otherwise write-once / read-many). */
+int pool_encode(polykv_pool* pool, const void* K_dev, const void* V_dev, void* stream);
+
+/* Decompress the whole pool to dense tensors (the paper's get_kv_for_layer, section
+ * "DynamicCache Injection", for all layers): K = code * s, V = H_d c[code] / sqrt(d).
+ * out_dtype: POLYKV_F16 or POLYKV_F32; K_out_dev, V_out_dev: [layers, kv_heads, tokens, head_dim].
+ * Either output may be NULL to skip it. */
+int pool_decode(const polykv_pool* pool, void* K_out_dev, void* V_out_dev, int out_dtype, void* stream);
+
+/* Copy the pool out in the canonical format used to compare implementations:
+ *   k_codes_dev  int8   [layers, kv_heads, tokens, head_dim]
+ *   k_scales_dev fp16   [layers, kv_heads, tokens, head_dim/32]
+ *   v_packed_dev uint8  [layers, kv_heads, tokens, 3*head_dim/8], little-endian bit stream:
+ *                code j of a vector occupies stream bits 3j..3j+2, stream bit i is bit (i mod 8)
+ *                of byte floor(i/8).
+ * (The in-HBM layout is tiled for the attention kernel and is not part of the ABI.)  Any of the
+ * three may be NULL. */
+int pool_export(const polykv_pool* pool, void* k_codes_dev, void* k_scales_dev, void* v_packed_dev,
+                void* stream);
+
+/* Decode attention of N agents directly over the packed pool (replaces the paper's per-agent
+ * decompress-and-inject read path of section "DynamicCache Injection"; the result equals softmax
+ * attention over pool_decode()'s tensors).  Every query row attends all pool tokens, then, if
+ * tails are given, the agent's own uncompressed continuation (section "Introduction": each agent
+ * generates independently after the shared prefix).  No mask, no positional transform: Q and K
+ * are taken as already position-encoded. */
+typedef struct {
+    int agents;       /* N >= 1                                                             */
+    int q_per_agent;  /* decode queries per agent per head (1 = plain decode)               */
+    int q_heads;      /* multiple of kv_heads; q head h reads kv head h / (q_heads/kv_heads) */
+    int layer_begin;  /* attend layers [layer_begin, layer_end)                             */
+    int layer_end;
+    float scale;      /* softmax scale; 0 means 1/sqrt(head_dim)                            */
+    /* Optional private tails: host arrays of `agents` device pointers / lengths (NULL = none).
+     * tail_K[a], tail_V[a]: fp16 [layers, kv_heads, tail_capacity, head_dim] (all pool layers),
+     * of which the first tail_len[a] tokens are attended by agent a's queries.  The arrays are
+     * read during the call only.  agents <= POLYKV_MAX_TAIL_AGENTS when tails are used. */
+    const void* const* tail_K;
+    const void* const* tail_V;
+    const int* tail_len;
+    int tail_capacity;
+    int kernel;       /* POLYKV_KERNEL_*                                                    */
+    int splits;       /* token-range splits per KV head; 0 = choose automatically           */
+    void* workspace_dev;     /* scratch for split partials, 256-byte aligned                */
+    size_t workspace_bytes;  /* >= pool_attend_workspace()                                  */
+} polykv_attend_params;
+
+/* Scratch bytes pool_attend needs for these parameters (workspace fields are ignored). */
+size_t pool_attend_workspace(const polykv_pool* pool, const polykv_attend_params* params);
+
+/* Q_dev: fp16 [layer_end-layer_begin, agents, q_per_agent, q_heads, head_dim];
+ * out_dev: fp32, same shape.  Reads the pool only; concurrent calls on different streams are
+ * safe if they use different workspaces. */
+int pool_attend(const polykv_pool* pool, const void* Q_dev, void* out_dev,
+                const polykv_attend_params* params, void* stream);
+
+/* The value codebook the library uses: 8 ascending centroids and the 7 decision thresholds
+ * (midpoints), as fp32 (section "TurboQuant", Lloyd-Max quantization).  Host call. */
+void polykv_codebook(float* centroids8, float* thresholds7);
+
+/* Description of the last error on this thread ("" if none). */
+const char* polykv_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POLYKV_H */

@@ -1,0 +1,313 @@
+// C ABI of libpolykv: argument validation, planning, and dispatch to the kernel launchers.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "polykv_internal.hpp"
+#include "polykv_layout.hpp"
+
+namespace polykv {
+
+static thread_local char g_err[256] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Resolve every choice pool_attend makes from the pool shape and the caller's parameters, so that
+// pool_attend_workspace() and pool_attend() agree by construction.
+static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, AttendPlan* plan) {
+    if (pool == nullptr || prm == nullptr) {
+        set_error("pool_attend: NULL pool or params");
+        return POLYKV_EINVAL;
+    }
+    if (prm->agents < 1 || prm->q_per_agent < 1 || prm->q_heads < 1 || prm->q_heads % pool->kv_heads != 0) {
+        set_error("pool_attend: agents=%d q_per_agent=%d q_heads=%d must be >= 1 and q_heads a multiple of kv_heads=%d",
+                  prm->agents, prm->q_per_agent, prm->q_heads, pool->kv_heads);
+        return POLYKV_ESHAPE;
+    }
+    if (prm->layer_begin < 0 || prm->layer_end > pool->layers || prm->layer_begin >= prm->layer_end) {
+        set_error("pool_attend: layer range [%d,%d) outside [0,%d)", prm->layer_begin, prm->layer_end, pool->layers);
+        return POLYKV_ESHAPE;
+    }
+    if (prm->kernel < POLYKV_KERNEL_AUTO || prm->kernel > POLYKV_KERNEL_MATRIX || prm->splits < 0) {
+        set_error("pool_attend: bad kernel selector %d or splits %d", prm->kernel, prm->splits);
+        return POLYKV_EINVAL;
+    }
+    const bool tails = prm->tail_len != nullptr;
+    if (tails) {
+        if (prm->tail_K == nullptr || prm->tail_V == nullptr) {
+            set_error("pool_attend: tail_len given without tail_K/tail_V");
+            return POLYKV_EINVAL;
+        }
+        if (prm->agents > POLYKV_MAX_TAIL_AGENTS) {
+            set_error("pool_attend: tails support at most %d agents", POLYKV_MAX_TAIL_AGENTS);
+            return POLYKV_ESHAPE;
+        }
+        for (int a = 0; a < prm->agents; ++a) {
+            if (prm->tail_len[a] < 0 || prm->tail_len[a] > prm->tail_capacity) {
+                set_error("pool_attend: tail_len[%d]=%d outside [0, tail_capacity=%d]", a, prm->tail_len[a], prm->tail_capacity);
+                return POLYKV_ESHAPE;
+            }
+            if (prm->tail_len[a] > 0 && (prm->tail_K[a] == nullptr || prm->tail_V[a] == nullptr)) {
+                set_error("pool_attend: agent %d has tail_len > 0 but a NULL tail pointer", a);
+                return POLYKV_EINVAL;
+            }
+        }
+    }
+    AttendPlan& p = *plan;
+    memset(&p, 0, sizeof(p));
+    p.D = pool->head_dim;
+    p.T = pool->tokens;
+    p.tiles = pool->tiles;
+    p.H = pool->kv_heads;
+    p.layer_begin = prm->layer_begin;
+    p.layers = prm->layer_end - prm->layer_begin;
+    p.A = prm->agents;
+    p.nq = prm->q_per_agent;
+    p.q_heads = prm->q_heads;
+    p.G = prm->q_heads / pool->kv_heads;
+    const long rows = (long)p.A * p.nq * p.G;
+    if (rows > (1 << 20)) {
+        set_error("pool_attend: %ld query rows per KV head is more than supported", rows);
+        return POLYKV_ESHAPE;
+    }
+    p.R = (int)rows;
+    const float scale = prm->scale != 0.0f ? prm->scale : 1.0f / sqrtf((float)p.D);
+    p.qscale = scale * 1.4426950408889634f;
+    p.has_tails = tails ? 1 : 0;
+    p.tail_capacity = tails ? prm->tail_capacity : 0;
+
+    const bool mat_ok = matrix_kernel_supports(p.D, p.R);
+    if (prm->kernel == POLYKV_KERNEL_MATRIX && !mat_ok) {
+        set_error("pool_attend: the matrix-core kernel does not support head_dim=%d rows=%d", p.D, p.R);
+        return POLYKV_ESHAPE;
+    }
+    p.kernel = prm->kernel == POLYKV_KERNEL_AUTO ? (mat_ok ? POLYKV_KERNEL_MATRIX : POLYKV_KERNEL_VECTOR) : prm->kernel;
+
+    // Token-range splits per KV head.  Work items are waves; aim at ~2 waves per SIMD of the 256 CUs.
+    const int units = p.layers * p.H;
+    int nsplit;
+    if (p.kernel == POLYKV_KERNEL_VECTOR) {
+        const int nchunks = (p.tiles + 1) / 2;
+        const long groups = (long)units * ((p.R + 7) / 8);
+        long want = prm->splits > 0 ? prm->splits : (2048 + groups - 1) / groups;
+        if (want > nchunks) want = nchunks;
+        if (want < 1) want = 1;
+        nsplit = (int)((want + 3) / 4 * 4);
+    } else {
+        const long groups = (long)units * ((p.R + 63) / 64);
+        long want = prm->splits > 0 ? prm->splits : (1024 + groups - 1) / groups;
+        if (want > p.tiles) want = p.tiles;
+        if (want < 1) want = 1;
+        nsplit = (int)((want + 3) / 4 * 4);
+    }
+    p.nsplit = nsplit;
+
+    size_t off = 0;
+    p.off_ml = off;
+    off = align_up(off + (size_t)units * nsplit * p.R * 2 * sizeof(float), 256);
+    p.off_o = off;
+    off = align_up(off + (size_t)units * nsplit * p.R * p.D * sizeof(float), 256);
+    p.off_tail_ml = off;
+    if (tails) off = align_up(off + (size_t)units * p.R * 2 * sizeof(float), 256);
+    p.off_tail_o = off;
+    if (tails) off = align_up(off + (size_t)units * p.R * p.D * sizeof(float), 256);
+    p.total = off;
+    return POLYKV_OK;
+}
+
+}  // namespace polykv
+
+using namespace polykv;
+
+extern "C" {
+
+int pool_create(int layers, int kv_heads, int head_dim, int tokens, polykv_pool** out) {
+    if (out == nullptr) {
+        set_error("pool_create: out is NULL");
+        return POLYKV_EINVAL;
+    }
+    *out = nullptr;
+    if (head_dim != 64 && head_dim != 128) {
+        set_error("pool_create: head_dim=%d not supported (64 or 128)", head_dim);
+        return POLYKV_ESHAPE;
+    }
+    if (layers < 1 || kv_heads < 1 || tokens < 1 || (long)layers * kv_heads > 65535) {
+        set_error("pool_create: layers=%d kv_heads=%d tokens=%d must be >= 1 and layers*kv_heads <= 65535",
+                  layers, kv_heads, tokens);
+        return POLYKV_ESHAPE;
+    }
+    polykv_pool* p = new (std::nothrow) polykv_pool();
+    if (p == nullptr) {
+        set_error("pool_create: out of host memory");
+        return POLYKV_ENOMEM;
+    }
+    p->layers = layers;
+    p->kv_heads = kv_heads;
+    p->head_dim = head_dim;
+    p->tokens = tokens;
+    p->tiles = tiles_of(tokens);
+    p->tile_bytes = head_dim == 128 ? Layout<128>::tile_bytes : Layout<64>::tile_bytes;
+    p->bytes = (size_t)layers * kv_heads * p->tiles * p->tile_bytes;
+    p->storage = nullptr;
+    p->encoded = false;
+    *out = p;
+    return POLYKV_OK;
+}
+
+void pool_destroy(polykv_pool* pool) { delete pool; }
+
+size_t pool_bytes(const polykv_pool* pool) { return pool ? pool->bytes : 0; }
+
+int pool_bind(polykv_pool* pool, void* dev_storage, size_t bytes) {
+    if (pool == nullptr || dev_storage == nullptr) {
+        set_error("pool_bind: NULL pool or storage");
+        return POLYKV_EINVAL;
+    }
+    if (((uintptr_t)dev_storage & 255) != 0) {
+        set_error("pool_bind: storage must be 256-byte aligned");
+        return POLYKV_EINVAL;
+    }
+    if (bytes < pool->bytes) {
+        set_error("pool_bind: %zu bytes given, %zu needed", bytes, pool->bytes);
+        return POLYKV_ENOMEM;
+    }
+    pool->storage = dev_storage;
+    pool->encoded = false;
+    return POLYKV_OK;
+}
+
+static int check_readable(const polykv_pool* pool, const char* who) {
+    if (pool == nullptr) {
+        set_error("%s: pool is NULL", who);
+        return POLYKV_EINVAL;
+    }
+    if (pool->storage == nullptr) {
+        set_error("%s: no storage bound", who);
+        return POLYKV_ESTATE;
+    }
+    if (!pool->encoded) {
+        set_error("%s: pool has not been encoded", who);
+        return POLYKV_ESTATE;
+    }
+    return POLYKV_OK;
+}
+
+static int hip_result(hipError_t e, const char* who) {
+    if (e == hipSuccess) return POLYKV_OK;
+    set_error("%s: HIP error %d (%s)", who, (int)e, hipGetErrorString(e));
+    return POLYKV_EHIP;
+}
+
+int pool_encode(polykv_pool* pool, const void* K_dev, const void* V_dev, void* stream) {
+    if (pool == nullptr || K_dev == nullptr || V_dev == nullptr) {
+        set_error("pool_encode: NULL argument");
+        return POLYKV_EINVAL;
+    }
+    if (pool->storage == nullptr) {
+        set_error("pool_encode: no storage bound");
+        return POLYKV_ESTATE;
+    }
+    if ((((uintptr_t)K_dev | (uintptr_t)V_dev) & 15) != 0) {
+        set_error("pool_encode: K and V must be 16-byte aligned");
+        return POLYKV_EINVAL;
+    }
+    const int rc = hip_result(launch_encode(pool, K_dev, V_dev, (hipStream_t)stream), "pool_encode");
+    if (rc == POLYKV_OK) pool->encoded = true;
+    return rc;
+}
+
+int pool_decode(const polykv_pool* pool, void* K_out_dev, void* V_out_dev, int out_dtype, void* stream) {
+    int rc = check_readable(pool, "pool_decode");
+    if (rc != POLYKV_OK) return rc;
+    if (out_dtype != POLYKV_F16 && out_dtype != POLYKV_F32) {
+        set_error("pool_decode: out_dtype %d is neither POLYKV_F16 nor POLYKV_F32", out_dtype);
+        return POLYKV_EINVAL;
+    }
+    if (K_out_dev == nullptr && V_out_dev == nullptr) return POLYKV_OK;
+    return hip_result(launch_decode(pool, K_out_dev, V_out_dev, out_dtype, (hipStream_t)stream), "pool_decode");
+}
+
+int pool_export(const polykv_pool* pool, void* k_codes_dev, void* k_scales_dev, void* v_packed_dev, void* stream) {
+    int rc = check_readable(pool, "pool_export");
+    if (rc != POLYKV_OK) return rc;
+    if (k_codes_dev == nullptr && k_scales_dev == nullptr && v_packed_dev == nullptr) return POLYKV_OK;
+    return hip_result(launch_export(pool, k_codes_dev, k_scales_dev, v_packed_dev, (hipStream_t)stream), "pool_export");
+}
+
+size_t pool_attend_workspace(const polykv_pool* pool, const polykv_attend_params* params) {
+    AttendPlan plan;
+    if (make_plan(pool, params, &plan) != POLYKV_OK) return 0;
+    return plan.total;
+}
+
+int pool_attend(const polykv_pool* pool, const void* Q_dev, void* out_dev, const polykv_attend_params* params,
+                void* stream) {
+    int rc = check_readable(pool, "pool_attend");
+    if (rc != POLYKV_OK) return rc;
+    AttendPlan plan;
+    rc = make_plan(pool, params, &plan);
+    if (rc != POLYKV_OK) return rc;
+    if (Q_dev == nullptr || out_dev == nullptr) {
+        set_error("pool_attend: NULL Q or out");
+        return POLYKV_EINVAL;
+    }
+    if (params->workspace_dev == nullptr || ((uintptr_t)params->workspace_dev & 255) != 0) {
+        set_error("pool_attend: workspace must be a 256-byte aligned device pointer");
+        return POLYKV_EINVAL;
+    }
+    if (params->workspace_bytes < plan.total) {
+        set_error("pool_attend: workspace has %zu bytes, %zu needed", params->workspace_bytes, plan.total);
+        return POLYKV_ENOMEM;
+    }
+    if (((uintptr_t)Q_dev & 15) != 0 || ((uintptr_t)out_dev & 15) != 0) {
+        set_error("pool_attend: Q and out must be 16-byte aligned");
+        return POLYKV_EINVAL;
+    }
+    TailPtrs tails;
+    if (plan.has_tails) {
+        memset(&tails, 0, sizeof(tails));
+        for (int a = 0; a < plan.A; ++a) {
+            tails.K[a] = params->tail_K[a];
+            tails.V[a] = params->tail_V[a];
+            tails.len[a] = params->tail_len[a];
+            if (tails.len[a] > 0 && ((((uintptr_t)tails.K[a]) | ((uintptr_t)tails.V[a])) & 15) != 0) {
+                set_error("pool_attend: tail pointers of agent %d must be 16-byte aligned", a);
+                return POLYKV_EINVAL;
+            }
+        }
+    }
+    return hip_result(launch_attend(pool, plan, Q_dev, out_dev, plan.has_tails ? &tails : nullptr,
+                                    params->workspace_dev, (hipStream_t)stream),
+                      "pool_attend");
+}
+
+void polykv_codebook(float* centroids8, float* thresholds7) {
+    const float c[4] = {POLYKV_C0, POLYKV_C1, POLYKV_C2, POLYKV_C3};
+    const float t[3] = {POLYKV_T1, POLYKV_T2, POLYKV_T3};
+    if (centroids8 != nullptr)
+        for (int i = 0; i < 4; ++i) {
+            centroids8[4 + i] = c[i];
+            centroids8[3 - i] = -c[i];
+        }
+    if (thresholds7 != nullptr) {
+        thresholds7[3] = 0.0f;
+        for (int i = 0; i < 3; ++i) {
+            thresholds7[4 + i] = t[i];
+            thresholds7[2 - i] = -t[i];
+        }
+    }
+}
+
+const char* polykv_last_error(void) { return g_err; }
+
+}  // extern "C"

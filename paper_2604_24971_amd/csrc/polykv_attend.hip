@@ -1,0 +1,399 @@
+// Decode attention of all agents' query rows over the packed pool (gfx950): vector (VALU) kernel,
+// private-tail kernel and the merge / inverse-rotation kernel.
+//
+// The pool part is accumulated in the ROTATED value domain: acc[r,:] = sum_t p[r,t] * c[code[t,:]].
+// Because the inverse rotation is linear, it is applied once per output row in the merge kernel
+// instead of once per pool token (sections "Compression Scheme" / "TurboQuant", dequantization).
+// Scores are kept in base-2 units (q is pre-multiplied by scale*log2 e) so exp2 is the only
+// transcendental.  Every split of the token range emits a partial (m, l, acc) per row; the merge
+// kernel combines them with log-sum-exp weights, rotates back, and folds in the agent's private
+// tail partial, which lives in the un-rotated domain.
+#include <hip/hip_fp16.h>
+
+#include "polykv_internal.hpp"
+#include "polykv_layout.hpp"
+
+namespace polykv {
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) x = fmaxf(x, __shfl_xor(x, m, 64));
+    return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
+    return x;
+}
+
+// Query row r of KV head kvh in selected layer ls -> offset (in vectors) into Q / out.
+__device__ __forceinline__ size_t q_row_index(const AttendPlan& p, int ls, int kvh, int r) {
+    const int g = r % p.G, ai = r / p.G;  // ai = a * nq + i
+    return ((size_t)ls * p.A * p.nq + ai) * p.q_heads + kvh * p.G + g;
+}
+
+constexpr int kRB = 8;  // query rows per pass of the vector kernels
+
+// ---------------------------------------------------------------------------- vector kernel ---
+// One wave = one token-range split of one (layer, kv head, block of kRB rows).  Per 64 tokens:
+//   scores  lane = token: the lane dequantizes its key (code * block scale, exact in fp32) and dots
+//           it with each row's query (LDS broadcast);
+//   softmax running max / sum per row across the wave;
+//   PV      lane = (half h, coordinate c) exactly as the value codes are stored: the lane owns the
+//           codes of 16 of the tile's tokens for coordinates 32*mt + c and accumulates its share;
+//           the two halves are added once at the end.
+template <int D>
+__global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __restrict__ pool,
+                                                            const __half* __restrict__ Q,
+                                                            float* __restrict__ ws_ml,
+                                                            float* __restrict__ ws_o, AttendPlan p) {
+    using LY = Layout<D>;
+    constexpr int MT = D / 32;
+    __shared__ __align__(16) float q_s[kRB][D];
+    __shared__ __align__(16) float p_s[4][kRB][64];
+    __shared__ float ctab[8];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int usel = blockIdx.y;  // selected unit: ls * H + kvh
+    const int ls = usel / p.H, kvh = usel - ls * p.H;
+    const int r0 = blockIdx.z * kRB;
+    const int sp = blockIdx.x * 4 + wave;
+
+    for (int i = tid; i < kRB * D; i += 256) {
+        const int r = i / D, jj = i - r * D;
+        float v = 0.0f;
+        if (r0 + r < p.R) v = __half2float(Q[q_row_index(p, ls, kvh, r0 + r) * D + jj]) * p.qscale;
+        q_s[r][jj] = v;
+    }
+    if (tid < 8) ctab[tid] = centroid_of(tid);
+    __syncthreads();
+
+    const int nchunks = (p.tiles + 1) / 2;
+    const int cps = (nchunks + p.nsplit - 1) / p.nsplit;
+    const int c_begin = sp * cps, c_end = min(nchunks, c_begin + cps);
+    const uint8_t* unit_base = pool + (size_t)((p.layer_begin + ls) * p.H + kvh) * p.tiles * LY::tile_bytes;
+
+    float m_run[kRB], l_run[kRB], acc[kRB][MT];
+#pragma unroll
+    for (int r = 0; r < kRB; ++r) {
+        m_run[r] = -INFINITY;
+        l_run[r] = 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[r][mt] = 0.0f;
+    }
+    const int hh = lane >> 5, cc = lane & 31;
+
+    for (int ch = c_begin; ch < c_end; ++ch) {
+        // ---- scores, lane = token
+        {
+            const int tile = ch * 2 + hh, tl = cc;
+            const bool valid = tile < p.tiles && tile * kTile + tl < p.T;
+            const uint8_t* tb = unit_base + (size_t)min(tile, p.tiles - 1) * LY::tile_bytes;
+            float k[D];
+            const __half* sc = reinterpret_cast<const __half*>(tb + LY::kscales_off) + tl * LY::NB;
+#pragma unroll
+            for (int j = 0; j < LY::NB; ++j) {
+                const float s = __half2float(sc[j]);
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    const uint4 raw = *reinterpret_cast<const uint4*>(tb + kcode_run_offset(tl, j, h2));
+                    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        k[32 * j + 16 * h2 + e] = (float)((int)((w[e >> 2] >> (8 * (e & 3))) & 0xFF) - 128) * s;
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < kRB; ++r) {
+                float s = 0.0f;
+#pragma unroll
+                for (int jj = 0; jj < D; jj += 4) {
+                    const float4 qv = *reinterpret_cast<const float4*>(&q_s[r][jj]);
+                    s = fmaf(qv.x, k[jj], s);
+                    s = fmaf(qv.y, k[jj + 1], s);
+                    s = fmaf(qv.z, k[jj + 2], s);
+                    s = fmaf(qv.w, k[jj + 3], s);
+                }
+                s = valid ? s : -INFINITY;
+                const float m_new = fmaxf(m_run[r], wave_max(s));  // finite: every chunk has a valid token
+                const float alpha = exp2f(m_run[r] - m_new);
+                const float pr = exp2f(s - m_new);
+                l_run[r] = l_run[r] * alpha + wave_sum(pr);
+                m_run[r] = m_new;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) acc[r][mt] *= alpha;
+                p_s[wave][r][lane] = pr;
+            }
+        }
+        // ---- PV, lane = (h, c) of the stored value codes; p_s is private to the wave
+        for (int sub = 0; sub < 2; ++sub) {
+            const int tile = ch * 2 + sub;
+            if (tile >= p.tiles) break;
+            const uint32_t* vreg = reinterpret_cast<const uint32_t*>(unit_base + (size_t)tile * LY::tile_bytes + LY::vcodes_off);
+#pragma unroll
+            for (int q = 0; q < LY::NT; ++q) {
+                uint32_t w[3];
+#pragma unroll
+                for (int i = 0; i < 3; ++i) w[i] = vreg[q * 192 + lane * 3 + i];
+#pragma unroll
+                for (int gi = 0; gi < 4; ++gi) {
+                    const int g = 4 * q + gi, mt = g >> 1, ks = g & 1;
+#pragma unroll
+                    for (int e4 = 0; e4 < 2; ++e4) {
+                        float cv[4];
+#pragma unroll
+                        for (int e3 = 0; e3 < 4; ++e3) {
+                            int code;
+                            if (gi < 3) code = (w[gi] >> (8 * e3 + 3 * e4)) & 7;
+                            else if (e4 == 0) code = ((w[0] >> (8 * e3 + 6)) & 3) | (((w[1] >> (8 * e3 + 6)) & 1) << 2);
+                            else code = ((w[2] >> (8 * e3 + 6)) & 3) | (((w[1] >> (8 * e3 + 7)) & 1) << 2);
+                            cv[e3] = ctab[code];
+                        }
+                        const int tk = sub * 32 + 16 * ks + 8 * e4 + 4 * hh;
+#pragma unroll
+                        for (int r = 0; r < kRB; ++r) {
+                            const float4 pv = *reinterpret_cast<const float4*>(&p_s[wave][r][tk]);
+                            acc[r][mt] = fmaf(pv.x, cv[0], acc[r][mt]);
+                            acc[r][mt] = fmaf(pv.y, cv[1], acc[r][mt]);
+                            acc[r][mt] = fmaf(pv.z, cv[2], acc[r][mt]);
+                            acc[r][mt] = fmaf(pv.w, cv[3], acc[r][mt]);
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- emit the split's partial
+#pragma unroll
+    for (int r = 0; r < kRB; ++r) {
+        if (r0 + r >= p.R) break;
+        const size_t prow = ((size_t)usel * p.nsplit + sp) * p.R + r0 + r;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const float v = acc[r][mt] + __shfl_xor(acc[r][mt], 32, 64);
+            if (hh == 0) ws_o[prow * D + 32 * mt + cc] = v;
+        }
+        if (lane == 0) {
+            ws_ml[prow * 2] = m_run[r];
+            ws_ml[prow * 2 + 1] = l_run[r];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------ tail kernel ---
+// Dense fp16 attention of one agent's rows over its private, uncompressed continuation.
+// One wave per (selected layer, kv head, agent, row block); emits (m, l, o) in the original domain.
+template <int D>
+__global__ __launch_bounds__(64) void attend_tail_kernel(const __half* __restrict__ Q, TailPtrs tails,
+                                                         float* __restrict__ tail_ml,
+                                                         float* __restrict__ tail_o, AttendPlan p) {
+    constexpr int EPL = D / 64;
+    __shared__ __align__(16) float q_s[kRB][D];
+    __shared__ __align__(16) float p_s[kRB][64];
+    const int lane = threadIdx.x;
+    const int usel = blockIdx.y, ls = usel / p.H, kvh = usel - ls * p.H;
+    const int a = blockIdx.x;
+    const int rows_a = p.nq * p.G;  // rows of this agent within the KV head, contiguous
+    const int r0 = a * rows_a + blockIdx.z * kRB;
+    const int r_end = min((a + 1) * rows_a, r0 + kRB);
+    if (r0 >= r_end) return;
+    const int len = tails.len[a];
+
+    for (int i = lane; i < kRB * D; i += 64) {
+        const int r = i / D, jj = i - r * D;
+        float v = 0.0f;
+        if (r0 + r < r_end) v = __half2float(Q[q_row_index(p, ls, kvh, r0 + r) * D + jj]) * p.qscale;
+        q_s[r][jj] = v;
+    }
+    __syncthreads();
+
+    const size_t head_off = ((size_t)(p.layer_begin + ls) * p.H + kvh) * p.tail_capacity * D;
+    const __half* Kt = reinterpret_cast<const __half*>(tails.K[a]) + head_off;
+    const __half* Vt = reinterpret_cast<const __half*>(tails.V[a]) + head_off;
+
+    float m_run[kRB], l_run[kRB], acc[kRB][EPL];
+#pragma unroll
+    for (int r = 0; r < kRB; ++r) {
+        m_run[r] = -INFINITY;
+        l_run[r] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc[r][i] = 0.0f;
+    }
+
+    for (int t0 = 0; t0 < len; t0 += 64) {
+        const int tok = t0 + lane;
+        const bool valid = tok < len;
+        float k[D];
+        const uint4* krow = reinterpret_cast<const uint4*>(Kt + (size_t)(valid ? tok : 0) * D);
+#pragma unroll
+        for (int i = 0; i < D / 8; ++i) {
+            const uint4 raw = krow[i];
+            const __half2* h2 = reinterpret_cast<const __half2*>(&raw);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const float2 f = __half22float2(h2[b]);
+                k[i * 8 + 2 * b] = f.x;
+                k[i * 8 + 2 * b + 1] = f.y;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < kRB; ++r) {
+            float s = 0.0f;
+#pragma unroll
+            for (int jj = 0; jj < D; jj += 4) {
+                const float4 qv = *reinterpret_cast<const float4*>(&q_s[r][jj]);
+                s = fmaf(qv.x, k[jj], s);
+                s = fmaf(qv.y, k[jj + 1], s);
+                s = fmaf(qv.z, k[jj + 2], s);
+                s = fmaf(qv.w, k[jj + 3], s);
+            }
+            s = valid ? s : -INFINITY;
+            const float m_new = fmaxf(m_run[r], wave_max(s));
+            const float alpha = exp2f(m_run[r] - m_new);
+            const float pr = exp2f(s - m_new);
+            l_run[r] = l_run[r] * alpha + wave_sum(pr);
+            m_run[r] = m_new;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[r][i] *= alpha;
+            p_s[r][lane] = pr;
+        }
+        __syncthreads();
+        const int cnt = min(64, len - t0);
+        for (int t = 0; t < cnt; ++t) {
+            float v[EPL];
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) v[i] = __half2float(Vt[(size_t)(t0 + t) * D + lane * EPL + i]);
+#pragma unroll
+            for (int r = 0; r < kRB; ++r) {
+                const float pr = p_s[r][t];
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) acc[r][i] = fmaf(pr, v[i], acc[r][i]);
+            }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int r = 0; r < kRB; ++r) {
+        if (r0 + r >= r_end) break;
+        const size_t prow = (size_t)usel * p.R + r0 + r;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) tail_o[prow * D + lane * EPL + i] = acc[r][i];
+        if (lane == 0) {
+            tail_ml[prow * 2] = m_run[r];
+            tail_ml[prow * 2 + 1] = l_run[r];
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------- merge kernel ---
+// One wave per query row: log-sum-exp merge of the split partials, o = H (acc / l) / sqrt(d),
+// then the tail partial (already in the original domain), then the fp32 store.
+template <int D>
+__global__ __launch_bounds__(256) void attend_merge_kernel(const float* __restrict__ ws_ml,
+                                                           const float* __restrict__ ws_o,
+                                                           const float* __restrict__ tail_ml,
+                                                           const float* __restrict__ tail_o,
+                                                           float* __restrict__ out, AttendPlan p) {
+    constexpr int EPL = D / 64;
+    const int lane = threadIdx.x & 63;
+    const long row_global = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long nrows = (long)p.layers * p.H * p.R;
+    const bool active = row_global < nrows;  // no early return: the butterflies need the whole wave
+    const long rg = active ? row_global : 0;
+    const int usel = (int)(rg / p.R), r = (int)(rg - (long)usel * p.R);
+    const int ls = usel / p.H, kvh = usel - ls * p.H;
+
+    float M = -INFINITY;
+    for (int s = 0; s < p.nsplit; ++s) M = fmaxf(M, ws_ml[(((size_t)usel * p.nsplit + s) * p.R + r) * 2]);
+    float Lsum = 0.0f, x[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) x[i] = 0.0f;
+    for (int s = 0; s < p.nsplit; ++s) {
+        const size_t prow = ((size_t)usel * p.nsplit + s) * p.R + r;
+        const float m = ws_ml[prow * 2], l = ws_ml[prow * 2 + 1];
+        if (l > 0.0f) {
+            const float w = exp2f(m - M);
+            Lsum = fmaf(l, w, Lsum);
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) x[i] = fmaf(ws_o[prow * D + lane * EPL + i], w, x[i]);
+        }
+    }
+    const float invL = 1.0f / Lsum;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) x[i] *= invL;
+    // Walsh-Hadamard over D = 64*EPL coordinates, coordinate = lane*EPL + i
+    wht_inlane<EPL>(x);
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+        x[i] = wht_lane_stage<1>(x[i], lane);
+        x[i] = wht_lane_stage<2>(x[i], lane);
+        x[i] = wht_lane_stage<4>(x[i], lane);
+        x[i] = wht_lane_stage<8>(x[i], lane);
+        x[i] = wht_lane_stage<16>(x[i], lane);
+        x[i] = wht_lane_stage<32>(x[i], lane);
+        x[i] *= (D == 64 ? 0.125f : 0.08838834764831845f);
+    }
+    if (p.has_tails) {
+        const size_t prow = (size_t)usel * p.R + r;
+        const float mt = tail_ml[prow * 2], lt = tail_ml[prow * 2 + 1];
+        if (lt > 0.0f) {
+            const float M2 = fmaxf(M, mt);
+            const float wa = exp2f(M - M2) * Lsum, wb = exp2f(mt - M2);
+            const float inv = 1.0f / (wa + wb * lt);
+#pragma unroll
+            for (int i = 0; i < EPL; ++i)
+                x[i] = (wa * x[i] + wb * tail_o[prow * D + lane * EPL + i]) * inv;
+        }
+    }
+    if (active) {
+        float* dst = out + q_row_index(p, ls, kvh, r) * D + lane * EPL;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) dst[i] = x[i];
+    }
+}
+
+// --------------------------------------------------------------------------------- launcher ---
+hipError_t launch_attend_matrix(const polykv_pool* pool, const AttendPlan& plan, const void* Q,
+                                float* ws_ml, float* ws_o, hipStream_t s);
+
+hipError_t launch_attend(const polykv_pool* pool, const AttendPlan& plan, const void* Q, void* out,
+                         const TailPtrs* tails, void* workspace, hipStream_t s) {
+    char* ws = reinterpret_cast<char*>(workspace);
+    float* ws_ml = reinterpret_cast<float*>(ws + plan.off_ml);
+    float* ws_o = reinterpret_cast<float*>(ws + plan.off_o);
+    float* tail_ml = reinterpret_cast<float*>(ws + plan.off_tail_ml);
+    float* tail_o = reinterpret_cast<float*>(ws + plan.off_tail_o);
+    const uint8_t* storage = reinterpret_cast<const uint8_t*>(pool->storage);
+    const int units = plan.layers * plan.H;
+    hipError_t err;
+
+    if (plan.kernel == POLYKV_KERNEL_MATRIX) {
+        err = launch_attend_matrix(pool, plan, Q, ws_ml, ws_o, s);
+        if (err != hipSuccess) return err;
+    } else {
+        dim3 grid(plan.nsplit / 4, units, (plan.R + kRB - 1) / kRB);
+        if (plan.D == 128)
+            attend_vector_kernel<128><<<grid, 256, 0, s>>>(storage, (const __half*)Q, ws_ml, ws_o, plan);
+        else
+            attend_vector_kernel<64><<<grid, 256, 0, s>>>(storage, (const __half*)Q, ws_ml, ws_o, plan);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
+    if (plan.has_tails) {
+        dim3 grid(plan.A, units, (plan.nq * plan.G + kRB - 1) / kRB);
+        if (plan.D == 128)
+            attend_tail_kernel<128><<<grid, 64, 0, s>>>((const __half*)Q, *tails, tail_ml, tail_o, plan);
+        else
+            attend_tail_kernel<64><<<grid, 64, 0, s>>>((const __half*)Q, *tails, tail_ml, tail_o, plan);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
+    const long nrows = (long)units * plan.R;
+    dim3 mgrid((unsigned)((nrows + 3) / 4));
+    if (plan.D == 128)
+        attend_merge_kernel<128><<<mgrid, 256, 0, s>>>(ws_ml, ws_o, tail_ml, tail_o, (float*)out, plan);
+    else
+        attend_merge_kernel<64><<<mgrid, 256, 0, s>>>(ws_ml, ws_o, tail_ml, tail_o, (float*)out, plan);
+    return hipGetLastError();
+}
+
+}  // namespace polykv

@@ -1,0 +1,50 @@
+// Host-side declarations shared by the translation units of libpolykv (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/polykv.h"
+
+struct polykv_pool {
+    int layers, kv_heads, head_dim, tokens;
+    int tiles;          // ceil(tokens / 32)
+    size_t tile_bytes;  // bytes of one tile record
+    size_t bytes;       // layers * kv_heads * tiles * tile_bytes
+    void* storage;      // device, caller-owned
+    bool encoded;
+};
+
+namespace polykv {
+
+void set_error(const char* fmt, ...);
+
+// Everything pool_attend needs after validation; passed by value to the kernels.
+struct AttendPlan {
+    int D, T, tiles, H;          // pool shape
+    int layer_begin, layers;     // selected layer range
+    int A, nq, q_heads, G, R;    // R = A * nq * G query rows per KV head
+    float qscale;                // softmax scale * log2(e): scores are kept in base-2 units
+    int kernel;                  // POLYKV_KERNEL_VECTOR / _MATRIX (resolved)
+    int nsplit;                  // token-range splits per KV head
+    int has_tails, tail_capacity;
+    // workspace carving (byte offsets from the 256-aligned workspace base)
+    size_t off_ml, off_o, off_tail_ml, off_tail_o, total;
+};
+
+struct TailPtrs {
+    const void* K[POLYKV_MAX_TAIL_AGENTS];
+    const void* V[POLYKV_MAX_TAIL_AGENTS];
+    int len[POLYKV_MAX_TAIL_AGENTS];
+};
+
+hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, hipStream_t s);
+hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dtype, hipStream_t s);
+hipError_t launch_export(const polykv_pool* p, void* kc, void* ks, void* vp, hipStream_t s);
+hipError_t launch_attend(const polykv_pool* p, const AttendPlan& plan, const void* Q, void* out,
+                         const TailPtrs* tails, void* workspace, hipStream_t s);
+
+// True if the matrix-core attention kernel supports this shape.
+bool matrix_kernel_supports(int head_dim, int rows_per_kv_head);
+
+}  // namespace polykv

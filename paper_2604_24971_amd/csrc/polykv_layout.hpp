@@ -1,0 +1,134 @@
+// In-HBM layout of the packed pool and small device helpers shared by the kernels.
+//
+// The pool is an array of tile records, [layer*kv_head][tile], one tile = 32 consecutive tokens of
+// one KV head (the last tile is zero-padded).  A record is laid out for the matrix-core attention
+// kernel so that every wave load is one contiguous, fully coalesced run and lands in registers in
+// MFMA operand order:
+//
+//   K codes   NB x 1024 B    NB = head_dim/32 q8_0 blocks.  Byte j*1024 + (h*32 + t)*16 + e holds
+//                            code(token t, element 32j + 16h + e) + 128 (offset binary, 0..255),
+//                            j < NB, h < 2, t < 32, e < 16.
+//   K scales  32 x NB fp16   scale(token t, block j) at index t*NB + j.
+//   V codes   NT x 768 B     NT = head_dim/64 triplets.  Triplet q, lane (h*32 + c), three dwords
+//                            at byte q*768 + (h*32 + c)*12.  They carry four groups of eight 3-bit
+//                            codes, group g = 4q + {0,1,2,3}; group g belongs to rotated coordinate
+//                            32*(g/2) + c and its code e (0..7) to token 16*(g%2) + 8*(e/4) + 4h + e%4.
+//                            Groups 4q+0..2 sit in dword 0..2: code e at bit 8*(e%4) + 3*(e/4).
+//                            Group 4q+3 uses the two spare top bits of every byte:
+//                              code e<4 : bits 1:0 = dword0 bits 8e+7:8e+6, bit 2 = dword1 bit 8e+6
+//                              code e>=4: bits 1:0 = dword2 bits 8(e-4)+7:8(e-4)+6, bit 2 = dword1 bit 8(e-4)+7
+//
+// Per token and KV head this is head_dim + head_dim/16 + 3*head_dim/8 bytes: 184 (d=128), 92 (d=64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace polykv {
+
+constexpr int kTile = 32;  // tokens per tile record
+
+template <int D> struct Layout {
+    static constexpr int NB = D / 32;             // q8_0 blocks per vector
+    static constexpr int NT = D / 64;             // value-code triplets per lane
+    static constexpr int kcodes_off = 0;
+    static constexpr int kscales_off = NB * 1024;
+    static constexpr int vcodes_off = kscales_off + kTile * NB * 2;
+    static constexpr int tile_bytes = vcodes_off + NT * 768;
+};
+
+__host__ __device__ inline int tiles_of(int tokens) { return (tokens + kTile - 1) / kTile; }
+
+// Lloyd-Max codebook for N(0,1), 8 levels: the converged fixed point of Lloyd's iteration
+// (thresholds = midpoints of neighbouring centroids, centroids = conditional means of their cells),
+// rounded to fp32.  They agree to three decimals with the values printed in the paper's section
+// "TurboQuant".
+#define POLYKV_C0 0.24509418f
+#define POLYKV_C1 0.75600528f
+#define POLYKV_C2 1.34390928f
+#define POLYKV_C3 2.15194570f
+#define POLYKV_T1 0.50054973f
+#define POLYKV_T2 1.04995728f
+#define POLYKV_T3 1.74792749f
+
+__device__ __forceinline__ float centroid_of(int code) {
+    // code 0..7 ascending; symmetric table
+    const int m = (code & 4) ? (code & 3) : (3 - code);
+    float c = (m == 0) ? POLYKV_C0 : (m == 1) ? POLYKV_C1 : (m == 2) ? POLYKV_C2 : POLYKV_C3;
+    return (code & 4) ? c : -c;
+}
+
+// Number of thresholds strictly below x (thresholds -T3,-T2,-T1,0,T1,T2,T3).
+__device__ __forceinline__ int quantize3(float x) {
+    int n = 0;
+    n += x > -POLYKV_T3;
+    n += x > -POLYKV_T2;
+    n += x > -POLYKV_T1;
+    n += x > 0.0f;
+    n += x > POLYKV_T1;
+    n += x > POLYKV_T2;
+    n += x > POLYKV_T3;
+    return n;
+}
+
+// Byte offset (inside the K-code region of a tile) of the 16-byte run holding elements
+// 32j + 16h .. +15 of token t.
+__device__ __forceinline__ int kcode_run_offset(int t, int j, int h) {
+    return j * 1024 + (h * 32 + t) * 16;
+}
+
+// Extract the 3-bit value code of (token t of the tile, rotated coordinate dv) from the V-code
+// region `v` (dword view) of a tile.
+__device__ __forceinline__ int vcode_extract(const uint32_t* v, int t, int dv) {
+    const int c = dv & 31, mt = dv >> 5;
+    const int ks = t >> 4, r = t & 15;
+    const int e = ((r >> 3) << 2) | (r & 3), h = (r >> 2) & 1;
+    const int g = mt * 2 + ks, q = g >> 2, gi = g & 3;
+    const uint32_t* w = v + q * 192 + (h * 32 + c) * 3;
+    if (gi < 3) return (w[gi] >> (8 * (e & 3) + 3 * (e >> 2))) & 7;
+    if (e < 4) return ((w[0] >> (8 * e + 6)) & 3) | (((w[1] >> (8 * e + 6)) & 1) << 2);
+    return ((w[2] >> (8 * (e - 4) + 6)) & 3) | (((w[1] >> (8 * (e - 4) + 7)) & 1) << 2);
+}
+
+// ---- cross-lane butterflies -------------------------------------------------------------------
+// Partner exchange lane ^ MASK with DPP where a single control word exists, ds_bpermute otherwise.
+template <int MASK> __device__ __forceinline__ float lane_xor(float x) {
+    int xi = __float_as_int(x), r;
+    if constexpr (MASK == 1) {
+        r = __builtin_amdgcn_update_dpp(xi, xi, 0xB1, 0xF, 0xF, false);  // quad_perm [1,0,3,2]
+    } else if constexpr (MASK == 2) {
+        r = __builtin_amdgcn_update_dpp(xi, xi, 0x4E, 0xF, 0xF, false);  // quad_perm [2,3,0,1]
+    } else if constexpr (MASK == 4) {
+        int y = __builtin_amdgcn_update_dpp(xi, xi, 0x1B, 0xF, 0xF, false);  // quad_perm [3,2,1,0]: ^3
+        r = __builtin_amdgcn_update_dpp(y, y, 0x141, 0xF, 0xF, false);       // row_half_mirror: ^7
+    } else if constexpr (MASK == 8) {
+        int y = __builtin_amdgcn_update_dpp(xi, xi, 0x141, 0xF, 0xF, false);  // ^7
+        r = __builtin_amdgcn_update_dpp(y, y, 0x140, 0xF, 0xF, false);        // row_mirror: ^15
+    } else {
+        r = __builtin_amdgcn_ds_bpermute((((int)threadIdx.x & 63) ^ MASK) << 2, xi);
+    }
+    return __int_as_float(r);
+}
+
+// One Walsh-Hadamard stage across lanes: lanes with bit MASK clear get a+b, the others a-b where
+// a is the value held by the lane with the bit clear.
+template <int MASK> __device__ __forceinline__ float wht_lane_stage(float x, int lane) {
+    const float p = lane_xor<MASK>(x);
+    return (lane & MASK) ? (p - x) : (x + p);
+}
+
+// In-register Walsh-Hadamard transform of N consecutive coordinates (natural order).
+template <int N> __device__ __forceinline__ void wht_inlane(float (&x)[N]) {
+#pragma unroll
+    for (int h = 1; h < N; h <<= 1) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            if ((i & h) == 0) {
+                const float a = x[i], b = x[i | h];
+                x[i] = a + b;
+                x[i | h] = a - b;
+            }
+        }
+    }
+}
+
+}  // namespace polykv

@@ -1,0 +1,215 @@
+"""ctypes binding of libpolykv.so: argument marshalling only -- every step of the hot path runs in
+the HIP kernels behind the C ABI declared in include/polykv.h.  torch supplies device memory and
+the current stream, nothing else.  Importing this module fails loudly if the library is missing."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpolykv.so")
+
+OK, EINVAL, ESHAPE, ESTATE, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
+F16, F32 = 0, 1
+KERNEL_AUTO, KERNEL_VECTOR, KERNEL_MATRIX = 0, 1, 2
+MAX_TAIL_AGENTS = 64
+
+
+class PolyKVError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("polykv status %d: %s" % (status, message))
+        self.status = status
+
+
+class AttendParams(C.Structure):
+    _fields_ = [
+        ("agents", C.c_int), ("q_per_agent", C.c_int), ("q_heads", C.c_int),
+        ("layer_begin", C.c_int), ("layer_end", C.c_int), ("scale", C.c_float),
+        ("tail_K", C.POINTER(C.c_void_p)), ("tail_V", C.POINTER(C.c_void_p)),
+        ("tail_len", C.POINTER(C.c_int)), ("tail_capacity", C.c_int),
+        ("kernel", C.c_int), ("splits", C.c_int),
+        ("workspace_dev", C.c_void_p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "libpolykv.so is not built (%s); run `python -m paper_2604_24971_amd.build`" % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    vp, ip, sz = C.c_void_p, C.c_int, C.c_size_t
+    lib.pool_create.argtypes = [ip, ip, ip, ip, C.POINTER(vp)]
+    lib.pool_create.restype = ip
+    lib.pool_destroy.argtypes = [vp]
+    lib.pool_destroy.restype = None
+    lib.pool_bytes.argtypes = [vp]
+    lib.pool_bytes.restype = sz
+    lib.pool_bind.argtypes = [vp, vp, sz]
+    lib.pool_bind.restype = ip
+    lib.pool_encode.argtypes = [vp, vp, vp, vp]
+    lib.pool_encode.restype = ip
+    lib.pool_decode.argtypes = [vp, vp, vp, ip, vp]
+    lib.pool_decode.restype = ip
+    lib.pool_export.argtypes = [vp, vp, vp, vp, vp]
+    lib.pool_export.restype = ip
+    lib.pool_attend_workspace.argtypes = [vp, C.POINTER(AttendParams)]
+    lib.pool_attend_workspace.restype = sz
+    lib.pool_attend.argtypes = [vp, vp, vp, C.POINTER(AttendParams), vp]
+    lib.pool_attend.restype = ip
+    lib.polykv_codebook.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_float)]
+    lib.polykv_codebook.restype = None
+    lib.polykv_last_error.argtypes = []
+    lib.polykv_last_error.restype = C.c_char_p
+    return lib
+
+
+lib = _load()
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise PolyKVError(rc, lib.polykv_last_error().decode())
+
+
+def codebook():
+    c = (C.c_float * 8)()
+    t = (C.c_float * 7)()
+    lib.polykv_codebook(c, t)
+    return list(c), list(t)
+
+
+def _stream_ptr(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dev_ptr(t: torch.Tensor, dtype, what: str):
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous CUDA tensor of dtype %s" % (what, dtype))
+    return C.c_void_p(t.data_ptr())
+
+
+class Pool:
+    """pool_create + pool_bind around a torch-owned storage tensor."""
+
+    def __init__(self, layers: int, kv_heads: int, head_dim: int, tokens: int, device="cuda:0"):
+        self.layers, self.kv_heads, self.head_dim, self.tokens = layers, kv_heads, head_dim, tokens
+        self.device = torch.device(device)
+        h = C.c_void_p()
+        _check(lib.pool_create(layers, kv_heads, head_dim, tokens, C.byref(h)))
+        self._h = h
+        self.nbytes = lib.pool_bytes(self._h)
+        self.storage = None
+        self._workspace = None
+
+    def bind(self, storage: torch.Tensor | None = None):
+        if storage is None:
+            storage = torch.empty(self.nbytes, dtype=torch.uint8, device=self.device)
+        _check(lib.pool_bind(self._h, _dev_ptr(storage, torch.uint8, "storage"), storage.numel()))
+        self.storage = storage
+        return self
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib.pool_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    # pool_encode(K, V)
+    def encode(self, K: torch.Tensor, V: torch.Tensor, stream=None):
+        shape = (self.layers, self.kv_heads, self.tokens, self.head_dim)
+        if tuple(K.shape) != shape or tuple(V.shape) != shape:
+            raise ValueError("K and V must have shape %s" % (shape,))
+        _check(lib.pool_encode(self._h, _dev_ptr(K, torch.float16, "K"), _dev_ptr(V, torch.float16, "V"),
+                               _stream_ptr(stream)))
+
+    # pool_decode(K_out, V_out)
+    def decode(self, dtype=torch.float32, K_out=None, V_out=None, stream=None):
+        shape = (self.layers, self.kv_heads, self.tokens, self.head_dim)
+        code = {torch.float16: F16, torch.float32: F32}[dtype]
+        if K_out is None:
+            K_out = torch.empty(shape, dtype=dtype, device=self.device)
+        if V_out is None:
+            V_out = torch.empty(shape, dtype=dtype, device=self.device)
+        _check(lib.pool_decode(self._h, _dev_ptr(K_out, dtype, "K_out"), _dev_ptr(V_out, dtype, "V_out"),
+                               code, _stream_ptr(stream)))
+        return K_out, V_out
+
+    def export(self, stream=None):
+        n = (self.layers, self.kv_heads, self.tokens)
+        kc = torch.empty(n + (self.head_dim,), dtype=torch.int8, device=self.device)
+        ks = torch.empty(n + (self.head_dim // 32,), dtype=torch.float16, device=self.device)
+        vp = torch.empty(n + (3 * self.head_dim // 8,), dtype=torch.uint8, device=self.device)
+        _check(lib.pool_export(self._h, C.c_void_p(kc.data_ptr()), C.c_void_p(ks.data_ptr()),
+                               C.c_void_p(vp.data_ptr()), _stream_ptr(stream)))
+        return kc, ks, vp
+
+    def _params(self, Q, q_heads, layer_begin, layer_end, scale, tails, kernel, splits):
+        if Q.dim() != 5:
+            raise ValueError("Q must be [layers_selected, agents, q_per_agent, q_heads, head_dim]")
+        layer_end = self.layers if layer_end is None else layer_end
+        Ls, A, nq, qh, d = Q.shape
+        if Ls != layer_end - layer_begin or d != self.head_dim or (q_heads is not None and qh != q_heads):
+            raise ValueError("Q shape %s does not match the layer range / head_dim" % (tuple(Q.shape),))
+        p = AttendParams()
+        p.agents, p.q_per_agent, p.q_heads = A, nq, qh
+        p.layer_begin, p.layer_end, p.scale = layer_begin, layer_end, float(scale or 0.0)
+        p.kernel, p.splits = kernel, splits
+        keep = []
+        if tails is not None:
+            if len(tails) != A:
+                raise ValueError("tails must have one entry per agent")
+            tk = (C.c_void_p * A)()
+            tv = (C.c_void_p * A)()
+            tl = (C.c_int * A)()
+            cap = None
+            for a, ent in enumerate(tails):
+                if ent is None:
+                    tl[a] = 0
+                    continue
+                Kt, Vt, n = ent
+                shape = (self.layers, self.kv_heads, Kt.shape[2], self.head_dim)
+                if tuple(Kt.shape) != shape or tuple(Vt.shape) != shape:
+                    raise ValueError("tail tensors must be [layers, kv_heads, capacity, head_dim]")
+                if cap is None:
+                    cap = Kt.shape[2]
+                elif cap != Kt.shape[2]:
+                    raise ValueError("all tails must share one capacity")
+                tk[a] = _dev_ptr(Kt, torch.float16, "tail K").value
+                tv[a] = _dev_ptr(Vt, torch.float16, "tail V").value
+                tl[a] = int(n)
+            p.tail_K = C.cast(tk, C.POINTER(C.c_void_p))
+            p.tail_V = C.cast(tv, C.POINTER(C.c_void_p))
+            p.tail_len = C.cast(tl, C.POINTER(C.c_int))
+            p.tail_capacity = cap or 0
+            keep += [tk, tv, tl]
+        return p, keep
+
+    def attend_workspace_bytes(self, Q, **kw):
+        p, _keep = self._params(Q, kw.get("q_heads"), kw.get("layer_begin", 0), kw.get("layer_end"),
+                                kw.get("scale"), kw.get("tails"), kw.get("kernel", KERNEL_AUTO),
+                                kw.get("splits", 0))
+        return lib.pool_attend_workspace(self._h, C.byref(p))
+
+    # pool_attend(Q[agents], out)
+    def attend(self, Q: torch.Tensor, out: torch.Tensor | None = None, *, q_heads=None, layer_begin=0,
+               layer_end=None, scale=None, tails=None, kernel=KERNEL_AUTO, splits=0, workspace=None,
+               stream=None):
+        p, _keep = self._params(Q, q_heads, layer_begin, layer_end, scale, tails, kernel, splits)
+        need = lib.pool_attend_workspace(self._h, C.byref(p))
+        if need == 0:
+            _check(lib.pool_attend(self._h, None, None, C.byref(p), None))  # surfaces the shape error
+        if workspace is None:
+            if self._workspace is None or self._workspace.numel() < need:
+                self._workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+            workspace = self._workspace
+        p.workspace_dev = _dev_ptr(workspace, torch.uint8, "workspace")
+        p.workspace_bytes = workspace.numel()
+        if out is None:
+            out = torch.empty(Q.shape, dtype=torch.float32, device=self.device)
+        _check(lib.pool_attend(self._h, _dev_ptr(Q, torch.float16, "Q"), _dev_ptr(out, torch.float32, "out"),
+                               C.byref(p), _stream_ptr(stream)))
+        return out

@@ -1,0 +1,137 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every function the header declares,
+and its host-side logic (validation, sizes, state machine, codebook) behaves as documented.
+No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from conftest import ROOT
+from oracle import polykv_oracle as O
+
+pk = pytest.importorskip("paper_2604_24971_amd.polykv")
+lib = pk.lib
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "polykv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:pool|polykv)_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    names = _declared_functions()
+    assert {"pool_create", "pool_bytes", "pool_bind", "pool_encode", "pool_decode", "pool_export",
+            "pool_attend_workspace", "pool_attend", "pool_destroy", "polykv_codebook",
+            "polykv_last_error"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_codebook_literals_equal_oracle_codebook_in_fp32():
+    c, t = pk.codebook()
+    oc, ot = O.codebook()
+    np.testing.assert_array_equal(np.array(c, np.float32), oc.astype(np.float32))
+    np.testing.assert_array_equal(np.array(t, np.float32), ot.astype(np.float32))
+
+
+def _create(L, H, d, T):
+    h = C.c_void_p()
+    rc = lib.pool_create(L, H, d, T, C.byref(h))
+    return rc, h
+
+
+def test_create_validation_and_byte_counts():
+    for bad in [(1, 1, 96, 10), (1, 1, 256, 10), (0, 1, 64, 10), (1, 0, 64, 10), (1, 1, 64, 0),
+                (1, 1, 64, -5), (70000, 1, 64, 10)]:
+        rc, h = _create(*bad)
+        assert rc == pk.ESHAPE and not h.value
+        assert lib.polykv_last_error()
+    assert lib.pool_create(1, 1, 64, 1, None) == pk.EINVAL
+    assert lib.pool_bytes(None) == 0
+    # tile-multiple token counts: exactly the oracle's stored byte count (184 / 92 B per token-head)
+    for (L, H, d, T) in [(32, 8, 128, 4096), (1, 4, 64, 640), (24, 32, 64, 1856)]:
+        rc, h = _create(L, H, d, T)
+        assert rc == pk.OK
+        assert lib.pool_bytes(h) == O.stored_bytes(L, H, T, d)["packed"]
+        lib.pool_destroy(h)
+    # ragged token counts are padded to whole tiles of 32
+    rc, h = _create(32, 8, 128, 7194)
+    assert lib.pool_bytes(h) == O.stored_bytes(32, 8, 7200, 128)["packed"]
+    lib.pool_destroy(h)
+    lib.pool_destroy(None)
+
+
+def test_state_machine_and_argument_errors_without_gpu():
+    rc, h = _create(2, 2, 64, 100)
+    assert rc == pk.OK
+    fake = C.c_void_p(0x10000)       # never dereferenced: every call below fails validation first
+    assert lib.pool_encode(h, fake, fake, None) == pk.ESTATE          # nothing bound
+    assert lib.pool_decode(h, fake, fake, pk.F32, None) == pk.ESTATE
+    assert lib.pool_export(h, fake, fake, fake, None) == pk.ESTATE
+    assert lib.pool_bind(h, None, 1 << 30) == pk.EINVAL
+    assert lib.pool_bind(h, C.c_void_p(0x10010), 1 << 30) == pk.EINVAL  # misaligned
+    assert lib.pool_bind(h, fake, 10) == pk.ENOMEM
+    assert b"needed" in lib.polykv_last_error()
+    assert lib.pool_bind(None, fake, 10) == pk.EINVAL
+    assert lib.pool_bind(h, fake, lib.pool_bytes(h)) == pk.OK
+    assert lib.pool_encode(h, None, fake, None) == pk.EINVAL
+    assert lib.pool_encode(h, C.c_void_p(0x10002), fake, None) == pk.EINVAL   # misaligned input
+    # bound but not encoded: reads refuse
+    assert lib.pool_decode(h, fake, fake, pk.F32, None) == pk.ESTATE
+    p = pk.AttendParams()
+    p.agents, p.q_per_agent, p.q_heads, p.layer_begin, p.layer_end = 3, 1, 2, 0, 2
+    assert lib.pool_attend(h, fake, fake, C.byref(p), None) == pk.ESTATE
+    assert b"not been encoded" in lib.polykv_last_error()
+    lib.pool_destroy(h)
+
+
+def test_attend_plan_validation_and_workspace_size():
+    rc, h = _create(4, 2, 128, 1000)
+    p = pk.AttendParams()
+    p.agents, p.q_per_agent, p.q_heads, p.layer_begin, p.layer_end = 3, 1, 8, 0, 4
+    need = lib.pool_attend_workspace(h, C.byref(p))
+    assert need > 0 and need % 256 == 0
+    # at least one partial (m, l, acc[d]) per row per split
+    rows = 3 * 1 * 4
+    assert need >= 4 * 2 * rows * (128 + 2) * 4
+    p.splits = 8
+    need8 = lib.pool_attend_workspace(h, C.byref(p))
+    p.splits = 16
+    assert lib.pool_attend_workspace(h, C.byref(p)) > need8
+    p.splits = 0
+    for field, val in [("q_heads", 7), ("agents", 0), ("q_per_agent", 0), ("layer_end", 5),
+                       ("layer_begin", 4), ("kernel", 9), ("splits", -1)]:
+        q = pk.AttendParams.from_buffer_copy(p)
+        setattr(q, field, val)
+        assert lib.pool_attend_workspace(h, C.byref(q)) == 0, field
+        assert lib.polykv_last_error()
+    assert lib.pool_attend_workspace(h, None) == 0
+    assert lib.pool_attend_workspace(None, C.byref(p)) == 0
+    # tails: lengths are checked against the capacity, agent count against the maximum
+    tl = (C.c_int * 3)(1, 5, 0)
+    tk = (C.c_void_p * 3)(0x1000, 0x2000, 0)
+    q = pk.AttendParams.from_buffer_copy(p)
+    q.tail_K = C.cast(tk, C.POINTER(C.c_void_p))
+    q.tail_V = C.cast(tk, C.POINTER(C.c_void_p))
+    q.tail_len = C.cast(tl, C.POINTER(C.c_int))
+    q.tail_capacity = 4
+    assert lib.pool_attend_workspace(h, C.byref(q)) == 0
+    q.tail_capacity = 8
+    assert lib.pool_attend_workspace(h, C.byref(q)) > need
+    lib.pool_destroy(h)
+
+
+def test_python_binding_rejects_wrong_tensors_before_any_launch():
+    import torch
+    pool = pk.Pool(1, 2, 64, 50)
+    assert pool.nbytes == 2 * 2 * 2944
+    with pytest.raises(TypeError):
+        pool.bind(torch.empty(pool.nbytes, dtype=torch.uint8))        # CPU tensor
+    with pytest.raises(ValueError):
+        pool.encode(torch.empty(1, 2, 49, 64), torch.empty(1, 2, 49, 64))
+    pool.close()
+    with pytest.raises(pk.PolyKVError):
+        pk.Pool(1, 2, 80, 50)

@@ -1,0 +1,253 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on identical
+seeded inputs (shapes and distributions of the workload configurations, reduced in layer count
+where the oracle would otherwise take minutes)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import polykv_oracle as O
+from paper_2604_24971_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _pk():
+    from paper_2604_24971_amd import polykv as pk
+    return pk
+
+
+def _pu():
+    import parity_util
+    return parity_util
+
+
+class Case:
+    """One encoded pool on both sides."""
+
+    def __init__(self, cfg, K=None, V=None):
+        pu = _pu()
+        self.cfg = cfg
+        if K is None:
+            K, V = W.kv_pool(cfg)
+        self.K, self.V = K, V
+        self.ref = O.pool_encode(K, V)
+        self.pool = pu.gpu_pool(K, V)
+        self.dirty, self.k_mis, self.v_mis = pu.compare_codes(self.pool, self.ref)
+        self._dec = None
+
+    def decoded(self):
+        if self._dec is None:
+            self._dec = O.pool_decode(self.ref)
+        return self._dec
+
+    def attend_check(self, Q, tails_np=None, tails_len=None, **kw):
+        pu = _pu()
+        Kh, Vh = self.decoded()
+        lb = kw.get("layer_begin", 0)
+        le = kw.get("layer_end") or self.cfg.layers
+        ref_tails = None
+        gpu_tails = None
+        if tails_np is not None:
+            ref_tails, gpu_tails = [], []
+            for (Kt, Vt), n in zip(tails_np, tails_len):
+                ref_tails.append((Kt[lb:le, :, :n], Vt[lb:le, :, :n]))
+                gpu_tails.append((pu.dev(Kt), pu.dev(Vt), n))
+        ref = O.pool_attend(Kh[lb:le], Vh[lb:le], Q, scale=kw.get("scale"), tails=ref_tails)
+        out = self.pool.attend(pu.dev(Q), tails=gpu_tails, **kw)
+        torch.cuda.synchronize()
+        return pu.compare_attend(out, ref, self.cfg.kv_heads, self.dirty, lb)
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    return Case(W.CONFIGS[1])
+
+
+@pytest.fixture(scope="module")
+def smol():
+    return Case(W.CONFIGS[2].scaled(layers=2))
+
+
+@pytest.fixture(scope="module")
+def llama():
+    return Case(W.CONFIGS[3].scaled(layers=2, tokens=1500))
+
+
+# ------------------------------------------------------------------ encode / decode ---
+@pytest.mark.parametrize("name", ["tiny", "smol", "llama"])
+def test_encode_codes_bit_exact_and_decode_within_tolerance(name, request):
+    case = request.getfixturevalue(name)
+    pu = _pu()
+    n = case.K.size
+    assert case.k_mis <= 1e-5 * n and case.v_mis <= 1e-4 * n     # threshold cases are rare
+    pu.compare_decode(case.pool, case.ref, case.dirty)
+    b = O.stored_bytes(case.cfg.layers, case.cfg.kv_heads, 32 * math.ceil(case.cfg.tokens / 32), case.cfg.head_dim)
+    assert case.pool.nbytes == b["packed"]
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("T", [1, 31, 32, 33, 95, 257])
+def test_encode_decode_ragged_token_counts(d, T):
+    pu = _pu()
+    rng = np.random.default_rng(100 * d + T)
+    K = (rng.standard_normal((2, 3, T, d)) * np.exp(rng.standard_normal((2, 3, T, 1)))).astype(np.float16)
+    V = (rng.standard_normal((2, 3, T, d)) * 1.3).astype(np.float16)
+    case = Case(W.PoolConfig(0, "ragged", 2, 3, 6, d, T, 2, 1), K, V)
+    pu.compare_decode(case.pool, case.ref, case.dirty)
+    Q = rng.standard_normal((2, 2, 1, 6, d)).astype(np.float16)
+    case.attend_check(Q)
+
+
+def test_encode_degenerate_blocks_zero_constant_extreme():
+    pu = _pu()
+    d, T = 128, 40
+    K = np.zeros((1, 2, T, d), dtype=np.float16)
+    V = np.zeros_like(K)
+    K[0, 0, 3, 32:64] = 0.375                 # constant block -> all +127
+    K[0, 0, 4, 5] = -60000.0                  # near fp16 max
+    K[0, 0, 5, 64:96] = 6e-8                  # fp16 subnormal input, subnormal scale
+    K[0, 1, 7] = np.linspace(-1, 1, d)
+    V[0, 0, 2] = 0.25                         # constant vector -> spike at coordinate 0
+    V[0, 0, 3, 17] = 8.0                      # spike -> +-8/sqrt(d) everywhere
+    V[0, 1, 9] = 300.0                        # saturates the outer centroid
+    case = Case(W.PoolConfig(0, "degenerate", 1, 2, 2, d, T, 1, 1), K, V)
+    assert case.k_mis == 0 and case.v_mis == 0
+    pu.compare_decode(case.pool, case.ref, case.dirty)
+    kc, ks, _ = case.pool.export()
+    assert int(kc[0, 0, 3, 32:64].min()) == 127 and float(ks[0, 0, 0, 0]) == 0.0
+    assert not kc[0, 0, 0].any()
+
+
+def test_reencode_overwrites_and_storage_is_exactly_pool_bytes():
+    pu = _pu()
+    pk = _pk()
+    cfg = W.CONFIGS[1]
+    K, V = W.kv_pool(cfg)
+    pool = pk.Pool(cfg.layers, cfg.kv_heads, cfg.head_dim, cfg.tokens)
+    guard = 4096
+    buf = torch.full((pool.nbytes + 2 * guard,), 0x5C, dtype=torch.uint8, device="cuda:0")
+    pool.bind(buf[guard:guard + pool.nbytes])
+    pool.encode(pu.dev(V), pu.dev(K))          # swapped on purpose, then overwritten
+    pool.encode(pu.dev(K), pu.dev(V))
+    ref = O.pool_encode(K, V)
+    pu.compare_codes(pool, ref)
+    assert bool((buf[:guard] == 0x5C).all()) and bool((buf[guard + pool.nbytes:] == 0x5C).all())
+
+
+# ------------------------------------------------------------------------- attention ---
+def test_attend_tiny_whole_config(tiny):
+    pk = _pk()
+    Q = W.queries(tiny.cfg)
+    for kernel in (pk.KERNEL_AUTO, pk.KERNEL_VECTOR):
+        tiny.attend_check(Q, kernel=kernel)
+
+
+def test_attend_smollm2_shape(smol):
+    smol.attend_check(W.queries(smol.cfg))
+
+
+def test_attend_llama_shape_gqa(llama):
+    pk = _pk()
+    Q = W.queries(llama.cfg)
+    llama.attend_check(Q, kernel=pk.KERNEL_VECTOR)
+    llama.attend_check(Q)
+
+
+@pytest.mark.parametrize("splits", [1, 4, 8, 28, 64])
+def test_attend_any_split_count_gives_the_same_answer(llama, splits):
+    pk = _pk()
+    Q = W.queries(llama.cfg)[:1, :3]
+    cfg1 = dict(layer_begin=0, layer_end=1, splits=splits)
+    llama.attend_check(Q, kernel=pk.KERNEL_VECTOR, **cfg1)
+    llama.attend_check(Q, **cfg1)
+
+
+def test_attend_layer_ranges_scale_and_multi_query(llama):
+    rng = np.random.default_rng(77)
+    cfg = llama.cfg
+    Q = rng.standard_normal((1, 2, 3, cfg.q_heads, cfg.head_dim)).astype(np.float16)
+    llama.attend_check(Q, layer_begin=1, layer_end=2)
+    llama.attend_check(Q, layer_begin=1, layer_end=2, scale=0.05)
+
+
+def test_attend_result_does_not_depend_on_other_agents(llama):
+    # agent-count invariance (paper, Findings 1 and 5): batching agents must not change any of them
+    pu = _pu()
+    Q = W.queries(llama.cfg)
+    full = llama.pool.attend(pu.dev(Q))
+    for sel in ([4], [0, 7, 14]):
+        part = llama.pool.attend(pu.dev(Q[:, sel]))
+        torch.testing.assert_close(part, full[:, sel], rtol=0, atol=2e-5)
+
+
+def test_attend_with_private_tails(llama):
+    cfg = llama.cfg
+    lens = [0, 1, 5, 63, 64, 17, 0, 2, 33, 64, 9, 40, 1, 64, 3][: cfg.agents]
+    tails = W.tails(cfg.scaled(cid=4), [64] * cfg.agents)
+    Q = W.queries(cfg, step=1)
+    llama.attend_check(Q, tails_np=tails, tails_len=lens)
+    # a tail of length zero everywhere is the same as no tail
+    pu = _pu()
+    a = llama.pool.attend(pu.dev(Q))
+    b = llama.pool.attend(pu.dev(Q), tails=[(pu.dev(t[0]), pu.dev(t[1]), 0) for t in tails])
+    assert torch.equal(a, b)
+
+
+def test_attend_tails_tiny_d64(tiny):
+    cfg = tiny.cfg
+    tails = W.tails(cfg, [70, 70, 70])
+    tiny.attend_check(W.queries(cfg, step=2), tails_np=tails, tails_len=[70, 0, 13])
+
+
+def test_attend_special_cases_zero_keys_and_dominant_key():
+    pu = _pu()
+    rng = np.random.default_rng(5)
+    d, T = 64, 200
+    V = rng.standard_normal((1, 1, T, d)).astype(np.float16)
+    K = np.zeros((1, 1, T, d), dtype=np.float16)
+    case = Case(W.PoolConfig(0, "zero-k", 1, 1, 2, d, T, 2, 1), K, V)
+    Q = rng.standard_normal((1, 2, 1, 2, d)).astype(np.float16)
+    out = case.pool.attend(pu.dev(Q)).cpu().numpy()
+    _, Vh = case.decoded()
+    np.testing.assert_allclose(out[0, 1, 0, 0], Vh[0, 0].mean(0), atol=2e-3)      # uniform weights
+    q = Q[0, 0, 0, 0].astype(np.float32)
+    K[0, 0, 123] = (40.0 * q / np.linalg.norm(q)).astype(np.float16)
+    case = Case(W.PoolConfig(0, "one-hot", 1, 1, 2, d, T, 2, 1), K, V)
+    out = case.pool.attend(pu.dev(Q), scale=1.0).cpu().numpy()
+    _, Vh = case.decoded()
+    np.testing.assert_allclose(out[0, 0, 0, 0], Vh[0, 0, 123], atol=2e-3)         # one dominant key
+
+
+def test_attend_equals_dense_attention_over_pool_decode_output(llama):
+    # property that holds at any size: the fused read path == softmax attention over pool_decode()
+    pu = _pu()
+    cfg = llama.cfg
+    Q = pu.dev(W.queries(cfg, step=3))
+    out = llama.pool.attend(Q)
+    Kd, Vd = llama.pool.decode(torch.float32)
+    G = cfg.group
+    q = Q.double().permute(0, 3, 1, 2, 4)                       # [L, qh, A, nq, d]
+    k = Kd.double().repeat_interleave(G, dim=1)                 # [L, qh, T, d]
+    v = Vd.double().repeat_interleave(G, dim=1)
+    s = torch.einsum("lhand,lhtd->lhant", q, k) / math.sqrt(cfg.head_dim)
+    ref = torch.einsum("lhant,lhtd->lhand", torch.softmax(s, dim=-1), v).permute(0, 2, 3, 1, 4)
+    assert float((out.double() - ref).abs().max()) < 2e-3
+
+
+def test_attend_error_paths_on_device(tiny):
+    pk = _pk()
+    pu = _pu()
+    Q = pu.dev(W.queries(tiny.cfg))
+    small = torch.empty(256, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(pk.PolyKVError) as e:
+        tiny.pool.attend(Q, workspace=small)
+    assert e.value.status == pk.ENOMEM
+    with pytest.raises(pk.PolyKVError) as e:
+        tiny.pool.attend(Q[:, :, :, :3].contiguous())            # 3 q heads over 4 kv heads
+    assert e.value.status == pk.ESHAPE
+    fresh = pk.Pool(1, 4, 64, 600).bind()
+    with pytest.raises(pk.PolyKVError) as e:
+        fresh.attend(Q)
+    assert e.value.status == pk.ESTATE
