@@ -98,17 +98,18 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
     int nsplit;
     if (p.kernel == POLYKV_KERNEL_VECTOR) {
         const int nchunks = (p.tiles + 1) / 2;
-        const long groups = (long)units * ((p.R + 7) / 8);
+        const long groups = (long)units * ((p.R + 3) / 4);
         long want = prm->splits > 0 ? prm->splits : (2048 + groups - 1) / groups;
         if (want > nchunks) want = nchunks;
         if (want < 1) want = 1;
         nsplit = (int)((want + 3) / 4 * 4);
     } else {
+        // one workgroup (4 waves, one per SIMD) per split: fill the 256 CUs once
         const long groups = (long)units * ((p.R + 63) / 64);
-        long want = prm->splits > 0 ? prm->splits : (1024 + groups - 1) / groups;
-        if (want > p.tiles) want = p.tiles;
+        long want = prm->splits > 0 ? prm->splits : (256 + groups - 1) / groups;
+        if (want > (p.tiles + 3) / 4) want = (p.tiles + 3) / 4;
         if (want < 1) want = 1;
-        nsplit = (int)((want + 3) / 4 * 4);
+        nsplit = (int)want;
     }
     p.nsplit = nsplit;
 

@@ -26,29 +26,23 @@ __device__ __forceinline__ float wave_sum(float x) {
     return x;
 }
 
-// Query row r of KV head kvh in selected layer ls -> offset (in vectors) into Q / out.
-__device__ __forceinline__ size_t q_row_index(const AttendPlan& p, int ls, int kvh, int r) {
-    const int g = r % p.G, ai = r / p.G;  // ai = a * nq + i
-    return ((size_t)ls * p.A * p.nq + ai) * p.q_heads + kvh * p.G + g;
-}
-
-constexpr int kRB = 8;  // query rows per pass of the vector kernels
+constexpr int kRB = 4;  // query rows per pass of the vector kernels
 
 // ---------------------------------------------------------------------------- vector kernel ---
 // One wave = one token-range split of one (layer, kv head, block of kRB rows).  Per 64 tokens:
 //   scores  lane = token: the lane dequantizes its key (code * block scale, exact in fp32) and dots
 //           it with each row's query (LDS broadcast);
 //   softmax running max / sum per row across the wave;
-//   PV      lane = (half h, coordinate c) exactly as the value codes are stored: the lane owns the
-//           codes of 16 of the tile's tokens for coordinates 32*mt + c and accumulates its share;
-//           the two halves are added once at the end.
+//   PV      lane = (group grp, coordinate m) exactly as the value codes are stored: the lane owns
+//           the codes of 8 of the tile's tokens for coordinates 16*g + m and accumulates its share;
+//           the four lane groups are added once at the end.
 template <int D>
 __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __restrict__ pool,
                                                             const __half* __restrict__ Q,
                                                             float* __restrict__ ws_ml,
                                                             float* __restrict__ ws_o, AttendPlan p) {
     using LY = Layout<D>;
-    constexpr int MT = D / 32;
+    constexpr int MT = D / 16;
     __shared__ __align__(16) float q_s[kRB][D];
     __shared__ __align__(16) float p_s[4][kRB][64];
     __shared__ float ctab[8];
@@ -81,7 +75,8 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[r][mt] = 0.0f;
     }
-    const int hh = lane >> 5, cc = lane & 31;
+    const int hh = lane >> 5, cc = lane & 31;   // scores: which tile of the pair, token in the tile
+    const int grp = lane >> 4, mm = lane & 15;  // PV: position of the lane in the value-code layout
 
     for (int ch = c_begin; ch < c_end; ++ch) {
         // ---- scores, lane = token
@@ -95,12 +90,12 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
             for (int j = 0; j < LY::NB; ++j) {
                 const float s = __half2float(sc[j]);
 #pragma unroll
-                for (int h2 = 0; h2 < 2; ++h2) {
-                    const uint4 raw = *reinterpret_cast<const uint4*>(tb + kcode_run_offset(tl, j, h2));
-                    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+                for (int g8 = 0; g8 < 4; ++g8) {
+                    const uint2 raw = *reinterpret_cast<const uint2*>(tb + kcode_run_offset(tl, j, g8));
+                    const uint32_t w[2] = {raw.x, raw.y};
 #pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        k[32 * j + 16 * h2 + e] = (float)((int)((w[e >> 2] >> (8 * (e & 3))) & 0xFF) - 128) * s;
+                    for (int e = 0; e < 8; ++e)
+                        k[32 * j + 8 * g8 + e] = (float)((int)((w[e >> 2] >> (8 * (e & 3))) & 0xFF) - 128) * s;
                 }
             }
 #pragma unroll
@@ -137,7 +132,7 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
                 for (int i = 0; i < 3; ++i) w[i] = vreg[q * 192 + lane * 3 + i];
 #pragma unroll
                 for (int gi = 0; gi < 4; ++gi) {
-                    const int g = 4 * q + gi, mt = g >> 1, ks = g & 1;
+                    const int g = 4 * q + gi;
 #pragma unroll
                     for (int e4 = 0; e4 < 2; ++e4) {
                         float cv[4];
@@ -149,14 +144,14 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
                             else code = ((w[2] >> (8 * e3 + 6)) & 3) | (((w[1] >> (8 * e3 + 7)) & 1) << 2);
                             cv[e3] = ctab[code];
                         }
-                        const int tk = sub * 32 + 16 * ks + 8 * e4 + 4 * hh;
+                        const int tk = sub * 32 + 16 * e4 + 4 * grp;   // tokens tk .. tk+3
 #pragma unroll
                         for (int r = 0; r < kRB; ++r) {
                             const float4 pv = *reinterpret_cast<const float4*>(&p_s[wave][r][tk]);
-                            acc[r][mt] = fmaf(pv.x, cv[0], acc[r][mt]);
-                            acc[r][mt] = fmaf(pv.y, cv[1], acc[r][mt]);
-                            acc[r][mt] = fmaf(pv.z, cv[2], acc[r][mt]);
-                            acc[r][mt] = fmaf(pv.w, cv[3], acc[r][mt]);
+                            acc[r][g] = fmaf(pv.x, cv[0], acc[r][g]);
+                            acc[r][g] = fmaf(pv.y, cv[1], acc[r][g]);
+                            acc[r][g] = fmaf(pv.z, cv[2], acc[r][g]);
+                            acc[r][g] = fmaf(pv.w, cv[3], acc[r][g]);
                         }
                     }
                 }
@@ -171,8 +166,10 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
         const size_t prow = ((size_t)usel * p.nsplit + sp) * p.R + r0 + r;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            const float v = acc[r][mt] + __shfl_xor(acc[r][mt], 32, 64);
-            if (hh == 0) ws_o[prow * D + 32 * mt + cc] = v;
+            float v = acc[r][mt];
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            if (grp == 0) ws_o[prow * D + 16 * mt + mm] = v;
         }
         if (lane == 0) {
             ws_ml[prow * 2] = m_run[r];
@@ -354,9 +351,6 @@ __global__ __launch_bounds__(256) void attend_merge_kernel(const float* __restri
 }
 
 // --------------------------------------------------------------------------------- launcher ---
-hipError_t launch_attend_matrix(const polykv_pool* pool, const AttendPlan& plan, const void* Q,
-                                float* ws_ml, float* ws_o, hipStream_t s);
-
 hipError_t launch_attend(const polykv_pool* pool, const AttendPlan& plan, const void* Q, void* out,
                          const TailPtrs* tails, void* workspace, hipStream_t s) {
     char* ws = reinterpret_cast<char*>(workspace);
@@ -369,8 +363,9 @@ hipError_t launch_attend(const polykv_pool* pool, const AttendPlan& plan, const 
     hipError_t err;
 
     if (plan.kernel == POLYKV_KERNEL_MATRIX) {
-        err = launch_attend_matrix(pool, plan, Q, ws_ml, ws_o, s);
+        err = launch_attend_matrix(pool, plan, Q, ws_ml, ws_o, (float*)out, s);
         if (err != hipSuccess) return err;
+        if (matrix_kernel_direct(plan)) return hipSuccess;
     } else {
         dim3 grid(plan.nsplit / 4, units, (plan.R + kRB - 1) / kRB);
         if (plan.D == 128)

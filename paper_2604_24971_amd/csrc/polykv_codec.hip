@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
     const int tok = tile * kTile + t;
     const bool valid = tok < T;
     const size_t row = ((size_t)unit * T + (valid ? tok : 0)) * D + c * EPT;
-    const int e0 = c * EPT, j = e0 >> 5, h = (e0 >> 4) & 1, off = e0 & 15;
+    const int e0 = c * EPT, j = e0 >> 5, g8 = (e0 >> 3) & 3;
 
     // ---- keys: block absmax -> fp16 scale -> codes with the stored scale
     {
@@ -87,9 +87,12 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
             }
             packed[i] = w;
         }
-        uint32_t* dst = reinterpret_cast<uint32_t*>(img + LY::kcodes_off + kcode_run_offset(t, j, h) + off);
 #pragma unroll
-        for (int i = 0; i < EPT / 4; ++i) dst[i] = packed[i];
+        for (int rr = 0; rr < EPT / 8; ++rr) {
+            uint32_t* dst = reinterpret_cast<uint32_t*>(img + LY::kcodes_off + kcode_run_offset(t, j, g8 + rr));
+            dst[0] = packed[2 * rr];
+            dst[1] = packed[2 * rr + 1];
+        }
         if ((e0 & 31) == 0)
             reinterpret_cast<__half*>(img + LY::kscales_off)[t * LY::NB + j] = s16;
     }
@@ -115,16 +118,15 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
     for (int idx = tid; idx < LY::NT * 192; idx += 256) {
         const int q = idx / 192, rem = idx - q * 192;
         const int lane = rem / 3, w = rem - lane * 3;
-        const int hh = lane >> 5, cc = lane & 31;
-        const int g = 4 * q + w, dv = 32 * (g >> 1) + cc, ks = g & 1;
-        const int dv3 = 32 * ((4 * q + 3) >> 1) + cc;  // spare-bit group 4q+3: ks = 1
+        const int grp = lane >> 4, m = lane & 15;
+        const int dv = 16 * (4 * q + w) + m;
+        const int dv3 = 16 * (4 * q + 3) + m;  // group 4q+3 lives in the spare bits
         uint32_t word = 0;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const int tk = 16 * ks + 8 * (e >> 2) + 4 * hh + (e & 3);
+            const int tk = vcode_token(grp, e);
             word |= (uint32_t)vstage[tk * D + dv] << (8 * (e & 3) + 3 * (e >> 2));
-            const int tk3 = 16 + 8 * (e >> 2) + 4 * hh + (e & 3);
-            const uint32_t c3 = vstage[tk3 * D + dv3];
+            const uint32_t c3 = vstage[tk * D + dv3];
             if (w == 0 && e < 4) word |= (c3 & 3) << (8 * e + 6);
             if (w == 2 && e >= 4) word |= (c3 & 3) << (8 * (e - 4) + 6);
             if (w == 1) word |= (c3 >> 2) << (e < 4 ? 8 * e + 6 : 8 * (e - 4) + 7);
@@ -168,14 +170,16 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
     const int tok = tile * kTile + t;
     const bool valid = tok < T;
     const size_t row = ((size_t)unit * T + (valid ? tok : 0)) * D + c * EPT;
-    const int e0 = c * EPT, j = e0 >> 5, h = (e0 >> 4) & 1, off = e0 & 15;
+    const int e0 = c * EPT, j = e0 >> 5, g8 = (e0 >> 3) & 3;
 
     if (K_out != nullptr) {
-        const uint8_t* codes = img + LY::kcodes_off + kcode_run_offset(t, j, h) + off;
         const float s = __half2float(reinterpret_cast<const __half*>(img + LY::kscales_off)[t * LY::NB + j]);
         if (valid) {
 #pragma unroll
-            for (int i = 0; i < EPT; ++i) K_out[row + i] = to_out<OutT>((float)((int)codes[i] - 128) * s);
+            for (int i = 0; i < EPT; ++i) {
+                const uint8_t* codes = img + LY::kcodes_off + kcode_run_offset(t, j, g8 + (i >> 3));
+                K_out[row + i] = to_out<OutT>((float)((int)codes[i & 7] - 128) * s);
+            }
         }
     }
     if (V_out != nullptr) {
@@ -206,11 +210,13 @@ __global__ __launch_bounds__(256) void export_kernel(const uint8_t* __restrict__
     const int tok = tile * kTile + t;
     if (tok >= T) return;
     const size_t vec = (size_t)unit * T + tok;
-    const int e0 = c * EPT, j = e0 >> 5, h = (e0 >> 4) & 1, off = e0 & 15;
+    const int e0 = c * EPT, j = e0 >> 5, g8 = (e0 >> 3) & 3;
     if (k_codes != nullptr) {
-        const uint8_t* codes = img + LY::kcodes_off + kcode_run_offset(t, j, h) + off;
 #pragma unroll
-        for (int i = 0; i < EPT; ++i) k_codes[vec * D + e0 + i] = (int8_t)((int)codes[i] - 128);
+        for (int i = 0; i < EPT; ++i) {
+            const uint8_t* codes = img + LY::kcodes_off + kcode_run_offset(t, j, g8 + (i >> 3));
+            k_codes[vec * D + e0 + i] = (int8_t)((int)codes[i & 7] - 128);
+        }
     }
     if (k_scales != nullptr && c < LY::NB)
         k_scales[vec * LY::NB + c] = reinterpret_cast<const __half*>(img + LY::kscales_off)[t * LY::NB + c];

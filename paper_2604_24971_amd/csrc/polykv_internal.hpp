@@ -46,5 +46,16 @@ hipError_t launch_attend(const polykv_pool* p, const AttendPlan& plan, const voi
 
 // True if the matrix-core attention kernel supports this shape.
 bool matrix_kernel_supports(int head_dim, int rows_per_kv_head);
+// True if the matrix-core kernel writes the final output itself (no merge kernel needed).
+bool matrix_kernel_direct(const AttendPlan& plan);
+hipError_t launch_attend_matrix(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,
+                                float* ws_o, float* out, hipStream_t s);
+
+// Query row r of KV head kvh in selected layer ls -> index (in vectors of head_dim) into Q / out.
+// Rows of a KV head are ordered (agent, query, head-in-group): r = (a * nq + i) * G + g.
+__host__ __device__ inline size_t q_row_index(const AttendPlan& p, int ls, int kvh, int r) {
+    const int g = r % p.G, ai = r / p.G;
+    return ((size_t)ls * p.A * p.nq + ai) * p.q_heads + kvh * p.G + g;
+}
 
 }  // namespace polykv

@@ -89,7 +89,7 @@ def test_state_machine_and_argument_errors_without_gpu():
 
 
 def test_attend_plan_validation_and_workspace_size():
-    rc, h = _create(4, 2, 128, 1000)
+    rc, h = _create(4, 2, 128, 4000)
     p = pk.AttendParams()
     p.agents, p.q_per_agent, p.q_heads, p.layer_begin, p.layer_end = 3, 1, 8, 0, 4
     need = lib.pool_attend_workspace(h, C.byref(p))

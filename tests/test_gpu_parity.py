@@ -192,7 +192,7 @@ def test_attend_with_private_tails(llama):
     pu = _pu()
     a = llama.pool.attend(pu.dev(Q))
     b = llama.pool.attend(pu.dev(Q), tails=[(pu.dev(t[0]), pu.dev(t[1]), 0) for t in tails])
-    assert torch.equal(a, b)
+    torch.testing.assert_close(a, b, rtol=0, atol=1e-5)     # fused epilogue vs merge kernel
 
 
 def test_attend_tails_tiny_d64(tiny):
