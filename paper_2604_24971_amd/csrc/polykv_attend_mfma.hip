@@ -3,9 +3,12 @@
 // One wave owns up to 64 query rows (NRT tiles of 16) of one KV head and streams 32-token tile
 // records.  Per tile, with tokens as the MFMA M dimension and query rows as N:
 //
-//   scores   S^T[t, r] = sum_j s[t, j] * (codes_j[t, :] . q_j[r, :])     one MFMA per q8_0 block j
-//            (K = 32 = one block): int8 codes are exact in fp16, the product is accumulated in fp32
-//            and multiplied by the block scale in fp32 afterwards, so key dequantization is exact.
+//   staging  the record is copied global -> LDS asynchronously (global_load_lds), three tiles ahead,
+//            into a per-wave ring; nothing passes through registers until it is used.
+//   scores   S^T[t, r] = sum_j sum_{k in block j} (code[t,k] * s[t,j]) * q[r,k].  The dequantized key
+//            code*s has up to 18 significant bits, so it is split exactly into two fp16 terms
+//            hi = fp16(code*s), lo = code*s - hi (one packed fma), each fed to one MFMA per q8_0 block
+//            (K = 32 = one block) with fp32 accumulation: key dequantization stays exact.
 //   softmax  online, per row, in base-2 units; the reference maximum is only raised when a row
 //            exceeds it by more than 2^8, so the accumulator rescale is rare; p <= 256 fits fp16.
 //   PV       O^T[v, r] += sum_t c[code[t, v]] * p[t, r]   with the score tile's accumulator layout
@@ -33,10 +36,9 @@ union H8 {
     uint32_t u[4];
 };
 
-// Centroids scaled by kCentroidScale and rounded to fp16.  The factor was searched in [1, 2) so that
-// all four magnitudes land within 1.9e-5 (relative) of an fp16 value -- ten times closer than the
-// unscaled centroids; it is divided out once per output row.
-constexpr float kCentroidScale = 1.6146639585494995f;
+// Centroids scaled by 1.6146639585494995 and rounded to fp16.  The factor was searched in [1, 2) so
+// that all four magnitudes land within 1.9e-5 (relative) of an fp16 value -- ten times closer than the
+// unscaled centroids; its inverse is applied once per output row.
 constexpr float kInvCentroidScale = 0.6193239123875222f;
 // fp16 bit patterns by code 0..7: C2F3 C057 BCE2 B655 3655 3CE2 4057 42F3, split into byte planes
 constexpr uint32_t kTabLoA = 0x55E257F3u, kTabLoB = 0xF357E255u;  // low bytes of codes 0..3 / 4..7
@@ -67,32 +69,170 @@ __device__ __forceinline__ float xor32_max(float x) {
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-template <int D> struct RawTile {
-    static constexpr int NB = D / 32, NTR = D / 64, SCV = NB / 2;  // SCV: 16-byte scale vectors per 16 tokens
-    uint4v k[NB];
-    union {
-        uint4v v[2][SCV];
-        _Float16 h[2][4 * NB];  // [mt][4 tokens x NB blocks]
-    } sc;
-    uint32_t v[NTR][3];
-};
+__device__ __forceinline__ float max8(const float4v& a, const float4v& b) {
+    return fmaxf(fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])), fmaxf(fmaxf(b[0], b[1]), fmaxf(b[2], b[3])));
+}
+
+// ---- asynchronous tile staging: global -> LDS without passing through registers ----------------
+// A tile record is copied verbatim into one slot of the wave's private LDS ring with
+// global_load_lds (each lane moves 16 bytes to base + lane*16, which is exactly how the
+// record is laid out).  The copies are tracked by vmcnt only, so the wave waits with an explicit
+// s_waitcnt for the oldest tile while up to kAhead younger ones stay in flight.
+constexpr int kSlots = 4, kAhead = 3;
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
 
 template <int D>
-__device__ __forceinline__ void load_tile(RawTile<D>& rt, const uint8_t* tb, int lane, int grp) {
+__device__ __forceinline__ void issue_tile(const uint8_t* g, uint8_t* lds, int lane) {
+    // The record is a byte stream for this purpose: whole kilobytes with all 64 lanes, the remainder
+    // (a multiple of 16 bytes) with the first lanes only.  (The 12-byte form of the copy strides lanes
+    // by 16 bytes in LDS, so only the 16-byte form reproduces the record verbatim.)
+    constexpr int TB = Layout<D>::tile_bytes, FULL = TB / 1024, REM = TB % 1024;
+    static_assert(REM % 16 == 0, "");
+#pragma unroll
+    for (int j = 0; j < FULL; ++j)
+        __builtin_amdgcn_global_load_lds((gptr_t)(g + j * 1024 + lane * 16), (lptr_t)(lds + j * 1024), 16, 0, 0);
+    if (REM != 0 && lane < REM / 16)
+        __builtin_amdgcn_global_load_lds((gptr_t)(g + FULL * 1024 + lane * 16), (lptr_t)(lds + FULL * 1024), 16, 0, 0);
+}
+
+// s_waitcnt vmcnt(N) only (expcnt / lgkmcnt untouched); N < 64.
+#define POLYKV_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14))
+
+template <int LPT> __device__ __forceinline__ void wait_tiles_in_flight(int younger) {
+    // `younger` tiles (each LPT copies) were issued after the one about to be read
+    if (younger >= 3) POLYKV_WAIT_VMCNT(3 * LPT);
+    else if (younger == 2) POLYKV_WAIT_VMCNT(2 * LPT);
+    else if (younger == 1) POLYKV_WAIT_VMCNT(1 * LPT);
+    else POLYKV_WAIT_VMCNT(0);
+    asm volatile("" ::: "memory");
+}
+
+// One 32-token tile from its LDS copy `lt`: scores, online softmax, PV.  RAGGED = the tile crosses the
+// end of the pool; tokens >= T are masked out.
+template <int D, int NRT, bool RAGGED>
+__device__ __forceinline__ void process_tile(const uint8_t* lt, int tile, int T, float qscale, float raise_thr,
+                                             int lane, const half8 (&qb)[NRT][D / 32], float4v (&O)[D / 16][NRT],
+                                             float4v (&Lacc)[NRT], float (&m_ref)[NRT], float (&m_thr)[NRT],
+                                             float (&mneg)[NRT]) {
     using LY = Layout<D>;
-    constexpr int NB = D / 32;
+    constexpr int NB = D / 32, NG = D / 16, NTR = D / 64;
+    const int grp = lane >> 4, n = lane & 15;
+    const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    H8 ones;
 #pragma unroll
-    for (int j = 0; j < NB; ++j) rt.k[j] = *reinterpret_cast<const uint4v*>(tb + j * 1024 + lane * 16);
+    for (int i = 0; i < 4; ++i) ones.u[i] = 0x3C003C00u;
+
+    // ---- scores
+    float4v S[NRT][2];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int nt = 0; nt < NRT; ++nt) S[nt][0] = S[nt][1] = float4v{0, 0, 0, 0};
 #pragma unroll
-        for (int x = 0; x < RawTile<D>::SCV; ++x)
-            rt.sc.v[mt][x] = *reinterpret_cast<const uint4v*>(tb + LY::kscales_off + (16 * mt + 4 * grp) * NB * 2 + 16 * x);
+    for (int mt = 0; mt < 2; ++mt) {
+        // scales of token 16mt + n, blocks 0..NB-1
+        union {
+            uint32_t u[NB / 2];
+            _Float16 h[NB];
+        } sc;
 #pragma unroll
-    for (int q = 0; q < RawTile<D>::NTR; ++q)
+        for (int x = 0; x < NB / 2; ++x)
+            sc.u[x] = *reinterpret_cast<const uint32_t*>(lt + LY::kscales_off + (16 * mt + n) * NB * 2 + 4 * x);
 #pragma unroll
-        for (int w = 0; w < 3; ++w)
-            rt.v[q][w] = *reinterpret_cast<const uint32_t*>(tb + LY::vcodes_off + q * 768 + lane * 12 + 4 * w);
+        for (int j = 0; j < NB; ++j) {
+            const uint2 kw = *reinterpret_cast<const uint2*>(lt + j * 1024 + lane * 16 + 8 * mt);
+            H8 a;
+            codes4_to_half(kw.x, a.u[0], a.u[1]);
+            codes4_to_half(kw.y, a.u[2], a.u[3]);
+            a.h = a.h - (_Float16)1152.0f;
+            const half8 sv = (half8)(sc.h[j]);
+            const half8 hi = a.h * sv;
+            const half8 lo = __builtin_elementwise_fma(a.h, sv, -hi);  // exact remainder of the product
+#pragma unroll
+            for (int nt = 0; nt < NRT; ++nt)
+                S[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hi, qb[nt][j], S[nt][mt], 0, 0, 0);
+#pragma unroll
+            for (int nt = 0; nt < NRT; ++nt)
+                S[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(lo, qb[nt][j], S[nt][mt], 0, 0, 0);
+        }
+    }
+    if (RAGGED) {  // tokens past the end never score
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (tile * kTile + 16 * mt + 4 * grp + i >= T) {
+#pragma unroll
+                    for (int nt = 0; nt < NRT; ++nt) S[nt][mt][i] = -INFINITY;
+                }
+    }
+
+    // ---- online softmax; the vote needs no cross-lane reduction, only the (rare) raise does
+    float mloc[NRT];
+    bool raise = false;
+#pragma unroll
+    for (int nt = 0; nt < NRT; ++nt) {
+        mloc[nt] = max8(S[nt][0], S[nt][1]);
+        raise |= mloc[nt] > m_thr[nt];  // also true while the reference is -inf
+    }
+    if (__builtin_expect(__any(raise), 0)) {
+        // Rare.  The accumulators live in accumulation registers that vector instructions cannot
+        // read; an MFMA with zero operands (D = 0*0 + C) carries them to vector registers and back,
+        // so the hot path never copies them.
+#pragma unroll
+        for (int nt = 0; nt < NRT; ++nt) {
+            const float m_new = fmaxf(m_ref[nt], xor32_max(xor16_max(mloc[nt])));
+            const float alpha = __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
+            m_ref[nt] = m_new;
+            m_thr[nt] = m_new + raise_thr;
+            mneg[nt] = -m_new * qscale;
+            float4v x = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, Lacc[nt], 0, 0, 0);
+            x *= alpha;
+            Lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, x, 0, 0, 0);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                float4v y = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, O[g][nt], 0, 0, 0);
+                y *= alpha;
+                O[g][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, y, 0, 0, 0);
+            }
+        }
+    }
+    H8 pb[NRT];
+#pragma unroll
+    for (int nt = 0; nt < NRT; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                pb[nt].h[4 * mt + i] = (_Float16)__builtin_amdgcn_exp2f(fmaf(S[nt][mt][i], qscale, mneg[nt]));
+
+    // ---- PV in the rotated domain
+#pragma unroll
+    for (int q = 0; q < NTR; ++q) {
+        const uint32_t* vw = reinterpret_cast<const uint32_t*>(lt + LY::vcodes_off + q * 768 + lane * 12);
+        const uint32_t w0 = vw[0], w1 = vw[1], w2 = vw[2];
+#pragma unroll
+        for (int gi = 0; gi < 4; ++gi) {
+            uint32_t sel_a, sel_b;
+            if (gi < 3) {
+                const uint32_t w = gi == 0 ? w0 : gi == 1 ? w1 : w2;
+                sel_a = w & 0x07070707u;
+                sel_b = (w >> 3) & 0x07070707u;
+            } else {
+                sel_a = ((w0 >> 6) & 0x03030303u) | ((w1 >> 4) & 0x04040404u);
+                sel_b = ((w2 >> 6) & 0x03030303u) | ((w1 >> 5) & 0x04040404u);
+            }
+            H8 va;
+            lookup4(sel_a, va.u[0], va.u[1]);
+            lookup4(sel_b, va.u[2], va.u[3]);
+#pragma unroll
+            for (int nt = 0; nt < NRT; ++nt)
+                O[4 * q + gi][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, pb[nt].h, O[4 * q + gi][nt], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int nt = 0; nt < NRT; ++nt)
+        Lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones.h, pb[nt].h, Lacc[nt], 0, 0, 0);
 }
 
 template <int D, int NRT>
@@ -101,24 +241,35 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
                                                           float* __restrict__ ws_ml, float* __restrict__ ws_o,
                                                           float* __restrict__ out, AttendPlan p, int direct) {
     using LY = Layout<D>;
-    constexpr int NB = D / 32, NG = D / 16, NTR = D / 64, ROWS = 16 * NRT;
+    constexpr int NB = D / 32, NG = D / 16, ROWS = 16 * NRT;
     constexpr int OSTRIDE = D + 4;
+    constexpr int TB = LY::tile_bytes;
+    constexpr int LPT = TB / 1024 + (TB % 1024 != 0);  // copies per tile
+    static_assert(kAhead * LPT < 64, "vmcnt is a 6-bit counter");
+    static_assert(ROWS * OSTRIDE * 4 <= 4 * kSlots * TB, "the merge buffer reuses the ring");
+    extern __shared__ __align__(16) uint8_t smem[];  // 4 waves x kSlots tile records; reused for the merge
     __shared__ float m_s[4][ROWS];
     __shared__ float l_s[ROWS];
-    __shared__ __align__(16) float o_s[ROWS * OSTRIDE];
+    float* o_s = reinterpret_cast<float*>(smem);
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: LDS bases go through M0
     const int grp = lane >> 4, n = lane & 15;
     const int usel = blockIdx.y, ls = usel / p.H, kvh = usel - ls * p.H;
     const int row0 = blockIdx.z * ROWS;
     const int split = blockIdx.x;
     const int tps = (p.tiles + p.nsplit - 1) / p.nsplit;
     const int t_begin = split * tps, t_end = min(p.tiles, t_begin + tps);
-    const uint8_t* unit_base = pool + (size_t)((p.layer_begin + ls) * p.H + kvh) * p.tiles * LY::tile_bytes;
+    const uint8_t* unit_base = pool + (size_t)((p.layer_begin + ls) * p.H + kvh) * p.tiles * TB;
     const float qscale = p.qscale;
+    uint8_t* ring = smem + wave * (kSlots * TB);
 
-    for (int i = tid; i < ROWS * OSTRIDE; i += 256) o_s[i] = 0.0f;
-    if (tid < ROWS) l_s[tid] = 0.0f;
+    // this wave's tiles: t_begin + wave, +4, +8, ...
+    const int my_first = t_begin + wave;
+    const int my_count = my_first < t_end ? (t_end - my_first + 3) / 4 : 0;
+#pragma unroll
+    for (int a = 0; a < kAhead; ++a)
+        if (a < my_count) issue_tile<D>(unit_base + (size_t)(my_first + 4 * a) * TB, ring + a * TB, lane);
 
     // ---- query rows as MFMA B operands: lane (n, grp) holds q[row 16nt+n][32j + 8grp .. +7]
     half8 qb[NRT][NB];
@@ -136,128 +287,45 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     }
 
     float4v O[NG][NRT], Lacc[NRT];
-    float m_ref[NRT];
+    float m_ref[NRT], m_thr[NRT], mneg[NRT];
 #pragma unroll
     for (int nt = 0; nt < NRT; ++nt) {
         m_ref[nt] = -INFINITY;
+        m_thr[nt] = -INFINITY;
+        mneg[nt] = 0.0f;
         Lacc[nt] = float4v{0, 0, 0, 0};
 #pragma unroll
         for (int g = 0; g < NG; ++g) O[g][nt] = float4v{0, 0, 0, 0};
     }
-    H8 ones;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) ones.u[i] = 0x3C003C00u;
     const float raise_thr = 8.0f / qscale;  // raise the reference only when a row exceeds it by 2^8
 
-    RawTile<D> cur, nxt;
-    int tile = t_begin + wave;
-    if (tile < t_end) load_tile<D>(cur, unit_base + (size_t)tile * LY::tile_bytes, lane, grp);
-
-    for (; tile < t_end; tile += 4) {
-        const int tile_n = tile + 4;
-        if (tile_n < t_end) load_tile<D>(nxt, unit_base + (size_t)tile_n * LY::tile_bytes, lane, grp);
-
-        // ---- scores
-        float4v S[NRT][2];
-#pragma unroll
-        for (int nt = 0; nt < NRT; ++nt) S[nt][0] = S[nt][1] = float4v{0, 0, 0, 0};
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            const uint32_t kw[4] = {cur.k[j].x, cur.k[j].y, cur.k[j].z, cur.k[j].w};
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                H8 a;
-                codes4_to_half(kw[2 * mt], a.u[0], a.u[1]);
-                codes4_to_half(kw[2 * mt + 1], a.u[2], a.u[3]);
-                a.h = a.h - (_Float16)1152.0f;
-#pragma unroll
-                for (int nt = 0; nt < NRT; ++nt) {
-                    const float4v X = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, qb[nt][j], float4v{0, 0, 0, 0}, 0, 0, 0);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        S[nt][mt][i] = fmaf(X[i], (float)cur.sc.h[mt][i * NB + j], S[nt][mt][i]);
-                }
-            }
-        }
-        if (tile * kTile + kTile > p.T) {  // ragged last tile: tokens past the end never score
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (tile * kTile + 16 * mt + 4 * grp + i >= p.T) {
-#pragma unroll
-                        for (int nt = 0; nt < NRT; ++nt) S[nt][mt][i] = -INFINITY;
-                    }
-        }
-
-        // ---- online softmax
-        float mx[NRT];
-        bool raise = false;
-#pragma unroll
-        for (int nt = 0; nt < NRT; ++nt) {
-            float m = fmaxf(fmaxf(S[nt][0][0], S[nt][0][1]), fmaxf(S[nt][0][2], S[nt][0][3]));
-            m = fmaxf(m, fmaxf(fmaxf(S[nt][1][0], S[nt][1][1]), fmaxf(S[nt][1][2], S[nt][1][3])));
-            m = xor32_max(xor16_max(m));
-            mx[nt] = m;
-            raise |= m > m_ref[nt] + raise_thr;   // also true while m_ref is -inf
-        }
-        if (__any(raise)) {
-#pragma unroll
-            for (int nt = 0; nt < NRT; ++nt) {
-                const float m_new = fmaxf(m_ref[nt], mx[nt]);
-                const float alpha = __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
-                m_ref[nt] = m_new;
-                Lacc[nt] *= alpha;
-#pragma unroll
-                for (int g = 0; g < NG; ++g) O[g][nt] *= alpha;
-            }
-        }
-        H8 pb[NRT];
-#pragma unroll
-        for (int nt = 0; nt < NRT; ++nt) {
-            const float mneg = -m_ref[nt] * qscale;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    pb[nt].h[4 * mt + i] = (_Float16)__builtin_amdgcn_exp2f(fmaf(S[nt][mt][i], qscale, mneg));
-        }
-
-        // ---- PV in the rotated domain
-#pragma unroll
-        for (int q = 0; q < NTR; ++q) {
-            const uint32_t w0 = cur.v[q][0], w1 = cur.v[q][1], w2 = cur.v[q][2];
-#pragma unroll
-            for (int gi = 0; gi < 4; ++gi) {
-                uint32_t sel_a, sel_b;
-                if (gi < 3) {
-                    const uint32_t w = gi == 0 ? w0 : gi == 1 ? w1 : w2;
-                    sel_a = w & 0x07070707u;
-                    sel_b = (w >> 3) & 0x07070707u;
-                } else {
-                    sel_a = ((w0 >> 6) & 0x03030303u) | ((w1 >> 4) & 0x04040404u);
-                    sel_b = ((w2 >> 6) & 0x03030303u) | ((w1 >> 5) & 0x04040404u);
-                }
-                H8 va;
-                lookup4(sel_a, va.u[0], va.u[1]);
-                lookup4(sel_b, va.u[2], va.u[3]);
-#pragma unroll
-                for (int nt = 0; nt < NRT; ++nt)
-                    O[4 * q + gi][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, pb[nt].h, O[4 * q + gi][nt], 0, 0, 0);
-            }
-        }
-#pragma unroll
-        for (int nt = 0; nt < NRT; ++nt)
-            Lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones.h, pb[nt].h, Lacc[nt], 0, 0, 0);
-
-        cur = nxt;
+    // Only the pool's very last tile can be ragged; it is peeled out of the loop so that the loop body
+    // is one straight-line block.
+    const bool last_ragged = my_count > 0 && (my_first + 4 * (my_count - 1)) * kTile + kTile > p.T;
+    const int full_count = last_ragged ? my_count - 1 : my_count;
+    for (int it = 0; it < full_count; ++it) {
+        const int tile = my_first + 4 * it;
+        if (it + kAhead < my_count)
+            issue_tile<D>(unit_base + (size_t)(tile + 4 * kAhead) * TB, ring + ((it + kAhead) % kSlots) * TB, lane);
+        wait_tiles_in_flight<LPT>(min(kAhead, my_count - 1 - it));
+        process_tile<D, NRT, false>(ring + (it % kSlots) * TB, tile, p.T, qscale, raise_thr, lane, qb, O, Lacc, m_ref,
+                                    m_thr, mneg);
+    }
+    if (last_ragged) {
+        const int it = my_count - 1;
+        wait_tiles_in_flight<LPT>(0);
+        process_tile<D, NRT, true>(ring + (it % kSlots) * TB, my_first + 4 * it, p.T, qscale, raise_thr, lane, qb, O,
+                                   Lacc, m_ref, m_thr, mneg);
     }
 
-    // ---- merge the four waves through LDS
+    // ---- merge the four waves through LDS (the ring is free now: every copy has been waited for)
     if (grp == 0) {
 #pragma unroll
         for (int nt = 0; nt < NRT; ++nt) m_s[wave][16 * nt + n] = m_ref[nt];
     }
+    __syncthreads();
+    for (int i = tid; i < ROWS * OSTRIDE; i += 256) o_s[i] = 0.0f;
+    if (tid < ROWS) l_s[tid] = 0.0f;
     __syncthreads();
     // waves add their share one after the other, so the summation order (and the result) is fixed
     for (int w = 0; w < 4; ++w) {
@@ -328,23 +396,31 @@ bool matrix_kernel_supports(int head_dim, int rows_per_kv_head) {
 
 bool matrix_kernel_direct(const AttendPlan& plan) { return plan.nsplit == 1 && !plan.has_tails; }
 
+template <int D, int NRT>
+static hipError_t launch_one(dim3 grid, const uint8_t* storage, const AttendPlan& plan, const void* Q, float* ws_ml,
+                             float* ws_o, float* out, int direct, hipStream_t s) {
+    constexpr int kRingBytes = 4 * kSlots * Layout<D>::tile_bytes;
+    auto kern = attend_mfma_kernel<D, NRT>;
+    static bool configured = false;  // per instantiation; the attribute is a property of the function
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    kern<<<grid, 256, kRingBytes, s>>>(storage, (const __half*)Q, ws_ml, ws_o, out, plan, direct);
+    return hipGetLastError();
+}
+
 template <int D>
 static hipError_t launch_d(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,
                            float* ws_o, float* out, hipStream_t s) {
     const uint8_t* storage = reinterpret_cast<const uint8_t*>(pool->storage);
     const int units = plan.layers * plan.H;
     const int direct = matrix_kernel_direct(plan) ? 1 : 0;
-    if (plan.R <= 16) {
-        dim3 grid(plan.nsplit, units, 1);
-        attend_mfma_kernel<D, 1><<<grid, 256, 0, s>>>(storage, (const __half*)Q, ws_ml, ws_o, out, plan, direct);
-    } else if (plan.R <= 32) {
-        dim3 grid(plan.nsplit, units, 1);
-        attend_mfma_kernel<D, 2><<<grid, 256, 0, s>>>(storage, (const __half*)Q, ws_ml, ws_o, out, plan, direct);
-    } else {
-        dim3 grid(plan.nsplit, units, (plan.R + 63) / 64);
-        attend_mfma_kernel<D, 4><<<grid, 256, 0, s>>>(storage, (const __half*)Q, ws_ml, ws_o, out, plan, direct);
-    }
-    return hipGetLastError();
+    if (plan.R <= 16) return launch_one<D, 1>(dim3(plan.nsplit, units, 1), storage, plan, Q, ws_ml, ws_o, out, direct, s);
+    if (plan.R <= 32) return launch_one<D, 2>(dim3(plan.nsplit, units, 1), storage, plan, Q, ws_ml, ws_o, out, direct, s);
+    return launch_one<D, 4>(dim3(plan.nsplit, units, (plan.R + 63) / 64), storage, plan, Q, ws_ml, ws_o, out, direct, s);
 }
 
 hipError_t launch_attend_matrix(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,
