@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload configuration (default: Llama-3-8B shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pools", type=int, default=3, help="distinct pool copies rotated between steps")
+    ap.add_argument("--phases", default="eda", help="subset of e(ncode) d(ecode) a(ttend) to run per step; "
+                    "anything but the default is for profiling one kernel and is marked partial")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the pool path shards by layer / KV head "
@@ -87,17 +89,24 @@ def main():
     pools = [pk.Pool(L, H, d, T).bind() for _ in range(max(1, args.pools))]
     ws = torch.empty(max(pools[0].attend_workspace_bytes(Q), 256), dtype=torch.uint8, device="cuda")
 
+    if args.phases != "eda":
+        for p in pools:
+            p.encode(K, V)
+
     def step(i, ev=None):
         p = pools[i % len(pools)]
         if ev:
             ev[0].record()
-        p.encode(K, V)
+        if "e" in args.phases:
+            p.encode(K, V)
         if ev:
             ev[1].record()
-        p.decode(torch.float16, Kd, Vd)
+        if "d" in args.phases:
+            p.decode(torch.float16, Kd, Vd)
         if ev:
             ev[2].record()
-        p.attend(Q, out, workspace=ws)
+        if "a" in args.phases:
+            p.attend(Q, out, workspace=ws)
         if ev:
             ev[3].record()
 
@@ -114,7 +123,7 @@ def main():
     enc = np.array([e[0].elapsed_time(e[1]) for e in events]) * 1e-3
     dec = np.array([e[1].elapsed_time(e[2]) for e in events]) * 1e-3
     att = np.array([e[2].elapsed_time(e[3]) for e in events]) * 1e-3
-    t_enc, t_dec, t_att = float(enc.mean()), float(dec.mean()), float(att.mean())
+    t_enc, t_dec, t_att = (max(float(x.mean()), 1e-9) for x in (enc, dec, att))
 
     units = L * H
     packed = units * T * (d + d // 16 + 3 * d // 8)                  # algorithmic pool bytes
@@ -140,6 +149,8 @@ def main():
                      "frac": att_gbps / HBM_PEAK_GBPS, "traffic": None,
                      "kernel": "pool_attend (attention + merge kernels), HIP events on the launch stream"},
     }
+    if args.phases != "eda":
+        result["partial"] = "phases=%s: not a full step" % args.phases
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, W)
     else:

@@ -5,6 +5,8 @@
 //
 //   staging  the record is copied global -> LDS asynchronously (global_load_lds), three tiles ahead,
 //            into a per-wave ring; nothing passes through registers until it is used.
+//   pipeline two tiles are in flight per wave: the scores of the next tile are computed on the matrix
+//            cores while the vector ALUs run the softmax and value dequantization of the current one.
 //   scores   S^T[t, r] = sum_j sum_{k in block j} (code[t,k] * s[t,j]) * q[r,k].  The dequantized key
 //            code*s has up to 18 significant bits, so it is split exactly into two fp16 terms
 //            hi = fp16(code*s), lo = code*s - hi (one packed fma), each fed to one MFMA per q8_0 block
@@ -21,6 +23,8 @@
 // when one workgroup covers the whole token range and there are no private tails, else in the merge
 // kernel.  The four waves of a workgroup take interleaved tiles and are merged through LDS.
 #include <hip/hip_fp16.h>
+
+#include <type_traits>
 
 #include "polykv_internal.hpp"
 #include "polykv_layout.hpp"
@@ -69,16 +73,13 @@ __device__ __forceinline__ float xor32_max(float x) {
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-__device__ __forceinline__ float max8(const float4v& a, const float4v& b) {
-    return fmaxf(fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])), fmaxf(fmaxf(b[0], b[1]), fmaxf(b[2], b[3])));
-}
 
 // ---- asynchronous tile staging: global -> LDS without passing through registers ----------------
 // A tile record is copied verbatim into one slot of the wave's private LDS ring with
 // global_load_lds (each lane moves 16 bytes to base + lane*16, which is exactly how the
 // record is laid out).  The copies are tracked by vmcnt only, so the wave waits with an explicit
 // s_waitcnt for the oldest tile while up to kAhead younger ones stay in flight.
-constexpr int kSlots = 4, kAhead = 3;
+constexpr int kSlots = 5, kAhead = 3;  // slots: tile A, tile B, kAhead copies in flight
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -109,104 +110,75 @@ template <int LPT> __device__ __forceinline__ void wait_tiles_in_flight(int youn
     asm volatile("" ::: "memory");
 }
 
-// One 32-token tile from its LDS copy `lt`: scores, online softmax, PV.  RAGGED = the tile crosses the
-// end of the pool; tokens >= T are masked out.
-template <int D, int NRT, bool RAGGED>
-__device__ __forceinline__ void process_tile(const uint8_t* lt, int tile, int T, float qscale, float raise_thr,
-                                             int lane, const half8 (&qb)[NRT][D / 32], float4v (&O)[D / 16][NRT],
-                                             float4v (&Lacc)[NRT], float (&m_ref)[NRT], float (&m_thr)[NRT],
-                                             float (&mneg)[NRT]) {
+__device__ __forceinline__ float max8(const float4v& a, const float4v& b) {
+    float m = fmaxf(fmaxf(a[0], a[1]), a[2]);
+    m = fmaxf(fmaxf(m, a[3]), b[0]);
+    m = fmaxf(fmaxf(m, b[1]), b[2]);
+    return fmaxf(m, b[3]);
+}
+
+// The pool's last tile when it crosses the end of the pool: scores, softmax and PV one after the
+// other, tokens >= T masked out.  Runs at most once per KV head.
+template <int D, int NRT>
+__device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile, int T, float qscale, float raise_thr,
+                                                 int lane, const half8 (&qb)[NRT][D / 32], float4v (&O)[D / 16][NRT],
+                                                 float4v (&Lacc)[NRT], float (&m_ref)[NRT], float (&m_thr)[NRT],
+                                                 float (&mneg)[NRT]) {
     using LY = Layout<D>;
     constexpr int NB = D / 32, NG = D / 16, NTR = D / 64;
     const int grp = lane >> 4, n = lane & 15;
-    const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     H8 ones;
 #pragma unroll
     for (int i = 0; i < 4; ++i) ones.u[i] = 0x3C003C00u;
-
-    // ---- scores
     float4v S[NRT][2];
 #pragma unroll
     for (int nt = 0; nt < NRT; ++nt) S[nt][0] = S[nt][1] = float4v{0, 0, 0, 0};
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
-        // scales of token 16mt + n, blocks 0..NB-1
-        union {
-            uint32_t u[NB / 2];
-            _Float16 h[NB];
-        } sc;
-#pragma unroll
-        for (int x = 0; x < NB / 2; ++x)
-            sc.u[x] = *reinterpret_cast<const uint32_t*>(lt + LY::kscales_off + (16 * mt + n) * NB * 2 + 4 * x);
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
+            const _Float16 sj = *reinterpret_cast<const _Float16*>(lt + LY::kscales_off + ((16 * mt + n) * NB + j) * 2);
             const uint2 kw = *reinterpret_cast<const uint2*>(lt + j * 1024 + lane * 16 + 8 * mt);
             H8 a;
             codes4_to_half(kw.x, a.u[0], a.u[1]);
             codes4_to_half(kw.y, a.u[2], a.u[3]);
             a.h = a.h - (_Float16)1152.0f;
-            const half8 sv = (half8)(sc.h[j]);
+            const half8 sv = (half8)(sj);
             const half8 hi = a.h * sv;
-            const half8 lo = __builtin_elementwise_fma(a.h, sv, -hi);  // exact remainder of the product
+            const half8 lo = __builtin_elementwise_fma(a.h, sv, -hi);
 #pragma unroll
-            for (int nt = 0; nt < NRT; ++nt)
+            for (int nt = 0; nt < NRT; ++nt) {
                 S[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hi, qb[nt][j], S[nt][mt], 0, 0, 0);
-#pragma unroll
-            for (int nt = 0; nt < NRT; ++nt)
                 S[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(lo, qb[nt][j], S[nt][mt], 0, 0, 0);
-        }
-    }
-    if (RAGGED) {  // tokens past the end never score
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (tile * kTile + 16 * mt + 4 * grp + i >= T) {
-#pragma unroll
-                    for (int nt = 0; nt < NRT; ++nt) S[nt][mt][i] = -INFINITY;
-                }
-    }
-
-    // ---- online softmax; the vote needs no cross-lane reduction, only the (rare) raise does
-    float mloc[NRT];
-    bool raise = false;
-#pragma unroll
-    for (int nt = 0; nt < NRT; ++nt) {
-        mloc[nt] = max8(S[nt][0], S[nt][1]);
-        raise |= mloc[nt] > m_thr[nt];  // also true while the reference is -inf
-    }
-    if (__builtin_expect(__any(raise), 0)) {
-        // Rare.  The accumulators live in accumulation registers that vector instructions cannot
-        // read; an MFMA with zero operands (D = 0*0 + C) carries them to vector registers and back,
-        // so the hot path never copies them.
-#pragma unroll
-        for (int nt = 0; nt < NRT; ++nt) {
-            const float m_new = fmaxf(m_ref[nt], xor32_max(xor16_max(mloc[nt])));
-            const float alpha = __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
-            m_ref[nt] = m_new;
-            m_thr[nt] = m_new + raise_thr;
-            mneg[nt] = -m_new * qscale;
-            float4v x = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, Lacc[nt], 0, 0, 0);
-            x *= alpha;
-            Lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, x, 0, 0, 0);
-#pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                float4v y = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, O[g][nt], 0, 0, 0);
-                y *= alpha;
-                O[g][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, y, 0, 0, 0);
             }
         }
     }
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (tile * kTile + 16 * mt + 4 * grp + i >= T) {
+#pragma unroll
+                for (int nt = 0; nt < NRT; ++nt) S[nt][mt][i] = -INFINITY;
+            }
     H8 pb[NRT];
 #pragma unroll
-    for (int nt = 0; nt < NRT; ++nt)
+    for (int nt = 0; nt < NRT; ++nt) {
+        // this path always re-references: cheap here, and it needs no vote
+        const float m_new = fmaxf(m_ref[nt], xor32_max(xor16_max(max8(S[nt][0], S[nt][1]))));
+        const float alpha = __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
+        m_ref[nt] = m_new;
+        m_thr[nt] = m_new + raise_thr;
+        mneg[nt] = -m_new * qscale;
+        Lacc[nt] *= alpha;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) O[g][nt] *= alpha;
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 pb[nt].h[4 * mt + i] = (_Float16)__builtin_amdgcn_exp2f(fmaf(S[nt][mt][i], qscale, mneg[nt]));
-
-    // ---- PV in the rotated domain
+    }
 #pragma unroll
     for (int q = 0; q < NTR; ++q) {
         const uint32_t* vw = reinterpret_cast<const uint32_t*>(lt + LY::vcodes_off + q * 768 + lane * 12);
@@ -233,6 +205,203 @@ __device__ __forceinline__ void process_tile(const uint8_t* lt, int tile, int T,
 #pragma unroll
     for (int nt = 0; nt < NRT; ++nt)
         Lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones.h, pb[nt].h, Lacc[nt], 0, 0, 0);
+}
+
+// One software-pipelined step.  While the matrix cores compute the scores of tile B (the next tile),
+// the vector ALUs turn the scores of tile A (the current tile, computed one step earlier) into
+// probabilities and dequantize A's values; then the matrix cores accumulate A's P.V.  Keeping two
+// tiles in flight is what lets MFMA and VALU work overlap within a single wave: the MFMA stream of a
+// step never depends on vector work of the same tile that has not had a full step to complete.
+//
+//   ltA, ltB   LDS copies of the two tile records (ltA's value codes, ltB's key codes and scales)
+//   Sa         scores of tile A on entry, of tile B on exit; mloc / raise: per-lane row maxima of the
+//              same tile and whether some row outgrew the reference
+// Only full tiles go through here; a ragged last tile is handled by process_ragged_tile.
+template <int D, int NRT, bool HAS_A, bool HAS_B>
+__device__ __forceinline__ void pipeline_step(const uint8_t* ltA, const uint8_t* ltB, float qscale,
+                                              float raise_thr, int lane, const half8 (&qb)[NRT][D / 32],
+                                              float4v (&O)[D / 16][NRT], float4v (&Lacc)[NRT], float (&m_ref)[NRT],
+                                              float (&m_thr)[NRT], float (&mneg)[NRT], float4v (&Sa)[NRT][2],
+                                              float (&mloc)[NRT], bool& raise) {
+    using LY = Layout<D>;
+    constexpr int NB = D / 32, NG = D / 16, NTR = D / 64;
+    const int n = lane & 15;
+    const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    H8 ones;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ones.u[i] = 0x3C003C00u;
+    float4v Sb[NRT][2];
+
+    if (HAS_A && __builtin_expect(__any(raise), 0)) {
+        // Rare: a row of tile A outgrew the softmax reference by more than 2^8.  The accumulators live
+        // in accumulation registers that vector instructions cannot read; an MFMA with zero operands
+        // (D = 0*0 + C) carries them to vector registers and back, so the hot path never copies them.
+#pragma unroll
+        for (int nt = 0; nt < NRT; ++nt) {
+            const float m_new = fmaxf(m_ref[nt], xor32_max(xor16_max(mloc[nt])));
+            const float alpha = __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
+            m_ref[nt] = m_new;
+            m_thr[nt] = m_new + raise_thr;
+            mneg[nt] = -m_new * qscale;
+            float4v x = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, Lacc[nt], 0, 0, 0);
+            x *= alpha;
+            Lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, x, 0, 0, 0);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                float4v y = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, O[g][nt], 0, 0, 0);
+                y *= alpha;
+                O[g][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, y, 0, 0, 0);
+            }
+        }
+    }
+
+    // The step is written as a sequence of slices.  Each slice pairs a batch of MFMAs whose operands
+    // are ready with the vector work that prepares the operands of the NEXT batch, and is closed by a
+    // scheduling barrier so that the compiler keeps the pairing; inside a slice the two streams are
+    // interleaved one MFMA to a few vector instructions.
+    constexpr int NQK = 2 * NB;     // key blocks of tile B: (mt, j)
+    constexpr int NCH = 2 * NRT;    // probability chunks of tile A: 4 scores each
+    auto slice_end = [](auto mfmas, auto valus) {
+        constexpr int M = decltype(mfmas)::value, V = decltype(valus)::value;
+        constexpr int per = M > 0 ? (V + M - 1) / M : 0;
+#pragma unroll
+        for (int i = 0; i < M; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (per > 0) __builtin_amdgcn_sched_group_barrier(0x402, per, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    using std::integral_constant;
+
+    // ---- LDS -> registers: key codes and scales of tile B, value codes of tile A
+    uint2 kraw[2][NB];
+    union {
+        uint32_t u[NB / 2];
+        _Float16 h[NB];
+    } sc[2];
+    uint32_t vraw[NTR][3];
+    if (HAS_B) {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+            for (int x = 0; x < NB / 2; ++x)
+                sc[mt].u[x] = *reinterpret_cast<const uint32_t*>(ltB + LY::kscales_off + (16 * mt + n) * NB * 2 + 4 * x);
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+                kraw[mt][j] = *reinterpret_cast<const uint2*>(ltB + j * 1024 + lane * 16 + 8 * mt);
+        }
+    }
+    if (HAS_A) {
+#pragma unroll
+        for (int q = 0; q < NTR; ++q)
+#pragma unroll
+            for (int w = 0; w < 3; ++w)
+                vraw[q][w] = *reinterpret_cast<const uint32_t*>(ltA + LY::vcodes_off + q * 768 + lane * 12 + 4 * w);
+    }
+
+    H8 pb[NRT];
+    half8 khi[2], klo[2];
+    H8 va[2];
+    auto exp_chunk = [&](int c) {  // probabilities of tile A: 4 of them, fp16, B operand of the PV products
+        const int nt = c >> 1, mt = c & 1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            pb[nt].h[4 * mt + i] = (_Float16)__builtin_amdgcn_exp2f(fmaf(Sa[nt][mt][i], qscale, mneg[nt]));
+    };
+    auto kdeq = [&](int k) {  // key block k of tile B: code * scale split exactly into hi + lo fp16 terms
+        const int mt = k / NB, j = k % NB;
+        H8 a;
+        codes4_to_half(kraw[mt][j].x, a.u[0], a.u[1]);
+        codes4_to_half(kraw[mt][j].y, a.u[2], a.u[3]);
+        a.h = a.h - (_Float16)1152.0f;
+        const half8 sv = (half8)(sc[mt].h[j]);
+        khi[k & 1] = a.h * sv;
+        klo[k & 1] = __builtin_elementwise_fma(a.h, sv, -khi[k & 1]);  // exact remainder of the product
+    };
+    auto qk = [&](int k) {
+        const int mt = k / NB, j = k % NB;
+#pragma unroll
+        for (int nt = 0; nt < NRT; ++nt)
+            Sb[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(khi[k & 1], qb[nt][j], Sb[nt][mt], 0, 0, 0);
+#pragma unroll
+        for (int nt = 0; nt < NRT; ++nt)
+            Sb[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(klo[k & 1], qb[nt][j], Sb[nt][mt], 0, 0, 0);
+    };
+    auto vdeq = [&](int g) {  // value group g of tile A: eight 3-bit codes -> fp16 centroids (A operand)
+        const int q = g >> 2, gi = g & 3;
+        const uint32_t w0 = vraw[q][0], w1 = vraw[q][1], w2 = vraw[q][2];
+        uint32_t sel_a, sel_b;
+        if (gi < 3) {
+            const uint32_t w = gi == 0 ? w0 : gi == 1 ? w1 : w2;
+            sel_a = w & 0x07070707u;
+            sel_b = (w >> 3) & 0x07070707u;
+        } else {
+            sel_a = ((w0 >> 6) & 0x03030303u) | ((w1 >> 4) & 0x04040404u);
+            sel_b = ((w2 >> 6) & 0x03030303u) | ((w1 >> 5) & 0x04040404u);
+        }
+        lookup4(sel_a, va[g & 1].u[0], va[g & 1].u[1]);
+        lookup4(sel_b, va[g & 1].u[2], va[g & 1].u[3]);
+    };
+    auto pv = [&](int g) {
+#pragma unroll
+        for (int nt = 0; nt < NRT; ++nt)
+            O[g][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[g & 1].h, pb[nt].h, O[g][nt], 0, 0, 0);
+    };
+
+    if (HAS_B) {
+#pragma unroll
+        for (int nt = 0; nt < NRT; ++nt) Sb[nt][0] = Sb[nt][1] = float4v{0, 0, 0, 0};
+        // lead-in: vector work only, while the LDS reads land
+        if (HAS_A) {
+#pragma unroll
+            for (int c = 0; c < NCH / NQK; ++c) exp_chunk(c);
+        }
+        kdeq(0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < NQK; ++k) {
+            qk(k);
+            if (k + 1 < NQK) kdeq(k + 1);
+            if (HAS_A) {
+                // spread the remaining probability chunks over the score slices
+                const int c0 = NCH / NQK + (k * (NCH - NCH / NQK)) / NQK, c1 = NCH / NQK + ((k + 1) * (NCH - NCH / NQK)) / NQK;
+#pragma unroll
+                for (int c = c0; c < c1; ++c) exp_chunk(c);
+                if (k + 1 == NQK) vdeq(0);
+            }
+            slice_end(integral_constant<int, 2 * NRT>{}, integral_constant<int, (HAS_A ? 28 : 16)>{});
+        }
+    } else if (HAS_A) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) exp_chunk(c);
+        vdeq(0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    if (HAS_A) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            pv(g);
+            if (g + 1 < NG) vdeq(g + 1);
+            slice_end(integral_constant<int, NRT>{}, integral_constant<int, 16>{});
+        }
+#pragma unroll
+        for (int nt = 0; nt < NRT; ++nt)
+            Lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones.h, pb[nt].h, Lacc[nt], 0, 0, 0);
+    }
+
+    // ---- row maxima of tile B for the next step's vote (no cross-lane reduction needed for the vote)
+    if (HAS_B) {
+        raise = false;
+#pragma unroll
+        for (int nt = 0; nt < NRT; ++nt) {
+            mloc[nt] = max8(Sb[nt][0], Sb[nt][1]);
+            raise |= mloc[nt] > m_thr[nt];  // also true while the reference is -inf
+            Sa[nt][0] = Sb[nt][0];
+            Sa[nt][1] = Sb[nt][1];
+        }
+    }
+    if (HAS_A) slice_end(integral_constant<int, NRT>{}, integral_constant<int, 24>{});
 }
 
 template <int D, int NRT>
@@ -264,11 +433,11 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     const float qscale = p.qscale;
     uint8_t* ring = smem + wave * (kSlots * TB);
 
-    // this wave's tiles: t_begin + wave, +4, +8, ...
+    // this wave's tiles: t_begin + wave, +4, +8, ...; local index k <-> tile my_first + 4k, slot k % kSlots
     const int my_first = t_begin + wave;
     const int my_count = my_first < t_end ? (t_end - my_first + 3) / 4 : 0;
 #pragma unroll
-    for (int a = 0; a < kAhead; ++a)
+    for (int a = 0; a <= kAhead; ++a)
         if (a < my_count) issue_tile<D>(unit_base + (size_t)(my_first + 4 * a) * TB, ring + a * TB, lane);
 
     // ---- query rows as MFMA B operands: lane (n, grp) holds q[row 16nt+n][32j + 8grp .. +7]
@@ -283,39 +452,56 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
             if (r < p.R) raw = *reinterpret_cast<const uint4v*>(Q + q_row_index(p, ls, kvh, r) * D + 32 * j + 8 * grp);
             t.u[0] = raw.x; t.u[1] = raw.y; t.u[2] = raw.z; t.u[3] = raw.w;
             qb[nt][j] = t.h;
+            // The queries are only ever MFMA operands: park them in accumulation registers so that the
+            // vector registers are left for the scores and the dequantization temporaries.
+            asm volatile("" : "+a"(qb[nt][j]));
         }
     }
 
     float4v O[NG][NRT], Lacc[NRT];
-    float m_ref[NRT], m_thr[NRT], mneg[NRT];
+    float m_ref[NRT], m_thr[NRT], mneg[NRT], mloc[NRT];
 #pragma unroll
     for (int nt = 0; nt < NRT; ++nt) {
         m_ref[nt] = -INFINITY;
         m_thr[nt] = -INFINITY;
         mneg[nt] = 0.0f;
+        mloc[nt] = -INFINITY;
         Lacc[nt] = float4v{0, 0, 0, 0};
 #pragma unroll
         for (int g = 0; g < NG; ++g) O[g][nt] = float4v{0, 0, 0, 0};
     }
     const float raise_thr = 8.0f / qscale;  // raise the reference only when a row exceeds it by 2^8
+    bool raise = false;
+    float4v S[NRT][2];  // scores of the tile whose softmax comes next
 
-    // Only the pool's very last tile can be ragged; it is peeled out of the loop so that the loop body
-    // is one straight-line block.
+    // Local tile k is "B" in step k-1 (scores) and "A" in step k (softmax, PV).  Before step s reads
+    // tile s+1 from LDS, tile s+1+kAhead is issued into the slot tile s-1 has just vacated.  Only the
+    // pool's very last tile can be ragged; it stays out of the pipeline and goes last.
     const bool last_ragged = my_count > 0 && (my_first + 4 * (my_count - 1)) * kTile + kTile > p.T;
     const int full_count = last_ragged ? my_count - 1 : my_count;
-    for (int it = 0; it < full_count; ++it) {
-        const int tile = my_first + 4 * it;
-        if (it + kAhead < my_count)
-            issue_tile<D>(unit_base + (size_t)(tile + 4 * kAhead) * TB, ring + ((it + kAhead) % kSlots) * TB, lane);
-        wait_tiles_in_flight<LPT>(min(kAhead, my_count - 1 - it));
-        process_tile<D, NRT, false>(ring + (it % kSlots) * TB, tile, p.T, qscale, raise_thr, lane, qb, O, Lacc, m_ref,
-                                    m_thr, mneg);
+    auto slot = [&](int k) { return ring + (k % kSlots) * TB; };
+    auto advance = [&](int s) {  // bookkeeping in front of step s (A = s, B = s + 1)
+        const int nxt = s + 1 + kAhead;
+        if (s >= 0 && nxt < my_count) issue_tile<D>(unit_base + (size_t)(my_first + 4 * nxt) * TB, slot(nxt), lane);
+        // copies younger than tile s+1: tiles s+2 .. min(s+1+kAhead, my_count-1)
+        wait_tiles_in_flight<LPT>(max(0, min(s + 1 + kAhead, my_count - 1) - (s + 1)));
+    };
+    if (full_count > 0) {
+        advance(-1);
+        pipeline_step<D, NRT, false, true>(nullptr, slot(0), qscale, raise_thr, lane, qb, O, Lacc, m_ref, m_thr, mneg, S,
+                                           mloc, raise);
+        for (int s = 0; s < full_count - 1; ++s) {
+            advance(s);
+            pipeline_step<D, NRT, true, true>(slot(s), slot(s + 1), qscale, raise_thr, lane, qb, O, Lacc, m_ref, m_thr,
+                                              mneg, S, mloc, raise);
+        }
+        pipeline_step<D, NRT, true, false>(slot(full_count - 1), nullptr, qscale, raise_thr, lane, qb, O, Lacc, m_ref,
+                                           m_thr, mneg, S, mloc, raise);
     }
     if (last_ragged) {
-        const int it = my_count - 1;
+        const int k = my_count - 1;
         wait_tiles_in_flight<LPT>(0);
-        process_tile<D, NRT, true>(ring + (it % kSlots) * TB, my_first + 4 * it, p.T, qscale, raise_thr, lane, qb, O,
-                                   Lacc, m_ref, m_thr, mneg);
+        process_ragged_tile<D, NRT>(slot(k), my_first + 4 * k, p.T, qscale, raise_thr, lane, qb, O, Lacc, m_ref, m_thr, mneg);
     }
 
     // ---- merge the four waves through LDS (the ring is free now: every copy has been waited for)

@@ -112,9 +112,9 @@ class Pool:
         return self
 
     def close(self):
-        if getattr(self, "_h", None):
-            lib.pool_destroy(self._h)
-            self._h = None
+        h, self._h = getattr(self, "_h", None), None
+        if h and lib is not None:      # `lib` is already gone when the interpreter shuts down
+            lib.pool_destroy(h)
 
     __del__ = close
 
