@@ -3,8 +3,9 @@
 // One wave owns up to 64 query rows (NRT tiles of 16) of one KV head and streams 32-token tile
 // records.  Per tile, with tokens as the MFMA M dimension and query rows as N:
 //
-//   staging  the record is copied global -> LDS asynchronously (global_load_lds), three tiles ahead,
-//            into a per-wave ring; nothing passes through registers until it is used.
+//   staging  a lane's share of a record (its key-code runs, its tokens' scales, its value-code
+//            triplets -- every wave load one contiguous run) is loaded into registers one step ahead
+//            of its use, so each load has a whole step to land.
 //   pipeline two tiles are in flight per wave: the scores of the next tile are computed on the matrix
 //            cores while the vector ALUs run the softmax and value dequantization of the current one.
 //   scores   S^T[t, r] = sum_j sum_{k in block j} (code[t,k] * s[t,j]) * q[r,k].  The dequantized key
@@ -74,40 +75,39 @@ __device__ __forceinline__ float xor32_max(float x) {
 }
 
 
-// ---- asynchronous tile staging: global -> LDS without passing through registers ----------------
-// A tile record is copied verbatim into one slot of the wave's private LDS ring with
-// global_load_lds (each lane moves 16 bytes to base + lane*16, which is exactly how the
-// record is laid out).  The copies are tracked by vmcnt only, so the wave waits with an explicit
-// s_waitcnt for the oldest tile while up to kAhead younger ones stay in flight.
-constexpr int kSlots = 5, kAhead = 3;  // slots: tile A, tile B, kAhead copies in flight
+// ---- tile staging: global -> registers, one step ahead ------------------------------------------
+// A lane's share of a tile record: its 16 bytes of every key block (the two 8-code A operands), the
+// scales of its two tokens, and its value-code triplets.  Every load is one contiguous, fully
+// coalesced run across the wave (the record is stored in exactly this order).
+template <int D> struct RawK {
+    uint2 k[2][D / 32];      // [mt][j]: codes of token 16mt + n, block j, elements 8grp .. 8grp+7
+    uint32_t sc[2][D / 64];  // [mt]: fp16 scales of token 16mt + n, blocks 0..NB-1
+};
+template <int D> struct RawV {
+    uint32_t w[D / 64][3];
+};
 
-typedef const __attribute__((address_space(1))) void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
-
-template <int D>
-__device__ __forceinline__ void issue_tile(const uint8_t* g, uint8_t* lds, int lane) {
-    // The record is a byte stream for this purpose: whole kilobytes with all 64 lanes, the remainder
-    // (a multiple of 16 bytes) with the first lanes only.  (The 12-byte form of the copy strides lanes
-    // by 16 bytes in LDS, so only the 16-byte form reproduces the record verbatim.)
-    constexpr int TB = Layout<D>::tile_bytes, FULL = TB / 1024, REM = TB % 1024;
-    static_assert(REM % 16 == 0, "");
-#pragma unroll
-    for (int j = 0; j < FULL; ++j)
-        __builtin_amdgcn_global_load_lds((gptr_t)(g + j * 1024 + lane * 16), (lptr_t)(lds + j * 1024), 16, 0, 0);
-    if (REM != 0 && lane < REM / 16)
-        __builtin_amdgcn_global_load_lds((gptr_t)(g + FULL * 1024 + lane * 16), (lptr_t)(lds + FULL * 1024), 16, 0, 0);
+template <int D> __device__ __forceinline__ uint2 load_kraw(const uint8_t* tile, int lane, int mt, int j) {
+    return *reinterpret_cast<const uint2*>(tile + j * 1024 + lane * 16 + 8 * mt);
 }
-
-// s_waitcnt vmcnt(N) only (expcnt / lgkmcnt untouched); N < 64.
-#define POLYKV_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14))
-
-template <int LPT> __device__ __forceinline__ void wait_tiles_in_flight(int younger) {
-    // `younger` tiles (each LPT copies) were issued after the one about to be read
-    if (younger >= 3) POLYKV_WAIT_VMCNT(3 * LPT);
-    else if (younger == 2) POLYKV_WAIT_VMCNT(2 * LPT);
-    else if (younger == 1) POLYKV_WAIT_VMCNT(1 * LPT);
-    else POLYKV_WAIT_VMCNT(0);
-    asm volatile("" ::: "memory");
+template <int D> __device__ __forceinline__ uint32_t load_sc(const uint8_t* tile, int n, int mt, int x) {
+    return *reinterpret_cast<const uint32_t*>(tile + Layout<D>::kscales_off + (16 * mt + n) * (D / 32) * 2 + 4 * x);
+}
+template <int D> __device__ __forceinline__ void load_rawk(RawK<D>& r, const uint8_t* tile, int lane) {
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+        for (int x = 0; x < D / 64; ++x) r.sc[mt][x] = load_sc<D>(tile, lane & 15, mt, x);
+#pragma unroll
+        for (int j = 0; j < D / 32; ++j) r.k[mt][j] = load_kraw<D>(tile, lane, mt, j);
+    }
+}
+template <int D> __device__ __forceinline__ void load_rawv(RawV<D>& r, const uint8_t* tile, int lane) {
+#pragma unroll
+    for (int q = 0; q < D / 64; ++q)
+#pragma unroll
+        for (int w = 0; w < 3; ++w)
+            r.w[q][w] = *reinterpret_cast<const uint32_t*>(tile + Layout<D>::vcodes_off + q * 768 + lane * 12 + 4 * w);
 }
 
 __device__ __forceinline__ float max8(const float4v& a, const float4v& b) {
@@ -117,8 +117,8 @@ __device__ __forceinline__ float max8(const float4v& a, const float4v& b) {
     return fmaxf(m, b[3]);
 }
 
-// The pool's last tile when it crosses the end of the pool: scores, softmax and PV one after the
-// other, tokens >= T masked out.  Runs at most once per KV head.
+// The pool's last tile when it crosses the end of the pool, read straight from memory: scores, softmax
+// and PV one after the other, tokens >= T masked out.  Runs at most once per KV head.
 template <int D, int NRT>
 __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile, int T, float qscale, float raise_thr,
                                                  int lane, const half8 (&qb)[NRT][D / 32], float4v (&O)[D / 16][NRT],
@@ -213,12 +213,15 @@ __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile,
 // tiles in flight is what lets MFMA and VALU work overlap within a single wave: the MFMA stream of a
 // step never depends on vector work of the same tile that has not had a full step to complete.
 //
-//   ltA, ltB   LDS copies of the two tile records (ltA's value codes, ltB's key codes and scales)
+//   rv, rk     tile A's value codes and tile B's key codes / scales, in registers
+//   rvN, rkN   the same for the next step, requested here from nextV (the tile after A) and nextK (the
+//              tile after B); the caller alternates the two register sets, so nothing is copied
 //   Sa         scores of tile A on entry, of tile B on exit; mloc / raise: per-lane row maxima of the
 //              same tile and whether some row outgrew the reference
 // Only full tiles go through here; a ragged last tile is handled by process_ragged_tile.
 template <int D, int NRT, bool HAS_A, bool HAS_B>
-__device__ __forceinline__ void pipeline_step(const uint8_t* ltA, const uint8_t* ltB, float qscale,
+__device__ __forceinline__ void pipeline_step(const RawV<D>& rv, const RawK<D>& rk, RawV<D>& rvN, RawK<D>& rkN,
+                                              const uint8_t* nextK, const uint8_t* nextV, float qscale,
                                               float raise_thr, int lane, const half8 (&qb)[NRT][D / 32],
                                               float4v (&O)[D / 16][NRT], float4v (&Lacc)[NRT], float (&m_ref)[NRT],
                                               float (&m_thr)[NRT], float (&mneg)[NRT], float4v (&Sa)[NRT][2],
@@ -273,31 +276,11 @@ __device__ __forceinline__ void pipeline_step(const uint8_t* ltA, const uint8_t*
     };
     using std::integral_constant;
 
-    // ---- LDS -> registers: key codes and scales of tile B, value codes of tile A
-    uint2 kraw[2][NB];
-    union {
-        uint32_t u[NB / 2];
-        _Float16 h[NB];
-    } sc[2];
-    uint32_t vraw[NTR][3];
-    if (HAS_B) {
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-            for (int x = 0; x < NB / 2; ++x)
-                sc[mt].u[x] = *reinterpret_cast<const uint32_t*>(ltB + LY::kscales_off + (16 * mt + n) * NB * 2 + 4 * x);
-#pragma unroll
-            for (int j = 0; j < NB; ++j)
-                kraw[mt][j] = *reinterpret_cast<const uint2*>(ltB + j * 1024 + lane * 16 + 8 * mt);
-        }
-    }
-    if (HAS_A) {
-#pragma unroll
-        for (int q = 0; q < NTR; ++q)
-#pragma unroll
-            for (int w = 0; w < 3; ++w)
-                vraw[q][w] = *reinterpret_cast<const uint32_t*>(ltA + LY::vcodes_off + q * 768 + lane * 12 + 4 * w);
-    }
+    // The next step's bytes are requested first thing, into the other set of registers, so that every
+    // load has the whole step (and more, for all but the first key block) to land.
+    if (HAS_B) load_rawk<D>(rkN, nextK, lane);
+    load_rawv<D>(rvN, nextV, lane);
+    __builtin_amdgcn_sched_barrier(0);
 
     H8 pb[NRT];
     half8 khi[2], klo[2];
@@ -311,10 +294,15 @@ __device__ __forceinline__ void pipeline_step(const uint8_t* ltA, const uint8_t*
     auto kdeq = [&](int k) {  // key block k of tile B: code * scale split exactly into hi + lo fp16 terms
         const int mt = k / NB, j = k % NB;
         H8 a;
-        codes4_to_half(kraw[mt][j].x, a.u[0], a.u[1]);
-        codes4_to_half(kraw[mt][j].y, a.u[2], a.u[3]);
+        codes4_to_half(rk.k[mt][j].x, a.u[0], a.u[1]);
+        codes4_to_half(rk.k[mt][j].y, a.u[2], a.u[3]);
         a.h = a.h - (_Float16)1152.0f;
-        const half8 sv = (half8)(sc[mt].h[j]);
+        union {
+            uint32_t u;
+            _Float16 h[2];
+        } s2;
+        s2.u = rk.sc[mt][j >> 1];
+        const half8 sv = (half8)(s2.h[j & 1]);
         khi[k & 1] = a.h * sv;
         klo[k & 1] = __builtin_elementwise_fma(a.h, sv, -khi[k & 1]);  // exact remainder of the product
     };
@@ -329,7 +317,7 @@ __device__ __forceinline__ void pipeline_step(const uint8_t* ltA, const uint8_t*
     };
     auto vdeq = [&](int g) {  // value group g of tile A: eight 3-bit codes -> fp16 centroids (A operand)
         const int q = g >> 2, gi = g & 3;
-        const uint32_t w0 = vraw[q][0], w1 = vraw[q][1], w2 = vraw[q][2];
+        const uint32_t w0 = rv.w[q][0], w1 = rv.w[q][1], w2 = rv.w[q][2];
         uint32_t sel_a, sel_b;
         if (gi < 3) {
             const uint32_t w = gi == 0 ? w0 : gi == 1 ? w1 : w2;
@@ -413,13 +401,9 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     constexpr int NB = D / 32, NG = D / 16, ROWS = 16 * NRT;
     constexpr int OSTRIDE = D + 4;
     constexpr int TB = LY::tile_bytes;
-    constexpr int LPT = TB / 1024 + (TB % 1024 != 0);  // copies per tile
-    static_assert(kAhead * LPT < 64, "vmcnt is a 6-bit counter");
-    static_assert(ROWS * OSTRIDE * 4 <= 4 * kSlots * TB, "the merge buffer reuses the ring");
-    extern __shared__ __align__(16) uint8_t smem[];  // 4 waves x kSlots tile records; reused for the merge
     __shared__ float m_s[4][ROWS];
     __shared__ float l_s[ROWS];
-    float* o_s = reinterpret_cast<float*>(smem);
+    __shared__ __align__(16) float o_s[ROWS * OSTRIDE];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: LDS bases go through M0
@@ -431,14 +415,19 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     const int t_begin = split * tps, t_end = min(p.tiles, t_begin + tps);
     const uint8_t* unit_base = pool + (size_t)((p.layer_begin + ls) * p.H + kvh) * p.tiles * TB;
     const float qscale = p.qscale;
-    uint8_t* ring = smem + wave * (kSlots * TB);
 
-    // this wave's tiles: t_begin + wave, +4, +8, ...; local index k <-> tile my_first + 4k, slot k % kSlots
+    // this wave's tiles: t_begin + wave, +4, +8, ...; local index k <-> tile my_first + 4k
     const int my_first = t_begin + wave;
     const int my_count = my_first < t_end ? (t_end - my_first + 3) / 4 : 0;
-#pragma unroll
-    for (int a = 0; a <= kAhead; ++a)
-        if (a < my_count) issue_tile<D>(unit_base + (size_t)(my_first + 4 * a) * TB, ring + a * TB, lane);
+    // pointer to local tile k; k past the end is clamped (the refill loads of the last steps then
+    // fetch the wave's own last tile again, harmlessly, instead of needing a branch per load)
+    auto tile_ptr = [&](int k) { return unit_base + (size_t)(my_first + 4 * min(k, max(my_count - 1, 0))) * TB; };
+    RawK<D> rk;
+    RawV<D> rv;
+    if (my_count > 0) {
+        load_rawk<D>(rk, tile_ptr(0), lane);
+        load_rawv<D>(rv, tile_ptr(0), lane);
+    }
 
     // ---- query rows as MFMA B operands: lane (n, grp) holds q[row 16nt+n][32j + 8grp .. +7]
     half8 qb[NRT][NB];
@@ -474,37 +463,39 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     bool raise = false;
     float4v S[NRT][2];  // scores of the tile whose softmax comes next
 
-    // Local tile k is "B" in step k-1 (scores) and "A" in step k (softmax, PV).  Before step s reads
-    // tile s+1 from LDS, tile s+1+kAhead is issued into the slot tile s-1 has just vacated.  Only the
-    // pool's very last tile can be ragged; it stays out of the pipeline and goes last.
+    // Local tile k is "B" in step k-1 (scores) and "A" in step k (softmax, PV).  Only the pool's very
+    // last tile can be ragged; it stays out of the pipeline and goes last.
     const bool last_ragged = my_count > 0 && (my_first + 4 * (my_count - 1)) * kTile + kTile > p.T;
     const int full_count = last_ragged ? my_count - 1 : my_count;
-    auto slot = [&](int k) { return ring + (k % kSlots) * TB; };
-    auto advance = [&](int s) {  // bookkeeping in front of step s (A = s, B = s + 1)
-        const int nxt = s + 1 + kAhead;
-        if (s >= 0 && nxt < my_count) issue_tile<D>(unit_base + (size_t)(my_first + 4 * nxt) * TB, slot(nxt), lane);
-        // copies younger than tile s+1: tiles s+2 .. min(s+1+kAhead, my_count-1)
-        wait_tiles_in_flight<LPT>(max(0, min(s + 1 + kAhead, my_count - 1) - (s + 1)));
-    };
     if (full_count > 0) {
-        advance(-1);
-        pipeline_step<D, NRT, false, true>(nullptr, slot(0), qscale, raise_thr, lane, qb, O, Lacc, m_ref, m_thr, mneg, S,
-                                           mloc, raise);
-        for (int s = 0; s < full_count - 1; ++s) {
-            advance(s);
-            pipeline_step<D, NRT, true, true>(slot(s), slot(s + 1), qscale, raise_thr, lane, qb, O, Lacc, m_ref, m_thr,
-                                              mneg, S, mloc, raise);
+        // register sets: (rk, rv) and (rk2, rv2) alternate between "current" and "being loaded"
+        RawK<D> rk2;
+        RawV<D> rv2;
+        // prologue: scores of tile 0 from rk; requests K of tile 1 and (again) V of tile 0 into set 2
+        pipeline_step<D, NRT, false, true>(rv, rk, rv2, rk2, tile_ptr(1), tile_ptr(0), qscale, raise_thr, lane, qb, O, Lacc,
+                                           m_ref, m_thr, mneg, S, mloc, raise);
+        int s = 0;
+        for (; s + 1 < full_count - 1; s += 2) {  // two steps per trip: the sets swap roles without copies
+            pipeline_step<D, NRT, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+                                              O, Lacc, m_ref, m_thr, mneg, S, mloc, raise);
+            pipeline_step<D, NRT, true, true>(rv, rk, rv2, rk2, tile_ptr(s + 3), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
+                                              O, Lacc, m_ref, m_thr, mneg, S, mloc, raise);
         }
-        pipeline_step<D, NRT, true, false>(slot(full_count - 1), nullptr, qscale, raise_thr, lane, qb, O, Lacc, m_ref,
-                                           m_thr, mneg, S, mloc, raise);
+        if (s < full_count - 1) {  // one step with a B tile left: current = set 2
+            pipeline_step<D, NRT, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+                                              O, Lacc, m_ref, m_thr, mneg, S, mloc, raise);
+            pipeline_step<D, NRT, true, false>(rv, rk, rv2, rk2, tile_ptr(s + 2), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
+                                               O, Lacc, m_ref, m_thr, mneg, S, mloc, raise);
+        } else {
+            pipeline_step<D, NRT, true, false>(rv2, rk2, rv, rk, tile_ptr(s + 1), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+                                               O, Lacc, m_ref, m_thr, mneg, S, mloc, raise);
+        }
     }
-    if (last_ragged) {
-        const int k = my_count - 1;
-        wait_tiles_in_flight<LPT>(0);
-        process_ragged_tile<D, NRT>(slot(k), my_first + 4 * k, p.T, qscale, raise_thr, lane, qb, O, Lacc, m_ref, m_thr, mneg);
-    }
+    if (last_ragged)
+        process_ragged_tile<D, NRT>(tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
+                                    Lacc, m_ref, m_thr, mneg);
 
-    // ---- merge the four waves through LDS (the ring is free now: every copy has been waited for)
+    // ---- merge the four waves through LDS
     if (grp == 0) {
 #pragma unroll
         for (int nt = 0; nt < NRT; ++nt) m_s[wave][16 * nt + n] = m_ref[nt];
@@ -585,16 +576,7 @@ bool matrix_kernel_direct(const AttendPlan& plan) { return plan.nsplit == 1 && !
 template <int D, int NRT>
 static hipError_t launch_one(dim3 grid, const uint8_t* storage, const AttendPlan& plan, const void* Q, float* ws_ml,
                              float* ws_o, float* out, int direct, hipStream_t s) {
-    constexpr int kRingBytes = 4 * kSlots * Layout<D>::tile_bytes;
-    auto kern = attend_mfma_kernel<D, NRT>;
-    static bool configured = false;  // per instantiation; the attribute is a property of the function
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
-    kern<<<grid, 256, kRingBytes, s>>>(storage, (const __half*)Q, ws_ml, ws_o, out, plan, direct);
+    attend_mfma_kernel<D, NRT><<<grid, 256, 0, s>>>(storage, (const __half*)Q, ws_ml, ws_o, out, plan, direct);
     return hipGetLastError();
 }
 
