@@ -22,17 +22,19 @@ import numpy as np
 HBM_PEAK_GBPS = 8000.0
 
 
-def cpu_baseline(cfg, W):
-    """The oracle, as it stands, on one layer of the workload (about 10-30 s of CPU work)."""
+def cpu_baseline(cfg, W, layers=8):
+    """The oracle, as it stands, on a bounded sample of the same workload (a few layers, all KV heads,
+    all tokens, all agents): about 10-30 s of CPU work."""
     from oracle import polykv_oracle as O
     try:
         from threadpoolctl import threadpool_info
         threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
     except Exception:
         threads = 1
-    one = cfg.scaled(layers=1)
-    K, V = W.kv_pool(one)
-    Q = W.queries(cfg)[:1]
+    layers = min(layers, cfg.layers)
+    part = cfg.scaled(layers=layers)
+    K, V = W.kv_pool(part)
+    Q = W.queries(cfg)[:layers]
     t0 = time.perf_counter()
     ref = O.pool_encode(K, V)
     t1 = time.perf_counter()
@@ -40,14 +42,15 @@ def cpu_baseline(cfg, W):
     t2 = time.perf_counter()
     O.pool_attend(Kh, Vh, Q)
     t3 = time.perf_counter()
-    b = O.stored_bytes(1, one.kv_heads, one.tokens, one.head_dim)
+    b = O.stored_bytes(layers, part.kv_heads, part.tokens, part.head_dim)
     attend_bytes = b["packed"] + Q.size * 2 + Q.size * 4
     return {
         "value": attend_bytes / (t3 - t2) / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
-        "sample": "1 of %d layers of the same workload (8 KV heads x %d tokens, %d agents); "
-                  "encode %.2f s, decode %.2f s, attend %.2f s" % (cfg.layers, one.tokens, cfg.agents,
-                                                                   t1 - t0, t2 - t1, t3 - t2),
-        "encode_tokens_per_s": one.tokens / (t1 - t0) / cfg.layers,
+        "sample": "%d of %d layers of the same workload (all %d KV heads x %d tokens, %d agents); "
+                  "encode %.2f s, decode %.2f s, attend %.2f s" % (layers, cfg.layers, part.kv_heads, part.tokens,
+                                                                   cfg.agents, t1 - t0, t2 - t1, t3 - t2),
+        # one token = one position across ALL layers and heads of the full pool
+        "encode_tokens_per_s": part.tokens / ((t1 - t0) * cfg.layers / layers),
     }
 
 
@@ -59,6 +62,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload configuration (default: Llama-3-8B shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pools", type=int, default=3, help="distinct pool copies rotated between steps")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain device copy of known size (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--phases", default="eda", help="subset of e(ncode) d(ecode) a(ttend) to run per step; "
                     "anything but the default is for profiling one kernel and is marked partial")
     args = ap.parse_args()
@@ -110,6 +115,9 @@ def main():
         if ev:
             ev[3].record()
 
+    if args.calibrate_copy:      # elementwise copy kernel: reads and writes K.numel()*2 bytes
+        for _ in range(3):
+            Kd.copy_(K)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -132,6 +140,17 @@ def main():
     att_bytes = packed + Q.numel() * 2 + out.numel() * 4
     att_gbps = att_bytes / t_att / 1e9
 
+    def roof(gbps, kernel):
+        return {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": gbps / HBM_PEAK_GBPS, "traffic": None, "kernel": kernel}
+
+    attend_roof = roof(att_gbps, "attend_mfma_kernel<128,4> (pool_attend); duration = HIP events on the launch "
+                                 "stream around the call; achieved = algorithmic bytes (packed pool + Q + out) / duration")
+    traffic_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                                "attend_hbm_traffic_%s.txt" % cfg.name)
+    if os.path.exists(traffic_file):     # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel
+        vals = dict(line.split()[:2] for line in open(traffic_file) if line.strip() and not line.startswith("#"))
+        attend_roof["traffic"] = float(vals["hbm_bytes_per_launch"])
     result = {
         "metric": "decode_attention_pool_GB_per_s", "value": att_gbps, "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -140,14 +159,14 @@ def main():
         "config": {"workload": cfg.name, "layers": L, "kv_heads": H, "q_heads": cfg.q_heads, "head_dim": d,
                    "tokens": T, "agents": cfg.agents, "q_per_agent": cfg.q_per_agent,
                    "rows_per_kv_head": cfg.rows_per_kv_head, "pool_bytes": packed, "pool_copies_rotated": len(pools)},
+        "step": "pool_encode -> pool_decode(fp16) -> pool_attend, all layers",
         "encode_tokens_per_s": T / t_enc, "encode_GB_per_s": enc_bytes / t_enc / 1e9,
-        "encode_frac_hbm_peak": enc_bytes / t_enc / 1e9 / HBM_PEAK_GBPS,
         "decode_GB_per_s": dec_bytes / t_dec / 1e9,
         "attend_ms": t_att * 1e3, "encode_ms": t_enc * 1e3, "decode_ms": t_dec * 1e3,
-        "attend_frac_hbm_peak": att_gbps / HBM_PEAK_GBPS,
-        "roofline": {"bound": "hbm", "achieved": att_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": att_gbps / HBM_PEAK_GBPS, "traffic": None,
-                     "kernel": "pool_attend (attention + merge kernels), HIP events on the launch stream"},
+        "attend_algorithmic_bytes": att_bytes,
+        "roofline": attend_roof,
+        "roofline_encode": roof(enc_bytes / t_enc / 1e9, "encode_kernel<128> (pool_encode); dense fp16 K,V in + packed out"),
+        "roofline_decode": roof(dec_bytes / t_dec / 1e9, "decode_kernel<128,half> (pool_decode); packed in + dense fp16 out"),
     }
     if args.phases != "eda":
         result["partial"] = "phases=%s: not a full step" % args.phases

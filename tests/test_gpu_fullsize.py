@@ -1,0 +1,66 @@
+"""Parity at the benchmark's full size and launch configuration: the Llama-3-8B-shaped pool
+(32 layers x 8 KV heads x head_dim 128 x 4096 tokens), 15 agents, all layers in one call -- exactly
+what bench.py times.  The oracle is run layer by layer on the same seeded tensors."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import polykv_oracle as O
+from paper_2604_24971_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def test_llama_shape_full_pool_encode_decode_attend_against_oracle():
+    import parity_util as pu
+    from paper_2604_24971_amd import polykv as pk
+
+    cfg = W.CONFIGS[3]
+    L, H, d, T = cfg.layers, cfg.kv_heads, cfg.head_dim, cfg.tokens
+    K, V = W.kv_pool(cfg)
+    Q = W.queries(cfg)
+    pool = pk.Pool(L, H, d, T).bind()
+    pool.encode(pu.dev(K), pu.dev(V))
+    kc, ks, vp = (t.cpu().numpy() for t in pool.export())
+    Kg, Vg = pool.decode(torch.float32)
+    out = pool.attend(pu.dev(Q))                      # AUTO kernel, automatic splits: the bench path
+    torch.cuda.synchronize()
+    out = out.cpu().numpy().astype(np.float64)
+    _, thr = O.codebook()
+
+    worst_att, mism_k, mism_v = 0.0, 0, 0
+    for l in range(L):
+        ref = O.pool_encode(K[l:l + 1], V[l:l + 1])
+        # scales bit-exact, codes bit-exact except on a decision threshold
+        assert np.array_equal(ks[l].view(np.uint16), ref["k_scales"][0].view(np.uint16)), "layer %d scales" % l
+        kd = kc[l] != ref["k_codes"][0]
+        if kd.any():
+            frac = np.abs(ref["k_pre"][0] - np.floor(ref["k_pre"][0]) - 0.5)
+            assert np.all(frac[kd] <= pu.CODE_WINDOW)
+        v_idx = O.v_unpack(vp[l], d)
+        vd = v_idx != ref["v_idx"][0]
+        if vd.any():
+            dist = np.min(np.abs(ref["v_rot"][0][vd][:, None] - thr[None, :]), axis=1)
+            assert np.all(dist <= pu.CODE_WINDOW), "layer %d: value code off a threshold by %g" % (l, dist.max())
+        mism_k += int(kd.sum())
+        mism_v += int(vd.sum())
+        dirty = kd.any(axis=(1, 2)) | vd.any(axis=(1, 2))                     # [H]
+        if l % 4 != 1:          # codes and scales: every layer; dequantization and attention: every 4th
+            continue
+        # dequantized tensors within 1e-3 relative, per vector
+        Kh, Vh = O.pool_decode(ref)
+        for g, o in ((Kg[l].cpu().numpy(), Kh[0]), (Vg[l].cpu().numpy(), Vh[0])):
+            err = np.abs(g - o).max(axis=-1)
+            bound = pu.DEQUANT_RTOL * np.abs(o).max(axis=-1)
+            assert not ((err > bound) & ~dirty[:, None]).any()
+        # attention within 2e-3 absolute
+        ref_out = O.pool_attend(Kh, Vh, Q[l:l + 1])[0]                        # [A, nq, q_heads, d]
+        err = np.abs(out[l] - ref_out)
+        mask = np.repeat(dirty, cfg.group)
+        err[:, :, mask, :] = 0.0
+        worst_att = max(worst_att, float(err.max()))
+        assert err.max() <= pu.ATTEND_ATOL, "layer %d attention off by %g" % (l, err.max())
+    n = K.size
+    assert mism_k <= 1e-5 * n and mism_v <= 1e-4 * n
+    print("full-size parity: worst attention error %.3g, threshold mismatches K %d V %d of %d" %
+          (worst_att, mism_k, mism_v, n))
