@@ -383,6 +383,8 @@ __device__ __forceinline__ void pipeline_step(const RawV<D>& rv, const RawK<D>& 
         raise = false;
 #pragma unroll
         for (int nt = 0; nt < NRT; ++nt) {
+            // the scores are consumed by vector instructions only: have the MFMAs deliver them there
+            asm volatile("" : "+v"(Sb[nt][0]), "+v"(Sb[nt][1]));
             mloc[nt] = max8(Sb[nt][0], Sb[nt][1]);
             raise |= mloc[nt] > m_thr[nt];  // also true while the reference is -inf
             Sa[nt][0] = Sb[nt][0];
@@ -402,8 +404,8 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     constexpr int OSTRIDE = D + 4;
     constexpr int TB = LY::tile_bytes;
     __shared__ float m_s[4][ROWS];
-    __shared__ float l_s[ROWS];
-    __shared__ __align__(16) float o_s[ROWS * OSTRIDE];
+    __shared__ float l_s[2 * ROWS];
+    extern __shared__ __align__(16) float o_s[];  // two merge buffers of ROWS x OSTRIDE floats
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: LDS bases go through M0
@@ -495,28 +497,28 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         process_ragged_tile<D, NRT>(tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
                                     Lacc, m_ref, m_thr, mneg);
 
-    // ---- merge the four waves through LDS
+    // ---- merge the four waves through LDS: waves 0 and 2 store their (rescaled) accumulators into
+    // two buffers, waves 1 and 3 add theirs on top, the final pass sums the two buffers.  The order of
+    // the additions is fixed, so the result is reproducible.
     if (grp == 0) {
 #pragma unroll
         for (int nt = 0; nt < NRT; ++nt) m_s[wave][16 * nt + n] = m_ref[nt];
     }
     __syncthreads();
-    for (int i = tid; i < ROWS * OSTRIDE; i += 256) o_s[i] = 0.0f;
-    if (tid < ROWS) l_s[tid] = 0.0f;
-    __syncthreads();
-    // waves add their share one after the other, so the summation order (and the result) is fixed
-    for (int w = 0; w < 4; ++w) {
-        if (wave == w) {
+    float* obuf = o_s + (wave >> 1) * (ROWS * OSTRIDE);
+    float* lbuf = l_s + (wave >> 1) * ROWS;
+    for (int round = 0; round < 2; ++round) {
+        if ((wave & 1) == round) {
 #pragma unroll
             for (int nt = 0; nt < NRT; ++nt) {
                 const int r = 16 * nt + n;
                 const float M = fmaxf(fmaxf(m_s[0][r], m_s[1][r]), fmaxf(m_s[2][r], m_s[3][r]));
                 const float f = m_ref[nt] == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f((m_ref[nt] - M) * qscale);
-                if (grp == 0) l_s[r] += Lacc[nt][0] * f;
+                if (grp == 0) lbuf[r] = (round == 0 ? 0.0f : lbuf[r]) + Lacc[nt][0] * f;
 #pragma unroll
                 for (int g = 0; g < NG; ++g) {
-                    float4* dst = reinterpret_cast<float4*>(&o_s[r * OSTRIDE + 16 * g + 4 * grp]);
-                    float4 v = *dst;
+                    float4* dst = reinterpret_cast<float4*>(&obuf[r * OSTRIDE + 16 * g + 4 * grp]);
+                    float4 v = round == 0 ? make_float4(0.0f, 0.0f, 0.0f, 0.0f) : *dst;
                     v.x = fmaf(O[g][nt][0], f, v.x);
                     v.y = fmaf(O[g][nt][1], f, v.y);
                     v.z = fmaf(O[g][nt][2], f, v.z);
@@ -533,10 +535,11 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         const int r = row0 + rr;
         if (r >= p.R) break;  // uniform over the wave
         const float Mr = fmaxf(fmaxf(m_s[0][rr], m_s[1][rr]), fmaxf(m_s[2][rr], m_s[3][rr]));
-        const float l = l_s[rr];
+        const float l = l_s[rr] + l_s[ROWS + rr];
         float x[EPL];
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) x[i] = o_s[rr * OSTRIDE + lane * EPL + i] * kInvCentroidScale;
+        for (int i = 0; i < EPL; ++i)
+            x[i] = (o_s[rr * OSTRIDE + lane * EPL + i] + o_s[(ROWS + rr) * OSTRIDE + lane * EPL + i]) * kInvCentroidScale;
         if (direct) {
             const float inv = 1.0f / l;
 #pragma unroll
@@ -576,7 +579,16 @@ bool matrix_kernel_direct(const AttendPlan& plan) { return plan.nsplit == 1 && !
 template <int D, int NRT>
 static hipError_t launch_one(dim3 grid, const uint8_t* storage, const AttendPlan& plan, const void* Q, float* ws_ml,
                              float* ws_o, float* out, int direct, hipStream_t s) {
-    attend_mfma_kernel<D, NRT><<<grid, 256, 0, s>>>(storage, (const __half*)Q, ws_ml, ws_o, out, plan, direct);
+    constexpr int kMergeBytes = 2 * 16 * NRT * (D + 4) * (int)sizeof(float);
+    auto kern = attend_mfma_kernel<D, NRT>;
+    static bool configured = false;  // per instantiation: the limit is a property of the function
+    if (!configured && kMergeBytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMergeBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    kern<<<grid, 256, kMergeBytes, s>>>(storage, (const __half*)Q, ws_ml, ws_o, out, plan, direct);
     return hipGetLastError();
 }
 
