@@ -54,7 +54,8 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
     using LY = Layout<D>;
     constexpr int EPT = D / 8;
     __shared__ __align__(16) uint8_t img[LY::tile_bytes];
-    __shared__ __align__(16) uint8_t vstage[kTile * D];
+    constexpr int VS = D + 4;  // row stride of the code staging area: +4 bytes rotates the LDS bank per token
+    __shared__ __align__(16) uint8_t vstage[kTile * VS];
 
     const int tile = blockIdx.x, unit = blockIdx.y;
     const int tid = threadIdx.x, t = tid >> 3, c = tid & 7;
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         float x[EPT];
         load_halfs<EPT>(V + row, valid, x);
         wht_8lanes<EPT>(x, tid);
-        uint32_t* dst = reinterpret_cast<uint32_t*>(vstage + t * D + e0);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(vstage + t * VS + e0);
 #pragma unroll
         for (int i = 0; i < EPT / 4; ++i) {
             uint32_t w = 0;
@@ -125,8 +126,8 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int tk = vcode_token(grp, e);
-            word |= (uint32_t)vstage[tk * D + dv] << (8 * (e & 3) + 3 * (e >> 2));
-            const uint32_t c3 = vstage[tk * D + dv3];
+            word |= (uint32_t)vstage[tk * VS + dv] << (8 * (e & 3) + 3 * (e >> 2));
+            const uint32_t c3 = vstage[tk * VS + dv3];
             if (w == 0 && e < 4) word |= (c3 & 3) << (8 * e + 6);
             if (w == 2 && e >= 4) word |= (c3 & 3) << (8 * (e - 4) + 6);
             if (w == 1) word |= (c3 >> 2) << (e < 4 ? 8 * e + 6 : 8 * (e - 4) + 7);
