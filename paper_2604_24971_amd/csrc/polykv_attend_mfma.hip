@@ -41,28 +41,6 @@ union H8 {
     uint32_t u[4];
 };
 
-// Centroids scaled by 1.6146639585494995 and rounded to fp16.  The factor was searched in [1, 2) so
-// that all four magnitudes land within 1.9e-5 (relative) of an fp16 value -- ten times closer than the
-// unscaled centroids; its inverse is applied once per output row.
-constexpr float kInvCentroidScale = 0.6193239123875222f;
-// fp16 bit patterns by code 0..7: C2F3 C057 BCE2 B655 3655 3CE2 4057 42F3, split into byte planes
-constexpr uint32_t kTabLoA = 0x55E257F3u, kTabLoB = 0xF357E255u;  // low bytes of codes 0..3 / 4..7
-constexpr uint32_t kTabHiA = 0xB6BCC0C2u, kTabHiB = 0x42403C36u;  // high bytes
-
-// Four 3-bit codes sitting in the four bytes of `sel` -> four fp16 centroids (two dwords).
-__device__ __forceinline__ void lookup4(uint32_t sel, uint32_t& out01, uint32_t& out23) {
-    const uint32_t lo = __builtin_amdgcn_perm(kTabLoB, kTabLoA, sel);
-    const uint32_t hi = __builtin_amdgcn_perm(kTabHiB, kTabHiA, sel);
-    out01 = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
-    out23 = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
-}
-
-// Four offset-binary key codes in a dword -> four exact fp16 integers: 0x6400 | b is 1024 + b.
-__device__ __forceinline__ void codes4_to_half(uint32_t w, uint32_t& out01, uint32_t& out23) {
-    out01 = __builtin_amdgcn_perm(0x64646464u, w, 0x04010400u);
-    out23 = __builtin_amdgcn_perm(0x64646464u, w, 0x04030402u);
-}
-
 __device__ __forceinline__ float xor16_max(float x) {
     const uint32_t xi = __float_as_uint(x);
     auto r = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);

@@ -1,49 +1,41 @@
 // Encode / decode / export kernels of the packed pool (gfx950).
 //
-// One workgroup of 256 threads handles one tile (32 tokens) of one KV head.  Thread (t, c), t =
-// tid/8, c = tid%8, owns the D/8 consecutive head_dim elements c*D/8 .. of token t, so a dense fp16
-// row is read (or written) by 8 neighbouring lanes with 16- or 32-byte accesses, and the Walsh-
-// Hadamard butterflies need log2(D/8) in-register stages plus three DPP stages across those 8 lanes.
-// The tile record is assembled in LDS and streamed out with 16-byte coalesced stores.
+// One workgroup of 256 threads handles one tile (32 tokens) of one KV head.  Thread (t, c) owns the
+// D/8 consecutive head_dim elements c*D/8 .. of token t, so a dense fp16 row is read (or written) by
+// 8 lanes with 16- or 32-byte accesses and a wave covers 8 whole rows.  The Walsh-Hadamard transform
+// is log2(D/8) in-register stages plus three one-instruction DPP stages across those 8 lanes.  Both
+// kernels are written to stay under the HBM time in vector instructions: conversions are fused with
+// multiplies, the key codes are rounded with one magic-number add, the value quantizer compares the
+// magnitude against three thresholds, and all bit (un)packing works on dwords.
 #include <hip/hip_fp16.h>
 
 #include "polykv_internal.hpp"
 #include "polykv_layout.hpp"
 
+// The quantizers take rounding decisions that must match the definition operation by operation
+// (product rounded to fp32, then rounded to an integer): no fused multiply-adds unless written out.
+#pragma clang fp contract(off)
+
 namespace polykv {
-
-template <int N> struct HalfVec { __half v[N]; };
-
-template <int N>
-__device__ __forceinline__ void load_halfs(const __half* p, bool valid, float (&x)[N]) {
-    static_assert(N % 8 == 0, "");
-#pragma unroll
-    for (int i = 0; i < N / 8; ++i) {
-        uint4 raw = valid ? reinterpret_cast<const uint4*>(p)[i] : make_uint4(0, 0, 0, 0);
-        const __half2* h2 = reinterpret_cast<const __half2*>(&raw);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            float2 f = __half22float2(h2[k]);
-            x[i * 8 + 2 * k] = f.x;
-            x[i * 8 + 2 * k + 1] = f.y;
-        }
-    }
-}
-
-// Walsh-Hadamard transform of a D-vector spread over 8 lanes (lane c holds elements c*N..c*N+N-1).
-template <int N> __device__ __forceinline__ void wht_8lanes(float (&x)[N], int lane) {
-    wht_inlane<N>(x);
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        x[i] = wht_lane_stage<1>(x[i], lane);
-        x[i] = wht_lane_stage<2>(x[i], lane);
-        x[i] = wht_lane_stage<4>(x[i], lane);
-    }
-}
 
 template <int D> __device__ __forceinline__ constexpr float inv_sqrt_d() {
     return D == 64 ? 0.125f : 0.08838834764831845f;
 }
+template <int D> __device__ __forceinline__ constexpr float sqrt_d() {
+    return D == 64 ? 8.0f : 11.313708498984761f;
+}
+
+union Half2Bits {
+    uint32_t u;
+    _Float16 h[2];
+};
+
+// Thread -> (token of the tile, chunk) for the codec kernels; see wht_cross_chunks().
+struct CodecThread {
+    int t, c;
+    __device__ __forceinline__ explicit CodecThread(int tid)
+        : t((tid >> 6) * 8 + codec_token_in_wave(tid & 63)), c(codec_chunk(tid & 63)) {}
+};
 
 // ------------------------------------------------------------------------------------ encode ---
 // Key quantization and value quantization of section "Compression Scheme", fused in one pass.
@@ -53,99 +45,139 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
                                                      uint8_t* __restrict__ pool, int T, int tiles) {
     using LY = Layout<D>;
     constexpr int EPT = D / 8;
-    __shared__ __align__(16) uint8_t img[LY::tile_bytes];
-    constexpr int VS = D + 4;  // row stride of the code staging area: +4 bytes rotates the LDS bank per token
-    __shared__ __align__(16) uint8_t vstage[kTile * VS];
+    constexpr int KBYTES = LY::vcodes_off;  // key codes + scales
+    constexpr int VS = kTile + 4;           // bytes per rotated coordinate in the code staging area
+    __shared__ __align__(16) uint8_t kimg[KBYTES];
+    __shared__ __align__(16) uint8_t vstage[D * VS];  // value codes as bytes, [coordinate][token]
 
     const int tile = blockIdx.x, unit = blockIdx.y;
-    const int tid = threadIdx.x, t = tid >> 3, c = tid & 7;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const CodecThread th(tid);
+    const int t = th.t, c = th.c;
     const int tok = tile * kTile + t;
     const bool valid = tok < T;
     const size_t row = ((size_t)unit * T + (valid ? tok : 0)) * D + c * EPT;
     const int e0 = c * EPT, j = e0 >> 5, g8 = (e0 >> 3) & 3;
 
+    uint4 kraw[EPT / 8], vraw[EPT / 8];
+#pragma unroll
+    for (int i = 0; i < EPT / 8; ++i) {
+        kraw[i] = valid ? reinterpret_cast<const uint4*>(K + row)[i] : make_uint4(0, 0, 0, 0);
+        vraw[i] = valid ? reinterpret_cast<const uint4*>(V + row)[i] : make_uint4(0, 0, 0, 0);
+    }
+
     // ---- keys: block absmax -> fp16 scale -> codes with the stored scale
     {
         float k[EPT];
-        load_halfs<EPT>(K + row, valid, k);
+#pragma unroll
+        for (int i = 0; i < EPT / 2; ++i) {
+            Half2Bits b;
+            b.u = reinterpret_cast<const uint32_t*>(kraw)[i];
+            k[2 * i] = (float)b.h[0];
+            k[2 * i + 1] = (float)b.h[1];
+        }
         float amax = 0.0f;
 #pragma unroll
-        for (int i = 0; i < EPT; ++i) amax = fmaxf(amax, fabsf(k[i]));
+        for (int i = 0; i < EPT; i += 2) amax = fmaxf(fmaxf(fabsf(k[i]), fabsf(k[i + 1])), amax);
         amax = fmaxf(amax, lane_xor<1>(amax));
         if (EPT == 8) amax = fmaxf(amax, lane_xor<2>(amax));
         const __half s16 = __float2half_rn(__fdiv_rn(amax, 127.0f));
         const float sf = __half2float(s16);
         const float inv = sf > 0.0f ? __fdiv_rn(1.0f, sf) : 0.0f;
-        uint32_t packed[EPT / 4];
+        // round(k * inv) + 128 in the low byte of a float: adding 1.5 * 2^23 + 128 rounds the product
+        // to an integer (nearest, ties to even) in the low mantissa bits; the clamp keeps the byte valid
+        // when a subnormal scale lets |k * inv| exceed 127.
+        constexpr float kMagic = 12582912.0f + 128.0f;
+        uint32_t r[EPT];
 #pragma unroll
-        for (int i = 0; i < EPT / 4; ++i) {
-            uint32_t w = 0;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                float q = rintf(__fmul_rn(k[i * 4 + b], inv));
-                q = fminf(fmaxf(q, -128.0f), 127.0f);
-                w |= (uint32_t)((int)q + 128) << (8 * b);
-            }
-            packed[i] = w;
+        for (int i = 0; i < EPT; ++i) {
+            const float q = k[i] * inv + kMagic;  // two roundings (contraction is off in this file)
+            r[i] = __float_as_uint(__builtin_amdgcn_fmed3f(q, kMagic - 128.0f, kMagic + 127.0f));
         }
 #pragma unroll
         for (int rr = 0; rr < EPT / 8; ++rr) {
-            uint32_t* dst = reinterpret_cast<uint32_t*>(img + LY::kcodes_off + kcode_run_offset(t, j, g8 + rr));
-            dst[0] = packed[2 * rr];
-            dst[1] = packed[2 * rr + 1];
+            uint2 w;
+            const uint32_t a01 = __builtin_amdgcn_perm(r[8 * rr + 1], r[8 * rr + 0], 0x0c0c0400u);
+            const uint32_t a23 = __builtin_amdgcn_perm(r[8 * rr + 3], r[8 * rr + 2], 0x04000c0cu);
+            const uint32_t b01 = __builtin_amdgcn_perm(r[8 * rr + 5], r[8 * rr + 4], 0x0c0c0400u);
+            const uint32_t b23 = __builtin_amdgcn_perm(r[8 * rr + 7], r[8 * rr + 6], 0x04000c0cu);
+            w.x = a01 | a23;
+            w.y = b01 | b23;
+            *reinterpret_cast<uint2*>(kimg + LY::kcodes_off + kcode_run_offset(t, j, g8 + rr)) = w;
         }
         if ((e0 & 31) == 0)
-            reinterpret_cast<__half*>(img + LY::kscales_off)[t * LY::NB + j] = s16;
+            reinterpret_cast<__half*>(kimg + LY::kscales_off)[t * LY::NB + j] = s16;
     }
 
-    // ---- values: rotate, nearest centroid, stage codes as bytes [t][dv]
+    // ---- values: rotate, nearest centroid, stage the codes as bytes [coordinate][token]
     {
-        float x[EPT];
-        load_halfs<EPT>(V + row, valid, x);
-        wht_8lanes<EPT>(x, tid);
-        uint32_t* dst = reinterpret_cast<uint32_t*>(vstage + t * VS + e0);
+        const float eps = codec_entry_sign(lane);
+        float y[EPT];
 #pragma unroll
-        for (int i = 0; i < EPT / 4; ++i) {
-            uint32_t w = 0;
+        for (int i = 0; i < EPT / 2; ++i) {
+            Half2Bits b;
+            b.u = reinterpret_cast<const uint32_t*>(vraw)[i];
+            y[2 * i] = __builtin_fmaf((float)b.h[0], eps, 0.0f);  // conversion and sign in one fma-mix
+            y[2 * i + 1] = __builtin_fmaf((float)b.h[1], eps, 0.0f);
+        }
+        wht_cross_chunks<EPT>(y, lane);
+        wht_inlane<EPT>(y);
+        // y = sqrt(D) * v_rot; the thresholds are scaled instead of the values.  The code is the number
+        // of thresholds below v_rot: 4 + n for positive values, 3 - n otherwise, with n the number of
+        // positive thresholds below |v_rot|.
+        constexpr float t1 = POLYKV_T1 * sqrt_d<D>(), t2 = POLYKV_T2 * sqrt_d<D>(), t3 = POLYKV_T3 * sqrt_d<D>();
+        uint8_t* dst = vstage + e0 * VS + t;
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
-                w |= (uint32_t)quantize3(__fmul_rn(x[i * 4 + b], inv_sqrt_d<D>())) << (8 * b);
-            dst[i] = w;
+        for (int i = 0; i < EPT; ++i) {
+            // Four compares into scalar masks, then a select and an add-with-carry chain.  On this target a
+            // vector instruction may read a scalar mask only two or more instructions after the compare
+            // that wrote it; the order below keeps that distance without padding.
+            int n, m;
+            unsigned long long sp, s1, s2, s3;
+            asm("v_cmp_lt_f32_e64 %2, 0, %6\n\t"
+                "v_cmp_gt_f32_e64 %3, |%6|, %7\n\t"
+                "v_cmp_gt_f32_e64 %4, |%6|, %8\n\t"
+                "v_cmp_gt_f32_e64 %5, |%6|, %9\n\t"
+                "v_cndmask_b32_e64 %1, 3, 4, %2\n\t"
+                "v_addc_co_u32_e64 %0, vcc, 0, 0, %3\n\t"
+                "v_addc_co_u32_e64 %0, vcc, 0, %0, %4\n\t"
+                "v_addc_co_u32_e64 %0, vcc, 0, %0, %5\n\t"
+                "v_xor_b32_e32 %0, %0, %1"
+                : "=&v"(n), "=&v"(m), "=&s"(sp), "=&s"(s1), "=&s"(s2), "=&s"(s3)
+                : "v"(y[i]), "v"(t1), "v"(t2), "v"(t3)
+                : "vcc");
+            dst[i * VS] = (uint8_t)n;
         }
     }
     __syncthreads();
 
-    // ---- bit-pack the value codes into the tile record
-    for (int idx = tid; idx < LY::NT * 192; idx += 256) {
-        const int q = idx / 192, rem = idx - q * 192;
-        const int lane = rem / 3, w = rem - lane * 3;
-        const int grp = lane >> 4, m = lane & 15;
-        const int dv = 16 * (4 * q + w) + m;
-        const int dv3 = 16 * (4 * q + 3) + m;  // group 4q+3 lives in the spare bits
-        uint32_t word = 0;
+    uint8_t* rec = pool + ((size_t)unit * tiles + tile) * LY::tile_bytes;
+    // ---- bit-pack the value codes: one lane triplet (three dwords, four coordinate groups) per thread
+    if (tid < LY::NT * 64) {
+        const int q = tid >> 6, grp = lane >> 4, m = lane & 15;
+        uint32_t lo[4], hi[4];  // codes of tokens 4grp..4grp+3 and 16+4grp..16+4grp+3, one per byte
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int tk = vcode_token(grp, e);
-            word |= (uint32_t)vstage[tk * VS + dv] << (8 * (e & 3) + 3 * (e >> 2));
-            const uint32_t c3 = vstage[tk * VS + dv3];
-            if (w == 0 && e < 4) word |= (c3 & 3) << (8 * e + 6);
-            if (w == 2 && e >= 4) word |= (c3 & 3) << (8 * (e - 4) + 6);
-            if (w == 1) word |= (c3 >> 2) << (e < 4 ? 8 * e + 6 : 8 * (e - 4) + 7);
+        for (int gi = 0; gi < 4; ++gi) {
+            const uint8_t* src = vstage + (16 * (4 * q + gi) + m) * VS + 4 * grp;
+            lo[gi] = *reinterpret_cast<const uint32_t*>(src);
+            hi[gi] = *reinterpret_cast<const uint32_t*>(src + 16);
         }
-        reinterpret_cast<uint32_t*>(img + LY::vcodes_off)[idx] = word;
+        uint32_t w0 = lo[0] | (hi[0] << 3), w1 = lo[1] | (hi[1] << 3), w2 = lo[2] | (hi[2] << 3);
+        w0 |= (lo[3] & 0x03030303u) << 6;
+        w2 |= (hi[3] & 0x03030303u) << 6;
+        w1 |= ((lo[3] & 0x04040404u) << 4) | ((hi[3] & 0x04040404u) << 5);
+        uint32_t* out = reinterpret_cast<uint32_t*>(rec + LY::vcodes_off + q * 768 + lane * 12);
+        out[0] = w0;
+        out[1] = w1;
+        out[2] = w2;
     }
-    __syncthreads();
-
-    uint4* out = reinterpret_cast<uint4*>(pool + ((size_t)unit * tiles + tile) * LY::tile_bytes);
-    const uint4* src = reinterpret_cast<const uint4*>(img);
-    for (int i = tid; i < LY::tile_bytes / 16; i += 256) out[i] = src[i];
+    // ---- key codes and scales: 16-byte coalesced stores
+    uint4* out = reinterpret_cast<uint4*>(rec);
+    const uint4* src = reinterpret_cast<const uint4*>(kimg);
+    for (int i = tid; i < KBYTES / 16; i += 256) out[i] = src[i];
 }
 
 // ------------------------------------------------------------------------------------ decode ---
-template <typename OutT> __device__ __forceinline__ OutT to_out(float x);
-template <> __device__ __forceinline__ float to_out<float>(float x) { return x; }
-template <> __device__ __forceinline__ __half to_out<__half>(float x) { return __float2half_rn(x); }
-
 template <int D>
 __device__ __forceinline__ void stage_tile(uint8_t* img, const uint8_t* pool, int unit, int tiles,
                                            int tile, int tid) {
@@ -156,6 +188,33 @@ __device__ __forceinline__ void stage_tile(uint8_t* img, const uint8_t* pool, in
     __syncthreads();
 }
 
+template <typename OutT, int N> struct RowStore;
+template <int N> struct RowStore<__half, N> {
+    // N fp32 values -> N halves, 16-byte stores
+    static __device__ __forceinline__ void store(__half* dst, const float (&x)[N]) {
+#pragma unroll
+        for (int i = 0; i < N / 8; ++i) {
+            uint4 o;
+            uint32_t* w = reinterpret_cast<uint32_t*>(&o);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                Half2Bits b;
+                b.h[0] = (_Float16)x[8 * i + 2 * k];
+                b.h[1] = (_Float16)x[8 * i + 2 * k + 1];
+                w[k] = b.u;
+            }
+            reinterpret_cast<uint4*>(dst)[i] = o;
+        }
+    }
+};
+template <int N> struct RowStore<float, N> {
+    static __device__ __forceinline__ void store(float* dst, const float (&x)[N]) {
+#pragma unroll
+        for (int i = 0; i < N / 4; ++i)
+            reinterpret_cast<float4*>(dst)[i] = make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
+    }
+};
+
 // K = code * s and V = H c[code] / sqrt(d)  (sections "Compression Scheme" and "TurboQuant",
 // dequantization; the inverse of the normalized rotation is the same normalized transform).
 template <int D, typename OutT>
@@ -164,35 +223,93 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
                                                      int T, int tiles) {
     using LY = Layout<D>;
     constexpr int EPT = D / 8;
-    __shared__ __align__(16) uint8_t img[LY::tile_bytes];
+    constexpr int KBYTES = LY::vcodes_off;
+    constexpr int CS = D + 8;  // halves per token row of the centroid staging area (16-byte aligned rows)
+    __shared__ __align__(16) uint8_t kimg[KBYTES];
+    __shared__ __align__(16) _Float16 cent[kTile * CS];  // fp16 centroids (scaled), [token][coordinate]
+
     const int tile = blockIdx.x, unit = blockIdx.y;
-    const int tid = threadIdx.x, t = tid >> 3, c = tid & 7;
-    stage_tile<D>(img, pool, unit, tiles, tile, tid);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const uint8_t* rec = pool + ((size_t)unit * tiles + tile) * LY::tile_bytes;
+
+    if (K_out != nullptr) {
+        const uint4* src = reinterpret_cast<const uint4*>(rec);
+        uint4* dst = reinterpret_cast<uint4*>(kimg);
+        for (int i = tid; i < KBYTES / 16; i += 256) dst[i] = src[i];
+    }
+    if (V_out != nullptr && tid < LY::NT * 128) {
+        // thread (half, q, lane): two of the four coordinate groups of one lane triplet
+        const int half = tid / (LY::NT * 64), ql = tid - half * (LY::NT * 64);
+        const int q = ql >> 6, grp = lane >> 4, m = lane & 15;
+        const uint32_t* w = reinterpret_cast<const uint32_t*>(rec + LY::vcodes_off + q * 768 + lane * 12);
+        const uint32_t w0 = w[0], w1 = w[1], w2 = w[2];
+#pragma unroll
+        for (int gg = 0; gg < 2; ++gg) {
+            uint32_t sel_a, sel_b;
+            if (half == 0)
+                vcode_selectors(w0, w1, w2, gg, sel_a, sel_b);
+            else
+                vcode_selectors(w0, w1, w2, 2 + gg, sel_a, sel_b);
+            Half2Bits c01, c23, c45, c67;
+            lookup4(sel_a, c01.u, c23.u);
+            lookup4(sel_b, c45.u, c67.u);
+            _Float16* col = cent + 16 * (4 * q + 2 * half + gg) + m;
+            col[(4 * grp + 0) * CS] = c01.h[0];
+            col[(4 * grp + 1) * CS] = c01.h[1];
+            col[(4 * grp + 2) * CS] = c23.h[0];
+            col[(4 * grp + 3) * CS] = c23.h[1];
+            col[(16 + 4 * grp + 0) * CS] = c45.h[0];
+            col[(16 + 4 * grp + 1) * CS] = c45.h[1];
+            col[(16 + 4 * grp + 2) * CS] = c67.h[0];
+            col[(16 + 4 * grp + 3) * CS] = c67.h[1];
+        }
+    }
+    __syncthreads();
+
+    const CodecThread th(tid);
+    const int t = th.t, c = th.c;
     const int tok = tile * kTile + t;
     const bool valid = tok < T;
     const size_t row = ((size_t)unit * T + (valid ? tok : 0)) * D + c * EPT;
     const int e0 = c * EPT, j = e0 >> 5, g8 = (e0 >> 3) & 3;
 
     if (K_out != nullptr) {
-        const float s = __half2float(reinterpret_cast<const __half*>(img + LY::kscales_off)[t * LY::NB + j]);
-        if (valid) {
+        const _Float16 s16 = reinterpret_cast<const _Float16*>(kimg + LY::kscales_off)[t * LY::NB + j];
+        float k[EPT];
 #pragma unroll
-            for (int i = 0; i < EPT; ++i) {
-                const uint8_t* codes = img + LY::kcodes_off + kcode_run_offset(t, j, g8 + (i >> 3));
-                K_out[row + i] = to_out<OutT>((float)((int)codes[i & 7] - 128) * s);
+        for (int rr = 0; rr < EPT / 8; ++rr) {
+            const uint2 raw = *reinterpret_cast<const uint2*>(kimg + LY::kcodes_off + kcode_run_offset(t, j, g8 + rr));
+            Half2Bits h[4];
+            codes4_to_half(raw.x, h[0].u, h[1].u);
+            codes4_to_half(raw.y, h[2].u, h[3].u);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                // (1024 + b) - 1152 = code, exact in fp16; code * s is exact in fp32
+                k[8 * rr + 2 * i] = (float)(h[i].h[0] - (_Float16)1152.0f) * (float)s16;
+                k[8 * rr + 2 * i + 1] = (float)(h[i].h[1] - (_Float16)1152.0f) * (float)s16;
             }
         }
+        if (valid) RowStore<OutT, EPT>::store(K_out + row, k);
     }
     if (V_out != nullptr) {
-        const uint32_t* vreg = reinterpret_cast<const uint32_t*>(img + LY::vcodes_off);
-        float x[EPT];
+        // the centroid scale, 1/sqrt(D) and the entry sign of the cross-lane stages ride on the conversion
+        const float f = codec_entry_sign(lane) * (kInvCentroidScale * inv_sqrt_d<D>());
+        float y[EPT];
 #pragma unroll
-        for (int i = 0; i < EPT; ++i) x[i] = centroid_of(vcode_extract(vreg, t, e0 + i));
-        wht_8lanes<EPT>(x, tid);
-        if (valid) {
+        for (int i = 0; i < EPT / 8; ++i) {
+            const uint4 raw = *reinterpret_cast<const uint4*>(cent + t * CS + e0 + 8 * i);
+            const uint32_t* w = reinterpret_cast<const uint32_t*>(&raw);
 #pragma unroll
-            for (int i = 0; i < EPT; ++i) V_out[row + i] = to_out<OutT>(x[i] * inv_sqrt_d<D>());
+            for (int k = 0; k < 4; ++k) {
+                Half2Bits b;
+                b.u = w[k];
+                y[8 * i + 2 * k] = __builtin_fmaf((float)b.h[0], f, 0.0f);
+                y[8 * i + 2 * k + 1] = __builtin_fmaf((float)b.h[1], f, 0.0f);
+            }
         }
+        wht_cross_chunks<EPT>(y, lane);
+        wht_inlane<EPT>(y);
+        if (valid) RowStore<OutT, EPT>::store(V_out + row, y);
     }
 }
 

@@ -92,6 +92,99 @@ __device__ __forceinline__ int vcode_extract(const uint32_t* v, int t, int dv) {
     return ((w[2] >> (8 * (e - 4) + 6)) & 3) | (((w[1] >> (8 * (e - 4) + 7)) & 1) << 2);
 }
 
+// ---- register-level dequantization helpers shared by the decode and attention kernels ---------
+// Centroids scaled by 1.6146639585494995 and rounded to fp16.  The factor was searched in [1, 2) so
+// that all four magnitudes land within 1.9e-5 (relative) of an fp16 value -- ten times closer than the
+// unscaled centroids; its inverse is applied once per output row.
+constexpr float kInvCentroidScale = 0.6193239123875222f;
+// fp16 bit patterns by code 0..7: C2F3 C057 BCE2 B655 3655 3CE2 4057 42F3, split into byte planes
+constexpr uint32_t kTabLoA = 0x55E257F3u, kTabLoB = 0xF357E255u;  // low bytes of codes 0..3 / 4..7
+constexpr uint32_t kTabHiA = 0xB6BCC0C2u, kTabHiB = 0x42403C36u;  // high bytes
+
+// Four 3-bit codes sitting in the four bytes of `sel` -> four fp16 centroids (two dwords).
+__device__ __forceinline__ void lookup4(uint32_t sel, uint32_t& out01, uint32_t& out23) {
+    const uint32_t lo = __builtin_amdgcn_perm(kTabLoB, kTabLoA, sel);
+    const uint32_t hi = __builtin_amdgcn_perm(kTabHiB, kTabHiA, sel);
+    out01 = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
+    out23 = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
+}
+
+// Four offset-binary key codes in a dword -> four exact fp16 integers: 0x6400 | b is 1024 + b.
+__device__ __forceinline__ void codes4_to_half(uint32_t w, uint32_t& out01, uint32_t& out23) {
+    out01 = __builtin_amdgcn_perm(0x64646464u, w, 0x04010400u);
+    out23 = __builtin_amdgcn_perm(0x64646464u, w, 0x04030402u);
+}
+
+// Value-code selectors of one lane's triplet (w0, w1, w2): group gi (0..3) -> the codes of its eight
+// tokens, e = 0..3 in the bytes of sel_a and e = 4..7 in the bytes of sel_b.
+__device__ __forceinline__ void vcode_selectors(uint32_t w0, uint32_t w1, uint32_t w2, int gi, uint32_t& sel_a,
+                                                uint32_t& sel_b) {
+    if (gi < 3) {
+        const uint32_t w = gi == 0 ? w0 : gi == 1 ? w1 : w2;
+        sel_a = w & 0x07070707u;
+        sel_b = (w >> 3) & 0x07070707u;
+    } else {
+        sel_a = ((w0 >> 6) & 0x03030303u) | ((w1 >> 4) & 0x04040404u);
+        sel_b = ((w2 >> 6) & 0x03030303u) | ((w1 >> 5) & 0x04040404u);
+    }
+}
+
+// ---- Walsh-Hadamard stages across the 8 lanes that share a token in the codec kernels ----------
+// Codec thread layout: lane bits 0, 1 and 3 carry the chunk index c (c = b0 + 2*b1 + 4*b3), the other
+// lane bits and the wave index carry the token.  Each of the three partner exchanges (lane ^ 1,
+// lane ^ 2, lane ^ 8) is then a single DPP pattern, and a butterfly stage is ONE instruction per
+// element:  y += kappa * y[partner]  (v_fmac_f32 with a DPP source).  That computes the true stage
+// output up to a per-lane sign; the signs of the three stages multiply to codec_entry_sign(), which
+// the caller applies when it converts its inputs to fp32 (for free, in the conversion's multiply),
+// so that what comes out is exactly H applied over the chunk index bits.
+__device__ __forceinline__ int codec_chunk(int lane) { return (lane & 3) | ((lane >> 1) & 4); }
+__device__ __forceinline__ int codec_token_in_wave(int lane) { return ((lane >> 2) & 1) | ((lane >> 3) & 6); }
+__device__ __forceinline__ float codec_entry_sign(int lane) {
+    return (__builtin_popcount(lane & 0xB) & 1) ? -1.0f : 1.0f;
+}
+// kappa of the stage over lane bit `bit`: +1 where the bit is set, -1 where it is clear
+__device__ __forceinline__ float codec_kappa(int lane, int bit) { return (lane >> bit) & 1 ? 1.0f : -1.0f; }
+
+// The three cross-lane stages on N values per lane.  On entry y holds codec_entry_sign() * x.
+template <int N> __device__ __forceinline__ void wht_cross_chunks(float (&y)[N], int lane) {
+    static_assert(N % 8 == 0, "");
+    const float k0 = codec_kappa(lane, 0), k1 = codec_kappa(lane, 1), k3 = codec_kappa(lane, 3);
+#pragma unroll
+    for (int b = 0; b < N; b += 8) {
+        // A DPP source must not have been written by the two preceding instructions: the leading
+        // s_nop covers the block entry, inside the block every register is reused 8 instructions later.
+        asm volatile(
+            "s_nop 1\n\t"
+            "v_fmac_f32_dpp %0, %0, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %1, %1, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %2, %2, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %3, %3, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %4, %4, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %5, %5, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %6, %6, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %7, %7, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %0, %0, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %1, %1, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %2, %2, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %3, %3, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %4, %4, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %5, %5, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %6, %6, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %7, %7, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %0, %0, %10 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %1, %1, %10 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %2, %2, %10 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %3, %3, %10 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %4, %4, %10 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %5, %5, %10 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %6, %6, %10 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %7, %7, %10 row_ror:8 row_mask:0xf bank_mask:0xf"
+            : "+v"(y[b]), "+v"(y[b + 1]), "+v"(y[b + 2]), "+v"(y[b + 3]), "+v"(y[b + 4]), "+v"(y[b + 5]),
+              "+v"(y[b + 6]), "+v"(y[b + 7])
+            : "v"(k0), "v"(k1), "v"(k3));
+    }
+}
+
 // ---- cross-lane butterflies -------------------------------------------------------------------
 // Partner exchange lane ^ MASK with DPP where a single control word exists, ds_bpermute otherwise.
 template <int MASK> __device__ __forceinline__ float lane_xor(float x) {
