@@ -33,16 +33,16 @@ constexpr int kRB = 4;  // query rows per pass of the vector kernels
 //   scores  lane = token: the lane dequantizes its key (code * block scale, exact in fp32) and dots
 //           it with each row's query (LDS broadcast);
 //   softmax running max / sum per row across the wave;
-//   PV      lane = (group grp, coordinate m) exactly as the value codes are stored: the lane owns
-//           the codes of 8 of the tile's tokens for coordinates 16*g + m and accumulates its share;
-//           the four lane groups are added once at the end.
+//   PV      lane = (half h, coordinate m) exactly as the value codes are stored: the lane owns the
+//           codes of 16 of the tile's tokens for coordinates 32*g + m and accumulates its share;
+//           the two lane halves are added once at the end.
 template <int D>
 __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __restrict__ pool,
                                                             const __half* __restrict__ Q,
                                                             float* __restrict__ ws_ml,
                                                             float* __restrict__ ws_o, AttendPlan p) {
     using LY = Layout<D>;
-    constexpr int MT = D / 16;
+    constexpr int MT = D / 32;
     __shared__ __align__(16) float q_s[kRB][D];
     __shared__ __align__(16) float p_s[4][kRB][64];
     __shared__ float ctab[8];
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
         for (int mt = 0; mt < MT; ++mt) acc[r][mt] = 0.0f;
     }
     const int hh = lane >> 5, cc = lane & 31;   // scores: which tile of the pair, token in the tile
-    const int grp = lane >> 4, mm = lane & 15;  // PV: position of the lane in the value-code layout
+    const int vh = lane >> 5, mm = lane & 31;   // PV: position of the lane in the value-code layout
 
     for (int ch = c_begin; ch < c_end; ++ch) {
         // ---- scores, lane = token
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
                 for (int i = 0; i < 3; ++i) w[i] = vreg[q * 192 + lane * 3 + i];
 #pragma unroll
                 for (int gi = 0; gi < 4; ++gi) {
-                    const int g = 4 * q + gi;
+                    const int G = 4 * q + gi, g = G >> 1;
 #pragma unroll
                     for (int e4 = 0; e4 < 2; ++e4) {
                         float cv[4];
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
                             else code = ((w[2] >> (8 * e3 + 6)) & 3) | (((w[1] >> (8 * e3 + 7)) & 1) << 2);
                             cv[e3] = ctab[code];
                         }
-                        const int tk = sub * 32 + 16 * e4 + 4 * grp;   // tokens tk .. tk+3
+                        const int tk = sub * 32 + vcode_token(G, lane, 4 * e4);  // tokens tk .. tk+3
 #pragma unroll
                         for (int r = 0; r < kRB; ++r) {
                             const float4 pv = *reinterpret_cast<const float4*>(&p_s[wave][r][tk]);
@@ -167,9 +167,8 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             float v = acc[r][mt];
-            v += __shfl_xor(v, 16, 64);
             v += __shfl_xor(v, 32, 64);
-            if (grp == 0) ws_o[prow * D + 16 * mt + mm] = v;
+            if (vh == 0) ws_o[prow * D + 32 * mt + mm] = v;
         }
         if (lane == 0) {
             ws_ml[prow * 2] = m_run[r];

@@ -1,23 +1,27 @@
-// Matrix-core decode attention over the packed pool (gfx950, v_mfma_f32_16x16x32_f16).
+// Matrix-core decode attention over the packed pool (gfx950, v_mfma_f32_32x32x16_f16).
 //
-// One wave owns up to 64 query rows (NRT tiles of 16) of one KV head and streams 32-token tile
+// One wave owns up to 64 query rows (NT tiles of 32) of one KV head and streams 32-token tile
 // records.  Per tile, with tokens as the MFMA M dimension and query rows as N:
 //
-//   staging  a lane's share of a record (its key-code runs, its tokens' scales, its value-code
+//   staging  a lane's share of a record (its key-code runs, its token's scales, its value-code
 //            triplets -- every wave load one contiguous run) is loaded into registers one step ahead
 //            of its use, so each load has a whole step to land.
 //   pipeline two tiles are in flight per wave: the scores of the next tile are computed on the matrix
 //            cores while the vector ALUs run the softmax and value dequantization of the current one.
 //   scores   S^T[t, r] = sum_j sum_{k in block j} (code[t,k] * s[t,j]) * q[r,k].  The dequantized key
 //            code*s has up to 18 significant bits, so it is split exactly into two fp16 terms
-//            hi = fp16(code*s), lo = code*s - hi (one packed fma), each fed to one MFMA per q8_0 block
-//            (K = 32 = one block) with fp32 accumulation: key dequantization stays exact.
+//            hi = fp16(code*s), lo = code*s - hi (one packed fma), each fed to the two K=16 MFMAs of a
+//            q8_0 block with fp32 accumulation: key dequantization stays exact.
 //   softmax  online, per row, in base-2 units; the reference maximum is only raised when a row
 //            exceeds it by more than 2^8, so the accumulator rescale is rare; p <= 256 fits fp16.
 //   PV       O^T[v, r] += sum_t c[code[t, v]] * p[t, r]   with the score tile's accumulator layout
 //            feeding the B operand directly (the value codes are stored in that k-order), centroids
-//            looked up with byte permutes.  A row of ones as an extra A operand yields the softmax
-//            denominator from the very same fp16-rounded p.
+//            looked up with byte permutes.  The softmax denominator is summed from the very same
+//            fp16-rounded p with packed dot products.
+//
+// Why 32x32x16: a wave that interleaves MFMAs with vector work pays about 11.5 issue cycles per MFMA
+// whatever its shape and 4 per vector instruction, so the larger tile halves the MFMA share of the
+// issue time for the same arithmetic.
 //
 // The accumulation stays in the rotated value domain; the inverse Walsh-Hadamard rotation is done
 // once per output row (sections "Compression Scheme" / "TurboQuant", dequantization), in this kernel
@@ -33,52 +37,50 @@
 namespace polykv {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef float float4v __attribute__((ext_vector_type(4)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float float16v __attribute__((ext_vector_type(16)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
 union H8 {
     half8 h;
     uint32_t u[4];
+    half2v p[4];
 };
 
-__device__ __forceinline__ float xor16_max(float x) {
-    const uint32_t xi = __float_as_uint(x);
-    auto r = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+__device__ __forceinline__ float16v mfma32(const half8& a, const half8& b, const float16v& c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
+
+// lane <-> lane ^ 32 combinations
 __device__ __forceinline__ float xor32_max(float x) {
     const uint32_t xi = __float_as_uint(x);
     auto r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
-
+__device__ __forceinline__ float xor32_sum(float x) {
+    const uint32_t xi = __float_as_uint(x);
+    auto r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 
 // ---- tile staging: global -> registers, one step ahead ------------------------------------------
-// A lane's share of a tile record: its 16 bytes of every key block (the two 8-code A operands), the
-// scales of its two tokens, and its value-code triplets.  Every load is one contiguous, fully
-// coalesced run across the wave (the record is stored in exactly this order).
+// A lane's share of a tile record: its 16 bytes of every key block (the A operands of the block's two
+// K=16 slices), the scales of its token, and its value-code triplets.  Every load is one contiguous,
+// fully coalesced run across the wave (the record is stored in exactly this order).
 template <int D> struct RawK {
-    uint2 k[2][D / 32];      // [mt][j]: codes of token 16mt + n, block j, elements 8grp .. 8grp+7
-    uint32_t sc[2][D / 64];  // [mt]: fp16 scales of token 16mt + n, blocks 0..NB-1
+    uint4v k[D / 32];      // [j]: codes of token m, block j: elements 8h..8h+7 (x, y) and 16+8h.. (z, w)
+    uint32_t sc[D / 64];   // fp16 scales of token m, blocks 0..NB-1
 };
 template <int D> struct RawV {
     uint32_t w[D / 64][3];
 };
 
-template <int D> __device__ __forceinline__ uint2 load_kraw(const uint8_t* tile, int lane, int mt, int j) {
-    return *reinterpret_cast<const uint2*>(tile + j * 1024 + lane * 16 + 8 * mt);
-}
-template <int D> __device__ __forceinline__ uint32_t load_sc(const uint8_t* tile, int n, int mt, int x) {
-    return *reinterpret_cast<const uint32_t*>(tile + Layout<D>::kscales_off + (16 * mt + n) * (D / 32) * 2 + 4 * x);
-}
 template <int D> __device__ __forceinline__ void load_rawk(RawK<D>& r, const uint8_t* tile, int lane) {
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
+    for (int x = 0; x < D / 64; ++x)
+        r.sc[x] = *reinterpret_cast<const uint32_t*>(tile + Layout<D>::kscales_off + (lane & 31) * (D / 32) * 2 + 4 * x);
 #pragma unroll
-        for (int x = 0; x < D / 64; ++x) r.sc[mt][x] = load_sc<D>(tile, lane & 15, mt, x);
-#pragma unroll
-        for (int j = 0; j < D / 32; ++j) r.k[mt][j] = load_kraw<D>(tile, lane, mt, j);
-    }
+    for (int j = 0; j < D / 32; ++j) r.k[j] = *reinterpret_cast<const uint4v*>(tile + j * 1024 + lane * 16);
 }
 template <int D> __device__ __forceinline__ void load_rawv(RawV<D>& r, const uint8_t* tile, int lane) {
 #pragma unroll
@@ -88,101 +90,110 @@ template <int D> __device__ __forceinline__ void load_rawv(RawV<D>& r, const uin
             r.w[q][w] = *reinterpret_cast<const uint32_t*>(tile + Layout<D>::vcodes_off + q * 768 + lane * 12 + 4 * w);
 }
 
-__device__ __forceinline__ float max8(const float4v& a, const float4v& b) {
+// Half block (j, s) of a lane's key codes -> the exact two-term fp16 split of code * scale.
+template <int D>
+__device__ __forceinline__ void key_split(const RawK<D>& rk, int j, int s, half8& hi, half8& lo) {
+    H8 a;
+    codes4_to_half(s == 0 ? rk.k[j].x : rk.k[j].z, a.u[0], a.u[1]);
+    codes4_to_half(s == 0 ? rk.k[j].y : rk.k[j].w, a.u[2], a.u[3]);
+    a.h = a.h - (_Float16)1152.0f;
+    union {
+        uint32_t u;
+        _Float16 h[2];
+    } s2;
+    s2.u = rk.sc[j >> 1];
+    const half8 sv = (half8)(s2.h[j & 1]);
+    hi = a.h * sv;
+    lo = __builtin_elementwise_fma(a.h, sv, -hi);  // exact remainder of the product
+}
+
+// Value group G of a lane: eight 3-bit codes -> fp16 centroids, the A operand of one P.V product.
+template <int D> __device__ __forceinline__ void value_group(const RawV<D>& rv, int G, H8& va) {
+    uint32_t sel_a, sel_b;
+    vcode_selectors(rv.w[G >> 2][0], rv.w[G >> 2][1], rv.w[G >> 2][2], G & 3, sel_a, sel_b);
+    lookup4(sel_a, va.u[0], va.u[1]);
+    lookup4(sel_b, va.u[2], va.u[3]);
+}
+
+__device__ __forceinline__ float max16(const float16v& a) {
     float m = fmaxf(fmaxf(a[0], a[1]), a[2]);
-    m = fmaxf(fmaxf(m, a[3]), b[0]);
-    m = fmaxf(fmaxf(m, b[1]), b[2]);
-    return fmaxf(m, b[3]);
+#pragma unroll
+    for (int i = 3; i < 15; i += 2) m = fmaxf(fmaxf(m, a[i]), a[i + 1]);
+    return fmaxf(m, a[15]);
+}
+
+// Four scores of a row -> fp16 probabilities (packed pairs) and their sum into the denominator.
+__device__ __forceinline__ void exp4(const float16v& S, int c, float qscale, float mneg, H8 (&pb)[2], float& lsum) {
+    const half2v one2 = {(_Float16)1.0f, (_Float16)1.0f};
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+        const int i = 4 * c + 2 * pr;
+        half2v p2;
+        p2[0] = (_Float16)__builtin_amdgcn_exp2f(fmaf(S[i], qscale, mneg));
+        p2[1] = (_Float16)__builtin_amdgcn_exp2f(fmaf(S[i + 1], qscale, mneg));
+        pb[i >> 3].p[(i & 7) >> 1] = p2;
+        lsum = __builtin_amdgcn_fdot2(p2, one2, lsum, false);
+    }
 }
 
 // The pool's last tile when it crosses the end of the pool, read straight from memory: scores, softmax
 // and PV one after the other, tokens >= T masked out.  Runs at most once per KV head.
-template <int D, int NRT>
+template <int D, int NT>
 __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile, int T, float qscale, float raise_thr,
-                                                 int lane, const half8 (&qb)[NRT][D / 32], float4v (&O)[D / 16][NRT],
-                                                 float4v (&Lacc)[NRT], float (&m_ref)[NRT], float (&m_thr)[NRT],
-                                                 float (&mneg)[NRT]) {
-    using LY = Layout<D>;
-    constexpr int NB = D / 32, NG = D / 16, NTR = D / 64;
-    const int grp = lane >> 4, n = lane & 15;
-    H8 ones;
+                                                 int lane, const half8 (&qb)[NT][D / 32][2], float16v (&O)[D / 32][NT],
+                                                 float (&Lsum)[NT], float (&m_ref)[NT], float (&m_thr)[NT],
+                                                 float (&mneg)[NT]) {
+    constexpr int NB = D / 32, NG = D / 16;
+    const int h = lane >> 5;
+    RawK<D> rk;
+    RawV<D> rv;
+    load_rawk<D>(rk, lt, lane);
+    load_rawv<D>(rv, lt, lane);
+    float16v S[NT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) ones.u[i] = 0x3C003C00u;
-    float4v S[NRT][2];
+    for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-    for (int nt = 0; nt < NRT; ++nt) S[nt][0] = S[nt][1] = float4v{0, 0, 0, 0};
+        for (int i = 0; i < 16; ++i) S[nt][i] = 0.0f;
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
+    for (int j = 0; j < NB; ++j)
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            const _Float16 sj = *reinterpret_cast<const _Float16*>(lt + LY::kscales_off + ((16 * mt + n) * NB + j) * 2);
-            const uint2 kw = *reinterpret_cast<const uint2*>(lt + j * 1024 + lane * 16 + 8 * mt);
-            H8 a;
-            codes4_to_half(kw.x, a.u[0], a.u[1]);
-            codes4_to_half(kw.y, a.u[2], a.u[3]);
-            a.h = a.h - (_Float16)1152.0f;
-            const half8 sv = (half8)(sj);
-            const half8 hi = a.h * sv;
-            const half8 lo = __builtin_elementwise_fma(a.h, sv, -hi);
+        for (int s = 0; s < 2; ++s) {
+            half8 hi, lo;
+            key_split<D>(rk, j, s, hi, lo);
 #pragma unroll
-            for (int nt = 0; nt < NRT; ++nt) {
-                S[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hi, qb[nt][j], S[nt][mt], 0, 0, 0);
-                S[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(lo, qb[nt][j], S[nt][mt], 0, 0, 0);
+            for (int nt = 0; nt < NT; ++nt) {
+                S[nt] = mfma32(hi, qb[nt][j][s], S[nt]);
+                S[nt] = mfma32(lo, qb[nt][j][s], S[nt]);
             }
         }
-    }
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int i = 0; i < 16; ++i)
+        if (tile * kTile + 8 * (i >> 2) + 4 * h + (i & 3) >= T) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (tile * kTile + 16 * mt + 4 * grp + i >= T) {
+            for (int nt = 0; nt < NT; ++nt) S[nt][i] = -INFINITY;
+        }
+    H8 pb[NT][2];
 #pragma unroll
-                for (int nt = 0; nt < NRT; ++nt) S[nt][mt][i] = -INFINITY;
-            }
-    H8 pb[NRT];
-#pragma unroll
-    for (int nt = 0; nt < NRT; ++nt) {
+    for (int nt = 0; nt < NT; ++nt) {
         // this path always re-references: cheap here, and it needs no vote
-        const float m_new = fmaxf(m_ref[nt], xor32_max(xor16_max(max8(S[nt][0], S[nt][1]))));
+        const float m_new = fmaxf(m_ref[nt], xor32_max(max16(S[nt])));
         const float alpha = __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
         m_ref[nt] = m_new;
         m_thr[nt] = m_new + raise_thr;
         mneg[nt] = -m_new * qscale;
-        Lacc[nt] *= alpha;
+        Lsum[nt] *= alpha;
 #pragma unroll
-        for (int g = 0; g < NG; ++g) O[g][nt] *= alpha;
+        for (int g = 0; g < D / 32; ++g) O[g][nt] *= alpha;
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                pb[nt].h[4 * mt + i] = (_Float16)__builtin_amdgcn_exp2f(fmaf(S[nt][mt][i], qscale, mneg[nt]));
+        for (int c = 0; c < 4; ++c) exp4(S[nt], c, qscale, mneg[nt], pb[nt], Lsum[nt]);
     }
 #pragma unroll
-    for (int q = 0; q < NTR; ++q) {
-        const uint32_t* vw = reinterpret_cast<const uint32_t*>(lt + LY::vcodes_off + q * 768 + lane * 12);
-        const uint32_t w0 = vw[0], w1 = vw[1], w2 = vw[2];
+    for (int G = 0; G < NG; ++G) {
+        H8 va;
+        value_group<D>(rv, G, va);
 #pragma unroll
-        for (int gi = 0; gi < 4; ++gi) {
-            uint32_t sel_a, sel_b;
-            if (gi < 3) {
-                const uint32_t w = gi == 0 ? w0 : gi == 1 ? w1 : w2;
-                sel_a = w & 0x07070707u;
-                sel_b = (w >> 3) & 0x07070707u;
-            } else {
-                sel_a = ((w0 >> 6) & 0x03030303u) | ((w1 >> 4) & 0x04040404u);
-                sel_b = ((w2 >> 6) & 0x03030303u) | ((w1 >> 5) & 0x04040404u);
-            }
-            H8 va;
-            lookup4(sel_a, va.u[0], va.u[1]);
-            lookup4(sel_b, va.u[2], va.u[3]);
-#pragma unroll
-            for (int nt = 0; nt < NRT; ++nt)
-                O[4 * q + gi][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, pb[nt].h, O[4 * q + gi][nt], 0, 0, 0);
-        }
+        for (int nt = 0; nt < NT; ++nt) O[G >> 1][nt] = mfma32(va.h, pb[nt][G & 1].h, O[G >> 1][nt]);
     }
-#pragma unroll
-    for (int nt = 0; nt < NRT; ++nt)
-        Lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones.h, pb[nt].h, Lacc[nt], 0, 0, 0);
 }
 
 // One software-pipelined step.  While the matrix cores compute the scores of tile B (the next tile),
@@ -197,41 +208,34 @@ __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile,
 //   Sa         scores of tile A on entry, of tile B on exit; mloc / raise: per-lane row maxima of the
 //              same tile and whether some row outgrew the reference
 // Only full tiles go through here; a ragged last tile is handled by process_ragged_tile.
-template <int D, int NRT, bool HAS_A, bool HAS_B>
+template <int D, int NT, bool HAS_A, bool HAS_B>
 __device__ __forceinline__ void pipeline_step(const RawV<D>& rv, const RawK<D>& rk, RawV<D>& rvN, RawK<D>& rkN,
                                               const uint8_t* nextK, const uint8_t* nextV, float qscale,
-                                              float raise_thr, int lane, const half8 (&qb)[NRT][D / 32],
-                                              float4v (&O)[D / 16][NRT], float4v (&Lacc)[NRT], float (&m_ref)[NRT],
-                                              float (&m_thr)[NRT], float (&mneg)[NRT], float4v (&Sa)[NRT][2],
-                                              float (&mloc)[NRT], bool& raise) {
-    using LY = Layout<D>;
-    constexpr int NB = D / 32, NG = D / 16, NTR = D / 64;
-    const int n = lane & 15;
+                                              float raise_thr, int lane, const half8 (&qb)[NT][D / 32][2],
+                                              float16v (&O)[D / 32][NT], float (&Lsum)[NT], float (&m_ref)[NT],
+                                              float (&m_thr)[NT], float (&mneg)[NT], float16v (&Sa)[NT],
+                                              float (&mloc)[NT], bool& raise) {
+    constexpr int NB = D / 32, NG = D / 16, MG = D / 32;
     const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-    H8 ones;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) ones.u[i] = 0x3C003C00u;
-    float4v Sb[NRT][2];
+    float16v Sb[NT];
 
     if (HAS_A && __builtin_expect(__any(raise), 0)) {
         // Rare: a row of tile A outgrew the softmax reference by more than 2^8.  The accumulators live
         // in accumulation registers that vector instructions cannot read; an MFMA with zero operands
         // (D = 0*0 + C) carries them to vector registers and back, so the hot path never copies them.
 #pragma unroll
-        for (int nt = 0; nt < NRT; ++nt) {
-            const float m_new = fmaxf(m_ref[nt], xor32_max(xor16_max(mloc[nt])));
+        for (int nt = 0; nt < NT; ++nt) {
+            const float m_new = fmaxf(m_ref[nt], xor32_max(mloc[nt]));
             const float alpha = __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
             m_ref[nt] = m_new;
             m_thr[nt] = m_new + raise_thr;
             mneg[nt] = -m_new * qscale;
-            float4v x = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, Lacc[nt], 0, 0, 0);
-            x *= alpha;
-            Lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, x, 0, 0, 0);
+            Lsum[nt] *= alpha;
 #pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                float4v y = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, O[g][nt], 0, 0, 0);
+            for (int g = 0; g < MG; ++g) {
+                float16v y = mfma32(zero8, zero8, O[g][nt]);
                 y *= alpha;
-                O[g][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(zero8, zero8, y, 0, 0, 0);
+                O[g][nt] = mfma32(zero8, zero8, y);
             }
         }
     }
@@ -240,8 +244,8 @@ __device__ __forceinline__ void pipeline_step(const RawV<D>& rv, const RawK<D>& 
     // are ready with the vector work that prepares the operands of the NEXT batch, and is closed by a
     // scheduling barrier so that the compiler keeps the pairing; inside a slice the two streams are
     // interleaved one MFMA to a few vector instructions.
-    constexpr int NQK = 2 * NB;     // key blocks of tile B: (mt, j)
-    constexpr int NCH = 2 * NRT;    // probability chunks of tile A: 4 scores each
+    constexpr int NQK = 2 * NB;   // half blocks of tile B: (j, s)
+    constexpr int NCH = 4 * NT;   // probability chunks of tile A: 4 scores each
     auto slice_end = [](auto mfmas, auto valus) {
         constexpr int M = decltype(mfmas)::value, V = decltype(valus)::value;
         constexpr int per = M > 0 ? (V + M - 1) / M : 0;
@@ -260,67 +264,34 @@ __device__ __forceinline__ void pipeline_step(const RawV<D>& rv, const RawK<D>& 
     load_rawv<D>(rvN, nextV, lane);
     __builtin_amdgcn_sched_barrier(0);
 
-    H8 pb[NRT];
+    H8 pb[NT][2];      // probabilities of tile A: B operands of the P.V products, [row tile][k slice]
     half8 khi[2], klo[2];
     H8 va[2];
-    auto exp_chunk = [&](int c) {  // probabilities of tile A: 4 of them, fp16, B operand of the PV products
-        const int nt = c >> 1, mt = c & 1;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            pb[nt].h[4 * mt + i] = (_Float16)__builtin_amdgcn_exp2f(fmaf(Sa[nt][mt][i], qscale, mneg[nt]));
-    };
-    auto kdeq = [&](int k) {  // key block k of tile B: code * scale split exactly into hi + lo fp16 terms
-        const int mt = k / NB, j = k % NB;
-        H8 a;
-        codes4_to_half(rk.k[mt][j].x, a.u[0], a.u[1]);
-        codes4_to_half(rk.k[mt][j].y, a.u[2], a.u[3]);
-        a.h = a.h - (_Float16)1152.0f;
-        union {
-            uint32_t u;
-            _Float16 h[2];
-        } s2;
-        s2.u = rk.sc[mt][j >> 1];
-        const half8 sv = (half8)(s2.h[j & 1]);
-        khi[k & 1] = a.h * sv;
-        klo[k & 1] = __builtin_elementwise_fma(a.h, sv, -khi[k & 1]);  // exact remainder of the product
-    };
+    auto exp_chunk = [&](int c) { exp4(Sa[c >> 2], c & 3, qscale, mneg[c >> 2], pb[c >> 2], Lsum[c >> 2]); };
+    auto kdeq = [&](int k) { key_split<D>(rk, k >> 1, k & 1, khi[k & 1], klo[k & 1]); };
     auto qk = [&](int k) {
-        const int mt = k / NB, j = k % NB;
+        const int j = k >> 1, s = k & 1;
 #pragma unroll
-        for (int nt = 0; nt < NRT; ++nt)
-            Sb[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(khi[k & 1], qb[nt][j], Sb[nt][mt], 0, 0, 0);
+        for (int nt = 0; nt < NT; ++nt) Sb[nt] = mfma32(khi[k & 1], qb[nt][j][s], Sb[nt]);
 #pragma unroll
-        for (int nt = 0; nt < NRT; ++nt)
-            Sb[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(klo[k & 1], qb[nt][j], Sb[nt][mt], 0, 0, 0);
+        for (int nt = 0; nt < NT; ++nt) Sb[nt] = mfma32(klo[k & 1], qb[nt][j][s], Sb[nt]);
     };
-    auto vdeq = [&](int g) {  // value group g of tile A: eight 3-bit codes -> fp16 centroids (A operand)
-        const int q = g >> 2, gi = g & 3;
-        const uint32_t w0 = rv.w[q][0], w1 = rv.w[q][1], w2 = rv.w[q][2];
-        uint32_t sel_a, sel_b;
-        if (gi < 3) {
-            const uint32_t w = gi == 0 ? w0 : gi == 1 ? w1 : w2;
-            sel_a = w & 0x07070707u;
-            sel_b = (w >> 3) & 0x07070707u;
-        } else {
-            sel_a = ((w0 >> 6) & 0x03030303u) | ((w1 >> 4) & 0x04040404u);
-            sel_b = ((w2 >> 6) & 0x03030303u) | ((w1 >> 5) & 0x04040404u);
-        }
-        lookup4(sel_a, va[g & 1].u[0], va[g & 1].u[1]);
-        lookup4(sel_b, va[g & 1].u[2], va[g & 1].u[3]);
-    };
-    auto pv = [&](int g) {
+    auto vdeq = [&](int G) { value_group<D>(rv, G, va[G & 1]); };
+    auto pv = [&](int G) {
 #pragma unroll
-        for (int nt = 0; nt < NRT; ++nt)
-            O[g][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[g & 1].h, pb[nt].h, O[g][nt], 0, 0, 0);
+        for (int nt = 0; nt < NT; ++nt) O[G >> 1][nt] = mfma32(va[G & 1].h, pb[nt][G & 1].h, O[G >> 1][nt]);
     };
 
     if (HAS_B) {
 #pragma unroll
-        for (int nt = 0; nt < NRT; ++nt) Sb[nt][0] = Sb[nt][1] = float4v{0, 0, 0, 0};
-        // lead-in: vector work only, while the LDS reads land
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) Sb[nt][i] = 0.0f;
+        // lead-in: vector work only
+        constexpr int lead = NCH / NQK > 0 ? NCH / NQK : 1;
         if (HAS_A) {
 #pragma unroll
-            for (int c = 0; c < NCH / NQK; ++c) exp_chunk(c);
+            for (int c = 0; c < lead; ++c) exp_chunk(c);
         }
         kdeq(0);
         __builtin_amdgcn_sched_barrier(0);
@@ -330,12 +301,12 @@ __device__ __forceinline__ void pipeline_step(const RawV<D>& rv, const RawK<D>& 
             if (k + 1 < NQK) kdeq(k + 1);
             if (HAS_A) {
                 // spread the remaining probability chunks over the score slices
-                const int c0 = NCH / NQK + (k * (NCH - NCH / NQK)) / NQK, c1 = NCH / NQK + ((k + 1) * (NCH - NCH / NQK)) / NQK;
+                const int c0 = lead + (k * (NCH - lead)) / NQK, c1 = lead + ((k + 1) * (NCH - lead)) / NQK;
 #pragma unroll
                 for (int c = c0; c < c1; ++c) exp_chunk(c);
                 if (k + 1 == NQK) vdeq(0);
             }
-            slice_end(integral_constant<int, 2 * NRT>{}, integral_constant<int, (HAS_A ? 28 : 16)>{});
+            slice_end(integral_constant<int, 2 * NT>{}, integral_constant<int, (HAS_A ? 30 : 16)>{});
         }
     } else if (HAS_A) {
 #pragma unroll
@@ -346,39 +317,32 @@ __device__ __forceinline__ void pipeline_step(const RawV<D>& rv, const RawK<D>& 
 
     if (HAS_A) {
 #pragma unroll
-        for (int g = 0; g < NG; ++g) {
-            pv(g);
-            if (g + 1 < NG) vdeq(g + 1);
-            slice_end(integral_constant<int, NRT>{}, integral_constant<int, 16>{});
+        for (int G = 0; G < NG; ++G) {
+            pv(G);
+            if (G + 1 < NG) vdeq(G + 1);
+            slice_end(integral_constant<int, NT>{}, integral_constant<int, 12>{});
         }
-#pragma unroll
-        for (int nt = 0; nt < NRT; ++nt)
-            Lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones.h, pb[nt].h, Lacc[nt], 0, 0, 0);
     }
 
     // ---- row maxima of tile B for the next step's vote (no cross-lane reduction needed for the vote)
     if (HAS_B) {
         raise = false;
 #pragma unroll
-        for (int nt = 0; nt < NRT; ++nt) {
-            // the scores are consumed by vector instructions only: have the MFMAs deliver them there
-            asm volatile("" : "+v"(Sb[nt][0]), "+v"(Sb[nt][1]));
-            mloc[nt] = max8(Sb[nt][0], Sb[nt][1]);
+        for (int nt = 0; nt < NT; ++nt) {
+            mloc[nt] = max16(Sb[nt]);
             raise |= mloc[nt] > m_thr[nt];  // also true while the reference is -inf
-            Sa[nt][0] = Sb[nt][0];
-            Sa[nt][1] = Sb[nt][1];
+            Sa[nt] = Sb[nt];
         }
     }
-    if (HAS_A) slice_end(integral_constant<int, NRT>{}, integral_constant<int, 24>{});
 }
 
-template <int D, int NRT>
+template <int D, int NT>
 __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restrict__ pool,
                                                           const __half* __restrict__ Q,
                                                           float* __restrict__ ws_ml, float* __restrict__ ws_o,
                                                           float* __restrict__ out, AttendPlan p, int direct) {
     using LY = Layout<D>;
-    constexpr int NB = D / 32, NG = D / 16, ROWS = 16 * NRT;
+    constexpr int NB = D / 32, MG = D / 32, ROWS = 32 * NT;
     constexpr int OSTRIDE = D + 4;
     constexpr int TB = LY::tile_bytes;
     __shared__ float m_s[4][ROWS];
@@ -386,8 +350,8 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     extern __shared__ __align__(16) float o_s[];  // two merge buffers of ROWS x OSTRIDE floats
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: LDS bases go through M0
-    const int grp = lane >> 4, n = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform
+    const int h = lane >> 5, n = lane & 31;
     const int usel = blockIdx.y, ls = usel / p.H, kvh = usel - ls * p.H;
     const int row0 = blockIdx.z * ROWS;
     const int split = blockIdx.x;
@@ -409,39 +373,44 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         load_rawv<D>(rv, tile_ptr(0), lane);
     }
 
-    // ---- query rows as MFMA B operands: lane (n, grp) holds q[row 16nt+n][32j + 8grp .. +7]
-    half8 qb[NRT][NB];
+    // ---- query rows as MFMA B operands: lane (n, h) holds q[row 32nt+n][32j + 16s + 8h .. +7]
+    half8 qb[NT][NB][2];
 #pragma unroll
-    for (int nt = 0; nt < NRT; ++nt) {
-        const int r = row0 + 16 * nt + n;
+    for (int nt = 0; nt < NT; ++nt) {
+        const int r = row0 + 32 * nt + n;
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            H8 t;
-            uint4v raw = {0, 0, 0, 0};
-            if (r < p.R) raw = *reinterpret_cast<const uint4v*>(Q + q_row_index(p, ls, kvh, r) * D + 32 * j + 8 * grp);
-            t.u[0] = raw.x; t.u[1] = raw.y; t.u[2] = raw.z; t.u[3] = raw.w;
-            qb[nt][j] = t.h;
-            // The queries are only ever MFMA operands: park them in accumulation registers so that the
-            // vector registers are left for the scores and the dequantization temporaries.
-            asm volatile("" : "+a"(qb[nt][j]));
-        }
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                H8 t;
+                uint4v raw = {0, 0, 0, 0};
+                if (r < p.R)
+                    raw = *reinterpret_cast<const uint4v*>(Q + q_row_index(p, ls, kvh, r) * D + 32 * j + 16 * s + 8 * h);
+                t.u[0] = raw.x; t.u[1] = raw.y; t.u[2] = raw.z; t.u[3] = raw.w;
+                qb[nt][j][s] = t.h;
+                // The queries are only ever MFMA operands: park them in accumulation registers so that
+                // the vector registers are left for the scores and the dequantization temporaries.
+                asm volatile("" : "+a"(qb[nt][j][s]));
+            }
     }
 
-    float4v O[NG][NRT], Lacc[NRT];
-    float m_ref[NRT], m_thr[NRT], mneg[NRT], mloc[NRT];
+    float16v O[MG][NT];
+    float Lsum[NT], m_ref[NT], m_thr[NT], mneg[NT], mloc[NT];
 #pragma unroll
-    for (int nt = 0; nt < NRT; ++nt) {
+    for (int nt = 0; nt < NT; ++nt) {
         m_ref[nt] = -INFINITY;
         m_thr[nt] = -INFINITY;
         mneg[nt] = 0.0f;
         mloc[nt] = -INFINITY;
-        Lacc[nt] = float4v{0, 0, 0, 0};
+        Lsum[nt] = 0.0f;
 #pragma unroll
-        for (int g = 0; g < NG; ++g) O[g][nt] = float4v{0, 0, 0, 0};
+        for (int g = 0; g < MG; ++g)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[g][nt][i] = 0.0f;
     }
     const float raise_thr = 8.0f / qscale;  // raise the reference only when a row exceeds it by 2^8
     bool raise = false;
-    float4v S[NRT][2];  // scores of the tile whose softmax comes next
+    float16v S[NT];  // scores of the tile whose softmax comes next
 
     // Local tile k is "B" in step k-1 (scores) and "A" in step k (softmax, PV).  Only the pool's very
     // last tile can be ragged; it stays out of the pipeline and goes last.
@@ -452,35 +421,35 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         RawK<D> rk2;
         RawV<D> rv2;
         // prologue: scores of tile 0 from rk; requests K of tile 1 and (again) V of tile 0 into set 2
-        pipeline_step<D, NRT, false, true>(rv, rk, rv2, rk2, tile_ptr(1), tile_ptr(0), qscale, raise_thr, lane, qb, O, Lacc,
-                                           m_ref, m_thr, mneg, S, mloc, raise);
+        pipeline_step<D, NT, false, true>(rv, rk, rv2, rk2, tile_ptr(1), tile_ptr(0), qscale, raise_thr, lane, qb, O, Lsum,
+                                          m_ref, m_thr, mneg, S, mloc, raise);
         int s = 0;
         for (; s + 1 < full_count - 1; s += 2) {  // two steps per trip: the sets swap roles without copies
-            pipeline_step<D, NRT, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
-                                              O, Lacc, m_ref, m_thr, mneg, S, mloc, raise);
-            pipeline_step<D, NRT, true, true>(rv, rk, rv2, rk2, tile_ptr(s + 3), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
-                                              O, Lacc, m_ref, m_thr, mneg, S, mloc, raise);
+            pipeline_step<D, NT, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+                                             O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
+            pipeline_step<D, NT, true, true>(rv, rk, rv2, rk2, tile_ptr(s + 3), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
+                                             O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         }
         if (s < full_count - 1) {  // one step with a B tile left: current = set 2
-            pipeline_step<D, NRT, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
-                                              O, Lacc, m_ref, m_thr, mneg, S, mloc, raise);
-            pipeline_step<D, NRT, true, false>(rv, rk, rv2, rk2, tile_ptr(s + 2), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
-                                               O, Lacc, m_ref, m_thr, mneg, S, mloc, raise);
+            pipeline_step<D, NT, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+                                             O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
+            pipeline_step<D, NT, true, false>(rv, rk, rv2, rk2, tile_ptr(s + 2), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
+                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         } else {
-            pipeline_step<D, NRT, true, false>(rv2, rk2, rv, rk, tile_ptr(s + 1), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
-                                               O, Lacc, m_ref, m_thr, mneg, S, mloc, raise);
+            pipeline_step<D, NT, true, false>(rv2, rk2, rv, rk, tile_ptr(s + 1), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         }
     }
     if (last_ragged)
-        process_ragged_tile<D, NRT>(tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
-                                    Lacc, m_ref, m_thr, mneg);
+        process_ragged_tile<D, NT>(tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
+                                   Lsum, m_ref, m_thr, mneg);
 
     // ---- merge the four waves through LDS: waves 0 and 2 store their (rescaled) accumulators into
     // two buffers, waves 1 and 3 add theirs on top, the final pass sums the two buffers.  The order of
     // the additions is fixed, so the result is reproducible.
-    if (grp == 0) {
+    if (h == 0) {
 #pragma unroll
-        for (int nt = 0; nt < NRT; ++nt) m_s[wave][16 * nt + n] = m_ref[nt];
+        for (int nt = 0; nt < NT; ++nt) m_s[wave][32 * nt + n] = m_ref[nt];
     }
     __syncthreads();
     float* obuf = o_s + (wave >> 1) * (ROWS * OSTRIDE);
@@ -488,61 +457,100 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     for (int round = 0; round < 2; ++round) {
         if ((wave & 1) == round) {
 #pragma unroll
-            for (int nt = 0; nt < NRT; ++nt) {
-                const int r = 16 * nt + n;
+            for (int nt = 0; nt < NT; ++nt) {
+                const int r = 32 * nt + n;
                 const float M = fmaxf(fmaxf(m_s[0][r], m_s[1][r]), fmaxf(m_s[2][r], m_s[3][r]));
                 const float f = m_ref[nt] == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f((m_ref[nt] - M) * qscale);
-                if (grp == 0) lbuf[r] = (round == 0 ? 0.0f : lbuf[r]) + Lacc[nt][0] * f;
+                const float l = xor32_sum(Lsum[nt]);  // the lane pair (n, h) shares a row
+                if (h == 0) lbuf[r] = (round == 0 ? 0.0f : lbuf[r]) + l * f;
 #pragma unroll
-                for (int g = 0; g < NG; ++g) {
-                    float4* dst = reinterpret_cast<float4*>(&obuf[r * OSTRIDE + 16 * g + 4 * grp]);
-                    float4 v = round == 0 ? make_float4(0.0f, 0.0f, 0.0f, 0.0f) : *dst;
-                    v.x = fmaf(O[g][nt][0], f, v.x);
-                    v.y = fmaf(O[g][nt][1], f, v.y);
-                    v.z = fmaf(O[g][nt][2], f, v.z);
-                    v.w = fmaf(O[g][nt][3], f, v.w);
-                    *dst = v;
-                }
+                for (int g = 0; g < MG; ++g)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        // registers 4b..4b+3 hold coordinates 32g + 8b + 4h + 0..3 of row r
+                        float4* dst = reinterpret_cast<float4*>(&obuf[r * OSTRIDE + 32 * g + 8 * b + 4 * h]);
+                        float4 v = round == 0 ? make_float4(0.0f, 0.0f, 0.0f, 0.0f) : *dst;
+                        v.x = fmaf(O[g][nt][4 * b + 0], f, v.x);
+                        v.y = fmaf(O[g][nt][4 * b + 1], f, v.y);
+                        v.z = fmaf(O[g][nt][4 * b + 2], f, v.z);
+                        v.w = fmaf(O[g][nt][4 * b + 3], f, v.w);
+                        *dst = v;
+                    }
             }
         }
         __syncthreads();
     }
 
+    // ---- final pass: every wave finishes ROWS/4 rows, several at a time so that their latency chains
+    // (LDS reads, the lane butterflies, the store) overlap
     constexpr int EPL = D / 64;
-    for (int rr = wave; rr < ROWS; rr += 4) {
-        const int r = row0 + rr;
-        if (r >= p.R) break;  // uniform over the wave
-        const float Mr = fmaxf(fmaxf(m_s[0][rr], m_s[1][rr]), fmaxf(m_s[2][rr], m_s[3][rr]));
-        const float l = l_s[rr] + l_s[ROWS + rr];
-        float x[EPL];
+    constexpr int RPW = ROWS / 4, RB = 4;
+#pragma unroll 1
+    for (int i0 = 0; i0 < RPW; i0 += RB) {
+        float x[RB][EPL], l[RB], Mr[RB];
 #pragma unroll
-        for (int i = 0; i < EPL; ++i)
-            x[i] = (o_s[rr * OSTRIDE + lane * EPL + i] + o_s[(ROWS + rr) * OSTRIDE + lane * EPL + i]) * kInvCentroidScale;
+        for (int u = 0; u < RB; ++u) {
+            const int rr = wave + 4 * (i0 + u);
+            Mr[u] = fmaxf(fmaxf(m_s[0][rr], m_s[1][rr]), fmaxf(m_s[2][rr], m_s[3][rr]));
+            l[u] = l_s[rr] + l_s[ROWS + rr];
+#pragma unroll
+            for (int i = 0; i < EPL; ++i)
+                x[u][i] = (o_s[rr * OSTRIDE + lane * EPL + i] + o_s[(ROWS + rr) * OSTRIDE + lane * EPL + i]) * kInvCentroidScale;
+        }
         if (direct) {
-            const float inv = 1.0f / l;
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) x[i] *= inv;
-            wht_inlane<EPL>(x);
+            for (int u = 0; u < RB; ++u) {
+                const float inv = 1.0f / l[u];
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) {
-                x[i] = wht_lane_stage<1>(x[i], lane);
-                x[i] = wht_lane_stage<2>(x[i], lane);
-                x[i] = wht_lane_stage<4>(x[i], lane);
-                x[i] = wht_lane_stage<8>(x[i], lane);
-                x[i] = wht_lane_stage<16>(x[i], lane);
-                x[i] = wht_lane_stage<32>(x[i], lane);
-                x[i] *= (D == 64 ? 0.125f : 0.08838834764831845f);
+                for (int i = 0; i < EPL; ++i) x[u][i] *= inv;
+                wht_inlane<EPL>(x[u]);
             }
-            float* dst = out + q_row_index(p, ls, kvh, r) * D + lane * EPL;
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) dst[i] = x[i];
+            for (int u = 0; u < RB; ++u)
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) x[u][i] = wht_lane_stage<1>(x[u][i], lane);
+#pragma unroll
+            for (int u = 0; u < RB; ++u)
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) x[u][i] = wht_lane_stage<2>(x[u][i], lane);
+#pragma unroll
+            for (int u = 0; u < RB; ++u)
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) x[u][i] = wht_lane_stage<4>(x[u][i], lane);
+#pragma unroll
+            for (int u = 0; u < RB; ++u)
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) x[u][i] = wht_lane_stage<8>(x[u][i], lane);
+#pragma unroll
+            for (int u = 0; u < RB; ++u)
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) x[u][i] = wht_lane_stage<16>(x[u][i], lane);
+#pragma unroll
+            for (int u = 0; u < RB; ++u)
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) x[u][i] = wht_lane_stage<32>(x[u][i], lane);
+#pragma unroll
+            for (int u = 0; u < RB; ++u) {
+                const int r = row0 + wave + 4 * (i0 + u);
+                if (r < p.R) {
+                    float* dst = out + q_row_index(p, ls, kvh, r) * D + lane * EPL;
+#pragma unroll
+                    for (int i = 0; i < EPL; ++i) dst[i] = x[u][i] * (D == 64 ? 0.125f : 0.08838834764831845f);
+                }
+            }
         } else {
-            const size_t prow = ((size_t)usel * p.nsplit + split) * p.R + r;
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) ws_o[prow * D + lane * EPL + i] = x[i];
-            if (lane == 0) {
-                ws_ml[prow * 2] = Mr * qscale;
-                ws_ml[prow * 2 + 1] = l;
+            for (int u = 0; u < RB; ++u) {
+                const int r = row0 + wave + 4 * (i0 + u);
+                if (r < p.R) {
+                    const size_t prow = ((size_t)usel * p.nsplit + split) * p.R + r;
+#pragma unroll
+                    for (int i = 0; i < EPL; ++i) ws_o[prow * D + lane * EPL + i] = x[u][i];
+                    if (lane == 0) {
+                        ws_ml[prow * 2] = Mr[u] * qscale;
+                        ws_ml[prow * 2 + 1] = l[u];
+                    }
+                }
             }
         }
     }
@@ -554,11 +562,11 @@ bool matrix_kernel_supports(int head_dim, int rows_per_kv_head) {
 
 bool matrix_kernel_direct(const AttendPlan& plan) { return plan.nsplit == 1 && !plan.has_tails; }
 
-template <int D, int NRT>
+template <int D, int NT>
 static hipError_t launch_one(dim3 grid, const uint8_t* storage, const AttendPlan& plan, const void* Q, float* ws_ml,
                              float* ws_o, float* out, int direct, hipStream_t s) {
-    constexpr int kMergeBytes = 2 * 16 * NRT * (D + 4) * (int)sizeof(float);
-    auto kern = attend_mfma_kernel<D, NRT>;
+    constexpr int kMergeBytes = 2 * 32 * NT * (D + 4) * (int)sizeof(float);
+    auto kern = attend_mfma_kernel<D, NT>;
     static bool configured = false;  // per instantiation: the limit is a property of the function
     if (!configured && kMergeBytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -576,9 +584,8 @@ static hipError_t launch_d(const polykv_pool* pool, const AttendPlan& plan, cons
     const uint8_t* storage = reinterpret_cast<const uint8_t*>(pool->storage);
     const int units = plan.layers * plan.H;
     const int direct = matrix_kernel_direct(plan) ? 1 : 0;
-    if (plan.R <= 16) return launch_one<D, 1>(dim3(plan.nsplit, units, 1), storage, plan, Q, ws_ml, ws_o, out, direct, s);
-    if (plan.R <= 32) return launch_one<D, 2>(dim3(plan.nsplit, units, 1), storage, plan, Q, ws_ml, ws_o, out, direct, s);
-    return launch_one<D, 4>(dim3(plan.nsplit, units, (plan.R + 63) / 64), storage, plan, Q, ws_ml, ws_o, out, direct, s);
+    if (plan.R <= 32) return launch_one<D, 1>(dim3(plan.nsplit, units, 1), storage, plan, Q, ws_ml, ws_o, out, direct, s);
+    return launch_one<D, 2>(dim3(plan.nsplit, units, (plan.R + 63) / 64), storage, plan, Q, ws_ml, ws_o, out, direct, s);
 }
 
 hipError_t launch_attend_matrix(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,

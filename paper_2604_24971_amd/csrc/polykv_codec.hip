@@ -154,13 +154,14 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
     uint8_t* rec = pool + ((size_t)unit * tiles + tile) * LY::tile_bytes;
     // ---- bit-pack the value codes: one lane triplet (three dwords, four coordinate groups) per thread
     if (tid < LY::NT * 64) {
-        const int q = tid >> 6, grp = lane >> 4, m = lane & 15;
-        uint32_t lo[4], hi[4];  // codes of tokens 4grp..4grp+3 and 16+4grp..16+4grp+3, one per byte
+        const int q = tid >> 6;
+        uint32_t lo[4], hi[4];  // codes e = 0..3 and e = 4..7 of each group, one per byte (consecutive tokens)
 #pragma unroll
         for (int gi = 0; gi < 4; ++gi) {
-            const uint8_t* src = vstage + (16 * (4 * q + gi) + m) * VS + 4 * grp;
+            const int G = 4 * q + gi;
+            const uint8_t* src = vstage + vcode_coord(G, lane) * VS + vcode_token(G, lane, 0);
             lo[gi] = *reinterpret_cast<const uint32_t*>(src);
-            hi[gi] = *reinterpret_cast<const uint32_t*>(src + 16);
+            hi[gi] = *reinterpret_cast<const uint32_t*>(src + 8);
         }
         uint32_t w0 = lo[0] | (hi[0] << 3), w1 = lo[1] | (hi[1] << 3), w2 = lo[2] | (hi[2] << 3);
         w0 |= (lo[3] & 0x03030303u) << 6;
@@ -240,7 +241,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
     if (V_out != nullptr && tid < LY::NT * 128) {
         // thread (half, q, lane): two of the four coordinate groups of one lane triplet
         const int half = tid / (LY::NT * 64), ql = tid - half * (LY::NT * 64);
-        const int q = ql >> 6, grp = lane >> 4, m = lane & 15;
+        const int q = ql >> 6;
         const uint32_t* w = reinterpret_cast<const uint32_t*>(rec + LY::vcodes_off + q * 768 + lane * 12);
         const uint32_t w0 = w[0], w1 = w[1], w2 = w[2];
 #pragma unroll
@@ -253,15 +254,16 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
             Half2Bits c01, c23, c45, c67;
             lookup4(sel_a, c01.u, c23.u);
             lookup4(sel_b, c45.u, c67.u);
-            _Float16* col = cent + 16 * (4 * q + 2 * half + gg) + m;
-            col[(4 * grp + 0) * CS] = c01.h[0];
-            col[(4 * grp + 1) * CS] = c01.h[1];
-            col[(4 * grp + 2) * CS] = c23.h[0];
-            col[(4 * grp + 3) * CS] = c23.h[1];
-            col[(16 + 4 * grp + 0) * CS] = c45.h[0];
-            col[(16 + 4 * grp + 1) * CS] = c45.h[1];
-            col[(16 + 4 * grp + 2) * CS] = c67.h[0];
-            col[(16 + 4 * grp + 3) * CS] = c67.h[1];
+            const int G = 4 * q + 2 * half + gg;
+            _Float16* col = cent + vcode_token(G, lane, 0) * CS + vcode_coord(G, lane);  // codes e: rows +0..3, +8..11
+            col[0 * CS] = c01.h[0];
+            col[1 * CS] = c01.h[1];
+            col[2 * CS] = c23.h[0];
+            col[3 * CS] = c23.h[1];
+            col[8 * CS] = c45.h[0];
+            col[9 * CS] = c45.h[1];
+            col[10 * CS] = c67.h[0];
+            col[11 * CS] = c67.h[1];
         }
     }
     __syncthreads();

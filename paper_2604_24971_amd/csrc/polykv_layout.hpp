@@ -2,19 +2,20 @@
 //
 // The pool is an array of tile records, [layer*kv_head][tile], one tile = 32 consecutive tokens of
 // one KV head (the last tile is zero-padded).  A record is laid out for the matrix-core attention
-// kernel (v_mfma_f32_16x16x32_f16) so that every wave load is one contiguous, fully coalesced run and
-// lands in registers in MFMA operand order.  "lane" below is a wave lane 0..63 = 16*grp + m.
+// kernel (v_mfma_f32_32x32x16_f16) so that every wave load is one contiguous, fully coalesced run and
+// lands in registers in MFMA operand order.  "lane" below is a wave lane 0..63 = 32*h + m.
 //
-//   K codes   NB x 1024 B    NB = head_dim/32 q8_0 blocks.  Byte j*1024 + lane*16 + mt*8 + e holds
-//                            code(token 16*mt + m, element 32j + 8*grp + e) + 128 (offset binary),
-//                            j < NB, mt < 2, e < 8: the lane's 16 bytes of block j are the A operands
-//                            (8 k-values each) of the two 16-token MFMA tiles.
+//   K codes   NB x 1024 B    NB = head_dim/32 q8_0 blocks.  Byte j*1024 + lane*16 + 8*s + e holds
+//                            code(token m, element 32j + 16s + 8h + e) + 128 (offset binary),
+//                            j < NB, s < 2, e < 8: the lane's 16 bytes of block j are the A operands
+//                            (8 k-values each) of the block's two K=16 MFMA slices, M = token.
 //   K scales  32 x NB fp16   scale(token t, block j) at index t*NB + j.
 //   V codes   NT x 768 B     NT = head_dim/64 triplets.  Triplet q, lane: three dwords at byte
 //                            q*768 + lane*12.  They carry four groups of eight 3-bit codes, group
-//                            g = 4q + {0,1,2,3}; group g belongs to rotated coordinate 16*g + m and its
-//                            code e (0..7) to token 16*(e/4) + 4*grp + e%4 (the k-order in which the
-//                            score tile leaves the MFMA accumulators).
+//                            G = 4q + {0,1,2,3}; group G belongs to rotated coordinate 32*(G/2) + m and
+//                            its code e (0..7) to token 16*(G%2) + 8*(e/4) + 4*h + e%4: the k-order in
+//                            which a 32x32 score tile leaves the MFMA accumulators, so the
+//                            probabilities feed the P.V products without any data movement.
 //                            Groups 4q+0..2 sit in dword 0..2: code e at bit 8*(e%4) + 3*(e/4).
 //                            Group 4q+3 uses the two spare top bits of every byte:
 //                              code e<4 : bits 1:0 = dword0 bits 8e+7:8e+6, bit 2 = dword1 bit 8e+6
@@ -75,18 +76,21 @@ __device__ __forceinline__ int quantize3(float x) {
 // Byte offset (inside the K-code region of a tile) of the 8-byte run holding elements
 // 32j + 8*g8 .. +7 of token t (g8 = 0..3).
 __device__ __forceinline__ int kcode_run_offset(int t, int j, int g8) {
-    return j * 1024 + (g8 * 16 + (t & 15)) * 16 + (t >> 4) * 8;
+    return j * 1024 + (32 * (g8 & 1) + t) * 16 + (g8 >> 1) * 8;
 }
 
-// Token (within the tile) of code e of a value-code group held by lane group grp.
-__device__ __forceinline__ int vcode_token(int grp, int e) { return 16 * (e >> 2) + 4 * grp + (e & 3); }
+// Value-code group G of a lane: its rotated coordinate, and the token (within the tile) of its code e.
+__device__ __forceinline__ int vcode_coord(int G, int lane) { return 32 * (G >> 1) + (lane & 31); }
+__device__ __forceinline__ int vcode_token(int G, int lane, int e) {
+    return 16 * (G & 1) + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+}
 
 // Extract the 3-bit value code of (token t of the tile, rotated coordinate dv) from the V-code
 // region `v` (dword view) of a tile.
 __device__ __forceinline__ int vcode_extract(const uint32_t* v, int t, int dv) {
-    const int m = dv & 15, g = dv >> 4, q = g >> 2, gi = g & 3;
-    const int e = ((t >> 4) << 2) | (t & 3), grp = (t >> 2) & 3;
-    const uint32_t* w = v + q * 192 + (grp * 16 + m) * 3;
+    const int G = 2 * (dv >> 5) + (t >> 4), q = G >> 2, gi = G & 3;
+    const int e = (((t >> 3) & 1) << 2) | (t & 3), lane = 32 * ((t >> 2) & 1) + (dv & 31);
+    const uint32_t* w = v + q * 192 + lane * 3;
     if (gi < 3) return (w[gi] >> (8 * (e & 3) + 3 * (e >> 2))) & 7;
     if (e < 4) return ((w[0] >> (8 * e + 6)) & 3) | (((w[1] >> (8 * e + 6)) & 1) << 2);
     return ((w[2] >> (8 * (e - 4) + 6)) & 3) | (((w[1] >> (8 * (e - 4) + 7)) & 1) << 2);
