@@ -481,76 +481,45 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         __syncthreads();
     }
 
-    // ---- final pass: every wave finishes ROWS/4 rows, several at a time so that their latency chains
-    // (LDS reads, the lane butterflies, the store) overlap
-    constexpr int EPL = D / 64;
-    constexpr int RPW = ROWS / 4, RB = 4;
-#pragma unroll 1
-    for (int i0 = 0; i0 < RPW; i0 += RB) {
-        float x[RB][EPL], l[RB], Mr[RB];
+    // ---- final pass: every wave finishes ROWS/4 rows, four lanes to a row, D/4 consecutive
+    // coordinates to a lane: the rotation is then log2(D/4) in-register stages and two DPP stages.
+    constexpr int CPL = D / 4, RPW = ROWS / 4;
+    const int ri = lane >> 2, qd = lane & 3;
+    if (ri < RPW) {
+        const int rr = wave + 4 * ri, r = row0 + rr;
+        const float Mr = fmaxf(fmaxf(m_s[0][rr], m_s[1][rr]), fmaxf(m_s[2][rr], m_s[3][rr]));
+        const float l = l_s[rr] + l_s[ROWS + rr];
+        // direct: 1/l, the centroid scale, 1/sqrt(D) and the entry sign of the DPP stages in one factor
+        const float f = direct ? quad_entry_sign(lane) * (kInvCentroidScale * (D == 64 ? 0.125f : 0.08838834764831845f)) *
+                                     __builtin_amdgcn_rcpf(l)
+                               : kInvCentroidScale;
+        float x[CPL];
+        const float4* a4 = reinterpret_cast<const float4*>(&o_s[rr * OSTRIDE + qd * CPL]);
+        const float4* b4 = reinterpret_cast<const float4*>(&o_s[(ROWS + rr) * OSTRIDE + qd * CPL]);
 #pragma unroll
-        for (int u = 0; u < RB; ++u) {
-            const int rr = wave + 4 * (i0 + u);
-            Mr[u] = fmaxf(fmaxf(m_s[0][rr], m_s[1][rr]), fmaxf(m_s[2][rr], m_s[3][rr]));
-            l[u] = l_s[rr] + l_s[ROWS + rr];
-#pragma unroll
-            for (int i = 0; i < EPL; ++i)
-                x[u][i] = (o_s[rr * OSTRIDE + lane * EPL + i] + o_s[(ROWS + rr) * OSTRIDE + lane * EPL + i]) * kInvCentroidScale;
+        for (int i = 0; i < CPL / 4; ++i) {
+            const float4 a = a4[i], b = b4[i];
+            x[4 * i + 0] = (a.x + b.x) * f;
+            x[4 * i + 1] = (a.y + b.y) * f;
+            x[4 * i + 2] = (a.z + b.z) * f;
+            x[4 * i + 3] = (a.w + b.w) * f;
         }
         if (direct) {
+            wht_cross_quad<CPL>(x, lane);
+            wht_inlane<CPL>(x);
+            if (r < p.R) {
+                float4* dst = reinterpret_cast<float4*>(out + q_row_index(p, ls, kvh, r) * D + qd * CPL);
 #pragma unroll
-            for (int u = 0; u < RB; ++u) {
-                const float inv = 1.0f / l[u];
-#pragma unroll
-                for (int i = 0; i < EPL; ++i) x[u][i] *= inv;
-                wht_inlane<EPL>(x[u]);
+                for (int i = 0; i < CPL / 4; ++i) dst[i] = make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
             }
+        } else if (r < p.R) {
+            const size_t prow = ((size_t)usel * p.nsplit + split) * p.R + r;
+            float4* dst = reinterpret_cast<float4*>(ws_o + prow * D + qd * CPL);
 #pragma unroll
-            for (int u = 0; u < RB; ++u)
-#pragma unroll
-                for (int i = 0; i < EPL; ++i) x[u][i] = wht_lane_stage<1>(x[u][i], lane);
-#pragma unroll
-            for (int u = 0; u < RB; ++u)
-#pragma unroll
-                for (int i = 0; i < EPL; ++i) x[u][i] = wht_lane_stage<2>(x[u][i], lane);
-#pragma unroll
-            for (int u = 0; u < RB; ++u)
-#pragma unroll
-                for (int i = 0; i < EPL; ++i) x[u][i] = wht_lane_stage<4>(x[u][i], lane);
-#pragma unroll
-            for (int u = 0; u < RB; ++u)
-#pragma unroll
-                for (int i = 0; i < EPL; ++i) x[u][i] = wht_lane_stage<8>(x[u][i], lane);
-#pragma unroll
-            for (int u = 0; u < RB; ++u)
-#pragma unroll
-                for (int i = 0; i < EPL; ++i) x[u][i] = wht_lane_stage<16>(x[u][i], lane);
-#pragma unroll
-            for (int u = 0; u < RB; ++u)
-#pragma unroll
-                for (int i = 0; i < EPL; ++i) x[u][i] = wht_lane_stage<32>(x[u][i], lane);
-#pragma unroll
-            for (int u = 0; u < RB; ++u) {
-                const int r = row0 + wave + 4 * (i0 + u);
-                if (r < p.R) {
-                    float* dst = out + q_row_index(p, ls, kvh, r) * D + lane * EPL;
-#pragma unroll
-                    for (int i = 0; i < EPL; ++i) dst[i] = x[u][i] * (D == 64 ? 0.125f : 0.08838834764831845f);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < RB; ++u) {
-                const int r = row0 + wave + 4 * (i0 + u);
-                if (r < p.R) {
-                    const size_t prow = ((size_t)usel * p.nsplit + split) * p.R + r;
-#pragma unroll
-                    for (int i = 0; i < EPL; ++i) ws_o[prow * D + lane * EPL + i] = x[u][i];
-                    if (lane == 0) {
-                        ws_ml[prow * 2] = Mr[u] * qscale;
-                        ws_ml[prow * 2 + 1] = l[u];
-                    }
-                }
+            for (int i = 0; i < CPL / 4; ++i) dst[i] = make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
+            if (qd == 0) {
+                ws_ml[prow * 2] = Mr * qscale;
+                ws_ml[prow * 2 + 1] = l;
             }
         }
     }

@@ -189,6 +189,38 @@ template <int N> __device__ __forceinline__ void wht_cross_chunks(float (&y)[N],
     }
 }
 
+// The same one-instruction butterfly for vectors spread over the four lanes of a quad (lane bits 0
+// and 1 carry the two top index bits).  On entry y holds quad_entry_sign() * x.
+__device__ __forceinline__ float quad_entry_sign(int lane) { return (__builtin_popcount(lane & 3) & 1) ? -1.0f : 1.0f; }
+template <int N> __device__ __forceinline__ void wht_cross_quad(float (&y)[N], int lane) {
+    static_assert(N % 8 == 0, "");
+    const float k0 = codec_kappa(lane, 0), k1 = codec_kappa(lane, 1);
+#pragma unroll
+    for (int b = 0; b < N; b += 8) {
+        asm volatile(
+            "s_nop 1\n\t"
+            "v_fmac_f32_dpp %0, %0, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %1, %1, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %2, %2, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %3, %3, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %4, %4, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %5, %5, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %6, %6, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %7, %7, %8 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %0, %0, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %1, %1, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %2, %2, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %3, %3, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %4, %4, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %5, %5, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %6, %6, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %7, %7, %9 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf"
+            : "+v"(y[b]), "+v"(y[b + 1]), "+v"(y[b + 2]), "+v"(y[b + 3]), "+v"(y[b + 4]), "+v"(y[b + 5]),
+              "+v"(y[b + 6]), "+v"(y[b + 7])
+            : "v"(k0), "v"(k1));
+    }
+}
+
 // ---- cross-lane butterflies -------------------------------------------------------------------
 // Partner exchange lane ^ MASK with DPP where a single control word exists, ds_bpermute otherwise.
 template <int MASK> __device__ __forceinline__ float lane_xor(float x) {
