@@ -227,15 +227,18 @@ __device__ __forceinline__ void pipeline_step(const RawV<D>& rv, const RawK<D>& 
         for (int nt = 0; nt < NT; ++nt) {
             const float m_new = fmaxf(m_ref[nt], xor32_max(mloc[nt]));
             const float alpha = __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
+            const bool first = __all(m_ref[nt] == -INFINITY);  // nothing accumulated yet: nothing to rescale
             m_ref[nt] = m_new;
             m_thr[nt] = m_new + raise_thr;
             mneg[nt] = -m_new * qscale;
-            Lsum[nt] *= alpha;
+            if (!first) {
+                Lsum[nt] *= alpha;
 #pragma unroll
-            for (int g = 0; g < MG; ++g) {
-                float16v y = mfma32(zero8, zero8, O[g][nt]);
-                y *= alpha;
-                O[g][nt] = mfma32(zero8, zero8, y);
+                for (int g = 0; g < MG; ++g) {
+                    float16v y = mfma32(zero8, zero8, O[g][nt]);
+                    y *= alpha;
+                    O[g][nt] = mfma32(zero8, zero8, y);
+                }
             }
         }
     }
@@ -346,8 +349,8 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     constexpr int OSTRIDE = D + 4;
     constexpr int TB = LY::tile_bytes;
     __shared__ float m_s[4][ROWS];
-    __shared__ float l_s[2 * ROWS];
-    extern __shared__ __align__(16) float o_s[];  // two merge buffers of ROWS x OSTRIDE floats
+    __shared__ float l_s[4 * ROWS];
+    extern __shared__ __align__(16) float o_s[];  // four merge buffers of ROWS x OSTRIDE floats
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform
@@ -373,26 +376,30 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         load_rawv<D>(rv, tile_ptr(0), lane);
     }
 
-    // ---- query rows as MFMA B operands: lane (n, h) holds q[row 32nt+n][32j + 16s + 8h .. +7]
+    // ---- query rows as MFMA B operands: lane (n, h) holds q[row 32nt+n][32j + 16s + 8h .. +7].
+    // The block of rows is fetched with fully coalesced 16-byte loads (16 lanes to a row) into LDS
+    // (the merge buffers are idle until the end) and picked up from there in operand order.
+    constexpr int QS = D + 8;  // halves per staged row: 16-byte aligned, rotates the banks
+    _Float16* q_s = reinterpret_cast<_Float16*>(o_s);
+    for (int i = tid; i < ROWS * (D / 8); i += 256) {
+        const int rr = i / (D / 8), piece = i - rr * (D / 8), r = row0 + rr;
+        uint4v raw = {0, 0, 0, 0};
+        if (r < p.R) raw = *reinterpret_cast<const uint4v*>(Q + q_row_index(p, ls, kvh, r) * D + 8 * piece);
+        *reinterpret_cast<uint4v*>(q_s + rr * QS + 8 * piece) = raw;
+    }
+    __syncthreads();
     half8 qb[NT][NB][2];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int r = row0 + 32 * nt + n;
+    for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
         for (int j = 0; j < NB; ++j)
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                H8 t;
-                uint4v raw = {0, 0, 0, 0};
-                if (r < p.R)
-                    raw = *reinterpret_cast<const uint4v*>(Q + q_row_index(p, ls, kvh, r) * D + 32 * j + 16 * s + 8 * h);
-                t.u[0] = raw.x; t.u[1] = raw.y; t.u[2] = raw.z; t.u[3] = raw.w;
-                qb[nt][j][s] = t.h;
+                qb[nt][j][s] = *reinterpret_cast<const half8*>(q_s + (32 * nt + n) * QS + 32 * j + 16 * s + 8 * h);
                 // The queries are only ever MFMA operands: park them in accumulation registers so that
                 // the vector registers are left for the scores and the dequantization temporaries.
                 asm volatile("" : "+a"(qb[nt][j][s]));
             }
-    }
 
     float16v O[MG][NT];
     float Lsum[NT], m_ref[NT], m_thr[NT], mneg[NT], mloc[NT];
@@ -444,42 +451,35 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         process_ragged_tile<D, NT>(tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
                                    Lsum, m_ref, m_thr, mneg);
 
-    // ---- merge the four waves through LDS: waves 0 and 2 store their (rescaled) accumulators into
-    // two buffers, waves 1 and 3 add theirs on top, the final pass sums the two buffers.  The order of
-    // the additions is fixed, so the result is reproducible.
+    // ---- merge the four waves through LDS: every wave stores its accumulators, rescaled to the
+    // common row maximum, into a buffer of its own; the final pass adds the four buffers in a fixed
+    // order, so the result is reproducible.
     if (h == 0) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) m_s[wave][32 * nt + n] = m_ref[nt];
     }
-    __syncthreads();
-    float* obuf = o_s + (wave >> 1) * (ROWS * OSTRIDE);
-    float* lbuf = l_s + (wave >> 1) * ROWS;
-    for (int round = 0; round < 2; ++round) {
-        if ((wave & 1) == round) {
+    __syncthreads();  // also: every wave has picked up its queries, the buffers may be overwritten
+    {
+        float* obuf = o_s + wave * (ROWS * OSTRIDE);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const int r = 32 * nt + n;
-                const float M = fmaxf(fmaxf(m_s[0][r], m_s[1][r]), fmaxf(m_s[2][r], m_s[3][r]));
-                const float f = m_ref[nt] == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f((m_ref[nt] - M) * qscale);
-                const float l = xor32_sum(Lsum[nt]);  // the lane pair (n, h) shares a row
-                if (h == 0) lbuf[r] = (round == 0 ? 0.0f : lbuf[r]) + l * f;
+        for (int nt = 0; nt < NT; ++nt) {
+            const int r = 32 * nt + n;
+            const float M = fmaxf(fmaxf(m_s[0][r], m_s[1][r]), fmaxf(m_s[2][r], m_s[3][r]));
+            const float f = m_ref[nt] == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f((m_ref[nt] - M) * qscale);
+            const float l = xor32_sum(Lsum[nt]);  // the lane pair (n, h) shares a row
+            if (h == 0) l_s[wave * ROWS + r] = l * f;
 #pragma unroll
-                for (int g = 0; g < MG; ++g)
+            for (int g = 0; g < MG; ++g)
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        // registers 4b..4b+3 hold coordinates 32g + 8b + 4h + 0..3 of row r
-                        float4* dst = reinterpret_cast<float4*>(&obuf[r * OSTRIDE + 32 * g + 8 * b + 4 * h]);
-                        float4 v = round == 0 ? make_float4(0.0f, 0.0f, 0.0f, 0.0f) : *dst;
-                        v.x = fmaf(O[g][nt][4 * b + 0], f, v.x);
-                        v.y = fmaf(O[g][nt][4 * b + 1], f, v.y);
-                        v.z = fmaf(O[g][nt][4 * b + 2], f, v.z);
-                        v.w = fmaf(O[g][nt][4 * b + 3], f, v.w);
-                        *dst = v;
-                    }
-            }
+                for (int b = 0; b < 4; ++b) {
+                    // registers 4b..4b+3 hold coordinates 32g + 8b + 4h + 0..3 of row r
+                    float4* dst = reinterpret_cast<float4*>(&obuf[r * OSTRIDE + 32 * g + 8 * b + 4 * h]);
+                    *dst = make_float4(O[g][nt][4 * b + 0] * f, O[g][nt][4 * b + 1] * f, O[g][nt][4 * b + 2] * f,
+                                       O[g][nt][4 * b + 3] * f);
+                }
         }
-        __syncthreads();
     }
+    __syncthreads();
 
     // ---- final pass: every wave finishes ROWS/4 rows, four lanes to a row, D/4 consecutive
     // coordinates to a lane: the rotation is then log2(D/4) in-register stages and two DPP stages.
@@ -488,21 +488,21 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     if (ri < RPW) {
         const int rr = wave + 4 * ri, r = row0 + rr;
         const float Mr = fmaxf(fmaxf(m_s[0][rr], m_s[1][rr]), fmaxf(m_s[2][rr], m_s[3][rr]));
-        const float l = l_s[rr] + l_s[ROWS + rr];
+        const float l = (l_s[rr] + l_s[ROWS + rr]) + (l_s[2 * ROWS + rr] + l_s[3 * ROWS + rr]);
         // direct: 1/l, the centroid scale, 1/sqrt(D) and the entry sign of the DPP stages in one factor
         const float f = direct ? quad_entry_sign(lane) * (kInvCentroidScale * (D == 64 ? 0.125f : 0.08838834764831845f)) *
                                      __builtin_amdgcn_rcpf(l)
                                : kInvCentroidScale;
         float x[CPL];
         const float4* a4 = reinterpret_cast<const float4*>(&o_s[rr * OSTRIDE + qd * CPL]);
-        const float4* b4 = reinterpret_cast<const float4*>(&o_s[(ROWS + rr) * OSTRIDE + qd * CPL]);
+        constexpr int BUF4 = ROWS * OSTRIDE / 4;  // one wave's buffer, in float4 units
 #pragma unroll
         for (int i = 0; i < CPL / 4; ++i) {
-            const float4 a = a4[i], b = b4[i];
-            x[4 * i + 0] = (a.x + b.x) * f;
-            x[4 * i + 1] = (a.y + b.y) * f;
-            x[4 * i + 2] = (a.z + b.z) * f;
-            x[4 * i + 3] = (a.w + b.w) * f;
+            const float4 a = a4[i], b = a4[BUF4 + i], c = a4[2 * BUF4 + i], d = a4[3 * BUF4 + i];
+            x[4 * i + 0] = ((a.x + b.x) + (c.x + d.x)) * f;
+            x[4 * i + 1] = ((a.y + b.y) + (c.y + d.y)) * f;
+            x[4 * i + 2] = ((a.z + b.z) + (c.z + d.z)) * f;
+            x[4 * i + 3] = ((a.w + b.w) + (c.w + d.w)) * f;
         }
         if (direct) {
             wht_cross_quad<CPL>(x, lane);
@@ -534,7 +534,7 @@ bool matrix_kernel_direct(const AttendPlan& plan) { return plan.nsplit == 1 && !
 template <int D, int NT>
 static hipError_t launch_one(dim3 grid, const uint8_t* storage, const AttendPlan& plan, const void* Q, float* ws_ml,
                              float* ws_o, float* out, int direct, hipStream_t s) {
-    constexpr int kMergeBytes = 2 * 32 * NT * (D + 4) * (int)sizeof(float);
+    constexpr int kMergeBytes = 4 * 32 * NT * (D + 4) * (int)sizeof(float);
     auto kern = attend_mfma_kernel<D, NT>;
     static bool configured = false;  // per instantiation: the limit is a property of the function
     if (!configured && kMergeBytes > 48 * 1024) {

@@ -201,6 +201,28 @@ def test_attend_tails_tiny_d64(tiny):
     tiny.attend_check(W.queries(cfg, step=2), tails_np=tails, tails_len=[70, 0, 13])
 
 
+@pytest.fixture(scope="module")
+def long_pool():
+    # the 7,194-token Llama-shaped pool of configurations 4 and 5 (ragged last tile), one layer
+    return Case(W.CONFIGS[4].scaled(layers=1))
+
+
+def test_attend_config4_shape_private_tails_growing_over_decode_steps(long_pool):
+    cfg = long_pool.cfg
+    tails = W.tails(cfg, [cfg.max_tail] * cfg.agents)
+    for step in (1, 23, 64):                 # every agent has produced `step` private tokens
+        long_pool.attend_check(W.queries(cfg, step=step), tails_np=tails, tails_len=[step] * cfg.agents)
+    long_pool.attend_check(W.queries(cfg))   # step 0: the pool alone, fused epilogue
+
+
+def test_attend_config5_shape_1024_rows_per_kv_head(long_pool):
+    # 64 agents x 4 queries x 4 query heads per KV head: 16 blocks of 64 rows per unit
+    cfg5 = W.CONFIGS[5].scaled(layers=1)
+    Q = W.queries(cfg5)
+    assert Q.shape[1] * Q.shape[2] * cfg5.group == 1024
+    long_pool.attend_check(Q)
+
+
 def test_attend_special_cases_zero_keys_and_dominant_key():
     pu = _pu()
     rng = np.random.default_rng(5)
