@@ -5,7 +5,8 @@ One step = one pass of the whole path over the Llama-3-8B-shaped pool (32 layers
 head_dim 128, 4096 tokens, 15 agents x 32 query heads): pool_encode -> pool_decode -> pool_attend.
 Inputs are synthetic and already resident in HBM when timing starts.  Prints ONE JSON line:
 `value` is the decode-attention rate in pool GB/s (packed pool + Q + out bytes over the duration of
-the pool_attend call); encode tokens/s and the other phase rates ride along as extra keys;
+the pool attention kernel, taken from HIP events that the runtime stamps at the kernel's begin and
+end); encode tokens/s and the other kernels' rates ride along as extra keys;
 `roofline` describes the attention kernel against HBM peak and `cpu_baseline` times the CPU oracle
 on a bounded sample of the same workload.
 """
@@ -64,6 +65,9 @@ def main():
     ap.add_argument("--pools", type=int, default=3, help="distinct pool copies rotated between steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of known size (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--extras", action="store_true",
+                    help="after the timed region also time a plain device copy and pool_attend launched back to back "
+                         "(context only; off by default so that a profile of the default run holds the timed steps only)")
     ap.add_argument("--phases", default="eda", help="subset of e(ncode) d(ecode) a(ttend) to run per step; "
                     "anything but the default is for profiling one kernel and is marked partial")
     args = ap.parse_args()
@@ -98,19 +102,28 @@ def main():
         for p in pools:
             p.encode(K, V)
 
-    def step(i, ev=None):
+    def step(i, ev=None, kev=None):
+        # ev: four events recorded on the stream between the calls (stream-level phase times, launch gaps
+        # included); kev: three (start, stop) pairs stamped by the runtime at the begin / end of each call's
+        # main kernel (kernel durations, what rocprofv3 --kernel-trace reports)
         p = pools[i % len(pools)]
         if ev:
             ev[0].record()
         if "e" in args.phases:
+            if kev:
+                pk.time_next_kernel(*kev[0])
             p.encode(K, V)
         if ev:
             ev[1].record()
         if "d" in args.phases:
+            if kev:
+                pk.time_next_kernel(*kev[1])
             p.decode(torch.float16, Kd, Vd)
         if ev:
             ev[2].record()
         if "a" in args.phases:
+            if kev:
+                pk.time_next_kernel(*kev[2])
             p.attend(Q, out, workspace=ws)
         if ev:
             ev[3].record()
@@ -122,30 +135,68 @@ def main():
         step(i)
     torch.cuda.synchronize()
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    kevents = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(3)]
+               for _ in range(args.steps)]
+    for trio in kevents:             # torch creates an event's handle at its first record()
+        for a, b in trio:
+            a.record()
+            b.record()
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i, events[i])
+        step(i, events[i], kevents[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+
+    # Context for the numbers above, outside the timed region: a plain device copy of the dense K tensor
+    # (what this GPU sustains for read + write traffic) and pool_attend launched back to back on its own
+    # (the attention kernel is issue-bound, so its duration follows the shader clock, which the power
+    # management keeps lower while memory-bound kernels run in between).
+    t_copy = t_att_iso = None
+    if args.extras:
+        def timed(fn, n):
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+            for a, b in evs:
+                a.record()
+                fn()
+                b.record()
+            torch.cuda.synchronize()
+            return float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e-3
+        t_copy = timed(lambda: Kd.copy_(K), 10)
+        iso = [0]
+
+        def attend_only():
+            pools[iso[0] % len(pools)].attend(Q, out, workspace=ws)
+            iso[0] += 1
+        timed(attend_only, 3)
+        t_att_iso = timed(attend_only, args.steps)
 
     enc = np.array([e[0].elapsed_time(e[1]) for e in events]) * 1e-3
     dec = np.array([e[1].elapsed_time(e[2]) for e in events]) * 1e-3
     att = np.array([e[2].elapsed_time(e[3]) for e in events]) * 1e-3
-    t_enc, t_dec, t_att = (max(float(x.mean()), 1e-9) for x in (enc, dec, att))
+    t_enc, t_dec, t_att = (max(float(x.mean()), 1e-9) for x in (enc, dec, att))       # stream-level, with launch gaps
+
+    def kernel_time(idx, phase, fallback):
+        if phase not in args.phases:
+            return fallback
+        return max(float(np.mean([k[idx][0].elapsed_time(k[idx][1]) for k in kevents])) * 1e-3, 1e-9)
+    k_enc, k_dec, k_att = kernel_time(0, "e", t_enc), kernel_time(1, "d", t_dec), kernel_time(2, "a", t_att)
 
     units = L * H
     packed = units * T * (d + d // 16 + 3 * d // 8)                  # algorithmic pool bytes
     enc_bytes = units * T * 4 * d + packed
     dec_bytes = packed + units * T * 4 * d
     att_bytes = packed + Q.numel() * 2 + out.numel() * 4
-    att_gbps = att_bytes / t_att / 1e9
+    att_gbps = att_bytes / k_att / 1e9
 
     def roof(gbps, kernel):
         return {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": gbps / HBM_PEAK_GBPS, "traffic": None, "kernel": kernel}
 
-    attend_roof = roof(att_gbps, "attend_mfma_kernel<128,4> (pool_attend); duration = HIP events on the launch "
-                                 "stream around the call; achieved = algorithmic bytes (packed pool + Q + out) / duration")
+    how = ("; duration = the kernel's own begin/end HIP events (hipExtLaunchKernel start/stop events on the launch "
+           "stream), averaged over the timed steps")
+    attend_roof = roof(att_gbps, "attend_mfma_kernel<128,2> (pool_attend)" + how +
+                       "; achieved = algorithmic bytes (packed pool + Q + out) / duration")
     traffic_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
                                 "attend_hbm_traffic_%s.txt" % cfg.name)
     if os.path.exists(traffic_file):     # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel
@@ -160,13 +211,19 @@ def main():
                    "tokens": T, "agents": cfg.agents, "q_per_agent": cfg.q_per_agent,
                    "rows_per_kv_head": cfg.rows_per_kv_head, "pool_bytes": packed, "pool_copies_rotated": len(pools)},
         "step": "pool_encode -> pool_decode(fp16) -> pool_attend, all layers",
-        "encode_tokens_per_s": T / t_enc, "encode_GB_per_s": enc_bytes / t_enc / 1e9,
-        "decode_GB_per_s": dec_bytes / t_dec / 1e9,
-        "attend_ms": t_att * 1e3, "encode_ms": t_enc * 1e3, "decode_ms": t_dec * 1e3,
+        "encode_tokens_per_s": T / k_enc, "encode_GB_per_s": enc_bytes / k_enc / 1e9,
+        "decode_GB_per_s": dec_bytes / k_dec / 1e9,
+        "kernel_ms": {"attend": k_att * 1e3, "encode": k_enc * 1e3, "decode": k_dec * 1e3},
+        "stream_ms": {"attend": t_att * 1e3, "encode": t_enc * 1e3, "decode": t_dec * 1e3,
+                      "note": "events recorded on the stream around each call: kernel + launch gaps"},
+        "attend_ms": k_att * 1e3, "encode_ms": k_enc * 1e3, "decode_ms": k_dec * 1e3,
         "attend_algorithmic_bytes": att_bytes,
+        "attend_back_to_back_ms": t_att_iso and t_att_iso * 1e3,
+        "attend_back_to_back_GB_per_s": t_att_iso and att_bytes / t_att_iso / 1e9,
+        "device_copy_GB_per_s": t_copy and 2 * K.numel() * 2 / t_copy / 1e9,
         "roofline": attend_roof,
-        "roofline_encode": roof(enc_bytes / t_enc / 1e9, "encode_kernel<128> (pool_encode); dense fp16 K,V in + packed out"),
-        "roofline_decode": roof(dec_bytes / t_dec / 1e9, "decode_kernel<128,half> (pool_decode); packed in + dense fp16 out"),
+        "roofline_encode": roof(enc_bytes / k_enc / 1e9, "encode_kernel<128> (pool_encode); dense fp16 K,V in + packed out"),
+        "roofline_decode": roof(dec_bytes / k_dec / 1e9, "decode_kernel<128,half> (pool_decode); packed in + dense fp16 out"),
     }
     if args.phases != "eda":
         result["partial"] = "phases=%s: not a full step" % args.phases

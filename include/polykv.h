@@ -129,6 +129,16 @@ int pool_attend(const polykv_pool* pool, const void* Q_dev, void* out_dev,
  * (midpoints), as fp32 (section "TurboQuant", Lloyd-Max quantization).  Host call. */
 void polykv_codebook(float* centroids8, float* thresholds7);
 
+/* Measurement hook (for benchmarks and profilers; not an operation of the method).  Arms the calling
+ * thread: the NEXT pool_encode, pool_decode or pool_attend call of this thread that launches has the HIP runtime
+ * record `start_event` when its main kernel (the encode kernel, the decode kernel, the pool attention
+ * kernel -- not the small tail / merge kernels) begins to execute and `stop_event` when it has finished,
+ * on the stream the kernel is launched on; the hook then disarms itself.  Both are hipEvent_t handles
+ * created (with timing enabled) and owned by the caller; either may be NULL.  hipEventElapsedTime(start,
+ * stop), after the stream has been synchronized, is then the kernel's own duration, without the launch
+ * gaps that events recorded around the call include.  Host pointers only; never fails (POLYKV_OK). */
+int polykv_time_next_kernel(void* start_event, void* stop_event);
+
 /* Description of the last error on this thread ("" if none). */
 const char* polykv_last_error(void);
 

@@ -20,6 +20,14 @@ void set_error(const char* fmt, ...) {
     va_end(ap);
 }
 
+static thread_local KernelEvents g_kernel_events;
+
+KernelEvents take_kernel_events() {
+    const KernelEvents ev = g_kernel_events;
+    g_kernel_events = KernelEvents{};
+    return ev;
+}
+
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Resolve every choice pool_attend makes from the pool shape and the caller's parameters, so that
@@ -307,6 +315,12 @@ void polykv_codebook(float* centroids8, float* thresholds7) {
             thresholds7[2 - i] = -t[i];
         }
     }
+}
+
+int polykv_time_next_kernel(void* start_event, void* stop_event) {
+    polykv::g_kernel_events.start = reinterpret_cast<hipEvent_t>(start_event);
+    polykv::g_kernel_events.stop = reinterpret_cast<hipEvent_t>(stop_event);
+    return POLYKV_OK;
 }
 
 const char* polykv_last_error(void) { return g_err; }

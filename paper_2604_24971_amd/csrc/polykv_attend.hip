@@ -368,9 +368,9 @@ hipError_t launch_attend(const polykv_pool* pool, const AttendPlan& plan, const 
     } else {
         dim3 grid(plan.nsplit / 4, units, (plan.R + kRB - 1) / kRB);
         if (plan.D == 128)
-            attend_vector_kernel<128><<<grid, 256, 0, s>>>(storage, (const __half*)Q, ws_ml, ws_o, plan);
+            launch_main_kernel(attend_vector_kernel<128>, grid, dim3(256), 0, s, storage, (const __half*)Q, ws_ml, ws_o, plan);
         else
-            attend_vector_kernel<64><<<grid, 256, 0, s>>>(storage, (const __half*)Q, ws_ml, ws_o, plan);
+            launch_main_kernel(attend_vector_kernel<64>, grid, dim3(256), 0, s, storage, (const __half*)Q, ws_ml, ws_o, plan);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     if (plan.has_tails) {

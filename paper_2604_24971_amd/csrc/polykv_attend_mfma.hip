@@ -543,7 +543,7 @@ static hipError_t launch_one(dim3 grid, const uint8_t* storage, const AttendPlan
         if (e != hipSuccess) return e;
         configured = true;
     }
-    kern<<<grid, 256, kMergeBytes, s>>>(storage, (const __half*)Q, ws_ml, ws_o, out, plan, direct);
+    launch_main_kernel(kern, grid, dim3(256), kMergeBytes, s, storage, (const __half*)Q, ws_ml, ws_o, out, plan, direct);
     return hipGetLastError();
 }
 

@@ -359,11 +359,11 @@ __global__ __launch_bounds__(256) void export_kernel(const uint8_t* __restrict__
 hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, hipStream_t s) {
     dim3 grid(p->tiles, p->layers * p->kv_heads);
     if (p->head_dim == 128)
-        encode_kernel<128><<<grid, 256, 0, s>>>((const __half*)K, (const __half*)V, (uint8_t*)p->storage,
-                                                p->tokens, p->tiles);
+        launch_main_kernel(encode_kernel<128>, grid, dim3(256), 0, s, (const __half*)K, (const __half*)V,
+                           (uint8_t*)p->storage, p->tokens, p->tiles);
     else
-        encode_kernel<64><<<grid, 256, 0, s>>>((const __half*)K, (const __half*)V, (uint8_t*)p->storage,
-                                               p->tokens, p->tiles);
+        launch_main_kernel(encode_kernel<64>, grid, dim3(256), 0, s, (const __half*)K, (const __half*)V,
+                           (uint8_t*)p->storage, p->tokens, p->tiles);
     return hipGetLastError();
 }
 
@@ -372,14 +372,18 @@ hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dty
     const uint8_t* pool = (const uint8_t*)p->storage;
     if (p->head_dim == 128) {
         if (dtype == POLYKV_F32)
-            decode_kernel<128, float><<<grid, 256, 0, s>>>(pool, (float*)K_out, (float*)V_out, p->tokens, p->tiles);
+            launch_main_kernel(decode_kernel<128, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out, p->tokens,
+                               p->tiles);
         else
-            decode_kernel<128, __half><<<grid, 256, 0, s>>>(pool, (__half*)K_out, (__half*)V_out, p->tokens, p->tiles);
+            launch_main_kernel(decode_kernel<128, __half>, grid, dim3(256), 0, s, pool, (__half*)K_out, (__half*)V_out, p->tokens,
+                               p->tiles);
     } else {
         if (dtype == POLYKV_F32)
-            decode_kernel<64, float><<<grid, 256, 0, s>>>(pool, (float*)K_out, (float*)V_out, p->tokens, p->tiles);
+            launch_main_kernel(decode_kernel<64, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out, p->tokens,
+                               p->tiles);
         else
-            decode_kernel<64, __half><<<grid, 256, 0, s>>>(pool, (__half*)K_out, (__half*)V_out, p->tokens, p->tiles);
+            launch_main_kernel(decode_kernel<64, __half>, grid, dim3(256), 0, s, pool, (__half*)K_out, (__half*)V_out, p->tokens,
+                               p->tiles);
     }
     return hipGetLastError();
 }

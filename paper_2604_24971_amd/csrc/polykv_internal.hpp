@@ -1,6 +1,7 @@
 // Host-side declarations shared by the translation units of libpolykv (not part of the ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -43,6 +44,24 @@ hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dty
 hipError_t launch_export(const polykv_pool* p, void* kc, void* ks, void* vp, hipStream_t s);
 hipError_t launch_attend(const polykv_pool* p, const AttendPlan& plan, const void* Q, void* out,
                          const TailPtrs* tails, void* workspace, hipStream_t s);
+
+// Events armed by polykv_time_next_kernel() for the calling thread; taking them disarms the hook.
+struct KernelEvents {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+KernelEvents take_kernel_events();
+
+// Launch of a call's main kernel: through hipExtLaunchKernelGGL when the caller asked for the kernel's own
+// start / stop timestamps, as a plain launch otherwise.
+template <typename... Params, typename... Args>
+inline void launch_main_kernel(void (*kern)(Params...), dim3 grid, dim3 block, size_t shmem, hipStream_t s,
+                               Args... args) {
+    const KernelEvents ev = take_kernel_events();
+    if (ev.start != nullptr || ev.stop != nullptr)
+        hipExtLaunchKernelGGL(kern, grid, block, (uint32_t)shmem, s, ev.start, ev.stop, 0, static_cast<Params>(args)...);
+    else
+        kern<<<grid, block, shmem, s>>>(static_cast<Params>(args)...);
+}
 
 // True if the matrix-core attention kernel supports this shape.
 bool matrix_kernel_supports(int head_dim, int rows_per_kv_head);

@@ -60,6 +60,8 @@ def _load():
     lib.pool_attend.restype = ip
     lib.polykv_codebook.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_float)]
     lib.polykv_codebook.restype = None
+    lib.polykv_time_next_kernel.argtypes = [vp, vp]
+    lib.polykv_time_next_kernel.restype = ip
     lib.polykv_last_error.argtypes = []
     lib.polykv_last_error.restype = C.c_char_p
     return lib
@@ -78,6 +80,13 @@ def codebook():
     t = (C.c_float * 7)()
     lib.polykv_codebook(c, t)
     return list(c), list(t)
+
+
+def time_next_kernel(start: torch.cuda.Event, stop: torch.cuda.Event):
+    """polykv_time_next_kernel(start, stop): the next encode / decode / attend call of this thread stamps the two
+    events at the begin and end of its main kernel.  The events must have been recorded once before, so
+    that torch has created their handles."""
+    _check(lib.polykv_time_next_kernel(C.c_void_p(start.cuda_event), C.c_void_p(stop.cuda_event)))
 
 
 def _stream_ptr(stream=None):

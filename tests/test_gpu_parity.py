@@ -273,3 +273,24 @@ def test_attend_error_paths_on_device(tiny):
     with pytest.raises(pk.PolyKVError) as e:
         fresh.attend(Q)
     assert e.value.status == pk.ESTATE
+
+
+def test_time_next_kernel_hook_stamps_the_kernel_and_disarms(tiny):
+    pk = _pk()
+    pu = _pu()
+    Q = pu.dev(W.queries(tiny.cfg))
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    for e in ev:
+        e.record()                       # creates the handles
+    torch.cuda.synchronize()
+    ref = tiny.pool.attend(Q)
+    ev[2].record()
+    pk.time_next_kernel(ev[0], ev[1])
+    out = tiny.pool.attend(Q)
+    again = tiny.pool.attend(Q)          # hook is disarmed: plain launch
+    ev[3].record()
+    torch.cuda.synchronize()
+    kernel_ms, around_ms = ev[0].elapsed_time(ev[1]), ev[2].elapsed_time(ev[3])
+    assert 0.0 < kernel_ms < around_ms
+    torch.testing.assert_close(out, ref, rtol=0, atol=0)
+    torch.testing.assert_close(again, ref, rtol=0, atol=0)
