@@ -75,19 +75,21 @@ template <int D> struct RawV {
     uint32_t w[D / 64][3];
 };
 
+// `tile` is wave-uniform and the lane's share sits at a 32-bit offset from it, so every load can use
+// the scalar-base + vector-offset addressing form and no per-lane 64-bit address is ever computed.
 template <int D> __device__ __forceinline__ void load_rawk(RawK<D>& r, const uint8_t* tile, int lane) {
+    const uint32_t soff = Layout<D>::kscales_off + (uint32_t)(lane & 31) * (D / 32) * 2, koff = (uint32_t)lane * 16;
 #pragma unroll
-    for (int x = 0; x < D / 64; ++x)
-        r.sc[x] = *reinterpret_cast<const uint32_t*>(tile + Layout<D>::kscales_off + (lane & 31) * (D / 32) * 2 + 4 * x);
+    for (int x = 0; x < D / 64; ++x) r.sc[x] = *reinterpret_cast<const uint32_t*>(tile + soff + 4 * x);
 #pragma unroll
-    for (int j = 0; j < D / 32; ++j) r.k[j] = *reinterpret_cast<const uint4v*>(tile + j * 1024 + lane * 16);
+    for (int j = 0; j < D / 32; ++j) r.k[j] = *reinterpret_cast<const uint4v*>(tile + koff + j * 1024);
 }
 template <int D> __device__ __forceinline__ void load_rawv(RawV<D>& r, const uint8_t* tile, int lane) {
+    const uint32_t voff = Layout<D>::vcodes_off + (uint32_t)lane * 12;
 #pragma unroll
     for (int q = 0; q < D / 64; ++q)
 #pragma unroll
-        for (int w = 0; w < 3; ++w)
-            r.w[q][w] = *reinterpret_cast<const uint32_t*>(tile + Layout<D>::vcodes_off + q * 768 + lane * 12 + 4 * w);
+        for (int w = 0; w < 3; ++w) r.w[q][w] = *reinterpret_cast<const uint32_t*>(tile + voff + q * 768 + 4 * w);
 }
 
 // Half block (j, s) of a lane's key codes -> the exact two-term fp16 split of code * scale.
@@ -368,7 +370,9 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     const int my_count = my_first < t_end ? (t_end - my_first + 3) / 4 : 0;
     // pointer to local tile k; k past the end is clamped (the refill loads of the last steps then
     // fetch the wave's own last tile again, harmlessly, instead of needing a branch per load)
-    auto tile_ptr = [&](int k) { return unit_base + (size_t)(my_first + 4 * min(k, max(my_count - 1, 0))) * TB; };
+    const uint8_t* wave_base = unit_base + (size_t)my_first * TB;
+    const int last_k = max(my_count - 1, 0);
+    auto tile_ptr = [&](int k) { return wave_base + (uint32_t)min(k, last_k) * (uint32_t)(4 * TB); };
     RawK<D> rk;
     RawV<D> rv;
     if (my_count > 0) {
