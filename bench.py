@@ -8,7 +8,7 @@ Inputs are synthetic and already resident in HBM when timing starts.  Prints ONE
 the pool attention kernel, taken from HIP events that the runtime stamps at the kernel's begin and
 end); encode tokens/s and the other kernels' rates ride along as extra keys;
 `roofline` describes the attention kernel against HBM peak and `cpu_baseline` times the CPU oracle
-on a bounded sample of the same workload.
+on the same workload, layer by layer.
 """
 from __future__ import annotations
 
@@ -23,35 +23,38 @@ import numpy as np
 HBM_PEAK_GBPS = 8000.0
 
 
-def cpu_baseline(cfg, W, layers=8):
-    """The oracle, as it stands, on a bounded sample of the same workload (a few layers, all KV heads,
-    all tokens, all agents): about 10-30 s of CPU work."""
+def cpu_baseline(cfg, W, layers=None):
+    """The oracle, as it stands, on the same workload, one layer at a time (all KV heads, all tokens, all
+    agents): about 10-30 s of CPU work for the whole Llama-shaped pool."""
     from oracle import polykv_oracle as O
     try:
         from threadpoolctl import threadpool_info
         threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
     except Exception:
         threads = 1
-    layers = min(layers, cfg.layers)
-    part = cfg.scaled(layers=layers)
-    K, V = W.kv_pool(part)
-    Q = W.queries(cfg)[:layers]
-    t0 = time.perf_counter()
-    ref = O.pool_encode(K, V)
-    t1 = time.perf_counter()
-    Kh, Vh = O.pool_decode(ref)
-    t2 = time.perf_counter()
-    O.pool_attend(Kh, Vh, Q)
-    t3 = time.perf_counter()
-    b = O.stored_bytes(layers, part.kv_heads, part.tokens, part.head_dim)
-    attend_bytes = b["packed"] + Q.size * 2 + Q.size * 4
+    layers = cfg.layers if layers is None else min(layers, cfg.layers)
+    Q = W.queries(cfg)
+    t_enc = t_dec = t_att = 0.0
+    for l in range(layers):
+        Kl, Vl = W.kv_layer(cfg, l)
+        t0 = time.perf_counter()
+        ref = O.pool_encode(Kl[None], Vl[None])
+        t1 = time.perf_counter()
+        Kh, Vh = O.pool_decode(ref)
+        t2 = time.perf_counter()
+        O.pool_attend(Kh, Vh, Q[l:l + 1])
+        t3 = time.perf_counter()
+        t_enc, t_dec, t_att = t_enc + (t1 - t0), t_dec + (t2 - t1), t_att + (t3 - t2)
+    b = O.stored_bytes(layers, cfg.kv_heads, cfg.tokens, cfg.head_dim)
+    q_part = Q[:layers]
+    attend_bytes = b["packed"] + q_part.size * 2 + q_part.size * 4
     return {
-        "value": attend_bytes / (t3 - t2) / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
-        "sample": "%d of %d layers of the same workload (all %d KV heads x %d tokens, %d agents); "
-                  "encode %.2f s, decode %.2f s, attend %.2f s" % (layers, cfg.layers, part.kv_heads, part.tokens,
-                                                                   cfg.agents, t1 - t0, t2 - t1, t3 - t2),
+        "value": attend_bytes / t_att / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+        "sample": "%d of %d layers of the same workload (all %d KV heads x %d tokens, %d agents), layer by layer; "
+                  "encode %.2f s, decode %.2f s, attend %.2f s" % (layers, cfg.layers, cfg.kv_heads, cfg.tokens,
+                                                                   cfg.agents, t_enc, t_dec, t_att),
         # one token = one position across ALL layers and heads of the full pool
-        "encode_tokens_per_s": part.tokens / ((t1 - t0) * cfg.layers / layers),
+        "encode_tokens_per_s": cfg.tokens / (t_enc * cfg.layers / layers),
     }
 
 
