@@ -68,6 +68,9 @@ def main():
     ap.add_argument("--pools", type=int, default=3, help="distinct pool copies rotated between steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of known size (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--tail-len", type=int, default=0,
+                    help="private uncompressed tokens per agent attended together with the pool (the decode step "
+                         "number of the tails configuration); their bytes count as attention traffic")
     ap.add_argument("--extras", action="store_true",
                     help="after the timed region also time a plain device copy and pool_attend launched back to back "
                          "(context only; off by default so that a profile of the default run holds the timed steps only)")
@@ -99,7 +102,12 @@ def main():
     Kd = torch.empty_like(K)
     Vd = torch.empty_like(V)
     pools = [pk.Pool(L, H, d, T).bind() for _ in range(max(1, args.pools))]
-    ws = torch.empty(max(pools[0].attend_workspace_bytes(Q), 256), dtype=torch.uint8, device="cuda")
+    tails = None
+    if args.tail_len > 0:        # every agent has produced tail_len private tokens (fp16, uncompressed)
+        cap = max(args.tail_len, cfg.max_tail)
+        tails = [(torch.from_numpy(kt).cuda(), torch.from_numpy(vt).cuda(), args.tail_len)
+                 for kt, vt in W.tails(cfg, [cap] * cfg.agents)]
+    ws = torch.empty(max(pools[0].attend_workspace_bytes(Q, tails=tails), 256), dtype=torch.uint8, device="cuda")
 
     if args.phases != "eda":
         for p in pools:
@@ -127,7 +135,7 @@ def main():
         if "a" in args.phases:
             if kev:
                 pk.time_next_kernel(*kev[2])
-            p.attend(Q, out, workspace=ws)
+            p.attend(Q, out, workspace=ws, tails=tails)
         if ev:
             ev[3].record()
 
@@ -169,7 +177,7 @@ def main():
         iso = [0]
 
         def attend_only():
-            pools[iso[0] % len(pools)].attend(Q, out, workspace=ws)
+            pools[iso[0] % len(pools)].attend(Q, out, workspace=ws, tails=tails)
             iso[0] += 1
         timed(attend_only, 3)
         t_att_iso = timed(attend_only, args.steps)
@@ -189,7 +197,10 @@ def main():
     packed = units * T * (d + d // 16 + 3 * d // 8)                  # algorithmic pool bytes
     enc_bytes = units * T * 4 * d + packed
     dec_bytes = packed + units * T * 4 * d
-    att_bytes = packed + Q.numel() * 2 + out.numel() * 4
+    tail_bytes = cfg.agents * args.tail_len * units * 4 * d                    # fp16 K and V of every agent's tail
+    att_bytes = packed + Q.numel() * 2 + out.numel() * 4 + tail_bytes
+    if tails is not None:        # tail kernel + pool kernel + merge kernel: only the stream-level time covers the call
+        k_att = t_att
     att_gbps = att_bytes / k_att / 1e9
 
     def roof(gbps, kernel):
@@ -212,7 +223,8 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "layers": L, "kv_heads": H, "q_heads": cfg.q_heads, "head_dim": d,
                    "tokens": T, "agents": cfg.agents, "q_per_agent": cfg.q_per_agent,
-                   "rows_per_kv_head": cfg.rows_per_kv_head, "pool_bytes": packed, "pool_copies_rotated": len(pools)},
+                   "rows_per_kv_head": cfg.rows_per_kv_head, "pool_bytes": packed, "pool_copies_rotated": len(pools),
+                   "tail_len": args.tail_len, "tail_bytes": tail_bytes},
         "step": "pool_encode -> pool_decode(fp16) -> pool_attend, all layers",
         "encode_tokens_per_s": T / k_enc, "encode_GB_per_s": enc_bytes / k_enc / 1e9,
         "decode_GB_per_s": dec_bytes / k_dec / 1e9,

@@ -300,21 +300,48 @@ __global__ __launch_bounds__(256) void attend_merge_kernel(const float* __restri
     const int usel = (int)(rg / p.R), r = (int)(rg - (long)usel * p.R);
     const int ls = usel / p.H, kvh = usel - ls * p.H;
 
+    // Every split wrote its partial (zeros with m = -inf, l = 0 where it had no tokens), so nothing here
+    // is conditional: the lanes fetch the (m, l) pairs of 64 splits at a time, the weights
+    // w_s = 2^(m_s - M) are handed out with readlane, and the loads of the partial rows are independent
+    // of each other (eight in flight per lane).
+    const size_t row0 = (size_t)usel * p.nsplit * p.R + r;     // partial row of split 0; split stride p.R rows
     float M = -INFINITY;
-    for (int s = 0; s < p.nsplit; ++s) M = fmaxf(M, ws_ml[(((size_t)usel * p.nsplit + s) * p.R + r) * 2]);
+    for (int s = lane; s < p.nsplit; s += 64) M = fmaxf(M, ws_ml[(row0 + (size_t)s * p.R) * 2]);
+    M = wave_max(M);
     float Lsum = 0.0f, x[EPL];
 #pragma unroll
     for (int i = 0; i < EPL; ++i) x[i] = 0.0f;
-    for (int s = 0; s < p.nsplit; ++s) {
-        const size_t prow = ((size_t)usel * p.nsplit + s) * p.R + r;
-        const float m = ws_ml[prow * 2], l = ws_ml[prow * 2 + 1];
-        if (l > 0.0f) {
-            const float w = exp2f(m - M);
-            Lsum = fmaf(l, w, Lsum);
+    for (int s0 = 0; s0 < p.nsplit; s0 += 64) {
+        const int s_mine = s0 + lane, cnt = min(64, p.nsplit - s0);
+        float w = 0.0f;
+        if (s_mine < p.nsplit) {
+            const float2 ml = *reinterpret_cast<const float2*>(ws_ml + (row0 + (size_t)s_mine * p.R) * 2);
+            w = ml.y > 0.0f ? exp2f(ml.x - M) : 0.0f;
+            Lsum = fmaf(ml.y, w, Lsum);
+        }
+        const float* src = ws_o + (row0 + (size_t)s0 * p.R) * D + lane * EPL;
+        const size_t stride = (size_t)p.R * D;
+        int k = 0;
+        for (; k + 8 <= cnt; k += 8) {
+            float v[8][EPL];
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) x[i] = fmaf(ws_o[prow * D + lane * EPL + i], w, x[i]);
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) v[u][i] = src[(size_t)(k + u) * stride + i];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), k + u));
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) x[i] = fmaf(v[u][i], wu, x[i]);
+            }
+        }
+        for (; k < cnt; ++k) {
+            const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), k));
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) x[i] = fmaf(src[(size_t)k * stride + i], wu, x[i]);
         }
     }
+    Lsum = wave_sum(Lsum);
     const float invL = 1.0f / Lsum;
 #pragma unroll
     for (int i = 0; i < EPL; ++i) x[i] *= invL;
