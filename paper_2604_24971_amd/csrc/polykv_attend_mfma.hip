@@ -227,8 +227,11 @@ __device__ __forceinline__ void pipeline_step(const RawV<D>& rv, const RawK<D>& 
         // (D = 0*0 + C) carries them to vector registers and back, so the hot path never copies them.
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            const float m_new = fmaxf(m_ref[nt], xor32_max(mloc[nt]));
-            const float alpha = __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
+            // Only the rows that outgrew their reference move it: a row's result then depends on that
+            // row's scores alone, whatever other agents' rows share the wave.
+            const float row_max = xor32_max(mloc[nt]);
+            const float m_new = row_max > m_thr[nt] ? fmaxf(m_ref[nt], row_max) : m_ref[nt];
+            const float alpha = m_new == m_ref[nt] ? 1.0f : __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
             const bool first = __all(m_ref[nt] == -INFINITY);  // nothing accumulated yet: nothing to rescale
             m_ref[nt] = m_new;
             m_thr[nt] = m_new + raise_thr;
