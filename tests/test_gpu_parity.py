@@ -213,7 +213,10 @@ def test_attend_config4_shape_private_tails_growing_over_decode_steps(long_pool)
     tails = W.tails(cfg, [cfg.max_tail] * cfg.agents)
     for step in (1, 23, 64):                 # every agent has produced `step` private tokens
         long_pool.attend_check(W.queries(cfg, step=step), tails_np=tails, tails_len=[step] * cfg.agents)
-    long_pool.attend_check(W.queries(cfg))   # step 0: the pool alone, fused epilogue
+    long_pool.attend_check(W.queries(cfg))   # step 0: the pool alone
+    # one workgroup per KV head over all 225 tiles, as when all 32 layers go in one call
+    long_pool.attend_check(W.queries(cfg), splits=1)
+    long_pool.attend_check(W.queries(cfg, step=7), tails_np=tails, tails_len=[7] * cfg.agents, splits=1)
 
 
 def test_attend_config5_shape_1024_rows_per_kv_head(long_pool):
@@ -222,6 +225,7 @@ def test_attend_config5_shape_1024_rows_per_kv_head(long_pool):
     Q = W.queries(cfg5)
     assert Q.shape[1] * Q.shape[2] * cfg5.group == 1024
     long_pool.attend_check(Q)
+    long_pool.attend_check(Q, splits=1)
 
 
 def test_attend_special_cases_zero_keys_and_dominant_key():
