@@ -28,6 +28,8 @@ __device__ __forceinline__ float wave_sum(float x) {
 
 constexpr int kRB = 4;  // query rows per pass of the vector kernels
 
+template <int N> struct __attribute__((aligned(2 * N))) HalfVecN { __half h[N]; };
+
 // ---------------------------------------------------------------------------- vector kernel ---
 // One wave = one token-range split of one (layer, kv head, block of kRB rows).  Per 64 tokens:
 //   scores  lane = token: the lane dequantizes its key (code * block scale, exact in fp32) and dots
@@ -196,17 +198,40 @@ __global__ __launch_bounds__(64) void attend_tail_kernel(const __half* __restric
     if (r0 >= r_end) return;
     const int len = tails.len[a];
 
-    for (int i = lane; i < kRB * D; i += 64) {
-        const int r = i / D, jj = i - r * D;
-        float v = 0.0f;
-        if (r0 + r < r_end) v = __half2float(Q[q_row_index(p, ls, kvh, r0 + r) * D + jj]) * p.qscale;
-        q_s[r][jj] = v;
-    }
-    __syncthreads();
-
     const size_t head_off = ((size_t)(p.layer_begin + ls) * p.H + kvh) * p.tail_capacity * D;
     const __half* Kt = reinterpret_cast<const __half*>(tails.K[a]) + head_off;
     const __half* Vt = reinterpret_cast<const __half*>(tails.V[a]) + head_off;
+
+    // Everything a block of 64 tokens needs is requested before anything is used: the lane's key row
+    // (lane = token) and, for the second phase (lane = coordinates), its EPL values of all 64 value rows.
+    // The first block's requests go out together with the query loads: one memory latency in all.
+    uint4 kraw[D / 8];
+    HalfVecN<EPL> vraw[64];
+    auto request = [&](int t0) {
+        const int cnt = min(64, len - t0);
+        const uint4* krow = reinterpret_cast<const uint4*>(Kt + (size_t)(t0 + min(lane, cnt - 1)) * D);
+#pragma unroll
+        for (int i = 0; i < D / 8; ++i) kraw[i] = krow[i];
+#pragma unroll
+        for (int t = 0; t < 64; ++t)
+            vraw[t] = *reinterpret_cast<const HalfVecN<EPL>*>(Vt + (size_t)(t0 + min(t, cnt - 1)) * D + lane * EPL);
+    };
+    if (len > 0) request(0);
+
+    // queries: 16-byte loads, D/8 lanes to a row
+    for (int i = lane; i < kRB * (D / 8); i += 64) {
+        const int r = i / (D / 8), piece = i - r * (D / 8);
+        uint4 raw = make_uint4(0, 0, 0, 0);
+        if (r0 + r < r_end) raw = *reinterpret_cast<const uint4*>(Q + q_row_index(p, ls, kvh, r0 + r) * D + 8 * piece);
+        const __half2* h2 = reinterpret_cast<const __half2*>(&raw);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const float2 f = __half22float2(h2[b]);
+            q_s[r][8 * piece + 2 * b] = f.x * p.qscale;
+            q_s[r][8 * piece + 2 * b + 1] = f.y * p.qscale;
+        }
+    }
+    __syncthreads();
 
     float m_run[kRB], l_run[kRB], acc[kRB][EPL];
 #pragma unroll
@@ -220,12 +245,11 @@ __global__ __launch_bounds__(64) void attend_tail_kernel(const __half* __restric
     for (int t0 = 0; t0 < len; t0 += 64) {
         const int tok = t0 + lane;
         const bool valid = tok < len;
+        if (t0 > 0) request(t0);
         float k[D];
-        const uint4* krow = reinterpret_cast<const uint4*>(Kt + (size_t)(valid ? tok : 0) * D);
 #pragma unroll
         for (int i = 0; i < D / 8; ++i) {
-            const uint4 raw = krow[i];
-            const __half2* h2 = reinterpret_cast<const __half2*>(&raw);
+            const __half2* h2 = reinterpret_cast<const __half2*>(&kraw[i]);
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const float2 f = __half22float2(h2[b]);
@@ -255,17 +279,21 @@ __global__ __launch_bounds__(64) void attend_tail_kernel(const __half* __restric
             p_s[r][lane] = pr;
         }
         __syncthreads();
-        const int cnt = min(64, len - t0);
-        for (int t = 0; t < cnt; ++t) {
-            float v[EPL];
+        // rows past the tail were re-reads of the last valid one; their weight exp2(-inf) is 0
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) v[i] = __half2float(Vt[(size_t)(t0 + t) * D + lane * EPL + i]);
+        for (int t4 = 0; t4 < 64; t4 += 4) {
+            float4 pr[kRB];
 #pragma unroll
-            for (int r = 0; r < kRB; ++r) {
-                const float pr = p_s[r][t];
+            for (int r = 0; r < kRB; ++r) pr[r] = *reinterpret_cast<const float4*>(&p_s[r][t4]);
 #pragma unroll
-                for (int i = 0; i < EPL; ++i) acc[r][i] = fmaf(pr, v[i], acc[r][i]);
-            }
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) {
+                    const float v = __half2float(vraw[t4 + u].h[i]);
+#pragma unroll
+                    for (int r = 0; r < kRB; ++r)
+                        acc[r][i] = fmaf(u == 0 ? pr[r].x : u == 1 ? pr[r].y : u == 2 ? pr[r].z : pr[r].w, v, acc[r][i]);
+                }
         }
         __syncthreads();
     }
@@ -305,6 +333,17 @@ __global__ __launch_bounds__(256) void attend_merge_kernel(const float* __restri
     // w_s = 2^(m_s - M) are handed out with readlane, and the loads of the partial rows are independent
     // of each other (eight in flight per lane).
     const size_t row0 = (size_t)usel * p.nsplit * p.R + r;     // partial row of split 0; split stride p.R rows
+    // the tail partial is requested now and used last
+    float tail_m = -INFINITY, tail_l = 0.0f, tail_x[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) tail_x[i] = 0.0f;
+    if (p.has_tails) {
+        const size_t prow = (size_t)usel * p.R + r;
+        tail_m = tail_ml[prow * 2];
+        tail_l = tail_ml[prow * 2 + 1];
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) tail_x[i] = tail_o[prow * D + lane * EPL + i];
+    }
     float M = -INFINITY;
     for (int s = lane; s < p.nsplit; s += 64) M = fmaxf(M, ws_ml[(row0 + (size_t)s * p.R) * 2]);
     M = wave_max(M);
@@ -357,17 +396,12 @@ __global__ __launch_bounds__(256) void attend_merge_kernel(const float* __restri
         x[i] = wht_lane_stage<32>(x[i], lane);
         x[i] *= (D == 64 ? 0.125f : 0.08838834764831845f);
     }
-    if (p.has_tails) {
-        const size_t prow = (size_t)usel * p.R + r;
-        const float mt = tail_ml[prow * 2], lt = tail_ml[prow * 2 + 1];
-        if (lt > 0.0f) {
-            const float M2 = fmaxf(M, mt);
-            const float wa = exp2f(M - M2) * Lsum, wb = exp2f(mt - M2);
-            const float inv = 1.0f / (wa + wb * lt);
+    if (tail_l > 0.0f) {
+        const float M2 = fmaxf(M, tail_m);
+        const float wa = exp2f(M - M2) * Lsum, wb = exp2f(tail_m - M2);
+        const float inv = 1.0f / (wa + wb * tail_l);
 #pragma unroll
-            for (int i = 0; i < EPL; ++i)
-                x[i] = (wa * x[i] + wb * tail_o[prow * D + lane * EPL + i]) * inv;
-        }
+        for (int i = 0; i < EPL; ++i) x[i] = (wa * x[i] + wb * tail_x[i]) * inv;
     }
     if (active) {
         float* dst = out + q_row_index(p, ls, kvh, r) * D + lane * EPL;
