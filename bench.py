@@ -71,6 +71,9 @@ def main():
     ap.add_argument("--tail-len", type=int, default=0,
                     help="private uncompressed tokens per agent attended together with the pool (the decode step "
                          "number of the tails configuration); their bytes count as attention traffic")
+    ap.add_argument("--per-layer", action="store_true",
+                    help="attention as the decode loop issues it: one pool_attend per layer (32 calls per step) instead "
+                         "of all layers in one call; the attention time is then the stream-level time of the 32 calls")
     ap.add_argument("--extras", action="store_true",
                     help="after the timed region also time a plain device copy and pool_attend launched back to back "
                          "(context only; off by default so that a profile of the default run holds the timed steps only)")
@@ -105,9 +108,14 @@ def main():
     tails = None
     if args.tail_len > 0:        # every agent has produced tail_len private tokens (fp16, uncompressed)
         cap = max(args.tail_len, cfg.max_tail)
-        tails = [(torch.from_numpy(kt).cuda(), torch.from_numpy(vt).cuda(), args.tail_len)
-                 for kt, vt in W.tails(cfg, [cap] * cfg.agents)]
+        tails = pk.Tails(pools[0], [(torch.from_numpy(kt).cuda(), torch.from_numpy(vt).cuda())
+                                    for kt, vt in W.tails(cfg, [cap] * cfg.agents)], [args.tail_len] * cfg.agents)
     ws = torch.empty(max(pools[0].attend_workspace_bytes(Q, tails=tails), 256), dtype=torch.uint8, device="cuda")
+    if args.per_layer:
+        Ql = [Q[l:l + 1].contiguous() for l in range(L)]
+        outl = [out[l:l + 1] for l in range(L)]
+        ws = torch.empty(max(pools[0].attend_workspace_bytes(Ql[0], tails=tails, layer_begin=0, layer_end=1), 256),
+                         dtype=torch.uint8, device="cuda")
 
     if args.phases != "eda":
         for p in pools:
@@ -133,9 +141,13 @@ def main():
         if ev:
             ev[2].record()
         if "a" in args.phases:
-            if kev:
-                pk.time_next_kernel(*kev[2])
-            p.attend(Q, out, workspace=ws, tails=tails)
+            if args.per_layer:
+                for l in range(L):
+                    p.attend(Ql[l], outl[l], layer_begin=l, layer_end=l + 1, workspace=ws, tails=tails)
+            else:
+                if kev:
+                    pk.time_next_kernel(*kev[2])
+                p.attend(Q, out, workspace=ws, tails=tails)
         if ev:
             ev[3].record()
 
@@ -199,7 +211,7 @@ def main():
     dec_bytes = packed + units * T * 4 * d
     tail_bytes = cfg.agents * args.tail_len * units * 4 * d                    # fp16 K and V of every agent's tail
     att_bytes = packed + Q.numel() * 2 + out.numel() * 4 + tail_bytes
-    if tails is not None:        # tail kernel + pool kernel + merge kernel: only the stream-level time covers the call
+    if tails is not None or args.per_layer:   # several kernels per step: only the stream-level time covers them
         k_att = t_att
     att_gbps = att_bytes / k_att / 1e9
 
@@ -224,7 +236,8 @@ def main():
         "config": {"workload": cfg.name, "layers": L, "kv_heads": H, "q_heads": cfg.q_heads, "head_dim": d,
                    "tokens": T, "agents": cfg.agents, "q_per_agent": cfg.q_per_agent,
                    "rows_per_kv_head": cfg.rows_per_kv_head, "pool_bytes": packed, "pool_copies_rotated": len(pools),
-                   "tail_len": args.tail_len, "tail_bytes": tail_bytes},
+                   "tail_len": args.tail_len, "tail_bytes": tail_bytes,
+                   "attend_calls_per_step": L if args.per_layer else 1},
         "step": "pool_encode -> pool_decode(fp16) -> pool_attend, all layers",
         "encode_tokens_per_s": T / k_enc, "encode_GB_per_s": enc_bytes / k_enc / 1e9,
         "decode_GB_per_s": dec_bytes / k_dec / 1e9,

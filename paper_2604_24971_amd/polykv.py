@@ -100,6 +100,47 @@ def _dev_ptr(t: torch.Tensor, dtype, what: str):
     return C.c_void_p(t.data_ptr())
 
 
+class Tails:
+    """The agents' private continuations, marshalled once: per agent a (K, V) pair of fp16 tensors
+    [layers, kv_heads, capacity, head_dim] (or None) that the caller keeps appending to, plus the current
+    lengths, which set_lengths() updates in place between decode steps."""
+
+    def __init__(self, pool: "Pool", tensors, lengths=None):
+        A = len(tensors)
+        if A > MAX_TAIL_AGENTS:
+            raise ValueError("at most %d agents can carry private tails" % MAX_TAIL_AGENTS)
+        self.agents = A
+        self.k = (C.c_void_p * A)()
+        self.v = (C.c_void_p * A)()
+        self.len = (C.c_int * A)()
+        self.capacity = 0
+        self._keep = []
+        for a, ent in enumerate(tensors):
+            if ent is None:
+                continue
+            Kt, Vt = ent[0], ent[1]
+            shape = (pool.layers, pool.kv_heads, Kt.shape[2], pool.head_dim)
+            if tuple(Kt.shape) != shape or tuple(Vt.shape) != shape:
+                raise ValueError("tail tensors must be [layers, kv_heads, capacity, head_dim]")
+            if self.capacity and self.capacity != Kt.shape[2]:
+                raise ValueError("all tails must share one capacity")
+            self.capacity = Kt.shape[2]
+            self.k[a] = _dev_ptr(Kt, torch.float16, "tail K").value
+            self.v[a] = _dev_ptr(Vt, torch.float16, "tail V").value
+            self._keep += [Kt, Vt]
+            if len(ent) > 2:
+                self.len[a] = int(ent[2])
+        if lengths is not None:
+            self.set_lengths(lengths)
+
+    def set_lengths(self, lengths):
+        if len(lengths) != self.agents:
+            raise ValueError("one length per agent")
+        for a, n in enumerate(lengths):
+            self.len[a] = int(n)
+        return self
+
+
 class Pool:
     """pool_create + pool_bind around a torch-owned storage tensor."""
 
@@ -169,32 +210,15 @@ class Pool:
         p.kernel, p.splits = kernel, splits
         keep = []
         if tails is not None:
-            if len(tails) != A:
+            if not isinstance(tails, Tails):
+                tails = Tails(self, tails)
+            if tails.agents != A:
                 raise ValueError("tails must have one entry per agent")
-            tk = (C.c_void_p * A)()
-            tv = (C.c_void_p * A)()
-            tl = (C.c_int * A)()
-            cap = None
-            for a, ent in enumerate(tails):
-                if ent is None:
-                    tl[a] = 0
-                    continue
-                Kt, Vt, n = ent
-                shape = (self.layers, self.kv_heads, Kt.shape[2], self.head_dim)
-                if tuple(Kt.shape) != shape or tuple(Vt.shape) != shape:
-                    raise ValueError("tail tensors must be [layers, kv_heads, capacity, head_dim]")
-                if cap is None:
-                    cap = Kt.shape[2]
-                elif cap != Kt.shape[2]:
-                    raise ValueError("all tails must share one capacity")
-                tk[a] = _dev_ptr(Kt, torch.float16, "tail K").value
-                tv[a] = _dev_ptr(Vt, torch.float16, "tail V").value
-                tl[a] = int(n)
-            p.tail_K = C.cast(tk, C.POINTER(C.c_void_p))
-            p.tail_V = C.cast(tv, C.POINTER(C.c_void_p))
-            p.tail_len = C.cast(tl, C.POINTER(C.c_int))
-            p.tail_capacity = cap or 0
-            keep += [tk, tv, tl]
+            p.tail_K = C.cast(tails.k, C.POINTER(C.c_void_p))
+            p.tail_V = C.cast(tails.v, C.POINTER(C.c_void_p))
+            p.tail_len = C.cast(tails.len, C.POINTER(C.c_int))
+            p.tail_capacity = tails.capacity
+            keep.append(tails)
         return p, keep
 
     def attend_workspace_bytes(self, Q, **kw):
