@@ -175,7 +175,7 @@ def main():
     # (what this GPU sustains for read + write traffic) and pool_attend launched back to back on its own
     # (the attention kernel is issue-bound, so its duration follows the shader clock, which the power
     # management keeps lower while memory-bound kernels run in between).
-    t_copy = t_att_iso = None
+    t_copy = t_att_iso = append_rate = None
     if args.extras:
         def timed(fn, n):
             evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
@@ -193,6 +193,20 @@ def main():
             iso[0] += 1
         timed(attend_only, 3)
         t_att_iso = timed(attend_only, args.steps)
+        # incremental fill: the same tensors appended 64 tokens at a time into a pool of the same capacity
+        chunk = 64
+        Kc = [K[:, :, i:i + chunk].contiguous() for i in range(0, T - chunk + 1, chunk)]
+        Vc = [V[:, :, i:i + chunk].contiguous() for i in range(0, T - chunk + 1, chunk)]
+        spare = pools[0]
+
+        def fill():
+            spare.bind(spare.storage)                      # empties the pool
+            for kc, vc in zip(Kc, Vc):
+                spare.append(kc, vc)
+        fill()
+        t_fill = timed(fill, 3)
+        append_rate = len(Kc) * chunk / t_fill
+        spare.encode(K, V)
 
     enc = np.array([e[0].elapsed_time(e[1]) for e in events]) * 1e-3
     dec = np.array([e[1].elapsed_time(e[2]) for e in events]) * 1e-3
@@ -249,6 +263,7 @@ def main():
         "attend_back_to_back_ms": t_att_iso and t_att_iso * 1e3,
         "attend_back_to_back_GB_per_s": t_att_iso and att_bytes / t_att_iso / 1e9,
         "device_copy_GB_per_s": t_copy and 2 * K.numel() * 2 / t_copy / 1e9,
+        "append_64_tokens_per_s": append_rate,
         "roofline": attend_roof,
         "roofline_encode": roof(enc_bytes / k_enc / 1e9, "encode_kernel<128> (pool_encode); dense fp16 K,V in + packed out"),
         "roofline_decode": roof(dec_bytes / k_dec / 1e9, "decode_kernel<128,half> (pool_decode); packed in + dense fp16 out"),

@@ -72,16 +72,29 @@ int pool_bind(polykv_pool* pool, void* dev_storage, size_t bytes);
  * overwrites the pool (the pool is otherwise write-once / read-many). */
 int pool_encode(polykv_pool* pool, const void* K_dev, const void* V_dev, void* stream);
 
+/* Incremental fill (an extension: the paper's pool is written once, section "PolyKV Architecture"):
+ * compress `count` further tokens, K_dev, V_dev fp16 [layers, kv_heads, count, head_dim], as pool tokens
+ * [pool_length(), pool_length() + count), with the same arithmetic as pool_encode -- the pool then holds
+ * exactly what one pool_encode of the concatenated tensors would have produced.  Starts from an empty
+ * pool after pool_bind; pool_encode fills the pool to its capacity (pool_create's `tokens`) in one go.
+ * POLYKV_ESHAPE if the tokens do not fit.  Calls that fill and calls that read must be ordered by the
+ * caller (same stream, or events). */
+int pool_append(polykv_pool* pool, const void* K_dev, const void* V_dev, int count, void* stream);
+
+/* Tokens encoded so far (0 .. tokens).  pool_decode, pool_export and pool_attend work on these;
+ * their dense tensors have pool_length() tokens per (layer, KV head). */
+int pool_length(const polykv_pool* pool);
+
 /* Decompress the whole pool to dense tensors (the paper's get_kv_for_layer, section
  * "DynamicCache Injection", for all layers): K = code * s, V = H_d c[code] / sqrt(d).
- * out_dtype: POLYKV_F16 or POLYKV_F32; K_out_dev, V_out_dev: [layers, kv_heads, tokens, head_dim].
+ * out_dtype: POLYKV_F16 or POLYKV_F32; K_out_dev, V_out_dev: [layers, kv_heads, pool_length(), head_dim].
  * Either output may be NULL to skip it. */
 int pool_decode(const polykv_pool* pool, void* K_out_dev, void* V_out_dev, int out_dtype, void* stream);
 
 /* Copy the pool out in the canonical format used to compare implementations:
- *   k_codes_dev  int8   [layers, kv_heads, tokens, head_dim]
- *   k_scales_dev fp16   [layers, kv_heads, tokens, head_dim/32]
- *   v_packed_dev uint8  [layers, kv_heads, tokens, 3*head_dim/8], little-endian bit stream:
+ *   k_codes_dev  int8   [layers, kv_heads, pool_length(), head_dim]
+ *   k_scales_dev fp16   [layers, kv_heads, pool_length(), head_dim/32]
+ *   v_packed_dev uint8  [layers, kv_heads, pool_length(), 3*head_dim/8], little-endian bit stream:
  *                code j of a vector occupies stream bits 3j..3j+2, stream bit i is bit (i mod 8)
  *                of byte floor(i/8).
  * (The in-HBM layout is tiled for the attention kernel and is not part of the ABI.)  Any of the

@@ -74,8 +74,9 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
     AttendPlan& p = *plan;
     memset(&p, 0, sizeof(p));
     p.D = pool->head_dim;
-    p.T = pool->tokens;
-    p.tiles = pool->tiles;
+    p.T = pool->length;
+    p.tiles = tiles_of(pool->length);
+    p.tiles_cap = pool->tiles;
     p.H = pool->kv_heads;
     p.layer_begin = prm->layer_begin;
     p.layers = prm->layer_end - prm->layer_begin;
@@ -102,10 +103,13 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
     p.kernel = prm->kernel == POLYKV_KERNEL_AUTO ? (mat_ok ? POLYKV_KERNEL_MATRIX : POLYKV_KERNEL_VECTOR) : prm->kernel;
 
     // Token-range splits per KV head.  Work items are waves; aim at ~2 waves per SIMD of the 256 CUs.
+    // The count is derived from the pool's capacity, not from its current fill, so that the workspace
+    // size of a call does not change while the pool grows (splits beyond the filled part are empty).
     const int units = p.layers * p.H;
+    const int cap_tiles = pool->tiles;
     int nsplit;
     if (p.kernel == POLYKV_KERNEL_VECTOR) {
-        const int nchunks = (p.tiles + 1) / 2;
+        const int nchunks = (cap_tiles + 1) / 2;
         const long groups = (long)units * ((p.R + 3) / 4);
         long want = prm->splits > 0 ? prm->splits : (2048 + groups - 1) / groups;
         if (want > nchunks) want = nchunks;
@@ -118,9 +122,9 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
         // 16 splits of 8 tiles 16.8 us, 32 splits of 4 tiles 19.3 us).
         const long groups = (long)units * ((p.R + 63) / 64);
         long want = (256 + groups - 1) / groups;
-        if (want > p.tiles / 8) want = p.tiles / 8;
+        if (want > cap_tiles / 8) want = cap_tiles / 8;
         if (prm->splits > 0) want = prm->splits;
-        if (want > (p.tiles + 3) / 4) want = (p.tiles + 3) / 4;
+        if (want > (cap_tiles + 3) / 4) want = (cap_tiles + 3) / 4;
         if (want < 1) want = 1;
         nsplit = (int)want;
     }
@@ -173,7 +177,7 @@ int pool_create(int layers, int kv_heads, int head_dim, int tokens, polykv_pool*
     p->tile_bytes = head_dim == 128 ? Layout<128>::tile_bytes : Layout<64>::tile_bytes;
     p->bytes = (size_t)layers * kv_heads * p->tiles * p->tile_bytes;
     p->storage = nullptr;
-    p->encoded = false;
+    p->length = 0;
     *out = p;
     return POLYKV_OK;
 }
@@ -196,7 +200,7 @@ int pool_bind(polykv_pool* pool, void* dev_storage, size_t bytes) {
         return POLYKV_ENOMEM;
     }
     pool->storage = dev_storage;
-    pool->encoded = false;
+    pool->length = 0;
     return POLYKV_OK;
 }
 
@@ -209,7 +213,7 @@ static int check_readable(const polykv_pool* pool, const char* who) {
         set_error("%s: no storage bound", who);
         return POLYKV_ESTATE;
     }
-    if (!pool->encoded) {
+    if (pool->length == 0) {
         set_error("%s: pool has not been encoded", who);
         return POLYKV_ESTATE;
     }
@@ -222,23 +226,38 @@ static int hip_result(hipError_t e, const char* who) {
     return POLYKV_EHIP;
 }
 
-int pool_encode(polykv_pool* pool, const void* K_dev, const void* V_dev, void* stream) {
+static int encode_range(polykv_pool* pool, const void* K_dev, const void* V_dev, int begin, int count, void* stream,
+                        const char* who) {
     if (pool == nullptr || K_dev == nullptr || V_dev == nullptr) {
-        set_error("pool_encode: NULL argument");
+        set_error("%s: NULL argument", who);
         return POLYKV_EINVAL;
     }
     if (pool->storage == nullptr) {
-        set_error("pool_encode: no storage bound");
+        set_error("%s: no storage bound", who);
         return POLYKV_ESTATE;
     }
     if ((((uintptr_t)K_dev | (uintptr_t)V_dev) & 15) != 0) {
-        set_error("pool_encode: K and V must be 16-byte aligned");
+        set_error("%s: K and V must be 16-byte aligned", who);
         return POLYKV_EINVAL;
     }
-    const int rc = hip_result(launch_encode(pool, K_dev, V_dev, (hipStream_t)stream), "pool_encode");
-    if (rc == POLYKV_OK) pool->encoded = true;
+    if (count < 1 || count > pool->tokens - begin) {
+        set_error("%s: %d tokens do not fit: %d of the pool's %d are in use", who, count, begin, pool->tokens);
+        return POLYKV_ESHAPE;
+    }
+    const int rc = hip_result(launch_encode(pool, K_dev, V_dev, begin, count, (hipStream_t)stream), who);
+    if (rc == POLYKV_OK) pool->length = begin + count;
     return rc;
 }
+
+int pool_encode(polykv_pool* pool, const void* K_dev, const void* V_dev, void* stream) {
+    return encode_range(pool, K_dev, V_dev, 0, pool ? pool->tokens : 0, stream, "pool_encode");
+}
+
+int pool_append(polykv_pool* pool, const void* K_dev, const void* V_dev, int count, void* stream) {
+    return encode_range(pool, K_dev, V_dev, pool ? pool->length : 0, count, stream, "pool_append");
+}
+
+int pool_length(const polykv_pool* pool) { return pool ? pool->length : 0; }
 
 int pool_decode(const polykv_pool* pool, void* K_out_dev, void* V_out_dev, int out_dtype, void* stream) {
     int rc = check_readable(pool, "pool_decode");

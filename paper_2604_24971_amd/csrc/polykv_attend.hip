@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
     const int nchunks = (p.tiles + 1) / 2;
     const int cps = (nchunks + p.nsplit - 1) / p.nsplit;
     const int c_begin = sp * cps, c_end = min(nchunks, c_begin + cps);
-    const uint8_t* unit_base = pool + (size_t)((p.layer_begin + ls) * p.H + kvh) * p.tiles * LY::tile_bytes;
+    const uint8_t* unit_base = pool + (size_t)((p.layer_begin + ls) * p.H + kvh) * p.tiles_cap * LY::tile_bytes;
 
     float m_run[kRB], l_run[kRB], acc[kRB][MT];
 #pragma unroll

@@ -365,7 +365,7 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     const int split = blockIdx.x;
     const int tps = (p.tiles + p.nsplit - 1) / p.nsplit;
     const int t_begin = split * tps, t_end = min(p.tiles, t_begin + tps);
-    const uint8_t* unit_base = pool + (size_t)((p.layer_begin + ls) * p.H + kvh) * p.tiles * TB;
+    const uint8_t* unit_base = pool + (size_t)((p.layer_begin + ls) * p.H + kvh) * p.tiles_cap * TB;
     const float qscale = p.qscale;
 
     // this wave's tiles: t_begin + wave, +4, +8, ...; local index k <-> tile my_first + 4k

@@ -42,7 +42,12 @@ struct CodecThread {
 template <int D>
 __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ K,
                                                      const __half* __restrict__ V,
-                                                     uint8_t* __restrict__ pool, int T, int tiles) {
+                                                     uint8_t* __restrict__ pool, int in_tokens, int tok_begin,
+                                                     int tok_end, int tiles_cap) {
+    // K, V hold in_tokens = tok_end - tok_begin tokens per (layer, KV head); they become pool tokens
+    // [tok_begin, tok_end).  blockIdx.x counts tiles from the first one touched.  Tokens of that tile that
+    // lie before tok_begin were encoded earlier and are carried over; tokens from tok_end on are padding
+    // and are encoded as zeros.
     using LY = Layout<D>;
     constexpr int EPT = D / 8;
     constexpr int KBYTES = LY::vcodes_off;  // key codes + scales
@@ -50,20 +55,46 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
     __shared__ __align__(16) uint8_t kimg[KBYTES];
     __shared__ __align__(16) uint8_t vstage[D * VS];  // value codes as bytes, [coordinate][token]
 
-    const int tile = blockIdx.x, unit = blockIdx.y;
+    const int tile = tok_begin / kTile + blockIdx.x, unit = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63;
     const CodecThread th(tid);
     const int t = th.t, c = th.c;
     const int tok = tile * kTile + t;
-    const bool valid = tok < T;
-    const size_t row = ((size_t)unit * T + (valid ? tok : 0)) * D + c * EPT;
+    const bool old_token = tok < tok_begin;              // keep what the record holds
+    const bool valid = !old_token && tok < tok_end;      // read from K, V
+    const bool has_old = tile * kTile < tok_begin;       // uniform over the workgroup
+    const size_t row = ((size_t)unit * in_tokens + (valid ? tok - tok_begin : 0)) * D + c * EPT;
     const int e0 = c * EPT, j = e0 >> 5, g8 = (e0 >> 3) & 3;
+    uint8_t* rec = pool + ((size_t)unit * tiles_cap + tile) * LY::tile_bytes;
 
     uint4 kraw[EPT / 8], vraw[EPT / 8];
 #pragma unroll
     for (int i = 0; i < EPT / 8; ++i) {
         kraw[i] = valid ? reinterpret_cast<const uint4*>(K + row)[i] : make_uint4(0, 0, 0, 0);
         vraw[i] = valid ? reinterpret_cast<const uint4*>(V + row)[i] : make_uint4(0, 0, 0, 0);
+    }
+
+    if (has_old) {
+        // carry the earlier tokens over: their key bytes and scales go back into the record image, their
+        // value codes are unpacked into the byte staging area (whole dwords: the slots of the new tokens
+        // are overwritten below)
+        const uint4* src = reinterpret_cast<const uint4*>(rec);
+        for (int i = tid; i < KBYTES / 16; i += 256) reinterpret_cast<uint4*>(kimg)[i] = src[i];
+        if (tid < LY::NT * 64) {
+            const int q = tid >> 6;
+            const uint32_t* w = reinterpret_cast<const uint32_t*>(rec + LY::vcodes_off + q * 768 + lane * 12);
+            const uint32_t w0 = w[0], w1 = w[1], w2 = w[2];
+#pragma unroll
+            for (int gi = 0; gi < 4; ++gi) {
+                const int G = 4 * q + gi;
+                uint32_t lo, hi;
+                vcode_selectors(w0, w1, w2, gi, lo, hi);
+                uint8_t* dst = vstage + vcode_coord(G, lane) * VS + vcode_token(G, lane, 0);
+                *reinterpret_cast<uint32_t*>(dst) = lo;
+                *reinterpret_cast<uint32_t*>(dst + 8) = hi;
+            }
+        }
+        __syncthreads();
     }
 
     // ---- keys: block absmax -> fp16 scale -> codes with the stored scale
@@ -96,6 +127,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         }
 #pragma unroll
         for (int rr = 0; rr < EPT / 8; ++rr) {
+            if (old_token) break;
             uint2 w;
             const uint32_t a01 = __builtin_amdgcn_perm(r[8 * rr + 1], r[8 * rr + 0], 0x0c0c0400u);
             const uint32_t a23 = __builtin_amdgcn_perm(r[8 * rr + 3], r[8 * rr + 2], 0x04000c0cu);
@@ -105,7 +137,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
             w.y = b01 | b23;
             *reinterpret_cast<uint2*>(kimg + LY::kcodes_off + kcode_run_offset(t, j, g8 + rr)) = w;
         }
-        if ((e0 & 31) == 0)
+        if ((e0 & 31) == 0 && !old_token)
             reinterpret_cast<__half*>(kimg + LY::kscales_off)[t * LY::NB + j] = s16;
     }
 
@@ -146,12 +178,11 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
                 : "=&v"(n), "=&v"(m), "=&s"(sp), "=&s"(s1), "=&s"(s2), "=&s"(s3)
                 : "v"(y[i]), "v"(t1), "v"(t2), "v"(t3)
                 : "vcc");
-            dst[i * VS] = (uint8_t)n;
+            if (!old_token) dst[i * VS] = (uint8_t)n;
         }
     }
     __syncthreads();
 
-    uint8_t* rec = pool + ((size_t)unit * tiles + tile) * LY::tile_bytes;
     // ---- bit-pack the value codes: one lane triplet (three dwords, four coordinate groups) per thread
     if (tid < LY::NT * 64) {
         const int q = tid >> 6;
@@ -356,45 +387,46 @@ __global__ __launch_bounds__(256) void export_kernel(const uint8_t* __restrict__
 }
 
 // ---------------------------------------------------------------------------------- launchers ---
-hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, hipStream_t s) {
-    dim3 grid(p->tiles, p->layers * p->kv_heads);
+hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, int begin, int count, hipStream_t s) {
+    const int end = begin + count;
+    dim3 grid(tiles_of(end) - begin / kTile, p->layers * p->kv_heads);
     if (p->head_dim == 128)
         launch_main_kernel(encode_kernel<128>, grid, dim3(256), 0, s, (const __half*)K, (const __half*)V,
-                           (uint8_t*)p->storage, p->tokens, p->tiles);
+                           (uint8_t*)p->storage, count, begin, end, p->tiles);
     else
         launch_main_kernel(encode_kernel<64>, grid, dim3(256), 0, s, (const __half*)K, (const __half*)V,
-                           (uint8_t*)p->storage, p->tokens, p->tiles);
+                           (uint8_t*)p->storage, count, begin, end, p->tiles);
     return hipGetLastError();
 }
 
 hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dtype, hipStream_t s) {
-    dim3 grid(p->tiles, p->layers * p->kv_heads);
+    dim3 grid(tiles_of(p->length), p->layers * p->kv_heads);  // the tokens encoded so far
     const uint8_t* pool = (const uint8_t*)p->storage;
     if (p->head_dim == 128) {
         if (dtype == POLYKV_F32)
-            launch_main_kernel(decode_kernel<128, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out, p->tokens,
+            launch_main_kernel(decode_kernel<128, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out, p->length,
                                p->tiles);
         else
-            launch_main_kernel(decode_kernel<128, __half>, grid, dim3(256), 0, s, pool, (__half*)K_out, (__half*)V_out, p->tokens,
+            launch_main_kernel(decode_kernel<128, __half>, grid, dim3(256), 0, s, pool, (__half*)K_out, (__half*)V_out, p->length,
                                p->tiles);
     } else {
         if (dtype == POLYKV_F32)
-            launch_main_kernel(decode_kernel<64, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out, p->tokens,
+            launch_main_kernel(decode_kernel<64, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out, p->length,
                                p->tiles);
         else
-            launch_main_kernel(decode_kernel<64, __half>, grid, dim3(256), 0, s, pool, (__half*)K_out, (__half*)V_out, p->tokens,
+            launch_main_kernel(decode_kernel<64, __half>, grid, dim3(256), 0, s, pool, (__half*)K_out, (__half*)V_out, p->length,
                                p->tiles);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_export(const polykv_pool* p, void* kc, void* ks, void* vp, hipStream_t s) {
-    dim3 grid(p->tiles, p->layers * p->kv_heads);
+    dim3 grid(tiles_of(p->length), p->layers * p->kv_heads);  // the tokens encoded so far
     const uint8_t* pool = (const uint8_t*)p->storage;
     if (p->head_dim == 128)
-        export_kernel<128><<<grid, 256, 0, s>>>(pool, (int8_t*)kc, (__half*)ks, (uint8_t*)vp, p->tokens, p->tiles);
+        export_kernel<128><<<grid, 256, 0, s>>>(pool, (int8_t*)kc, (__half*)ks, (uint8_t*)vp, p->length, p->tiles);
     else
-        export_kernel<64><<<grid, 256, 0, s>>>(pool, (int8_t*)kc, (__half*)ks, (uint8_t*)vp, p->tokens, p->tiles);
+        export_kernel<64><<<grid, 256, 0, s>>>(pool, (int8_t*)kc, (__half*)ks, (uint8_t*)vp, p->length, p->tiles);
     return hipGetLastError();
 }
 

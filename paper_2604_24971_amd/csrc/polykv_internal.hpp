@@ -9,11 +9,11 @@
 
 struct polykv_pool {
     int layers, kv_heads, head_dim, tokens;
-    int tiles;          // ceil(tokens / 32)
+    int tiles;          // ceil(tokens / 32): tile records per (layer, KV head), the record stride
     size_t tile_bytes;  // bytes of one tile record
     size_t bytes;       // layers * kv_heads * tiles * tile_bytes
     void* storage;      // device, caller-owned
-    bool encoded;
+    int length;         // tokens encoded so far (0 = nothing to read yet), <= tokens
 };
 
 namespace polykv {
@@ -22,7 +22,8 @@ void set_error(const char* fmt, ...);
 
 // Everything pool_attend needs after validation; passed by value to the kernels.
 struct AttendPlan {
-    int D, T, tiles, H;          // pool shape
+    int D, T, tiles, H;          // pool shape: T tokens encoded so far, in `tiles` tiles
+    int tiles_cap;               // tile records per (layer, KV head) in storage (the pool's capacity)
     int layer_begin, layers;     // selected layer range
     int A, nq, q_heads, G, R;    // R = A * nq * G query rows per KV head
     float qscale;                // softmax scale * log2(e): scores are kept in base-2 units
@@ -39,7 +40,9 @@ struct TailPtrs {
     int len[POLYKV_MAX_TAIL_AGENTS];
 };
 
-hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, hipStream_t s);
+// Encodes dense tokens [0, count) of K, V ([layers, kv_heads, count, head_dim]) as pool tokens
+// [begin, begin + count); tokens of the first touched tile that lie before `begin` are kept.
+hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, int begin, int count, hipStream_t s);
 hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dtype, hipStream_t s);
 hipError_t launch_export(const polykv_pool* p, void* kc, void* ks, void* vp, hipStream_t s);
 hipError_t launch_attend(const polykv_pool* p, const AttendPlan& plan, const void* Q, void* out,

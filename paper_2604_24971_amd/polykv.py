@@ -50,6 +50,10 @@ def _load():
     lib.pool_bind.restype = ip
     lib.pool_encode.argtypes = [vp, vp, vp, vp]
     lib.pool_encode.restype = ip
+    lib.pool_append.argtypes = [vp, vp, vp, ip, vp]
+    lib.pool_append.restype = ip
+    lib.pool_length.argtypes = [vp]
+    lib.pool_length.restype = ip
     lib.pool_decode.argtypes = [vp, vp, vp, ip, vp]
     lib.pool_decode.restype = ip
     lib.pool_export.argtypes = [vp, vp, vp, vp, vp]
@@ -176,9 +180,21 @@ class Pool:
         _check(lib.pool_encode(self._h, _dev_ptr(K, torch.float16, "K"), _dev_ptr(V, torch.float16, "V"),
                                _stream_ptr(stream)))
 
+    # pool_append(K, V, count)
+    def append(self, K: torch.Tensor, V: torch.Tensor, stream=None):
+        if K.dim() != 4 or tuple(K.shape) != tuple(V.shape) or \
+                tuple(K.shape[:2]) != (self.layers, self.kv_heads) or K.shape[3] != self.head_dim:
+            raise ValueError("K and V must be [layers, kv_heads, count, head_dim]")
+        _check(lib.pool_append(self._h, _dev_ptr(K, torch.float16, "K"), _dev_ptr(V, torch.float16, "V"),
+                               int(K.shape[2]), _stream_ptr(stream)))
+
+    @property
+    def length(self) -> int:
+        return lib.pool_length(self._h)
+
     # pool_decode(K_out, V_out)
     def decode(self, dtype=torch.float32, K_out=None, V_out=None, stream=None):
-        shape = (self.layers, self.kv_heads, self.tokens, self.head_dim)
+        shape = (self.layers, self.kv_heads, self.length, self.head_dim)
         code = {torch.float16: F16, torch.float32: F32}[dtype]
         if K_out is None:
             K_out = torch.empty(shape, dtype=dtype, device=self.device)
@@ -189,7 +205,7 @@ class Pool:
         return K_out, V_out
 
     def export(self, stream=None):
-        n = (self.layers, self.kv_heads, self.tokens)
+        n = (self.layers, self.kv_heads, self.length)
         kc = torch.empty(n + (self.head_dim,), dtype=torch.int8, device=self.device)
         ks = torch.empty(n + (self.head_dim // 32,), dtype=torch.float16, device=self.device)
         vp = torch.empty(n + (3 * self.head_dim // 8,), dtype=torch.uint8, device=self.device)

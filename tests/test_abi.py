@@ -25,7 +25,7 @@ def test_library_exports_every_declared_function():
     names = _declared_functions()
     assert {"pool_create", "pool_bytes", "pool_bind", "pool_encode", "pool_decode", "pool_export",
             "pool_attend_workspace", "pool_attend", "pool_destroy", "polykv_codebook",
-            "polykv_last_error"} <= set(names)
+            "polykv_last_error", "pool_append", "pool_length", "polykv_time_next_kernel"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -85,6 +85,17 @@ def test_state_machine_and_argument_errors_without_gpu():
     p.agents, p.q_per_agent, p.q_heads, p.layer_begin, p.layer_end = 3, 1, 2, 0, 2
     assert lib.pool_attend(h, fake, fake, C.byref(p), None) == pk.ESTATE
     assert b"not been encoded" in lib.polykv_last_error()
+    # incremental fill: an empty pool after bind, capacity checked before anything is launched
+    assert lib.pool_length(h) == 0 and lib.pool_length(None) == 0
+    assert lib.pool_append(h, fake, fake, 101, None) == pk.ESHAPE
+    assert b"do not fit" in lib.polykv_last_error()
+    assert lib.pool_append(h, fake, fake, 0, None) == pk.ESHAPE
+    assert lib.pool_append(h, None, fake, 5, None) == pk.EINVAL
+    assert lib.pool_append(None, fake, fake, 5, None) == pk.EINVAL
+    assert lib.pool_length(h) == 0
+    lib.pool_destroy(h)
+    rc, h = _create(1, 1, 64, 10)
+    assert lib.pool_append(h, fake, fake, 5, None) == pk.ESTATE           # nothing bound
     lib.pool_destroy(h)
 
 

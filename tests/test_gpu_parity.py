@@ -337,3 +337,42 @@ def test_per_layer_calls_captured_in_a_hip_graph_replay_identically(llama):
         for o, e in zip(outs, eager):
             assert torch.equal(o, e), "replay %d differs from the eager result" % rep
         assert torch.equal(scratch, ref)
+
+
+# --------------------------------------------------------------------- incremental fill ---
+@pytest.mark.parametrize("d,chunks", [(128, [37, 1, 90, 32, 5, 64, 27]), (64, [1, 1, 30, 33, 95]),
+                                      (128, [32, 64]), (64, [200])])
+def test_append_in_chunks_equals_one_encode_of_the_concatenation(d, chunks):
+    pk = _pk()
+    pu = _pu()
+    rng = np.random.default_rng(7 * d + len(chunks))
+    Lr, H, cap = 2, 3, sum(chunks) + 40
+    T = sum(chunks)
+    K = (rng.standard_normal((Lr, H, T, d)) * np.exp(0.7 * rng.standard_normal((Lr, H, T, 1)))).astype(np.float16)
+    V = (rng.standard_normal((Lr, H, T, d)) * 1.2).astype(np.float16)
+    pool = pk.Pool(Lr, H, d, cap).bind()
+    pool.storage.fill_(0xA5)             # stale bytes must never leak into results
+    assert pool.length == 0
+    Q = rng.standard_normal((Lr, 3, 1, 2 * H, d)).astype(np.float16)
+    pos = 0
+    for n in chunks:
+        pool.append(pu.dev(np.ascontiguousarray(K[:, :, pos:pos + n])), pu.dev(np.ascontiguousarray(V[:, :, pos:pos + n])))
+        pos += n
+        assert pool.length == pos
+        # everything encoded so far equals the oracle's encoding of the prefix, and reads work on it
+        ref = O.pool_encode(K[:, :, :pos], V[:, :, :pos])
+        dirty, k_mis, v_mis = pu.compare_codes(pool, ref)
+        pu.compare_decode(pool, ref, dirty)
+        Kh, Vh = O.pool_decode(ref)
+        out = pool.attend(pu.dev(Q))
+        torch.cuda.synchronize()
+        pu.compare_attend(out, O.pool_attend(Kh, Vh, Q), H, dirty, 0)
+    with pytest.raises(pk.PolyKVError) as e:
+        pool.append(pu.dev(np.zeros((Lr, H, 41, d), np.float16)), pu.dev(np.zeros((Lr, H, 41, d), np.float16)))
+    assert e.value.status == pk.ESHAPE
+    # a full re-encode starts over at the pool's capacity
+    Kc = np.concatenate([K, np.zeros((Lr, H, cap - T, d), np.float16)], axis=2)
+    Vc = np.concatenate([V, np.zeros((Lr, H, cap - T, d), np.float16)], axis=2)
+    pool.encode(pu.dev(Kc), pu.dev(Vc))
+    assert pool.length == cap
+    pu.compare_codes(pool, O.pool_encode(Kc, Vc))
