@@ -91,6 +91,11 @@ int pool_length(const polykv_pool* pool);
  * Either output may be NULL to skip it. */
 int pool_decode(const polykv_pool* pool, void* K_out_dev, void* V_out_dev, int out_dtype, void* stream);
 
+/* The same for layers [layer_begin, layer_end) only (one layer = the paper's get_kv_for_layer(l));
+ * K_out_dev, V_out_dev: [layer_end - layer_begin, kv_heads, pool_length(), head_dim]. */
+int pool_decode_layers(const polykv_pool* pool, void* K_out_dev, void* V_out_dev, int out_dtype, int layer_begin,
+                       int layer_end, void* stream);
+
 /* Copy the pool out in the canonical format used to compare implementations:
  *   k_codes_dev  int8   [layers, kv_heads, pool_length(), head_dim]
  *   k_scales_dev fp16   [layers, kv_heads, pool_length(), head_dim/32]

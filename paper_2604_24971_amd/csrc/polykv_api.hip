@@ -259,15 +259,29 @@ int pool_append(polykv_pool* pool, const void* K_dev, const void* V_dev, int cou
 
 int pool_length(const polykv_pool* pool) { return pool ? pool->length : 0; }
 
-int pool_decode(const polykv_pool* pool, void* K_out_dev, void* V_out_dev, int out_dtype, void* stream) {
+int pool_decode_layers(const polykv_pool* pool, void* K_out_dev, void* V_out_dev, int out_dtype, int layer_begin,
+                       int layer_end, void* stream) {
     int rc = check_readable(pool, "pool_decode");
     if (rc != POLYKV_OK) return rc;
     if (out_dtype != POLYKV_F16 && out_dtype != POLYKV_F32) {
         set_error("pool_decode: out_dtype %d is neither POLYKV_F16 nor POLYKV_F32", out_dtype);
         return POLYKV_EINVAL;
     }
+    if (layer_begin < 0 || layer_end > pool->layers || layer_begin >= layer_end) {
+        set_error("pool_decode: layer range [%d,%d) outside [0,%d)", layer_begin, layer_end, pool->layers);
+        return POLYKV_ESHAPE;
+    }
+    if ((((uintptr_t)K_out_dev | (uintptr_t)V_out_dev) & 15) != 0) {
+        set_error("pool_decode: outputs must be 16-byte aligned");
+        return POLYKV_EINVAL;
+    }
     if (K_out_dev == nullptr && V_out_dev == nullptr) return POLYKV_OK;
-    return hip_result(launch_decode(pool, K_out_dev, V_out_dev, out_dtype, (hipStream_t)stream), "pool_decode");
+    return hip_result(launch_decode(pool, K_out_dev, V_out_dev, out_dtype, layer_begin, layer_end, (hipStream_t)stream),
+                      "pool_decode");
+}
+
+int pool_decode(const polykv_pool* pool, void* K_out_dev, void* V_out_dev, int out_dtype, void* stream) {
+    return pool_decode_layers(pool, K_out_dev, V_out_dev, out_dtype, 0, pool ? pool->layers : 0, stream);
 }
 
 int pool_export(const polykv_pool* pool, void* k_codes_dev, void* k_scales_dev, void* v_packed_dev, void* stream) {

@@ -399,9 +399,10 @@ hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, int
     return hipGetLastError();
 }
 
-hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dtype, hipStream_t s) {
-    dim3 grid(tiles_of(p->length), p->layers * p->kv_heads);  // the tokens encoded so far
-    const uint8_t* pool = (const uint8_t*)p->storage;
+hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dtype, int layer_begin, int layer_end,
+                         hipStream_t s) {
+    dim3 grid(tiles_of(p->length), (layer_end - layer_begin) * p->kv_heads);  // the tokens encoded so far
+    const uint8_t* pool = (const uint8_t*)p->storage + (size_t)layer_begin * p->kv_heads * p->tiles * p->tile_bytes;
     if (p->head_dim == 128) {
         if (dtype == POLYKV_F32)
             launch_main_kernel(decode_kernel<128, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out, p->length,

@@ -43,7 +43,8 @@ struct TailPtrs {
 // Encodes dense tokens [0, count) of K, V ([layers, kv_heads, count, head_dim]) as pool tokens
 // [begin, begin + count); tokens of the first touched tile that lie before `begin` are kept.
 hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, int begin, int count, hipStream_t s);
-hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dtype, hipStream_t s);
+hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dtype, int layer_begin, int layer_end,
+                         hipStream_t s);
 hipError_t launch_export(const polykv_pool* p, void* kc, void* ks, void* vp, hipStream_t s);
 hipError_t launch_attend(const polykv_pool* p, const AttendPlan& plan, const void* Q, void* out,
                          const TailPtrs* tails, void* workspace, hipStream_t s);

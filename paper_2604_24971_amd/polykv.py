@@ -54,6 +54,8 @@ def _load():
     lib.pool_append.restype = ip
     lib.pool_length.argtypes = [vp]
     lib.pool_length.restype = ip
+    lib.pool_decode_layers.argtypes = [vp, vp, vp, ip, ip, ip, vp]
+    lib.pool_decode_layers.restype = ip
     lib.pool_decode.argtypes = [vp, vp, vp, ip, vp]
     lib.pool_decode.restype = ip
     lib.pool_export.argtypes = [vp, vp, vp, vp, vp]
@@ -193,15 +195,18 @@ class Pool:
         return lib.pool_length(self._h)
 
     # pool_decode(K_out, V_out)
-    def decode(self, dtype=torch.float32, K_out=None, V_out=None, stream=None):
-        shape = (self.layers, self.kv_heads, self.length, self.head_dim)
+    def decode(self, dtype=torch.float32, K_out=None, V_out=None, stream=None, layer_begin=0, layer_end=None):
+        layer_end = self.layers if layer_end is None else layer_end
+        shape = (max(layer_end - layer_begin, 0), self.kv_heads, self.length, self.head_dim)
         code = {torch.float16: F16, torch.float32: F32}[dtype]
         if K_out is None:
             K_out = torch.empty(shape, dtype=dtype, device=self.device)
         if V_out is None:
             V_out = torch.empty(shape, dtype=dtype, device=self.device)
-        _check(lib.pool_decode(self._h, _dev_ptr(K_out, dtype, "K_out"), _dev_ptr(V_out, dtype, "V_out"),
-                               code, _stream_ptr(stream)))
+        if tuple(K_out.shape) != shape or tuple(V_out.shape) != shape:
+            raise ValueError("decode outputs must have shape %s" % (shape,))
+        _check(lib.pool_decode_layers(self._h, _dev_ptr(K_out, dtype, "K_out"), _dev_ptr(V_out, dtype, "V_out"),
+                                      code, layer_begin, layer_end, _stream_ptr(stream)))
         return K_out, V_out
 
     def export(self, stream=None):

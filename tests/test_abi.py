@@ -25,7 +25,7 @@ def test_library_exports_every_declared_function():
     names = _declared_functions()
     assert {"pool_create", "pool_bytes", "pool_bind", "pool_encode", "pool_decode", "pool_export",
             "pool_attend_workspace", "pool_attend", "pool_destroy", "polykv_codebook",
-            "polykv_last_error", "pool_append", "pool_length", "polykv_time_next_kernel"} <= set(names)
+            "polykv_last_error", "pool_append", "pool_length", "pool_decode_layers", "polykv_time_next_kernel"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 

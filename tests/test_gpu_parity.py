@@ -120,6 +120,19 @@ def test_encode_degenerate_blocks_zero_constant_extreme():
     assert not kc[0, 0, 0].any()
 
 
+def test_decode_of_a_layer_range_equals_the_slice_of_the_full_decode(llama):
+    pk = _pk()
+    Kf, Vf = llama.pool.decode(torch.float32)
+    for lb, le in ((0, 1), (1, 2), (0, 2)):
+        Kl, Vl = llama.pool.decode(torch.float32, layer_begin=lb, layer_end=le)
+        assert torch.equal(Kl, Kf[lb:le]) and torch.equal(Vl, Vf[lb:le])
+    Kh, _ = llama.pool.decode(torch.float16, layer_begin=1, layer_end=2)
+    assert torch.equal(Kh, Kf[1:2].to(torch.float16))
+    with pytest.raises(pk.PolyKVError) as e:
+        llama.pool.decode(torch.float32, layer_begin=1, layer_end=3)
+    assert e.value.status == pk.ESHAPE
+
+
 def test_reencode_overwrites_and_storage_is_exactly_pool_bytes():
     pu = _pu()
     pk = _pk()
