@@ -128,6 +128,11 @@ typedef struct {
     const void* const* tail_V;
     const int* tail_len;
     int tail_capacity;
+    /* Nonzero: the agent's q_per_agent queries sit at its last q_per_agent tail positions (a multi-token
+     * decode step): query i attends the pool and the first tail_len[a] - (q_per_agent - 1 - i) tail tokens
+     * (none if that is <= 0) -- ordinary causal attention among the new tokens.  Zero: every query attends
+     * the whole tail. */
+    int tail_causal;
     int kernel;       /* POLYKV_KERNEL_*                                                    */
     int splits;       /* token-range splits per KV head; 0 = choose automatically           */
     void* workspace_dev;     /* scratch for split partials, 256-byte aligned                */

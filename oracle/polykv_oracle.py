@@ -280,12 +280,15 @@ def softmax_attend_one(q, Kmat, Vmat, scale):
     return p @ Vmat
 
 
-def pool_attend(K_hat, V_hat, Q, scale: float | None = None, tails=None):
+def pool_attend(K_hat, V_hat, Q, scale: float | None = None, tails=None, tail_causal: bool = False):
     """K_hat, V_hat: decoded pool, float64 [L, H, T, d].
     Q: [L, A, nq, q_heads, d] (any float dtype); q head h reads kv head h // (q_heads // H).
     tails: optional list over agents of (tail_K, tail_V) float16 [L, H, t_a, d] (t_a may be 0) or
     None: the agent's private, uncompressed continuation, attended together with the pool.
-    No mask: each query sees the whole pool and its agent's whole tail.
+    No mask by default: each query sees the whole pool and its agent's whole tail.  With
+    tail_causal the agent's nq queries are taken to sit at its last nq tail positions (a multi-token
+    decode step): query i sees the pool and the first t_a - (nq - 1 - i) tail tokens, i.e. the last
+    query sees everything and each earlier one a token less (ordinary causal attention among them).
     Returns float64 [L, A, nq, q_heads, d]."""
     K_hat = np.asarray(K_hat, dtype=np.float64)
     V_hat = np.asarray(V_hat, dtype=np.float64)
@@ -303,10 +306,13 @@ def pool_attend(K_hat, V_hat, Q, scale: float | None = None, tails=None):
             tail = None if tails is None else tails[a]
             for h in range(q_heads):
                 kv = h // G
-                Km, Vm = K_hat[l, kv], V_hat[l, kv]
-                if tail is not None and tail[0].shape[2] > 0:
-                    Km = np.concatenate([Km, np.asarray(tail[0][l, kv], dtype=np.float64)], axis=0)
-                    Vm = np.concatenate([Vm, np.asarray(tail[1][l, kv], dtype=np.float64)], axis=0)
                 for i in range(nq):
+                    Km, Vm = K_hat[l, kv], V_hat[l, kv]
+                    if tail is not None:
+                        t_a = tail[0].shape[2]
+                        seen = max(0, t_a - (nq - 1 - i)) if tail_causal else t_a
+                        if seen > 0:
+                            Km = np.concatenate([Km, np.asarray(tail[0][l, kv, :seen], dtype=np.float64)], axis=0)
+                            Vm = np.concatenate([Vm, np.asarray(tail[1][l, kv, :seen], dtype=np.float64)], axis=0)
                     out[l, a, i, h] = softmax_attend_one(Q[l, a, i, h], Km, Vm, scale)
     return out

@@ -94,6 +94,7 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
     p.qscale = scale * 1.4426950408889634f;
     p.has_tails = tails ? 1 : 0;
     p.tail_capacity = tails ? prm->tail_capacity : 0;
+    p.tail_causal = (tails && prm->tail_causal != 0) ? 1 : 0;
 
     const bool mat_ok = matrix_kernel_supports(p.D, p.R);
     if (prm->kernel == POLYKV_KERNEL_MATRIX && !mat_ok) {

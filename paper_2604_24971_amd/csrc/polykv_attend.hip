@@ -197,6 +197,14 @@ __global__ __launch_bounds__(64) void attend_tail_kernel(const __half* __restric
     const int r_end = min((a + 1) * rows_a, r0 + kRB);
     if (r0 >= r_end) return;
     const int len = tails.len[a];
+    // tokens each of the wave's rows may see: all of them, or, for a causal multi-token step, one less for
+    // every query position before the agent's last (row r0 + r is query (r0 + r - a * rows_a) / G)
+    int len_r[kRB];
+#pragma unroll
+    for (int r = 0; r < kRB; ++r) {
+        const int qi = (r0 + r - a * rows_a) / p.G;
+        len_r[r] = p.tail_causal ? max(0, len - (p.nq - 1 - min(qi, p.nq - 1))) : len;
+    }
 
     const size_t head_off = ((size_t)(p.layer_begin + ls) * p.H + kvh) * p.tail_capacity * D;
     const __half* Kt = reinterpret_cast<const __half*>(tails.K[a]) + head_off;
@@ -244,7 +252,6 @@ __global__ __launch_bounds__(64) void attend_tail_kernel(const __half* __restric
 
     for (int t0 = 0; t0 < len; t0 += 64) {
         const int tok = t0 + lane;
-        const bool valid = tok < len;
         if (t0 > 0) request(t0);
         float k[D];
 #pragma unroll
@@ -268,10 +275,11 @@ __global__ __launch_bounds__(64) void attend_tail_kernel(const __half* __restric
                 s = fmaf(qv.z, k[jj + 2], s);
                 s = fmaf(qv.w, k[jj + 3], s);
             }
-            s = valid ? s : -INFINITY;
+            s = tok < len_r[r] ? s : -INFINITY;
             const float m_new = fmaxf(m_run[r], wave_max(s));
-            const float alpha = exp2f(m_run[r] - m_new);
-            const float pr = exp2f(s - m_new);
+            // a row that has seen no token yet keeps m = -inf: nothing to rescale, every weight 0
+            const float alpha = m_new == -INFINITY ? 1.0f : exp2f(m_run[r] - m_new);
+            const float pr = m_new == -INFINITY ? 0.0f : exp2f(s - m_new);
             l_run[r] = l_run[r] * alpha + wave_sum(pr);
             m_run[r] = m_new;
 #pragma unroll

@@ -29,7 +29,7 @@ struct AttendPlan {
     float qscale;                // softmax scale * log2(e): scores are kept in base-2 units
     int kernel;                  // POLYKV_KERNEL_VECTOR / _MATRIX (resolved)
     int nsplit;                  // token-range splits per KV head
-    int has_tails, tail_capacity;
+    int has_tails, tail_capacity, tail_causal;
     // workspace carving (byte offsets from the 256-aligned workspace base)
     size_t off_ml, off_o, off_tail_ml, off_tail_o, total;
 };

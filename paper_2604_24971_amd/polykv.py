@@ -28,7 +28,7 @@ class AttendParams(C.Structure):
         ("agents", C.c_int), ("q_per_agent", C.c_int), ("q_heads", C.c_int),
         ("layer_begin", C.c_int), ("layer_end", C.c_int), ("scale", C.c_float),
         ("tail_K", C.POINTER(C.c_void_p)), ("tail_V", C.POINTER(C.c_void_p)),
-        ("tail_len", C.POINTER(C.c_int)), ("tail_capacity", C.c_int),
+        ("tail_len", C.POINTER(C.c_int)), ("tail_capacity", C.c_int), ("tail_causal", C.c_int),
         ("kernel", C.c_int), ("splits", C.c_int),
         ("workspace_dev", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
@@ -218,7 +218,7 @@ class Pool:
                                C.c_void_p(vp.data_ptr()), _stream_ptr(stream)))
         return kc, ks, vp
 
-    def _params(self, Q, q_heads, layer_begin, layer_end, scale, tails, kernel, splits):
+    def _params(self, Q, q_heads, layer_begin, layer_end, scale, tails, kernel, splits, tail_causal=False):
         if Q.dim() != 5:
             raise ValueError("Q must be [layers_selected, agents, q_per_agent, q_heads, head_dim]")
         layer_end = self.layers if layer_end is None else layer_end
@@ -239,20 +239,21 @@ class Pool:
             p.tail_V = C.cast(tails.v, C.POINTER(C.c_void_p))
             p.tail_len = C.cast(tails.len, C.POINTER(C.c_int))
             p.tail_capacity = tails.capacity
+            p.tail_causal = 1 if tail_causal else 0
             keep.append(tails)
         return p, keep
 
     def attend_workspace_bytes(self, Q, **kw):
         p, _keep = self._params(Q, kw.get("q_heads"), kw.get("layer_begin", 0), kw.get("layer_end"),
                                 kw.get("scale"), kw.get("tails"), kw.get("kernel", KERNEL_AUTO),
-                                kw.get("splits", 0))
+                                kw.get("splits", 0), kw.get("tail_causal", False))
         return lib.pool_attend_workspace(self._h, C.byref(p))
 
     # pool_attend(Q[agents], out)
     def attend(self, Q: torch.Tensor, out: torch.Tensor | None = None, *, q_heads=None, layer_begin=0,
                layer_end=None, scale=None, tails=None, kernel=KERNEL_AUTO, splits=0, workspace=None,
-               stream=None):
-        p, _keep = self._params(Q, q_heads, layer_begin, layer_end, scale, tails, kernel, splits)
+               stream=None, tail_causal=False):
+        p, _keep = self._params(Q, q_heads, layer_begin, layer_end, scale, tails, kernel, splits, tail_causal)
         need = lib.pool_attend_workspace(self._h, C.byref(p))
         if need == 0:
             _check(lib.pool_attend(self._h, None, None, C.byref(p), None))  # surfaces the shape error

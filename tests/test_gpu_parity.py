@@ -209,6 +209,28 @@ def test_attend_with_private_tails(llama):
     torch.testing.assert_close(a, b, rtol=0, atol=1e-5)     # fused epilogue vs merge kernel
 
 
+def test_attend_causal_tails_for_multi_token_steps(llama):
+    # three new tokens per agent: query i sees the tail up to its own position
+    pu = _pu()
+    cfg = llama.cfg
+    rng = np.random.default_rng(21)
+    A, nq = 4, 3
+    Q = rng.standard_normal((cfg.layers, A, nq, cfg.q_heads, cfg.head_dim)).astype(np.float16)
+    lens = [7, 1, 0, 64]                 # 1 < nq - 1: that agent's first query sees no tail token at all
+    tails = W.tails(cfg.scaled(cid=4, agents=A), [64] * A)
+    Kh, Vh = llama.decoded()
+    ref = O.pool_attend(Kh, Vh, Q, tails=[(t[0][:, :, :n], t[1][:, :, :n]) for t, n in zip(tails, lens)],
+                        tail_causal=True)
+    gpu_tails = [(pu.dev(t[0]), pu.dev(t[1]), n) for t, n in zip(tails, lens)]
+    out = llama.pool.attend(pu.dev(Q), tails=gpu_tails, tail_causal=True)
+    torch.cuda.synchronize()
+    pu.compare_attend(out, ref, cfg.kv_heads, llama.dirty, 0)
+    # the flag matters: without it the earlier queries see more
+    plain = llama.pool.attend(pu.dev(Q), tails=gpu_tails)
+    assert float((plain - out)[:, 0, 0].abs().max()) > 1e-3
+    torch.testing.assert_close(plain[:, :, -1], out[:, :, -1], rtol=0, atol=1e-6)
+
+
 def test_attend_tails_tiny_d64(tiny):
     cfg = tiny.cfg
     tails = W.tails(cfg, [70, 70, 70])

@@ -351,3 +351,35 @@ def test_end_to_end_pool_roundtrip_and_linearity_of_rotation():
     p = rng.random(T); p /= p.sum()
     once = O.fwht(p @ c[pool["v_idx"][0, 1]]) / math.sqrt(d)
     np.testing.assert_allclose(once, p @ Vh[0, 1], atol=1e-13)
+
+
+def test_causal_tail_attention_equals_dense_masked_attention():
+    """Multi-token decode step: query i of an agent sees the pool and the tail up to its own position.
+    Checked against a dense masked softmax written independently (one score matrix, one mask)."""
+    rng = np.random.default_rng(11)
+    L, H, T, d, A, nq, G = 1, 2, 9, 16, 2, 3, 2
+    Kp = rng.standard_normal((L, H, T, d))
+    Vp = rng.standard_normal((L, H, T, d))
+    Q = rng.standard_normal((L, A, nq, H * G, d))
+    lens = [5, 1]                     # agent 1: shorter than nq - 1, so its first query sees no tail token
+    tails = [(rng.standard_normal((L, H, n, d)), rng.standard_normal((L, H, n, d))) for n in lens]
+    out = O.pool_attend(Kp, Vp, Q, tails=tails, tail_causal=True)
+    for a in range(A):
+        t_a = lens[a]
+        for h in range(H * G):
+            kv = h // G
+            Kall = np.concatenate([Kp[0, kv], tails[a][0][0, kv]], axis=0)
+            Vall = np.concatenate([Vp[0, kv], tails[a][1][0, kv]], axis=0)
+            S = Q[0, a, :, h] @ Kall.T / np.sqrt(d)                           # [nq, T + t_a]
+            pos = np.arange(T + t_a)[None, :]
+            allowed = pos < (T + t_a - (nq - 1 - np.arange(nq)))[:, None]     # query i: all but the last nq-1-i
+            allowed |= pos < T                                                # the pool is always visible
+            S = np.where(allowed, S, -np.inf)
+            P = np.exp(S - S.max(axis=1, keepdims=True))
+            P /= P.sum(axis=1, keepdims=True)
+            np.testing.assert_allclose(out[0, a, :, h], P @ Vall, rtol=1e-12, atol=1e-12)
+    # the last query sees everything; with one query per agent the flag changes nothing
+    full = O.pool_attend(Kp, Vp, Q, tails=tails)
+    np.testing.assert_array_equal(out[:, :, -1], full[:, :, -1])
+    np.testing.assert_array_equal(O.pool_attend(Kp, Vp, Q[:, :, :1], tails=tails, tail_causal=True),
+                                  O.pool_attend(Kp, Vp, Q[:, :, :1], tails=tails))
