@@ -242,6 +242,8 @@ def main():
     if os.path.exists(traffic_file):     # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel
         vals = dict(line.split()[:2] for line in open(traffic_file) if line.strip() and not line.startswith("#"))
         attend_roof["traffic"] = float(vals["hbm_bytes_per_launch"])
+    else:
+        vals = {}
     result = {
         "metric": "decode_attention_pool_GB_per_s", "value": att_gbps, "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -268,6 +270,9 @@ def main():
         "roofline_encode": roof(enc_bytes / k_enc / 1e9, "encode_kernel<128> (pool_encode); dense fp16 K,V in + packed out"),
         "roofline_decode": roof(dec_bytes / k_dec / 1e9, "decode_kernel<128,half> (pool_decode); packed in + dense fp16 out"),
     }
+    for key, name in (("roofline_encode", "encode_hbm_bytes_per_launch"), ("roofline_decode", "decode_hbm_bytes_per_launch")):
+        if name in vals:
+            result[key]["traffic"] = float(vals[name])
     if args.phases != "eda":
         result["partial"] = "phases=%s: not a full step" % args.phases
     if not args.no_cpu_baseline:
