@@ -22,6 +22,11 @@ What it follows (PolyKV paper, section "Compression Scheme" unless noted):
     attention, grouped-query head mapping (section "Experimental Setup": Llama-3-8B
     uses GQA with 8 KV heads).
 
+  * Variant "scaled values" (not in the PolyKV paper's steps; the TurboQuant analysis it cites in
+    section "TurboQuant" assumes rotated coordinates of unit variance, which a raw cache does not
+    have): a per-vector scale g = fp16(min(rms(v), 128)) is stored next to the codes, the thresholds
+    and centroids are multiplied by g.  See v_encode_scaled.
+
 Precision: float64 everywhere, except the steps whose float32/float16 rounding is
 part of the stored format (the fp16 block scale and the code decision of q8_0).
 
@@ -234,34 +239,87 @@ def v_decode(idx):
 
 
 # --------------------------------------------------------------------------- #
+# Values, variant with a per-vector scale
+# --------------------------------------------------------------------------- #
+V_SCALE_MAX = 128.0    # largest stored scale (a format limit: probability x scale must fit fp16)
+
+
+def v_scale(V):
+    """Per-vector scale of the scaled-values variant.  Returns (g16 float16 [...], rms float64 [...]).
+
+    rms = ||v||_2 / sqrt(d).  The rotation is orthonormal, so this is also the root mean square of the
+    rotated coordinates; dividing by it gives the unit-variance coordinates that the N(0,1) codebook
+    is optimal for (section "TurboQuant": unit-norm input, coordinates ~ N(0, 1/d), i.e. the same
+    thing up to the factor sqrt(d) that the codebook's own scaling absorbs).  Stored value:
+    g = fp16(min(rms, V_SCALE_MAX)), rounded once, to nearest even."""
+    v = np.asarray(V).astype(np.float64)
+    rms = np.sqrt(np.mean(v * v, axis=-1))
+    return np.minimum(rms, V_SCALE_MAX).astype(np.float16), rms
+
+
+def v_quantize_scaled(v_rot, g16):
+    """idx = #{k : v_rot > t_k * g}: the quantizer of v_quantize applied to v_rot / g, written without
+    the division.  A vector whose scale is stored as zero decodes to the zero vector whatever its
+    codes; it gets the codes of the zero vector, 3 (as v_quantize gives for 0)."""
+    _, t = codebook()
+    g = np.asarray(g16).astype(np.float64)[..., None]
+    idx = np.zeros(np.shape(v_rot), dtype=np.uint8)
+    for tk in t:
+        idx += (v_rot > tk * g).astype(np.uint8)
+    return np.where(g > 0, idx, np.uint8(3)).astype(np.uint8)
+
+
+def v_encode_scaled(V):
+    """V: float16 [..., d] -> (idx uint8 [..., d], g16 float16 [...], v_rot float64 [..., d],
+    rms float64 [...])."""
+    V = np.asarray(V)
+    if V.dtype != np.float16:
+        raise TypeError("V must be float16")
+    g16, rms = v_scale(V)
+    v_rot = v_rotate(V)
+    return v_quantize_scaled(v_rot, g16), g16, v_rot, rms
+
+
+def v_decode_scaled(idx, g16):
+    """V_dequant = g * H c[idx] / sqrt(d)."""
+    return v_decode(idx) * np.asarray(g16).astype(np.float64)[..., None]
+
+
+# --------------------------------------------------------------------------- #
 # Pool = encode of a whole [L, H, T, d] cache; decode back
 # --------------------------------------------------------------------------- #
-def pool_encode(K, V):
+def pool_encode(K, V, scaled_values: bool = False):
     """K, V float16 [L, H, T, d] -> dict with the canonical stored arrays and the pre-rounding
     values a parity test needs to find elements that sit on a decision threshold."""
     k_codes, k_scales, k_pre = k_encode(K)
-    v_idx, v_rot = v_encode(V)
-    return {
-        "k_codes": k_codes, "k_scales": k_scales, "v_packed": v_pack(v_idx),
-        "v_idx": v_idx, "k_pre": k_pre, "v_rot": v_rot,
-    }
+    out = {"k_codes": k_codes, "k_scales": k_scales, "k_pre": k_pre}
+    if scaled_values:
+        v_idx, g16, v_rot, rms = v_encode_scaled(V)
+        out.update(v_scales=g16, v_rms=rms)
+    else:
+        v_idx, v_rot = v_encode(V)
+    out.update(v_packed=v_pack(v_idx), v_idx=v_idx, v_rot=v_rot)
+    return out
 
 
 def pool_decode(pool):
     d = pool["k_codes"].shape[-1]
-    return k_decode(pool["k_codes"], pool["k_scales"]), v_decode(v_unpack(pool["v_packed"], d))
+    idx = v_unpack(pool["v_packed"], d)
+    V_hat = v_decode_scaled(idx, pool["v_scales"]) if "v_scales" in pool else v_decode(idx)
+    return k_decode(pool["k_codes"], pool["k_scales"]), V_hat
 
 
-def stored_bytes(L: int, H: int, T: int, d: int) -> dict:
+def stored_bytes(L: int, H: int, T: int, d: int, scaled_values: bool = False) -> dict:
     """Byte accounting (section "Compression Scheme", paragraph "Compression ratio")."""
     n = L * H * T
     k_codes = n * d
     k_scales = n * (d // Q8_BLOCK) * 2
     v_codes = n * d * V_BITS // 8
+    v_scales = n * 2 if scaled_values else 0
     dense16 = 2 * n * d * 2
-    packed = k_codes + k_scales + v_codes
+    packed = k_codes + k_scales + v_codes + v_scales
     return {
-        "k_codes": k_codes, "k_scales": k_scales, "v_codes": v_codes, "packed": packed,
+        "k_codes": k_codes, "k_scales": k_scales, "v_codes": v_codes, "v_scales": v_scales, "packed": packed,
         "dense16": dense16,
         "ratio_payload": 16.0 / ((8 + V_BITS) / 2.0),      # the paper's 16/5.5
         "ratio_stored": dense16 / packed,                   # with the fp16 block scales

@@ -383,3 +383,107 @@ def test_causal_tail_attention_equals_dense_masked_attention():
     np.testing.assert_array_equal(out[:, :, -1], full[:, :, -1])
     np.testing.assert_array_equal(O.pool_attend(Kp, Vp, Q[:, :, :1], tails=tails, tail_causal=True),
                                   O.pool_attend(Kp, Vp, Q[:, :, :1], tails=tails))
+
+
+# ------------------------------------------------ value codec, scaled variant ---
+def test_scaled_values_closed_forms():
+    c, _ = O.codebook()
+    d = 64
+    # constant vector a: rms = a, rotated = a*sqrt(d) e_0 -> code 7 at coordinate 0, exact zeros elsewhere
+    v = np.full((1, d), 0.75, dtype=np.float16)
+    idx, g16, v_rot, rms = O.v_encode_scaled(v)
+    assert rms[0] == 0.75 and g16[0] == np.float16(0.75)
+    assert idx[0, 0] == 7 and np.all(idx[0, 1:] == 3)
+    # decode, by a dense library matrix: g * H c[idx] / sqrt(d)
+    want = 0.75 * (scipy.linalg.hadamard(d) @ c[idx[0]]) / math.sqrt(d)
+    np.testing.assert_allclose(O.v_decode_scaled(idx, g16)[0], want, atol=1e-12)
+    # one spike a e_j: rms = a/sqrt(d); rotated coordinates +-a/sqrt(d) = +-1 in units of the scale
+    v = np.zeros((1, d), dtype=np.float16); v[0, 9] = 4.0
+    idx, g16, v_rot, rms = O.v_encode_scaled(v)
+    assert rms[0] == 0.5 and g16[0] == np.float16(0.5)
+    signs = np.array([(-1) ** bin(i & 9).count("1") for i in range(d)])
+    np.testing.assert_array_equal(idx[0], np.where(signs > 0, 5, 2))   # +-1.0 -> centroids +-0.756
+    # zero scale (the zero vector, or one too short for fp16): the codes of the zero vector, decodes to zero
+    tiny = np.zeros((2, d), dtype=np.float16); tiny[1, 3] = 6e-8
+    idx, g16, _, rms = O.v_encode_scaled(tiny)
+    assert rms[1] > 0 and np.all(g16 == 0) and np.all(idx == 3) and np.all(O.v_decode_scaled(idx, g16) == 0)
+    assert np.array_equal(idx[0], O.v_encode(tiny[:1])[0][0])
+    # the format limit: scales above 128 are stored as 128
+    v = np.full((1, d), 300.0, dtype=np.float16)
+    idx, g16, _, rms = O.v_encode_scaled(v)
+    assert rms[0] == 300.0 and g16[0] == np.float16(128.0)
+
+
+def test_scaled_values_are_the_unscaled_codec_on_the_normalized_vector():
+    # dividing by the stored scale and running the paper's own value quantizer gives the same codes
+    # (wherever the division does not land within rounding of a threshold)
+    rng = np.random.default_rng(21)
+    d = 128
+    sigma = np.exp(rng.normal(0.0, 1.5, size=(512, 1)))
+    V = (rng.standard_normal((512, d)) * sigma).astype(np.float16)
+    idx, g16, v_rot, rms = O.v_encode_scaled(V)
+    g = g16.astype(np.float64)[:, None]
+    u = v_rot / g
+    _, t = O.codebook()
+    near = np.min(np.abs(u[..., None] - t), axis=-1) < 1e-9
+    assert np.array_equal(O.v_quantize(u)[~near], idx[~near])
+    # rms is ||v|| / sqrt(d), by the library norm, and the stored scale is its fp16 rounding
+    np.testing.assert_allclose(rms, np.linalg.norm(V.astype(np.float64), axis=-1) / math.sqrt(d), rtol=1e-14)
+    np.testing.assert_array_equal(g16, rms.astype(np.float16))
+    assert abs(np.mean(u ** 2) - 1) < 1e-3                          # unit-variance coordinates
+
+
+def test_scaled_values_scale_invariance_and_distortion():
+    c, t = O.codebook()
+    rng = np.random.default_rng(22)
+    d = 128
+    base = rng.standard_normal((4096, d)).astype(np.float16)
+    idx1, g1, _, _ = O.v_encode_scaled(base)
+    for k in (-6, 3, 5):                                            # powers of two: exact in fp16
+        Vk = (base.astype(np.float32) * 2.0 ** k).astype(np.float16)
+        idxk, gk, _, _ = O.v_encode_scaled(Vk)
+        np.testing.assert_array_equal(idxk, idx1)
+        np.testing.assert_array_equal(gk.astype(np.float64), g1.astype(np.float64) * 2.0 ** k)
+    # relative distortion = the Lloyd-Max MSE of N(0,1), whatever the vectors' lengths; it meets the
+    # bound of section "TurboQuant".  The unscaled codec on the same data does not.
+    sigma = np.exp(rng.normal(0.0, 1.0, size=(4096, 1)))
+    V = (base.astype(np.float64) * sigma).astype(np.float16)
+    V64 = V.astype(np.float64)
+    idx, g16, _, _ = O.v_encode_scaled(V)
+    rel = np.sum((O.v_decode_scaled(idx, g16) - V64) ** 2, axis=-1) / np.sum(V64 ** 2, axis=-1)
+    assert abs(np.mean(rel) / O.lloyd_max_mse(c, t) - 1) < 0.02
+    assert np.mean(rel) < O.turboquant_mse_bound(3)
+    idx0, _ = O.v_encode(V)
+    rel0 = np.sum((O.v_decode(idx0) - V64) ** 2, axis=-1) / np.sum(V64 ** 2, axis=-1)
+    assert np.mean(rel0) > 2 * np.mean(rel)
+
+
+def test_scaled_values_match_turboquant_on_unit_vectors():
+    # TurboQuant's statement (section "TurboQuant"): a unit vector's rotated coordinates are ~N(0, 1/d)
+    # and are quantized with the N(0,1) codebook scaled by 1/sqrt(d).  Brute-force nearest centroid.
+    c, t = O.codebook()
+    rng = np.random.default_rng(23)
+    d = 128
+    x = rng.standard_normal((256, d))
+    x /= np.linalg.norm(x, axis=-1, keepdims=True)
+    V = (x * 64.0).astype(np.float16)                               # any length: only the direction matters
+    idx, g16, v_rot, rms = O.v_encode_scaled(V)
+    unit_rot = v_rot / (rms[:, None] * math.sqrt(d))                # rotation of v/||v||
+    want = np.argmin(np.abs(unit_rot[..., None] - c / math.sqrt(d)), axis=-1)
+    # the stored scale is rms rounded to fp16 (relative 2^-11): codes may differ only that close to a threshold
+    near = np.min(np.abs(unit_rot[..., None] * math.sqrt(d) - t), axis=-1) < 2.2 * 2.0 ** -11
+    assert np.array_equal(want[~near], idx[~near])
+    assert near.mean() < 0.01
+
+
+def test_scaled_values_pool_roundtrip_and_bytes():
+    rng = np.random.default_rng(24)
+    K = rng.standard_normal((1, 2, 40, 64)).astype(np.float16)
+    V = (rng.standard_normal((1, 2, 40, 64)) * 3.0).astype(np.float16)
+    ref = O.pool_encode(K, V, scaled_values=True)
+    assert ref["v_scales"].shape == (1, 2, 40) and ref["v_scales"].dtype == np.float16
+    Kh, Vh = O.pool_decode(ref)
+    np.testing.assert_array_equal(Vh, O.v_decode_scaled(ref["v_idx"], ref["v_scales"]))
+    assert np.mean((Vh - V.astype(np.float64)) ** 2) / np.mean(V.astype(np.float64) ** 2) < 0.05
+    b = O.stored_bytes(32, 8, 4096, 128, scaled_values=True)
+    assert b["packed"] == 32 * 8 * 4096 * 186 and abs(b["ratio_stored"] - 512 / 186) < 1e-12
