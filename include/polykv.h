@@ -48,15 +48,28 @@ enum { POLYKV_MAX_TAIL_AGENTS = 64 };
  * shape, else the vector kernel.  The explicit values exist for tests and profiling. */
 enum { POLYKV_KERNEL_AUTO = 0, POLYKV_KERNEL_VECTOR = 1, POLYKV_KERNEL_MATRIX = 2 };
 
+/* Value codecs.
+ *   POLYKV_VALUES_TQ3         the paper's: rotate, 3-bit Lloyd-Max codes for N(0,1) applied to the rotated
+ *                             coordinates as they are (section "Compression Scheme", value quantization).
+ *   POLYKV_VALUES_TQ3_SCALED  a variant: each vector also stores g = fp16(min(|v|_2 / sqrt(head_dim), 128)) and
+ *                             its rotated coordinates are quantized in units of g (code = number of
+ *                             thresholds t_k with t_k * g strictly below v_rot; all codes 3 if g = 0), so the
+ *                             codebook sees the unit-variance coordinates that the analysis cited in section
+ *                             "TurboQuant" assumes; V = g * H_d c[code] / sqrt(d).  Two more bytes per vector. */
+enum { POLYKV_VALUES_TQ3 = 0, POLYKV_VALUES_TQ3_SCALED = 1 };
+
 /* Host descriptor for a pool of `layers` x `kv_heads` x `tokens` vectors of `head_dim` elements.
  * head_dim must be 64 or 128; all other dimensions >= 1.  (SharedKVPool, section "PolyKV
  * Architecture".)  *out receives the handle; release it with pool_destroy. */
 int pool_create(int layers, int kv_heads, int head_dim, int tokens, polykv_pool** out);
+/* The same with a choice of value codec (POLYKV_VALUES_*); pool_create uses POLYKV_VALUES_TQ3. */
+int pool_create_codec(int layers, int kv_heads, int head_dim, int tokens, int value_codec, polykv_pool** out);
 void pool_destroy(polykv_pool* pool);
 
 /* Bytes of device storage the packed pool needs (tokens are padded to tiles of 32; per token and
  * KV head: head_dim code bytes + head_dim/16 scale bytes + 3*head_dim/8 value-code bytes, the
- * byte counts behind section "Compression Scheme", compression ratio).  0 if pool is NULL. */
+ * byte counts behind section "Compression Scheme", compression ratio; + 2 bytes with value scales).
+ * 0 if pool is NULL. */
 size_t pool_bytes(const polykv_pool* pool);
 
 /* Attach caller-owned device storage (256-byte aligned, >= pool_bytes()).  Re-binding is allowed
@@ -106,6 +119,10 @@ int pool_decode_layers(const polykv_pool* pool, void* K_out_dev, void* V_out_dev
  * three may be NULL. */
 int pool_export(const polykv_pool* pool, void* k_codes_dev, void* k_scales_dev, void* v_packed_dev,
                 void* stream);
+
+/* The per-vector value scales of a POLYKV_VALUES_TQ3_SCALED pool: v_scales_dev fp16
+ * [layers, kv_heads, pool_length()].  POLYKV_ESTATE for a pool of another codec. */
+int pool_export_value_scales(const polykv_pool* pool, void* v_scales_dev, void* stream);
 
 /* Decode attention of N agents directly over the packed pool (replaces the paper's per-agent
  * decompress-and-inject read path of section "DynamicCache Injection"; the result equals softmax

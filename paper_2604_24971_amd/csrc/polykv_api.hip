@@ -74,6 +74,7 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
     AttendPlan& p = *plan;
     memset(&p, 0, sizeof(p));
     p.D = pool->head_dim;
+    p.vscaled = pool->value_codec == POLYKV_VALUES_TQ3_SCALED ? 1 : 0;
     p.T = pool->length;
     p.tiles = tiles_of(pool->length);
     p.tiles_cap = pool->tiles;
@@ -151,11 +152,19 @@ using namespace polykv;
 extern "C" {
 
 int pool_create(int layers, int kv_heads, int head_dim, int tokens, polykv_pool** out) {
+    return pool_create_codec(layers, kv_heads, head_dim, tokens, POLYKV_VALUES_TQ3, out);
+}
+
+int pool_create_codec(int layers, int kv_heads, int head_dim, int tokens, int value_codec, polykv_pool** out) {
     if (out == nullptr) {
         set_error("pool_create: out is NULL");
         return POLYKV_EINVAL;
     }
     *out = nullptr;
+    if (value_codec != POLYKV_VALUES_TQ3 && value_codec != POLYKV_VALUES_TQ3_SCALED) {
+        set_error("pool_create: unknown value codec %d", value_codec);
+        return POLYKV_EINVAL;
+    }
     if (head_dim != 64 && head_dim != 128) {
         set_error("pool_create: head_dim=%d not supported (64 or 128)", head_dim);
         return POLYKV_ESHAPE;
@@ -175,7 +184,10 @@ int pool_create(int layers, int kv_heads, int head_dim, int tokens, polykv_pool*
     p->head_dim = head_dim;
     p->tokens = tokens;
     p->tiles = tiles_of(tokens);
-    p->tile_bytes = head_dim == 128 ? Layout<128>::tile_bytes : Layout<64>::tile_bytes;
+    p->value_codec = value_codec;
+    const bool vs = value_codec == POLYKV_VALUES_TQ3_SCALED;
+    p->tile_bytes = head_dim == 128 ? (vs ? Layout<128, true>::tile_bytes : Layout<128, false>::tile_bytes)
+                                    : (vs ? Layout<64, true>::tile_bytes : Layout<64, false>::tile_bytes);
     p->bytes = (size_t)layers * kv_heads * p->tiles * p->tile_bytes;
     p->storage = nullptr;
     p->length = 0;
@@ -289,7 +301,23 @@ int pool_export(const polykv_pool* pool, void* k_codes_dev, void* k_scales_dev, 
     int rc = check_readable(pool, "pool_export");
     if (rc != POLYKV_OK) return rc;
     if (k_codes_dev == nullptr && k_scales_dev == nullptr && v_packed_dev == nullptr) return POLYKV_OK;
-    return hip_result(launch_export(pool, k_codes_dev, k_scales_dev, v_packed_dev, (hipStream_t)stream), "pool_export");
+    return hip_result(launch_export(pool, k_codes_dev, k_scales_dev, v_packed_dev, nullptr, (hipStream_t)stream),
+                      "pool_export");
+}
+
+int pool_export_value_scales(const polykv_pool* pool, void* v_scales_dev, void* stream) {
+    int rc = check_readable(pool, "pool_export_value_scales");
+    if (rc != POLYKV_OK) return rc;
+    if (pool->value_codec != POLYKV_VALUES_TQ3_SCALED) {
+        set_error("pool_export_value_scales: the pool's value codec stores no scales");
+        return POLYKV_ESTATE;
+    }
+    if (v_scales_dev == nullptr) {
+        set_error("pool_export_value_scales: NULL output");
+        return POLYKV_EINVAL;
+    }
+    return hip_result(launch_export(pool, nullptr, nullptr, nullptr, v_scales_dev, (hipStream_t)stream),
+                      "pool_export_value_scales");
 }
 
 size_t pool_attend_workspace(const polykv_pool* pool, const polykv_attend_params* params) {

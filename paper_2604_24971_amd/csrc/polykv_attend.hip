@@ -38,12 +38,12 @@ template <int N> struct __attribute__((aligned(2 * N))) HalfVecN { __half h[N]; 
 //   PV      lane = (half h, coordinate m) exactly as the value codes are stored: the lane owns the
 //           codes of 16 of the tile's tokens for coordinates 32*g + m and accumulates its share;
 //           the two lane halves are added once at the end.
-template <int D>
+template <int D, bool VS>
 __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __restrict__ pool,
                                                             const __half* __restrict__ Q,
                                                             float* __restrict__ ws_ml,
                                                             float* __restrict__ ws_o, AttendPlan p) {
-    using LY = Layout<D>;
+    using LY = Layout<D, VS>;
     constexpr int MT = D / 32;
     __shared__ __align__(16) float q_s[kRB][D];
     __shared__ __align__(16) float p_s[4][kRB][64];
@@ -88,6 +88,8 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
             const uint8_t* tb = unit_base + (size_t)min(tile, p.tiles - 1) * LY::tile_bytes;
             float k[D];
             const __half* sc = reinterpret_cast<const __half*>(tb + LY::kscales_off) + tl * LY::NB;
+            // scaled-values codec: the token's value scale rides on its probability in the P.V sum
+            const float vscale = VS ? __half2float(reinterpret_cast<const __half*>(tb + LY::vscales_off)[tl]) : 1.0f;
 #pragma unroll
             for (int j = 0; j < LY::NB; ++j) {
                 const float s = __half2float(sc[j]);
@@ -119,7 +121,7 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
                 m_run[r] = m_new;
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) acc[r][mt] *= alpha;
-                p_s[wave][r][lane] = pr;
+                p_s[wave][r][lane] = VS ? pr * vscale : pr;
             }
         }
         // ---- PV, lane = (h, c) of the stored value codes; p_s is private to the wave
@@ -436,10 +438,9 @@ hipError_t launch_attend(const polykv_pool* pool, const AttendPlan& plan, const 
         if (matrix_kernel_direct(plan)) return hipSuccess;
     } else {
         dim3 grid(plan.nsplit / 4, units, (plan.R + kRB - 1) / kRB);
-        if (plan.D == 128)
-            launch_main_kernel(attend_vector_kernel<128>, grid, dim3(256), 0, s, storage, (const __half*)Q, ws_ml, ws_o, plan);
-        else
-            launch_main_kernel(attend_vector_kernel<64>, grid, dim3(256), 0, s, storage, (const __half*)Q, ws_ml, ws_o, plan);
+        auto kern = plan.D == 128 ? (plan.vscaled ? attend_vector_kernel<128, true> : attend_vector_kernel<128, false>)
+                                  : (plan.vscaled ? attend_vector_kernel<64, true> : attend_vector_kernel<64, false>);
+        launch_main_kernel(kern, grid, dim3(256), 0, s, storage, (const __half*)Q, ws_ml, ws_o, plan);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     if (plan.has_tails) {

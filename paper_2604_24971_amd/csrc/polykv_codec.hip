@@ -9,6 +9,8 @@
 // magnitude against three thresholds, and all bit (un)packing works on dwords.
 #include <hip/hip_fp16.h>
 
+#include <type_traits>
+
 #include "polykv_internal.hpp"
 #include "polykv_layout.hpp"
 
@@ -39,7 +41,10 @@ struct CodecThread {
 
 // ------------------------------------------------------------------------------------ encode ---
 // Key quantization and value quantization of section "Compression Scheme", fused in one pass.
-template <int D>
+// VS: the scaled-values codec.  Each value vector also stores g = fp16(min(rms, 128)), rms = |v|/sqrt(D),
+// and its rotated coordinates are quantized in units of g, which gives the codebook the unit-variance
+// input that the analysis of section "TurboQuant" assumes.
+template <int D, bool VS>
 __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ K,
                                                      const __half* __restrict__ V,
                                                      uint8_t* __restrict__ pool, int in_tokens, int tok_begin,
@@ -48,12 +53,12 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
     // [tok_begin, tok_end).  blockIdx.x counts tiles from the first one touched.  Tokens of that tile that
     // lie before tok_begin were encoded earlier and are carried over; tokens from tok_end on are padding
     // and are encoded as zeros.
-    using LY = Layout<D>;
+    using LY = Layout<D, VS>;
     constexpr int EPT = D / 8;
-    constexpr int KBYTES = LY::vcodes_off;  // key codes + scales
-    constexpr int VS = kTile + 4;           // bytes per rotated coordinate in the code staging area
+    constexpr int KBYTES = LY::vcodes_off;  // key codes + key scales (+ value scales)
+    constexpr int VST = kTile + 4;          // bytes per rotated coordinate in the code staging area
     __shared__ __align__(16) uint8_t kimg[KBYTES];
-    __shared__ __align__(16) uint8_t vstage[D * VS];  // value codes as bytes, [coordinate][token]
+    __shared__ __align__(16) uint8_t vstage[D * VST];  // value codes as bytes, [coordinate][token]
 
     const int tile = tok_begin / kTile + blockIdx.x, unit = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -89,7 +94,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
                 const int G = 4 * q + gi;
                 uint32_t lo, hi;
                 vcode_selectors(w0, w1, w2, gi, lo, hi);
-                uint8_t* dst = vstage + vcode_coord(G, lane) * VS + vcode_token(G, lane, 0);
+                uint8_t* dst = vstage + vcode_coord(G, lane) * VST + vcode_token(G, lane, 0);
                 *reinterpret_cast<uint32_t*>(dst) = lo;
                 *reinterpret_cast<uint32_t*>(dst + 8) = hi;
             }
@@ -152,13 +157,37 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
             y[2 * i] = __builtin_fmaf((float)b.h[0], eps, 0.0f);  // conversion and sign in one fma-mix
             y[2 * i + 1] = __builtin_fmaf((float)b.h[1], eps, 0.0f);
         }
+        // y = sqrt(D) * v_rot after the transform; the thresholds are scaled instead of the values.  The
+        // code is the number of thresholds below v_rot: 4 + n for positive values, 3 - n otherwise, with
+        // n the number of positive thresholds below |v_rot|.
+        float t1 = POLYKV_T1 * sqrt_d<D>(), t2 = POLYKV_T2 * sqrt_d<D>(), t3 = POLYKV_T3 * sqrt_d<D>();
+        float zref = 0.0f;  // what "positive" is measured against
+        if (VS) {
+            // |v|^2 over the 8 lanes of the token (the signs do not matter); every lane gets the same sum
+            float ss = 0.0f;
+#pragma unroll
+            for (int i = 0; i < EPT; ++i) ss = __builtin_fmaf(y[i], y[i], ss);
+            ss += lane_xor<1>(ss);
+            ss += lane_xor<2>(ss);
+            ss += __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(ss), __float_as_int(ss), 0x128, 0xF, 0xF,
+                                                               false));  // row_ror:8 = lane ^ 8
+            const float rms = __fsqrt_rn(ss * (1.0f / D));
+            const __half g16 = __float2half_rn(fminf(rms, 128.0f));
+            const float g = __half2float(g16);
+            t1 = t1 * g;
+            t2 = t2 * g;
+            t3 = t3 * g;
+            // a scale of zero stores the zero vector, code 3 everywhere: nothing counts as positive and no
+            // magnitude exceeds a threshold
+            if (!(g > 0.0f)) {
+                zref = INFINITY;
+                t1 = t2 = t3 = INFINITY;
+            }
+            if (c == 0 && !old_token) reinterpret_cast<__half*>(kimg + LY::vscales_off)[t] = g16;
+        }
         wht_cross_chunks<EPT>(y, lane);
         wht_inlane<EPT>(y);
-        // y = sqrt(D) * v_rot; the thresholds are scaled instead of the values.  The code is the number
-        // of thresholds below v_rot: 4 + n for positive values, 3 - n otherwise, with n the number of
-        // positive thresholds below |v_rot|.
-        constexpr float t1 = POLYKV_T1 * sqrt_d<D>(), t2 = POLYKV_T2 * sqrt_d<D>(), t3 = POLYKV_T3 * sqrt_d<D>();
-        uint8_t* dst = vstage + e0 * VS + t;
+        uint8_t* dst = vstage + e0 * VST + t;
 #pragma unroll
         for (int i = 0; i < EPT; ++i) {
             // Four compares into scalar masks, then a select and an add-with-carry chain.  On this target a
@@ -166,7 +195,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
             // that wrote it; the order below keeps that distance without padding.
             int n, m;
             unsigned long long sp, s1, s2, s3;
-            asm("v_cmp_lt_f32_e64 %2, 0, %6\n\t"
+            asm("v_cmp_lt_f32_e64 %2, %10, %6\n\t"
                 "v_cmp_gt_f32_e64 %3, |%6|, %7\n\t"
                 "v_cmp_gt_f32_e64 %4, |%6|, %8\n\t"
                 "v_cmp_gt_f32_e64 %5, |%6|, %9\n\t"
@@ -176,9 +205,9 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
                 "v_addc_co_u32_e64 %0, vcc, 0, %0, %5\n\t"
                 "v_xor_b32_e32 %0, %0, %1"
                 : "=&v"(n), "=&v"(m), "=&s"(sp), "=&s"(s1), "=&s"(s2), "=&s"(s3)
-                : "v"(y[i]), "v"(t1), "v"(t2), "v"(t3)
+                : "v"(y[i]), "v"(t1), "v"(t2), "v"(t3), "v"(zref)
                 : "vcc");
-            if (!old_token) dst[i * VS] = (uint8_t)n;
+            if (!old_token) dst[i * VST] = (uint8_t)n;
         }
     }
     __syncthreads();
@@ -190,7 +219,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
 #pragma unroll
         for (int gi = 0; gi < 4; ++gi) {
             const int G = 4 * q + gi;
-            const uint8_t* src = vstage + vcode_coord(G, lane) * VS + vcode_token(G, lane, 0);
+            const uint8_t* src = vstage + vcode_coord(G, lane) * VST + vcode_token(G, lane, 0);
             lo[gi] = *reinterpret_cast<const uint32_t*>(src);
             hi[gi] = *reinterpret_cast<const uint32_t*>(src + 8);
         }
@@ -210,10 +239,10 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------ decode ---
-template <int D>
+template <int D, bool VS>
 __device__ __forceinline__ void stage_tile(uint8_t* img, const uint8_t* pool, int unit, int tiles,
                                            int tile, int tid) {
-    using LY = Layout<D>;
+    using LY = Layout<D, VS>;
     const uint4* src = reinterpret_cast<const uint4*>(pool + ((size_t)unit * tiles + tile) * LY::tile_bytes);
     uint4* dst = reinterpret_cast<uint4*>(img);
     for (int i = tid; i < LY::tile_bytes / 16; i += 256) dst[i] = src[i];
@@ -248,12 +277,13 @@ template <int N> struct RowStore<float, N> {
 };
 
 // K = code * s and V = H c[code] / sqrt(d)  (sections "Compression Scheme" and "TurboQuant",
-// dequantization; the inverse of the normalized rotation is the same normalized transform).
-template <int D, typename OutT>
+// dequantization; the inverse of the normalized rotation is the same normalized transform); times the
+// vector's scale in the scaled-values codec (VS).
+template <int D, bool VS, typename OutT>
 __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ pool,
                                                      OutT* __restrict__ K_out, OutT* __restrict__ V_out,
                                                      int T, int tiles) {
-    using LY = Layout<D>;
+    using LY = Layout<D, VS>;
     constexpr int EPT = D / 8;
     constexpr int KBYTES = LY::vcodes_off;
     constexpr int CS = D + 8;  // halves per token row of the centroid staging area (16-byte aligned rows)
@@ -263,7 +293,11 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
     const int tile = blockIdx.x, unit = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63;
     const uint8_t* rec = pool + ((size_t)unit * tiles + tile) * LY::tile_bytes;
+    const CodecThread th(tid);
+    const int t = th.t, c = th.c;
 
+    float vscale = 1.0f;
+    if (VS && V_out != nullptr) vscale = (float)reinterpret_cast<const _Float16*>(rec + LY::vscales_off)[t];
     if (K_out != nullptr) {
         const uint4* src = reinterpret_cast<const uint4*>(rec);
         uint4* dst = reinterpret_cast<uint4*>(kimg);
@@ -299,8 +333,6 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
     }
     __syncthreads();
 
-    const CodecThread th(tid);
-    const int t = th.t, c = th.c;
     const int tok = tile * kTile + t;
     const bool valid = tok < T;
     const size_t row = ((size_t)unit * T + (valid ? tok : 0)) * D + c * EPT;
@@ -326,7 +358,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
     }
     if (V_out != nullptr) {
         // the centroid scale, 1/sqrt(D) and the entry sign of the cross-lane stages ride on the conversion
-        const float f = codec_entry_sign(lane) * (kInvCentroidScale * inv_sqrt_d<D>());
+        const float f = codec_entry_sign(lane) * (kInvCentroidScale * inv_sqrt_d<D>()) * vscale;
         float y[EPT];
 #pragma unroll
         for (int i = 0; i < EPT / 8; ++i) {
@@ -347,17 +379,18 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
 }
 
 // ------------------------------------------------------------------------------------ export ---
-template <int D>
+template <int D, bool VS>
 __global__ __launch_bounds__(256) void export_kernel(const uint8_t* __restrict__ pool,
                                                      int8_t* __restrict__ k_codes,
                                                      __half* __restrict__ k_scales,
-                                                     uint8_t* __restrict__ v_packed, int T, int tiles) {
-    using LY = Layout<D>;
+                                                     uint8_t* __restrict__ v_packed,
+                                                     __half* __restrict__ v_scales, int T, int tiles) {
+    using LY = Layout<D, VS>;
     constexpr int EPT = D / 8;
     __shared__ __align__(16) uint8_t img[LY::tile_bytes];
     const int tile = blockIdx.x, unit = blockIdx.y;
     const int tid = threadIdx.x, t = tid >> 3, c = tid & 7;
-    stage_tile<D>(img, pool, unit, tiles, tile, tid);
+    stage_tile<D, VS>(img, pool, unit, tiles, tile, tid);
     const int tok = tile * kTile + t;
     if (tok >= T) return;
     const size_t vec = (size_t)unit * T + tok;
@@ -371,6 +404,8 @@ __global__ __launch_bounds__(256) void export_kernel(const uint8_t* __restrict__
     }
     if (k_scales != nullptr && c < LY::NB)
         k_scales[vec * LY::NB + c] = reinterpret_cast<const __half*>(img + LY::kscales_off)[t * LY::NB + c];
+    if (VS && v_scales != nullptr && c == 0)
+        v_scales[vec] = reinterpret_cast<const __half*>(img + LY::vscales_off)[t];
     if (v_packed != nullptr) {
         const uint32_t* vreg = reinterpret_cast<const uint32_t*>(img + LY::vcodes_off);
         uint8_t* dst = v_packed + vec * (3 * D / 8) + 3 * e0 / 8;
@@ -387,15 +422,30 @@ __global__ __launch_bounds__(256) void export_kernel(const uint8_t* __restrict__
 }
 
 // ---------------------------------------------------------------------------------- launchers ---
+// Calls f(integral_constant<int, D>, integral_constant<bool, VS>) for the pool's head_dim and value codec.
+template <typename F> static void for_pool_shape(const polykv_pool* p, F&& f) {
+    using std::integral_constant;
+    const bool vs = p->value_codec == POLYKV_VALUES_TQ3_SCALED;
+    if (p->head_dim == 128) {
+        if (vs)
+            f(integral_constant<int, 128>{}, integral_constant<bool, true>{});
+        else
+            f(integral_constant<int, 128>{}, integral_constant<bool, false>{});
+    } else {
+        if (vs)
+            f(integral_constant<int, 64>{}, integral_constant<bool, true>{});
+        else
+            f(integral_constant<int, 64>{}, integral_constant<bool, false>{});
+    }
+}
+
 hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, int begin, int count, hipStream_t s) {
     const int end = begin + count;
     dim3 grid(tiles_of(end) - begin / kTile, p->layers * p->kv_heads);
-    if (p->head_dim == 128)
-        launch_main_kernel(encode_kernel<128>, grid, dim3(256), 0, s, (const __half*)K, (const __half*)V,
-                           (uint8_t*)p->storage, count, begin, end, p->tiles);
-    else
-        launch_main_kernel(encode_kernel<64>, grid, dim3(256), 0, s, (const __half*)K, (const __half*)V,
-                           (uint8_t*)p->storage, count, begin, end, p->tiles);
+    for_pool_shape(p, [&](auto d, auto vs) {
+        launch_main_kernel(encode_kernel<decltype(d)::value, decltype(vs)::value>, grid, dim3(256), 0, s, (const __half*)K,
+                           (const __half*)V, (uint8_t*)p->storage, count, begin, end, p->tiles);
+    });
     return hipGetLastError();
 }
 
@@ -403,31 +453,26 @@ hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dty
                          hipStream_t s) {
     dim3 grid(tiles_of(p->length), (layer_end - layer_begin) * p->kv_heads);  // the tokens encoded so far
     const uint8_t* pool = (const uint8_t*)p->storage + (size_t)layer_begin * p->kv_heads * p->tiles * p->tile_bytes;
-    if (p->head_dim == 128) {
+    for_pool_shape(p, [&](auto d, auto vs) {
+        constexpr int D = decltype(d)::value;
+        constexpr bool VS = decltype(vs)::value;
         if (dtype == POLYKV_F32)
-            launch_main_kernel(decode_kernel<128, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out, p->length,
-                               p->tiles);
+            launch_main_kernel(decode_kernel<D, VS, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out,
+                               p->length, p->tiles);
         else
-            launch_main_kernel(decode_kernel<128, __half>, grid, dim3(256), 0, s, pool, (__half*)K_out, (__half*)V_out, p->length,
-                               p->tiles);
-    } else {
-        if (dtype == POLYKV_F32)
-            launch_main_kernel(decode_kernel<64, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out, p->length,
-                               p->tiles);
-        else
-            launch_main_kernel(decode_kernel<64, __half>, grid, dim3(256), 0, s, pool, (__half*)K_out, (__half*)V_out, p->length,
-                               p->tiles);
-    }
+            launch_main_kernel(decode_kernel<D, VS, __half>, grid, dim3(256), 0, s, pool, (__half*)K_out, (__half*)V_out,
+                               p->length, p->tiles);
+    });
     return hipGetLastError();
 }
 
-hipError_t launch_export(const polykv_pool* p, void* kc, void* ks, void* vp, hipStream_t s) {
+hipError_t launch_export(const polykv_pool* p, void* kc, void* ks, void* vp, void* vs_out, hipStream_t s) {
     dim3 grid(tiles_of(p->length), p->layers * p->kv_heads);  // the tokens encoded so far
     const uint8_t* pool = (const uint8_t*)p->storage;
-    if (p->head_dim == 128)
-        export_kernel<128><<<grid, 256, 0, s>>>(pool, (int8_t*)kc, (__half*)ks, (uint8_t*)vp, p->length, p->tiles);
-    else
-        export_kernel<64><<<grid, 256, 0, s>>>(pool, (int8_t*)kc, (__half*)ks, (uint8_t*)vp, p->length, p->tiles);
+    for_pool_shape(p, [&](auto d, auto vs) {
+        export_kernel<decltype(d)::value, decltype(vs)::value>
+            <<<grid, 256, 0, s>>>(pool, (int8_t*)kc, (__half*)ks, (uint8_t*)vp, (__half*)vs_out, p->length, p->tiles);
+    });
     return hipGetLastError();
 }
 

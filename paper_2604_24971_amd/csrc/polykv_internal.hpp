@@ -9,6 +9,7 @@
 
 struct polykv_pool {
     int layers, kv_heads, head_dim, tokens;
+    int value_codec;    // POLYKV_VALUES_*
     int tiles;          // ceil(tokens / 32): tile records per (layer, KV head), the record stride
     size_t tile_bytes;  // bytes of one tile record
     size_t bytes;       // layers * kv_heads * tiles * tile_bytes
@@ -23,6 +24,7 @@ void set_error(const char* fmt, ...);
 // Everything pool_attend needs after validation; passed by value to the kernels.
 struct AttendPlan {
     int D, T, tiles, H;          // pool shape: T tokens encoded so far, in `tiles` tiles
+    int vscaled;                 // 1: the pool stores per-vector value scales (POLYKV_VALUES_TQ3_SCALED)
     int tiles_cap;               // tile records per (layer, KV head) in storage (the pool's capacity)
     int layer_begin, layers;     // selected layer range
     int A, nq, q_heads, G, R;    // R = A * nq * G query rows per KV head
@@ -45,7 +47,7 @@ struct TailPtrs {
 hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, int begin, int count, hipStream_t s);
 hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dtype, int layer_begin, int layer_end,
                          hipStream_t s);
-hipError_t launch_export(const polykv_pool* p, void* kc, void* ks, void* vp, hipStream_t s);
+hipError_t launch_export(const polykv_pool* p, void* kc, void* ks, void* vp, void* vs, hipStream_t s);
 hipError_t launch_attend(const polykv_pool* p, const AttendPlan& plan, const void* Q, void* out,
                          const TailPtrs* tails, void* workspace, hipStream_t s);
 

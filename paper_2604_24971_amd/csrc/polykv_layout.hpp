@@ -21,7 +21,13 @@
 //                              code e<4 : bits 1:0 = dword0 bits 8e+7:8e+6, bit 2 = dword1 bit 8e+6
 //                              code e>=4: bits 1:0 = dword2 bits 8(e-4)+7:8(e-4)+6, bit 2 = dword1 bit 8(e-4)+7
 //
-// Per token and KV head this is head_dim + head_dim/16 + 3*head_dim/8 bytes: 184 (d=128), 92 (d=64).
+//
+// With per-vector value scales (the scaled-values codec) a region of 32 fp16 scales, one per token,
+// sits between the key scales and the value codes:
+//   V scales  32 fp16        scale(token t) at index t.
+//
+// Per token and KV head this is head_dim + head_dim/16 + 3*head_dim/8 bytes: 184 (d=128), 92 (d=64),
+// plus 2 with value scales.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -30,12 +36,13 @@ namespace polykv {
 
 constexpr int kTile = 32;  // tokens per tile record
 
-template <int D> struct Layout {
+template <int D, bool VS = false> struct Layout {
     static constexpr int NB = D / 32;             // q8_0 blocks per vector
     static constexpr int NT = D / 64;             // value-code triplets per lane
     static constexpr int kcodes_off = 0;
     static constexpr int kscales_off = NB * 1024;
-    static constexpr int vcodes_off = kscales_off + kTile * NB * 2;
+    static constexpr int vscales_off = kscales_off + kTile * NB * 2;  // present only if VS
+    static constexpr int vcodes_off = vscales_off + (VS ? kTile * 2 : 0);
     static constexpr int tile_bytes = vcodes_off + NT * 768;
 };
 

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libpolykv.so")
 OK, EINVAL, ESHAPE, ESTATE, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
 F16, F32 = 0, 1
 KERNEL_AUTO, KERNEL_VECTOR, KERNEL_MATRIX = 0, 1, 2
+VALUES_TQ3, VALUES_TQ3_SCALED = 0, 1
 MAX_TAIL_AGENTS = 64
 
 
@@ -42,6 +43,8 @@ def _load():
     vp, ip, sz = C.c_void_p, C.c_int, C.c_size_t
     lib.pool_create.argtypes = [ip, ip, ip, ip, C.POINTER(vp)]
     lib.pool_create.restype = ip
+    lib.pool_create_codec.argtypes = [ip, ip, ip, ip, ip, C.POINTER(vp)]
+    lib.pool_create_codec.restype = ip
     lib.pool_destroy.argtypes = [vp]
     lib.pool_destroy.restype = None
     lib.pool_bytes.argtypes = [vp]
@@ -60,6 +63,8 @@ def _load():
     lib.pool_decode.restype = ip
     lib.pool_export.argtypes = [vp, vp, vp, vp, vp]
     lib.pool_export.restype = ip
+    lib.pool_export_value_scales.argtypes = [vp, vp, vp]
+    lib.pool_export_value_scales.restype = ip
     lib.pool_attend_workspace.argtypes = [vp, C.POINTER(AttendParams)]
     lib.pool_attend_workspace.restype = sz
     lib.pool_attend.argtypes = [vp, vp, vp, C.POINTER(AttendParams), vp]
@@ -150,11 +155,13 @@ class Tails:
 class Pool:
     """pool_create + pool_bind around a torch-owned storage tensor."""
 
-    def __init__(self, layers: int, kv_heads: int, head_dim: int, tokens: int, device="cuda:0"):
+    def __init__(self, layers: int, kv_heads: int, head_dim: int, tokens: int, device="cuda:0",
+                 value_codec: int = VALUES_TQ3):
         self.layers, self.kv_heads, self.head_dim, self.tokens = layers, kv_heads, head_dim, tokens
+        self.value_codec = value_codec
         self.device = torch.device(device)
         h = C.c_void_p()
-        _check(lib.pool_create(layers, kv_heads, head_dim, tokens, C.byref(h)))
+        _check(lib.pool_create_codec(layers, kv_heads, head_dim, tokens, value_codec, C.byref(h)))
         self._h = h
         self.nbytes = lib.pool_bytes(self._h)
         self.storage = None
@@ -217,6 +224,11 @@ class Pool:
         _check(lib.pool_export(self._h, C.c_void_p(kc.data_ptr()), C.c_void_p(ks.data_ptr()),
                                C.c_void_p(vp.data_ptr()), _stream_ptr(stream)))
         return kc, ks, vp
+
+    def export_value_scales(self, stream=None):
+        vs = torch.empty((self.layers, self.kv_heads, self.length), dtype=torch.float16, device=self.device)
+        _check(lib.pool_export_value_scales(self._h, C.c_void_p(vs.data_ptr()), _stream_ptr(stream)))
+        return vs
 
     def _params(self, Q, q_heads, layer_begin, layer_end, scale, tails, kernel, splits, tail_causal=False):
         if Q.dim() != 5:

@@ -2,6 +2,9 @@
 CPU oracle and compare to the stated bars:
   * stored codes / scales bit-exact, except elements whose pre-rounding value (oracle's) lies within
     1e-6 of a decision threshold, which may take the neighbouring code;
+  * scaled-values codec: the stored per-vector scale bit-exact, except vectors whose exact rms (oracle's,
+    fp64) lies within 1e-6 relative of the midpoint of two fp16 numbers, which may store either; the
+    codes of such a vector are then checked against the oracle's codes for the scale it stores;
   * dequantized K/V within 1e-3 relative, per vector, infinity norm;
   * attention output within 2e-3 absolute.
 """
@@ -12,6 +15,7 @@ from oracle import polykv_oracle as O
 from paper_2604_24971_amd import polykv as pk
 
 CODE_WINDOW = 1e-6
+SCALE_WINDOW = 1e-6
 DEQUANT_RTOL = 1e-3
 ATTEND_ATOL = 2e-3
 
@@ -20,18 +24,45 @@ def dev(x):
     return torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
 
 
-def gpu_pool(K, V):
+def gpu_pool(K, V, scaled_values=False):
     L, H, T, d = K.shape
-    pool = pk.Pool(L, H, d, T).bind()
+    pool = pk.Pool(L, H, d, T, value_codec=pk.VALUES_TQ3_SCALED if scaled_values else pk.VALUES_TQ3).bind()
     pool.storage.fill_(0xA5)            # stale bytes must never leak into results
     pool.encode(dev(K), dev(V))
     return pool
+
+
+def settle_value_scales(gs, ref):
+    """Scaled-values codec: compares the stored scales gs (the library's, fp16, shaped like ref's).  Where the library stores the other fp16 neighbour
+    of a vector's rms, and the rms is within SCALE_WINDOW of the midpoint (both roundings are then valid),
+    the reference is switched to the oracle's encoding with that neighbour.  Returns the number of
+    such vectors."""
+    g_ref = ref["v_scales"]
+    diff = gs.view(np.uint16) != g_ref.view(np.uint16)
+    if not diff.any():
+        return 0
+    rms = np.minimum(ref["v_rms"][diff], O.V_SCALE_MAX)
+    g0 = g_ref[diff]
+    toward = np.where(rms > g0.astype(np.float64), np.float16(np.inf), np.float16(-np.inf)).astype(np.float16)
+    alt = np.nextafter(g0, toward)                                   # the fp16 neighbour on the rms's side
+    mid = 0.5 * (g0.astype(np.float64) + alt.astype(np.float64))
+    assert np.all(np.abs(rms - mid) <= SCALE_WINDOW * rms), "value scale differs away from a rounding tie"
+    np.testing.assert_array_equal(gs[diff].view(np.uint16), alt.view(np.uint16))
+    ref["v_scales"] = g_ref.copy()
+    ref["v_scales"][diff] = alt
+    ref["v_idx"] = ref["v_idx"].copy()
+    ref["v_idx"][diff] = O.v_quantize_scaled(ref["v_rot"][diff], alt)
+    ref["v_packed"] = O.v_pack(ref["v_idx"])
+    return int(diff.sum())
 
 
 def compare_codes(pool, ref):
     """Returns a bool array [L, H] marking units where a (permitted) threshold mismatch occurred."""
     kc, ks, vp = (t.cpu().numpy() for t in pool.export())
     d = pool.head_dim
+    scaled = "v_scales" in ref
+    if scaled:
+        settle_value_scales(pool.export_value_scales().cpu().numpy(), ref)
     # scales: bit-exact
     np.testing.assert_array_equal(ks.view(np.uint16), ref["k_scales"].view(np.uint16))
     # key codes
@@ -45,7 +76,12 @@ def compare_codes(pool, ref):
     v_diff = v_idx != ref["v_idx"]
     if v_diff.any():
         _, t = O.codebook()
-        dist = np.min(np.abs(ref["v_rot"][v_diff][:, None] - t[None, :]), axis=1)
+        if scaled:   # thresholds and window in units of the vector's scale
+            g = np.broadcast_to(ref["v_scales"].astype(np.float64)[..., None], v_idx.shape)[v_diff]
+            assert np.all(g > 0)
+            dist = np.min(np.abs(ref["v_rot"][v_diff][:, None] - t[None, :] * g[:, None]), axis=1) / g
+        else:
+            dist = np.min(np.abs(ref["v_rot"][v_diff][:, None] - t[None, :]), axis=1)
         assert np.all(dist <= CODE_WINDOW), "value code differs away from a threshold (max dist %g)" % dist.max()
         assert np.all(np.abs(v_idx.astype(np.int32) - ref["v_idx"])[v_diff] == 1)
     # packed stream identical wherever the codes are

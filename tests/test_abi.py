@@ -25,7 +25,8 @@ def test_library_exports_every_declared_function():
     names = _declared_functions()
     assert {"pool_create", "pool_bytes", "pool_bind", "pool_encode", "pool_decode", "pool_export",
             "pool_attend_workspace", "pool_attend", "pool_destroy", "polykv_codebook",
-            "polykv_last_error", "pool_append", "pool_length", "pool_decode_layers", "polykv_time_next_kernel"} <= set(names)
+            "polykv_last_error", "pool_append", "pool_length", "pool_decode_layers", "polykv_time_next_kernel",
+            "pool_create_codec", "pool_export_value_scales"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -62,6 +63,22 @@ def test_create_validation_and_byte_counts():
     assert lib.pool_bytes(h) == O.stored_bytes(32, 8, 7200, 128)["packed"]
     lib.pool_destroy(h)
     lib.pool_destroy(None)
+
+
+def test_value_codec_choice_byte_counts_and_errors():
+    h = C.c_void_p()
+    assert lib.pool_create_codec(1, 1, 64, 10, 7, C.byref(h)) == pk.EINVAL and not h.value
+    for (L, H, d, T) in [(32, 8, 128, 4096), (1, 4, 64, 640)]:
+        assert lib.pool_create_codec(L, H, d, T, pk.VALUES_TQ3_SCALED, C.byref(h)) == pk.OK
+        assert lib.pool_bytes(h) == O.stored_bytes(L, H, T, d, scaled_values=True)["packed"]
+        lib.pool_destroy(h)
+        assert lib.pool_create_codec(L, H, d, T, pk.VALUES_TQ3, C.byref(h)) == pk.OK
+        assert lib.pool_bytes(h) == O.stored_bytes(L, H, T, d)["packed"]
+        lib.pool_destroy(h)
+    fake = C.c_void_p(0x10000)       # never dereferenced
+    assert lib.pool_create_codec(1, 1, 64, 10, pk.VALUES_TQ3_SCALED, C.byref(h)) == pk.OK
+    assert lib.pool_export_value_scales(h, fake, None) == pk.ESTATE   # nothing bound / encoded
+    lib.pool_destroy(h)
 
 
 def test_state_machine_and_argument_errors_without_gpu():
