@@ -26,6 +26,9 @@ What it follows (PolyKV paper, section "Compression Scheme" unless noted):
     section "TurboQuant" assumes rotated coordinates of unit variance, which a raw cache does not
     have): a per-vector scale g = fp16(min(rms(v), 128)) is stored next to the codes, the thresholds
     and centroids are multiplied by g.  See v_encode_scaled.
+  * Variant "int8 values": the uniform int8 value quantizer without rotation that the paper proposes
+    as an ablation (sections "Discussion" hypothesis and "Future Work"): the key formula applied to
+    each value vector with one scale per vector.  See v_encode_int8.
 
 Precision: float64 everywhere, except the steps whose float32/float16 rounding is
 part of the stored format (the fp16 block scale and the code decision of q8_0).
@@ -286,13 +289,48 @@ def v_decode_scaled(idx, g16):
 
 
 # --------------------------------------------------------------------------- #
+# Values, variant: uniform int8 without rotation (the paper's proposed ablation)
+# --------------------------------------------------------------------------- #
+def v_encode_int8(V):
+    """V: float16 [..., d] -> (codes int8 [..., d], scales float16 [...], pre float32 [..., d]).
+
+    The key quantizer's formula (section "Compression Scheme", key quantization) on each value vector,
+    one scale per vector: s = fp16(min(fp32(max|v|) / 127, V_SCALE_MAX)) (stored), codes formed with the
+    stored scale, inv = fp32(1)/fp32(s), q = clip(rint(fp32(v) * inv), -128, 127), ties to even; a zero
+    vector stores s = 0 and zero codes.  The cap is the same format limit as for the scaled variant:
+    only with max|v| > 127 * 128 does the clip act, and elements beyond the range saturate at code
+    127 or -128."""
+    V = np.asarray(V)
+    if V.dtype != np.float16:
+        raise TypeError("V must be float16")
+    v32 = V.astype(np.float32)
+    amax = np.max(np.abs(v32), axis=-1)
+    s16 = np.minimum((amax / np.float32(127.0)).astype(np.float32), np.float32(V_SCALE_MAX)).astype(np.float16)
+    s32 = s16.astype(np.float32)
+    with np.errstate(divide="ignore"):
+        inv = np.where(s32 > 0, np.float32(1.0) / s32, np.float32(0.0)).astype(np.float32)
+    pre = (v32 * inv[..., None]).astype(np.float32)
+    q = np.clip(np.rint(pre), -128, 127).astype(np.int8)
+    return q, s16, pre
+
+
+def v_decode_int8(codes, scales):
+    """V_dequant = q * s."""
+    return np.asarray(codes).astype(np.float64) * np.asarray(scales).astype(np.float64)[..., None]
+
+
+# --------------------------------------------------------------------------- #
 # Pool = encode of a whole [L, H, T, d] cache; decode back
 # --------------------------------------------------------------------------- #
-def pool_encode(K, V, scaled_values: bool = False):
+def pool_encode(K, V, scaled_values: bool = False, int8_values: bool = False):
     """K, V float16 [L, H, T, d] -> dict with the canonical stored arrays and the pre-rounding
     values a parity test needs to find elements that sit on a decision threshold."""
     k_codes, k_scales, k_pre = k_encode(K)
     out = {"k_codes": k_codes, "k_scales": k_scales, "k_pre": k_pre}
+    if int8_values:
+        v_codes, v_scales, v_pre = v_encode_int8(V)
+        out.update(v_codes=v_codes, v_scales=v_scales, v_pre=v_pre)
+        return out
     if scaled_values:
         v_idx, g16, v_rot, rms = v_encode_scaled(V)
         out.update(v_scales=g16, v_rms=rms)
@@ -303,19 +341,22 @@ def pool_encode(K, V, scaled_values: bool = False):
 
 
 def pool_decode(pool):
+    K_hat = k_decode(pool["k_codes"], pool["k_scales"])
+    if "v_codes" in pool:
+        return K_hat, v_decode_int8(pool["v_codes"], pool["v_scales"])
     d = pool["k_codes"].shape[-1]
     idx = v_unpack(pool["v_packed"], d)
     V_hat = v_decode_scaled(idx, pool["v_scales"]) if "v_scales" in pool else v_decode(idx)
-    return k_decode(pool["k_codes"], pool["k_scales"]), V_hat
+    return K_hat, V_hat
 
 
-def stored_bytes(L: int, H: int, T: int, d: int, scaled_values: bool = False) -> dict:
+def stored_bytes(L: int, H: int, T: int, d: int, scaled_values: bool = False, int8_values: bool = False) -> dict:
     """Byte accounting (section "Compression Scheme", paragraph "Compression ratio")."""
     n = L * H * T
     k_codes = n * d
     k_scales = n * (d // Q8_BLOCK) * 2
-    v_codes = n * d * V_BITS // 8
-    v_scales = n * 2 if scaled_values else 0
+    v_codes = n * d if int8_values else n * d * V_BITS // 8
+    v_scales = n * 2 if (scaled_values or int8_values) else 0
     dense16 = 2 * n * d * 2
     packed = k_codes + k_scales + v_codes + v_scales
     return {

@@ -487,3 +487,63 @@ def test_scaled_values_pool_roundtrip_and_bytes():
     assert np.mean((Vh - V.astype(np.float64)) ** 2) / np.mean(V.astype(np.float64) ** 2) < 0.05
     b = O.stored_bytes(32, 8, 4096, 128, scaled_values=True)
     assert b["packed"] == 32 * 8 * 4096 * 186 and abs(b["ratio_stored"] - 512 / 186) < 1e-12
+
+
+# ------------------------------------------------ value codec, int8 variant ---
+def test_int8_values_error_bound_extremes_and_bruteforce():
+    rng = np.random.default_rng(31)
+    d = 128
+    V = (rng.standard_normal((300, d)) * np.exp(rng.standard_normal((300, 1)))).astype(np.float16)
+    q, s, pre = O.v_encode_int8(V)
+    assert q.dtype == np.int8 and s.dtype == np.float16 and s.shape == (300,)
+    V64, s64 = V.astype(np.float64), s.astype(np.float64)
+    # one scale per vector = max|v|/127 to fp16 accuracy; the maximum maps to +-127; half-step error
+    np.testing.assert_allclose(s64 * 127, np.abs(V64).max(-1), rtol=2.0 ** -11)
+    assert np.all(np.abs(q.astype(np.int32)).max(-1) == 127) and q.min() >= -127
+    assert np.all(np.abs(O.v_decode_int8(q, s) - V64) <= s64[:, None] / 2 * (1 + 1e-6))
+    # brute force: the code is a nearest multiple of the stored scale (fp32 ties aside)
+    cand = np.arange(-128, 128, dtype=np.float64)
+    best = np.abs(V64[:40, :, None] - cand * s64[:40, None, None]).min(-1)
+    got = np.abs(V64[:40] - q[:40] * s64[:40, None])
+    near_tie = np.abs(np.abs(pre[:40] - np.floor(pre[:40])) - 0.5) < 1e-4
+    assert np.all((got <= best * (1 + 1e-9) + 1e-12) | near_tie) and near_tie.mean() < 0.01
+    # no rotation: a spike stays a spike, a constant stays a constant
+    one = np.zeros((1, d), dtype=np.float16); one[0, 9] = -3.0
+    q1, s1, _ = O.v_encode_int8(one)
+    assert q1[0, 9] == -127 and np.count_nonzero(q1) == 1 and O.v_decode_int8(q1, s1)[0, 9] == -127 * float(s1[0])
+    z, sz, _ = O.v_encode_int8(np.zeros((1, d), dtype=np.float16))
+    assert not z.any() and sz[0] == 0 and not O.v_decode_int8(z, sz).any()
+    # power-of-two scale invariance; ties to even with s = 1
+    q2, s2, _ = O.v_encode_int8((V.astype(np.float32) * 8).astype(np.float16))
+    np.testing.assert_array_equal(q2, q)
+    np.testing.assert_array_equal(s2.astype(np.float32), s.astype(np.float32) * 8)
+    blk = np.zeros((1, d), dtype=np.float16); blk[0, :5] = [127.0, 0.5, 1.5, 2.5, -0.5]
+    qt, st, _ = O.v_encode_int8(blk)
+    assert float(st[0]) == 1.0 and qt[0, :5].tolist() == [127, 0, 2, 2, 0]
+
+
+def test_int8_values_scale_cap_and_pool_roundtrip():
+    d = 64
+    v = np.zeros((1, d), dtype=np.float16)
+    v[0, :4] = [40000.0, -40000.0, 16256.0, 130.0]                  # 40000/127 > 128: the cap acts
+    q, s, _ = O.v_encode_int8(v)
+    assert float(s[0]) == 128.0 and q[0, :4].tolist() == [127, -128, 127, 1]
+    v[0, :2] = [16256.0, -16256.0]                                  # exactly at the cap: 16256/127 = 128
+    q, s, _ = O.v_encode_int8(v)
+    assert float(s[0]) == 128.0 and q[0, :3].tolist() == [127, -127, 127]
+    rng = np.random.default_rng(32)
+    K = rng.standard_normal((1, 2, 40, d)).astype(np.float16)
+    V = (rng.standard_normal((1, 2, 40, d)) * 3.0).astype(np.float16)
+    ref = O.pool_encode(K, V, int8_values=True)
+    assert ref["v_codes"].shape == V.shape and ref["v_scales"].shape == (1, 2, 40)
+    Kh, Vh = O.pool_decode(ref)
+    np.testing.assert_array_equal(Vh, ref["v_codes"].astype(np.float64) * ref["v_scales"].astype(np.float64)[..., None])
+    assert np.abs(Vh - V.astype(np.float64)).max() <= float(ref["v_scales"].max()) / 2 * (1 + 1e-6)
+    b = O.stored_bytes(32, 8, 4096, 128, int8_values=True)
+    assert b["packed"] == 32 * 8 * 4096 * (136 + 130) and abs(b["ratio_stored"] - 512 / 266) < 1e-12
+    # with head_dim 32 a vector is one q8_0 block: the key quantizer, re-called through its own entry point
+    V32 = rng.standard_normal((50, 32)).astype(np.float16)
+    qa, sa, _ = O.v_encode_int8(V32)
+    qb, sb, _ = O.k_encode(V32)
+    np.testing.assert_array_equal(qa, qb)
+    np.testing.assert_array_equal(sa, sb[:, 0])
