@@ -77,9 +77,9 @@ def main():
     ap.add_argument("--extras", action="store_true",
                     help="after the timed region also time a plain device copy and pool_attend launched back to back "
                          "(context only; off by default so that a profile of the default run holds the timed steps only)")
-    ap.add_argument("--scaled-values", action="store_true",
-                    help="use the scaled-values codec (a per-vector fp16 scale next to the value codes) instead of "
-                    "the paper's; a variant, not the headline configuration")
+    ap.add_argument("--value-codec", choices=("tq3", "tq3-scaled", "int8"), default="tq3",
+                    help="value codec: tq3 = the paper's (headline configuration); tq3-scaled = the same with a "
+                    "per-vector fp16 scale; int8 = uniform int8 without rotation (the paper's proposed ablation)")
     ap.add_argument("--phases", default="eda", help="subset of e(ncode) d(ecode) a(ttend) to run per step; "
                     "anything but the default is for profiling one kernel and is marked partial")
     args = ap.parse_args()
@@ -107,7 +107,7 @@ def main():
     out = torch.empty(Q.shape, dtype=torch.float32, device="cuda")
     Kd = torch.empty_like(K)
     Vd = torch.empty_like(V)
-    codec = pk.VALUES_TQ3_SCALED if args.scaled_values else pk.VALUES_TQ3
+    codec = {"tq3": pk.VALUES_TQ3, "tq3-scaled": pk.VALUES_TQ3_SCALED, "int8": pk.VALUES_INT8}[args.value_codec]
     pools = [pk.Pool(L, H, d, T, value_codec=codec).bind() for _ in range(max(1, args.pools))]
     tails = None
     if args.tail_len > 0:        # every agent has produced tail_len private tokens (fp16, uncompressed)
@@ -224,7 +224,8 @@ def main():
     k_enc, k_dec, k_att = kernel_time(0, "e", t_enc), kernel_time(1, "d", t_dec), kernel_time(2, "a", t_att)
 
     units = L * H
-    packed = units * T * (d + d // 16 + 3 * d // 8 + (2 if args.scaled_values else 0))   # algorithmic pool bytes
+    v_bytes = {"tq3": 3 * d // 8, "tq3-scaled": 3 * d // 8 + 2, "int8": d + 2}[args.value_codec]
+    packed = units * T * (d + d // 16 + v_bytes)                     # algorithmic pool bytes
     enc_bytes = units * T * 4 * d + packed
     dec_bytes = packed + units * T * 4 * d
     tail_bytes = cfg.agents * args.tail_len * units * 4 * d                    # fp16 K and V of every agent's tail
@@ -243,7 +244,7 @@ def main():
                        "; achieved = algorithmic bytes (packed pool + Q + out) / duration")
     traffic_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
                                 "attend_hbm_traffic_%s.txt" % cfg.name)
-    if os.path.exists(traffic_file) and not args.scaled_values:     # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel
+    if os.path.exists(traffic_file) and args.value_codec == "tq3":     # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel
         vals = dict(line.split()[:2] for line in open(traffic_file) if line.strip() and not line.startswith("#"))
         attend_roof["traffic"] = float(vals["hbm_bytes_per_launch"])
     else:
@@ -256,7 +257,7 @@ def main():
         "config": {"workload": cfg.name, "layers": L, "kv_heads": H, "q_heads": cfg.q_heads, "head_dim": d,
                    "tokens": T, "agents": cfg.agents, "q_per_agent": cfg.q_per_agent,
                    "rows_per_kv_head": cfg.rows_per_kv_head, "pool_bytes": packed, "pool_copies_rotated": len(pools),
-                   "value_codec": "tq3-scaled" if args.scaled_values else "tq3",
+                   "value_codec": args.value_codec,
                    "tail_len": args.tail_len, "tail_bytes": tail_bytes,
                    "attend_calls_per_step": L if args.per_layer else 1},
         "step": "pool_encode -> pool_decode(fp16) -> pool_attend, all layers",

@@ -55,8 +55,12 @@ enum { POLYKV_KERNEL_AUTO = 0, POLYKV_KERNEL_VECTOR = 1, POLYKV_KERNEL_MATRIX = 
  *                             its rotated coordinates are quantized in units of g (code = number of
  *                             thresholds t_k with t_k * g strictly below v_rot; all codes 3 if g = 0), so the
  *                             codebook sees the unit-variance coordinates that the analysis cited in section
- *                             "TurboQuant" assumes; V = g * H_d c[code] / sqrt(d).  Two more bytes per vector. */
-enum { POLYKV_VALUES_TQ3 = 0, POLYKV_VALUES_TQ3_SCALED = 1 };
+ *                             "TurboQuant" assumes; V = g * H_d c[code] / sqrt(d).  Two more bytes per vector.
+ *   POLYKV_VALUES_INT8        uniform int8 without rotation, the ablation proposed in sections "Discussion" and
+ *                             "Future Work": the key formula on each value vector with one scale per vector,
+ *                             s = fp16(min(max|v| / 127, 128)), code = clip(rint(v / s), -128, 127) formed with the
+ *                             stored s, V = code * s.  head_dim + 2 bytes per vector. */
+enum { POLYKV_VALUES_TQ3 = 0, POLYKV_VALUES_TQ3_SCALED = 1, POLYKV_VALUES_INT8 = 2 };
 
 /* Host descriptor for a pool of `layers` x `kv_heads` x `tokens` vectors of `head_dim` elements.
  * head_dim must be 64 or 128; all other dimensions >= 1.  (SharedKVPool, section "PolyKV
@@ -115,13 +119,15 @@ int pool_decode_layers(const polykv_pool* pool, void* K_out_dev, void* V_out_dev
  *   v_packed_dev uint8  [layers, kv_heads, pool_length(), 3*head_dim/8], little-endian bit stream:
  *                code j of a vector occupies stream bits 3j..3j+2, stream bit i is bit (i mod 8)
  *                of byte floor(i/8).
+ *                A POLYKV_VALUES_INT8 pool writes int8 [layers, kv_heads, pool_length(), head_dim] here,
+ *                the value codes themselves.
  * (The in-HBM layout is tiled for the attention kernel and is not part of the ABI.)  Any of the
  * three may be NULL. */
 int pool_export(const polykv_pool* pool, void* k_codes_dev, void* k_scales_dev, void* v_packed_dev,
                 void* stream);
 
-/* The per-vector value scales of a POLYKV_VALUES_TQ3_SCALED pool: v_scales_dev fp16
- * [layers, kv_heads, pool_length()].  POLYKV_ESTATE for a pool of another codec. */
+/* The per-vector value scales of a POLYKV_VALUES_TQ3_SCALED or POLYKV_VALUES_INT8 pool: v_scales_dev fp16
+ * [layers, kv_heads, pool_length()].  POLYKV_ESTATE for a pool of the paper's codec, which has none. */
 int pool_export_value_scales(const polykv_pool* pool, void* v_scales_dev, void* stream);
 
 /* Decode attention of N agents directly over the packed pool (replaces the paper's per-agent

@@ -74,7 +74,7 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
     AttendPlan& p = *plan;
     memset(&p, 0, sizeof(p));
     p.D = pool->head_dim;
-    p.vscaled = pool->value_codec == POLYKV_VALUES_TQ3_SCALED ? 1 : 0;
+    p.vcodec = pool->value_codec;
     p.T = pool->length;
     p.tiles = tiles_of(pool->length);
     p.tiles_cap = pool->tiles;
@@ -122,7 +122,8 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
         // tiles per wave -- below that the per-workgroup prologue, epilogue and the partials written for
         // the merge kernel cost more than the idle CUs (measured on one-layer calls of the Llama shape:
         // 16 splits of 8 tiles 16.8 us, 32 splits of 4 tiles 19.3 us).
-        const long groups = (long)units * ((p.R + 63) / 64);
+        const int block_rows = (p.vcodec == POLYKV_VALUES_INT8 && p.D == 128) ? 32 : 64;  // rows per workgroup
+        const long groups = (long)units * ((p.R + block_rows - 1) / block_rows);
         long want = (256 + groups - 1) / groups;
         if (want > cap_tiles / 8) want = cap_tiles / 8;
         if (prm->splits > 0) want = prm->splits;
@@ -161,7 +162,7 @@ int pool_create_codec(int layers, int kv_heads, int head_dim, int tokens, int va
         return POLYKV_EINVAL;
     }
     *out = nullptr;
-    if (value_codec != POLYKV_VALUES_TQ3 && value_codec != POLYKV_VALUES_TQ3_SCALED) {
+    if (value_codec < POLYKV_VALUES_TQ3 || value_codec > POLYKV_VALUES_INT8) {
         set_error("pool_create: unknown value codec %d", value_codec);
         return POLYKV_EINVAL;
     }
@@ -185,9 +186,9 @@ int pool_create_codec(int layers, int kv_heads, int head_dim, int tokens, int va
     p->tokens = tokens;
     p->tiles = tiles_of(tokens);
     p->value_codec = value_codec;
-    const bool vs = value_codec == POLYKV_VALUES_TQ3_SCALED;
-    p->tile_bytes = head_dim == 128 ? (vs ? Layout<128, true>::tile_bytes : Layout<128, false>::tile_bytes)
-                                    : (vs ? Layout<64, true>::tile_bytes : Layout<64, false>::tile_bytes);
+    const int tb128[3] = {Layout<128, 0>::tile_bytes, Layout<128, 1>::tile_bytes, Layout<128, 2>::tile_bytes};
+    const int tb64[3] = {Layout<64, 0>::tile_bytes, Layout<64, 1>::tile_bytes, Layout<64, 2>::tile_bytes};
+    p->tile_bytes = head_dim == 128 ? tb128[value_codec] : tb64[value_codec];
     p->bytes = (size_t)layers * kv_heads * p->tiles * p->tile_bytes;
     p->storage = nullptr;
     p->length = 0;
@@ -308,7 +309,7 @@ int pool_export(const polykv_pool* pool, void* k_codes_dev, void* k_scales_dev, 
 int pool_export_value_scales(const polykv_pool* pool, void* v_scales_dev, void* stream) {
     int rc = check_readable(pool, "pool_export_value_scales");
     if (rc != POLYKV_OK) return rc;
-    if (pool->value_codec != POLYKV_VALUES_TQ3_SCALED) {
+    if (pool->value_codec == POLYKV_VALUES_TQ3) {
         set_error("pool_export_value_scales: the pool's value codec stores no scales");
         return POLYKV_ESTATE;
     }

@@ -38,12 +38,13 @@ template <int N> struct __attribute__((aligned(2 * N))) HalfVecN { __half h[N]; 
 //   PV      lane = (half h, coordinate m) exactly as the value codes are stored: the lane owns the
 //           codes of 16 of the tile's tokens for coordinates 32*g + m and accumulates its share;
 //           the two lane halves are added once at the end.
-template <int D, bool VS>
+template <int D, int VC>
 __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __restrict__ pool,
                                                             const __half* __restrict__ Q,
                                                             float* __restrict__ ws_ml,
                                                             float* __restrict__ ws_o, AttendPlan p) {
-    using LY = Layout<D, VS>;
+    using LY = Layout<D, VC>;
+    constexpr bool VS = LY::has_vscales, V8 = VC == 2;
     constexpr int MT = D / 32;
     __shared__ __align__(16) float q_s[kRB][D];
     __shared__ __align__(16) float p_s[4][kRB][64];
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
             const uint8_t* tb = unit_base + (size_t)min(tile, p.tiles - 1) * LY::tile_bytes;
             float k[D];
             const __half* sc = reinterpret_cast<const __half*>(tb + LY::kscales_off) + tl * LY::NB;
-            // scaled-values codec: the token's value scale rides on its probability in the P.V sum
+            // codecs with a per-vector value scale: it rides on the token's probability in the P.V sum
             const float vscale = VS ? __half2float(reinterpret_cast<const __half*>(tb + LY::vscales_off)[tl]) : 1.0f;
 #pragma unroll
             for (int j = 0; j < LY::NB; ++j) {
@@ -129,6 +130,30 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
             const int tile = ch * 2 + sub;
             if (tile >= p.tiles) break;
             const uint32_t* vreg = reinterpret_cast<const uint32_t*>(unit_base + (size_t)tile * LY::tile_bytes + LY::vcodes_off);
+            if (V8) {
+                // int8 values: the lane's 16 bytes of coordinate group g, token 16ks + 8*e4 + 4*vh + e3 at byte 8ks + 4e4 + e3
+#pragma unroll
+                for (int g = 0; g < MT; ++g) {
+                    const uint4 raw = *reinterpret_cast<const uint4*>(vreg + g * 256 + lane * 4);
+                    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {  // x = 2*ks + e4
+                        float cv[4];
+#pragma unroll
+                        for (int e3 = 0; e3 < 4; ++e3) cv[e3] = (float)((int)((w[x] >> (8 * e3)) & 0xFF) - 128);
+                        const int tk = sub * 32 + 8 * x + 4 * vh;  // tokens tk .. tk+3
+#pragma unroll
+                        for (int r = 0; r < kRB; ++r) {
+                            const float4 pv = *reinterpret_cast<const float4*>(&p_s[wave][r][tk]);
+                            acc[r][g] = fmaf(pv.x, cv[0], acc[r][g]);
+                            acc[r][g] = fmaf(pv.y, cv[1], acc[r][g]);
+                            acc[r][g] = fmaf(pv.z, cv[2], acc[r][g]);
+                            acc[r][g] = fmaf(pv.w, cv[3], acc[r][g]);
+                        }
+                    }
+                }
+                continue;
+            }
 #pragma unroll
             for (int q = 0; q < LY::NT; ++q) {
                 uint32_t w[3];
@@ -394,10 +419,11 @@ __global__ __launch_bounds__(256) void attend_merge_kernel(const float* __restri
     const float invL = 1.0f / Lsum;
 #pragma unroll
     for (int i = 0; i < EPL; ++i) x[i] *= invL;
-    // Walsh-Hadamard over D = 64*EPL coordinates, coordinate = lane*EPL + i
-    wht_inlane<EPL>(x);
+    // Walsh-Hadamard over D = 64*EPL coordinates, coordinate = lane*EPL + i (int8 values were never rotated)
+    if (p.vcodec != POLYKV_VALUES_INT8) wht_inlane<EPL>(x);
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
+        if (p.vcodec == POLYKV_VALUES_INT8) break;
         x[i] = wht_lane_stage<1>(x[i], lane);
         x[i] = wht_lane_stage<2>(x[i], lane);
         x[i] = wht_lane_stage<4>(x[i], lane);
@@ -438,8 +464,10 @@ hipError_t launch_attend(const polykv_pool* pool, const AttendPlan& plan, const 
         if (matrix_kernel_direct(plan)) return hipSuccess;
     } else {
         dim3 grid(plan.nsplit / 4, units, (plan.R + kRB - 1) / kRB);
-        auto kern = plan.D == 128 ? (plan.vscaled ? attend_vector_kernel<128, true> : attend_vector_kernel<128, false>)
-                                  : (plan.vscaled ? attend_vector_kernel<64, true> : attend_vector_kernel<64, false>);
+        decltype(&attend_vector_kernel<128, 0>) table[2][3] = {
+            {attend_vector_kernel<64, 0>, attend_vector_kernel<64, 1>, attend_vector_kernel<64, 2>},
+            {attend_vector_kernel<128, 0>, attend_vector_kernel<128, 1>, attend_vector_kernel<128, 2>}};
+        auto kern = table[plan.D == 128][plan.vcodec];
         launch_main_kernel(kern, grid, dim3(256), 0, s, storage, (const __half*)Q, ws_ml, ws_o, plan);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }

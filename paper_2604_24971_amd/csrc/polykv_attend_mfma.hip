@@ -71,11 +71,12 @@ template <int D> struct RawK {
     uint4v k[D / 32];      // [j]: codes of token m, block j: elements 8h..8h+7 (x, y) and 16+8h.. (z, w)
     uint32_t sc[D / 64];   // fp16 scales of token m, blocks 0..NB-1
 };
-template <int D, bool VS> struct RawV {
-    uint32_t w[D / 64][3];
-    // scaled-values codec: the value scales of the lane's 16 tokens as fp16 pairs, in the order in which
+template <int D, int VC> struct RawV {
+    uint32_t w[VC == 2 ? 1 : D / 64][3];  // 3-bit codecs: the lane's code triplets
+    uint4v c[VC == 2 ? D / 32 : 1];       // int8 codec: the lane's 16 code bytes of every coordinate group
+    // codecs with value scales: the scales of the lane's 16 tokens as fp16 pairs, in the order in which
     // the lane holds their probabilities (tokens 8b + 4h + {0,1} in g[2b], + {2,3} in g[2b+1])
-    uint32_t g[VS ? 8 : 1];
+    uint32_t g[VC != 0 ? 8 : 1];
 };
 
 // `tile` is wave-uniform and the lane's share sits at a 32-bit offset from it, so every load can use
@@ -87,14 +88,20 @@ template <int D> __device__ __forceinline__ void load_rawk(RawK<D>& r, const uin
 #pragma unroll
     for (int j = 0; j < D / 32; ++j) r.k[j] = *reinterpret_cast<const uint4v*>(tile + koff + j * 1024);
 }
-template <int D, bool VS> __device__ __forceinline__ void load_rawv(RawV<D, VS>& r, const uint8_t* tile, int lane) {
-    const uint32_t voff = Layout<D, VS>::vcodes_off + (uint32_t)lane * 12;
+template <int D, int VC> __device__ __forceinline__ void load_rawv(RawV<D, VC>& r, const uint8_t* tile, int lane) {
+    if (VC == 2) {
+        const uint32_t voff = Layout<D, VC>::vcodes_off + (uint32_t)lane * 16;
 #pragma unroll
-    for (int q = 0; q < D / 64; ++q)
+        for (int g = 0; g < D / 32; ++g) r.c[g] = *reinterpret_cast<const uint4v*>(tile + voff + g * 1024);
+    } else {
+        const uint32_t voff = Layout<D, VC>::vcodes_off + (uint32_t)lane * 12;
 #pragma unroll
-        for (int w = 0; w < 3; ++w) r.w[q][w] = *reinterpret_cast<const uint32_t*>(tile + voff + q * 768 + 4 * w);
-    if (VS) {
-        const uint32_t goff = Layout<D, VS>::vscales_off + (uint32_t)(lane >> 5) * 8;
+        for (int q = 0; q < D / 64; ++q)
+#pragma unroll
+            for (int w = 0; w < 3; ++w) r.w[q][w] = *reinterpret_cast<const uint32_t*>(tile + voff + q * 768 + 4 * w);
+    }
+    if (VC != 0) {
+        const uint32_t goff = Layout<D, VC>::vscales_off + (uint32_t)(lane >> 5) * 8;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             const uint2 two = *reinterpret_cast<const uint2*>(tile + goff + 16 * b);
@@ -122,7 +129,15 @@ __device__ __forceinline__ void key_split(const RawK<D>& rk, int j, int s, half8
 }
 
 // Value group G of a lane: eight 3-bit codes -> fp16 centroids, the A operand of one P.V product.
-template <int D, bool VS> __device__ __forceinline__ void value_group(const RawV<D, VS>& rv, int G, H8& va) {
+template <int D, int VC> __device__ __forceinline__ void value_group(const RawV<D, VC>& rv, int G, H8& va) {
+    if (VC == 2) {
+        // int8 codes of coordinate group G/2, token half G%2 -> exact fp16 integers (the scale rides on P)
+        const uint4v& c = rv.c[G >> 1];
+        codes4_to_half((G & 1) == 0 ? c.x : c.z, va.u[0], va.u[1]);
+        codes4_to_half((G & 1) == 0 ? c.y : c.w, va.u[2], va.u[3]);
+        va.h = va.h - (_Float16)1152.0f;
+        return;
+    }
     uint32_t sel_a, sel_b;
     vcode_selectors(rv.w[G >> 2][0], rv.w[G >> 2][1], rv.w[G >> 2][2], G & 3, sel_a, sel_b);
     lookup4(sel_a, va.u[0], va.u[1]);
@@ -164,7 +179,7 @@ __device__ __forceinline__ void exp4(const float16v& S, int c, float qscale, flo
 
 // The pool's last tile when it crosses the end of the pool, read straight from memory: scores, softmax
 // and PV one after the other, tokens >= T masked out.  Runs at most once per KV head.
-template <int D, int NT, bool VS>
+template <int D, int NT, int VC>
 __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile, int T, float qscale, float raise_thr,
                                                  int lane, const half8 (&qb)[NT][D / 32][2], float16v (&O)[D / 32][NT],
                                                  float (&Lsum)[NT], float (&m_ref)[NT], float (&m_thr)[NT],
@@ -172,9 +187,9 @@ __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile,
     constexpr int NB = D / 32, NG = D / 16;
     const int h = lane >> 5;
     RawK<D> rk;
-    RawV<D, VS> rv;
+    RawV<D, VC> rv;
     load_rawk<D>(rk, lt, lane);
-    load_rawv<D, VS>(rv, lt, lane);
+    load_rawv<D, VC>(rv, lt, lane);
     float16v S[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
@@ -211,12 +226,12 @@ __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile,
 #pragma unroll
         for (int g = 0; g < D / 32; ++g) O[g][nt] *= alpha;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) exp4<VS>(S[nt], c, qscale, mneg[nt], pb[nt], Lsum[nt], rv.g);
+        for (int c = 0; c < 4; ++c) exp4<VC != 0>(S[nt], c, qscale, mneg[nt], pb[nt], Lsum[nt], rv.g);
     }
 #pragma unroll
     for (int G = 0; G < NG; ++G) {
         H8 va;
-        value_group<D, VS>(rv, G, va);
+        value_group<D, VC>(rv, G, va);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) O[G >> 1][nt] = mfma32(va.h, pb[nt][G & 1].h, O[G >> 1][nt]);
     }
@@ -234,8 +249,8 @@ __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile,
 //   Sa         scores of tile A on entry, of tile B on exit; mloc / raise: per-lane row maxima of the
 //              same tile and whether some row outgrew the reference
 // Only full tiles go through here; a ragged last tile is handled by process_ragged_tile.
-template <int D, int NT, bool VS, bool HAS_A, bool HAS_B>
-__device__ __forceinline__ void pipeline_step(const RawV<D, VS>& rv, const RawK<D>& rk, RawV<D, VS>& rvN, RawK<D>& rkN,
+template <int D, int NT, int VC, bool HAS_A, bool HAS_B>
+__device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<D>& rk, RawV<D, VC>& rvN, RawK<D>& rkN,
                                               const uint8_t* nextK, const uint8_t* nextV, float qscale,
                                               float raise_thr, int lane, const half8 (&qb)[NT][D / 32][2],
                                               float16v (&O)[D / 32][NT], float (&Lsum)[NT], float (&m_ref)[NT],
@@ -293,13 +308,13 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VS>& rv, const RawK<
     // The next step's bytes are requested first thing, into the other set of registers, so that every
     // load has the whole step (and more, for all but the first key block) to land.
     if (HAS_B) load_rawk<D>(rkN, nextK, lane);
-    load_rawv<D, VS>(rvN, nextV, lane);
+    load_rawv<D, VC>(rvN, nextV, lane);
     __builtin_amdgcn_sched_barrier(0);
 
     H8 pb[NT][2];      // probabilities of tile A: B operands of the P.V products, [row tile][k slice]
     half8 khi[2], klo[2];
     H8 va[2];
-    auto exp_chunk = [&](int c) { exp4<VS>(Sa[c >> 2], c & 3, qscale, mneg[c >> 2], pb[c >> 2], Lsum[c >> 2], rv.g); };
+    auto exp_chunk = [&](int c) { exp4<VC != 0>(Sa[c >> 2], c & 3, qscale, mneg[c >> 2], pb[c >> 2], Lsum[c >> 2], rv.g); };
     auto kdeq = [&](int k) { key_split<D>(rk, k >> 1, k & 1, khi[k & 1], klo[k & 1]); };
     auto qk = [&](int k) {
         const int j = k >> 1, s = k & 1;
@@ -308,7 +323,7 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VS>& rv, const RawK<
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) Sb[nt] = mfma32(klo[k & 1], qb[nt][j][s], Sb[nt]);
     };
-    auto vdeq = [&](int G) { value_group<D, VS>(rv, G, va[G & 1]); };
+    auto vdeq = [&](int G) { value_group<D, VC>(rv, G, va[G & 1]); };
     auto pv = [&](int G) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) O[G >> 1][nt] = mfma32(va[G & 1].h, pb[nt][G & 1].h, O[G >> 1][nt]);
@@ -368,12 +383,12 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VS>& rv, const RawK<
     }
 }
 
-template <int D, int NT, bool VS>
+template <int D, int NT, int VC>
 __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restrict__ pool,
                                                           const __half* __restrict__ Q,
                                                           float* __restrict__ ws_ml, float* __restrict__ ws_o,
                                                           float* __restrict__ out, AttendPlan p, int direct) {
-    using LY = Layout<D, VS>;
+    using LY = Layout<D, VC>;
     constexpr int NB = D / 32, MG = D / 32, ROWS = 32 * NT;
     constexpr int OSTRIDE = D + 4;
     constexpr int TB = LY::tile_bytes;
@@ -401,10 +416,10 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     const int last_k = max(my_count - 1, 0);
     auto tile_ptr = [&](int k) { return wave_base + (uint32_t)min(k, last_k) * (uint32_t)(4 * TB); };
     RawK<D> rk;
-    RawV<D, VS> rv;
+    RawV<D, VC> rv;
     if (my_count > 0) {
         load_rawk<D>(rk, tile_ptr(0), lane);
-        load_rawv<D, VS>(rv, tile_ptr(0), lane);
+        load_rawv<D, VC>(rv, tile_ptr(0), lane);
     }
 
     // ---- query rows as MFMA B operands: lane (n, h) holds q[row 32nt+n][32j + 16s + 8h .. +7].
@@ -457,29 +472,29 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     if (full_count > 0) {
         // register sets: (rk, rv) and (rk2, rv2) alternate between "current" and "being loaded"
         RawK<D> rk2;
-        RawV<D, VS> rv2;
+        RawV<D, VC> rv2;
         // prologue: scores of tile 0 from rk; requests K of tile 1 and (again) V of tile 0 into set 2
-        pipeline_step<D, NT, VS, false, true>(rv, rk, rv2, rk2, tile_ptr(1), tile_ptr(0), qscale, raise_thr, lane, qb, O, Lsum,
+        pipeline_step<D, NT, VC, false, true>(rv, rk, rv2, rk2, tile_ptr(1), tile_ptr(0), qscale, raise_thr, lane, qb, O, Lsum,
                                           m_ref, m_thr, mneg, S, mloc, raise);
         int s = 0;
         for (; s + 1 < full_count - 1; s += 2) {  // two steps per trip: the sets swap roles without copies
-            pipeline_step<D, NT, VS, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
-            pipeline_step<D, NT, VS, true, true>(rv, rk, rv2, rk2, tile_ptr(s + 3), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, true, true>(rv, rk, rv2, rk2, tile_ptr(s + 3), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         }
         if (s < full_count - 1) {  // one step with a B tile left: current = set 2
-            pipeline_step<D, NT, VS, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
-            pipeline_step<D, NT, VS, true, false>(rv, rk, rv2, rk2, tile_ptr(s + 2), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, true, false>(rv, rk, rv2, rk2, tile_ptr(s + 2), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
                                               O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         } else {
-            pipeline_step<D, NT, VS, true, false>(rv2, rk2, rv, rk, tile_ptr(s + 1), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, true, false>(rv2, rk2, rv, rk, tile_ptr(s + 1), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
                                               O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         }
     }
     if (last_ragged)
-        process_ragged_tile<D, NT, VS>(tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
+        process_ragged_tile<D, NT, VC>(tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
                                    Lsum, m_ref, m_thr, mneg);
 
     // ---- merge the four waves through LDS: every wave stores its accumulators, rescaled to the
@@ -521,9 +536,11 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         const float Mr = fmaxf(fmaxf(m_s[0][rr], m_s[1][rr]), fmaxf(m_s[2][rr], m_s[3][rr]));
         const float l = (l_s[rr] + l_s[ROWS + rr]) + (l_s[2 * ROWS + rr] + l_s[3 * ROWS + rr]);
         // direct: 1/l, the centroid scale, 1/sqrt(D) and the entry sign of the DPP stages in one factor
-        const float f = direct ? quad_entry_sign(lane) * (kInvCentroidScale * (D == 64 ? 0.125f : 0.08838834764831845f)) *
-                                     __builtin_amdgcn_rcpf(l)
-                               : kInvCentroidScale;
+        // int8 values are accumulated unrotated and unscaled: 1/l is all that is left to do
+        const float f = VC == 2 ? (direct ? __builtin_amdgcn_rcpf(l) : 1.0f)
+                        : direct ? quad_entry_sign(lane) * (kInvCentroidScale * (D == 64 ? 0.125f : 0.08838834764831845f)) *
+                                       __builtin_amdgcn_rcpf(l)
+                                 : kInvCentroidScale;
         float x[CPL];
         const float4* a4 = reinterpret_cast<const float4*>(&o_s[rr * OSTRIDE + qd * CPL]);
         constexpr int BUF4 = ROWS * OSTRIDE / 4;  // one wave's buffer, in float4 units
@@ -536,8 +553,10 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
             x[4 * i + 3] = ((a.w + b.w) + (c.w + d.w)) * f;
         }
         if (direct) {
-            wht_cross_quad<CPL>(x, lane);
-            wht_inlane<CPL>(x);
+            if (VC != 2) {
+                wht_cross_quad<CPL>(x, lane);
+                wht_inlane<CPL>(x);
+            }
             if (r < p.R) {
                 float4* dst = reinterpret_cast<float4*>(out + q_row_index(p, ls, kvh, r) * D + qd * CPL);
 #pragma unroll
@@ -562,11 +581,11 @@ bool matrix_kernel_supports(int head_dim, int rows_per_kv_head) {
 
 bool matrix_kernel_direct(const AttendPlan& plan) { return plan.nsplit == 1 && !plan.has_tails; }
 
-template <int D, int NT, bool VS>
+template <int D, int NT, int VC>
 static hipError_t launch_one(dim3 grid, const uint8_t* storage, const AttendPlan& plan, const void* Q, float* ws_ml,
                              float* ws_o, float* out, int direct, hipStream_t s) {
     constexpr int kMergeBytes = 4 * 32 * NT * (D + 4) * (int)sizeof(float);
-    auto kern = attend_mfma_kernel<D, NT, VS>;
+    auto kern = attend_mfma_kernel<D, NT, VC>;
     static bool configured = false;  // per instantiation: the limit is a property of the function
     if (!configured && kMergeBytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -585,12 +604,20 @@ static hipError_t launch_d(const polykv_pool* pool, const AttendPlan& plan, cons
     const int units = plan.layers * plan.H;
     const int direct = matrix_kernel_direct(plan) ? 1 : 0;
     const dim3 grid1(plan.nsplit, units, 1), grid2(plan.nsplit, units, (plan.R + 63) / 64);
-    if (plan.vscaled) {
-        if (plan.R <= 32) return launch_one<D, 1, true>(grid1, storage, plan, Q, ws_ml, ws_o, out, direct, s);
-        return launch_one<D, 2, true>(grid2, storage, plan, Q, ws_ml, ws_o, out, direct, s);
+    if (plan.vcodec == POLYKV_VALUES_TQ3_SCALED) {
+        if (plan.R <= 32) return launch_one<D, 1, 1>(grid1, storage, plan, Q, ws_ml, ws_o, out, direct, s);
+        return launch_one<D, 2, 1>(grid2, storage, plan, Q, ws_ml, ws_o, out, direct, s);
     }
-    if (plan.R <= 32) return launch_one<D, 1, false>(grid1, storage, plan, Q, ws_ml, ws_o, out, direct, s);
-    return launch_one<D, 2, false>(grid2, storage, plan, Q, ws_ml, ws_o, out, direct, s);
+    if (plan.vcodec == POLYKV_VALUES_INT8) {
+        // At head_dim 128 the staged int8 value codes (16 registers per tile, twice) do not fit beside 64
+        // rows of accumulators: that shape runs blocks of 32 rows.
+        if (D == 128 || plan.R <= 32)
+            return launch_one<D, 1, 2>(dim3(plan.nsplit, units, (plan.R + 31) / 32), storage, plan, Q, ws_ml, ws_o, out,
+                                       direct, s);
+        if constexpr (D != 128) return launch_one<D, 2, 2>(grid2, storage, plan, Q, ws_ml, ws_o, out, direct, s);
+    }
+    if (plan.R <= 32) return launch_one<D, 1, 0>(grid1, storage, plan, Q, ws_ml, ws_o, out, direct, s);
+    return launch_one<D, 2, 0>(grid2, storage, plan, Q, ws_ml, ws_o, out, direct, s);
 }
 
 hipError_t launch_attend_matrix(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,

@@ -41,10 +41,13 @@ struct CodecThread {
 
 // ------------------------------------------------------------------------------------ encode ---
 // Key quantization and value quantization of section "Compression Scheme", fused in one pass.
-// VS: the scaled-values codec.  Each value vector also stores g = fp16(min(rms, 128)), rms = |v|/sqrt(D),
+// VC = 1, the scaled-values codec: each value vector also stores g = fp16(min(rms, 128)), rms = |v|/sqrt(D),
 // and its rotated coordinates are quantized in units of g, which gives the codebook the unit-variance
 // input that the analysis of section "TurboQuant" assumes.
-template <int D, bool VS>
+// VC = 2, int8 values: no rotation; the key formula on the whole vector with one scale per vector,
+// s = fp16(min(max|v|/127, 128)) (the uniform int8 ablation proposed in sections "Discussion" and
+// "Future Work").
+template <int D, int VC>
 __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ K,
                                                      const __half* __restrict__ V,
                                                      uint8_t* __restrict__ pool, int in_tokens, int tok_begin,
@@ -53,7 +56,8 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
     // [tok_begin, tok_end).  blockIdx.x counts tiles from the first one touched.  Tokens of that tile that
     // lie before tok_begin were encoded earlier and are carried over; tokens from tok_end on are padding
     // and are encoded as zeros.
-    using LY = Layout<D, VS>;
+    using LY = Layout<D, VC>;
+    constexpr bool VS = VC == 1, V8 = VC == 2;
     constexpr int EPT = D / 8;
     constexpr int KBYTES = LY::vcodes_off;  // key codes + key scales (+ value scales)
     constexpr int VST = kTile + 4;          // bytes per rotated coordinate in the code staging area
@@ -85,7 +89,17 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         // are overwritten below)
         const uint4* src = reinterpret_cast<const uint4*>(rec);
         for (int i = tid; i < KBYTES / 16; i += 256) reinterpret_cast<uint4*>(kimg)[i] = src[i];
-        if (tid < LY::NT * 64) {
+        if (V8) {
+            if (tid < LY::NB * 64) {
+                const int g = tid >> 6;
+                const uint4 w = *reinterpret_cast<const uint4*>(rec + LY::vcodes_off + g * 1024 + lane * 16);
+                uint8_t* dst = vstage + (32 * g + (lane & 31)) * VST + 4 * (lane >> 5);  // tokens 4h.., 8+4h.., 16+4h.., 24+4h..
+                *reinterpret_cast<uint32_t*>(dst) = w.x;
+                *reinterpret_cast<uint32_t*>(dst + 8) = w.y;
+                *reinterpret_cast<uint32_t*>(dst + 16) = w.z;
+                *reinterpret_cast<uint32_t*>(dst + 24) = w.w;
+            }
+        } else if (tid < LY::NT * 64) {
             const int q = tid >> 6;
             const uint32_t* w = reinterpret_cast<const uint32_t*>(rec + LY::vcodes_off + q * 768 + lane * 12);
             const uint32_t w0 = w[0], w1 = w[1], w2 = w[2];
@@ -146,8 +160,37 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
             reinterpret_cast<__half*>(kimg + LY::kscales_off)[t * LY::NB + j] = s16;
     }
 
+    // ---- values, int8 codec: vector absmax -> fp16 scale -> codes with the stored scale, staged as bytes
+    if (V8) {
+        float v[EPT];
+#pragma unroll
+        for (int i = 0; i < EPT / 2; ++i) {
+            Half2Bits b;
+            b.u = reinterpret_cast<const uint32_t*>(vraw)[i];
+            v[2 * i] = (float)b.h[0];
+            v[2 * i + 1] = (float)b.h[1];
+        }
+        float amax = 0.0f;
+#pragma unroll
+        for (int i = 0; i < EPT; i += 2) amax = fmaxf(fmaxf(fabsf(v[i]), fabsf(v[i + 1])), amax);
+        amax = fmaxf(amax, lane_xor<1>(amax));
+        amax = fmaxf(amax, lane_xor<2>(amax));
+        amax = fmaxf(amax, lane_xor<8>(amax));
+        const __half s16 = __float2half_rn(fminf(__fdiv_rn(amax, 127.0f), 128.0f));
+        const float sf = __half2float(s16);
+        const float inv = sf > 0.0f ? __fdiv_rn(1.0f, sf) : 0.0f;
+        constexpr float kMagic = 12582912.0f + 128.0f;  // as for the keys: the low byte is round(v * inv) + 128
+        uint8_t* dst = vstage + e0 * VST + t;
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+            const float q = v[i] * inv + kMagic;
+            const uint32_t r = __float_as_uint(__builtin_amdgcn_fmed3f(q, kMagic - 128.0f, kMagic + 127.0f));
+            if (!old_token) dst[i * VST] = (uint8_t)r;
+        }
+        if (c == 0 && !old_token) reinterpret_cast<__half*>(kimg + LY::vscales_off)[t] = s16;
+    }
     // ---- values: rotate, nearest centroid, stage the codes as bytes [coordinate][token]
-    {
+    if (!V8) {
         const float eps = codec_entry_sign(lane);
         float y[EPT];
 #pragma unroll
@@ -212,8 +255,20 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
     }
     __syncthreads();
 
-    // ---- bit-pack the value codes: one lane triplet (three dwords, four coordinate groups) per thread
-    if (tid < LY::NT * 64) {
+    // ---- int8 values: one lane's 16 bytes of a coordinate group per thread, in P.V operand order
+    if (V8) {
+        if (tid < LY::NB * 64) {
+            const int g = tid >> 6;
+            const uint8_t* src = vstage + (32 * g + (lane & 31)) * VST + 4 * (lane >> 5);
+            uint4 w;
+            w.x = *reinterpret_cast<const uint32_t*>(src);
+            w.y = *reinterpret_cast<const uint32_t*>(src + 8);
+            w.z = *reinterpret_cast<const uint32_t*>(src + 16);
+            w.w = *reinterpret_cast<const uint32_t*>(src + 24);
+            *reinterpret_cast<uint4*>(rec + LY::vcodes_off + g * 1024 + lane * 16) = w;
+        }
+    } else if (tid < LY::NT * 64) {
+        // ---- bit-pack the value codes: one lane triplet (three dwords, four coordinate groups) per thread
         const int q = tid >> 6;
         uint32_t lo[4], hi[4];  // codes e = 0..3 and e = 4..7 of each group, one per byte (consecutive tokens)
 #pragma unroll
@@ -239,10 +294,10 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------ decode ---
-template <int D, bool VS>
+template <int D, int VC>
 __device__ __forceinline__ void stage_tile(uint8_t* img, const uint8_t* pool, int unit, int tiles,
                                            int tile, int tid) {
-    using LY = Layout<D, VS>;
+    using LY = Layout<D, VC>;
     const uint4* src = reinterpret_cast<const uint4*>(pool + ((size_t)unit * tiles + tile) * LY::tile_bytes);
     uint4* dst = reinterpret_cast<uint4*>(img);
     for (int i = tid; i < LY::tile_bytes / 16; i += 256) dst[i] = src[i];
@@ -278,17 +333,21 @@ template <int N> struct RowStore<float, N> {
 
 // K = code * s and V = H c[code] / sqrt(d)  (sections "Compression Scheme" and "TurboQuant",
 // dequantization; the inverse of the normalized rotation is the same normalized transform); times the
-// vector's scale in the scaled-values codec (VS).
-template <int D, bool VS, typename OutT>
+// vector's scale in the scaled-values codec (VC = 1).  Int8 values (VC = 2): V = code * s, no rotation.
+template <int D, int VC, typename OutT>
 __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ pool,
                                                      OutT* __restrict__ K_out, OutT* __restrict__ V_out,
                                                      int T, int tiles) {
-    using LY = Layout<D, VS>;
+    using LY = Layout<D, VC>;
     constexpr int EPT = D / 8;
     constexpr int KBYTES = LY::vcodes_off;
+    constexpr bool VS = LY::has_vscales, V8 = VC == 2;
     constexpr int CS = D + 8;  // halves per token row of the centroid staging area (16-byte aligned rows)
+    constexpr int VST = kTile + 4;  // int8 values: bytes per coordinate of the code staging area
     __shared__ __align__(16) uint8_t kimg[KBYTES];
-    __shared__ __align__(16) _Float16 cent[kTile * CS];  // fp16 centroids (scaled), [token][coordinate]
+    // 3-bit codecs: fp16 centroids (scaled), [token][coordinate]; int8 codec: code bytes, [coordinate][token]
+    __shared__ __align__(16) uint8_t vbuf[V8 ? D * VST : kTile * CS * 2];
+    _Float16* cent = reinterpret_cast<_Float16*>(vbuf);
 
     const int tile = blockIdx.x, unit = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -303,7 +362,17 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
         uint4* dst = reinterpret_cast<uint4*>(kimg);
         for (int i = tid; i < KBYTES / 16; i += 256) dst[i] = src[i];
     }
-    if (V_out != nullptr && tid < LY::NT * 128) {
+    if (V8) {
+        if (V_out != nullptr && tid < LY::NB * 64) {
+            const int g = tid >> 6;
+            const uint4 w = *reinterpret_cast<const uint4*>(rec + LY::vcodes_off + g * 1024 + lane * 16);
+            uint8_t* dst = vbuf + (32 * g + (lane & 31)) * VST + 4 * (lane >> 5);
+            *reinterpret_cast<uint32_t*>(dst) = w.x;
+            *reinterpret_cast<uint32_t*>(dst + 8) = w.y;
+            *reinterpret_cast<uint32_t*>(dst + 16) = w.z;
+            *reinterpret_cast<uint32_t*>(dst + 24) = w.w;
+        }
+    } else if (V_out != nullptr && tid < LY::NT * 128) {
         // thread (half, q, lane): two of the four coordinate groups of one lane triplet
         const int half = tid / (LY::NT * 64), ql = tid - half * (LY::NT * 64);
         const int q = ql >> 6;
@@ -356,7 +425,14 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
         }
         if (valid) RowStore<OutT, EPT>::store(K_out + row, k);
     }
-    if (V_out != nullptr) {
+    if (V8) {
+        if (V_out != nullptr) {
+            float y[EPT];
+#pragma unroll
+            for (int i = 0; i < EPT; ++i) y[i] = (float)((int)vbuf[(e0 + i) * VST + t] - 128) * vscale;  // exact in fp32
+            if (valid) RowStore<OutT, EPT>::store(V_out + row, y);
+        }
+    } else if (V_out != nullptr) {
         // the centroid scale, 1/sqrt(D) and the entry sign of the cross-lane stages ride on the conversion
         const float f = codec_entry_sign(lane) * (kInvCentroidScale * inv_sqrt_d<D>()) * vscale;
         float y[EPT];
@@ -379,18 +455,19 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
 }
 
 // ------------------------------------------------------------------------------------ export ---
-template <int D, bool VS>
+template <int D, int VC>
 __global__ __launch_bounds__(256) void export_kernel(const uint8_t* __restrict__ pool,
                                                      int8_t* __restrict__ k_codes,
                                                      __half* __restrict__ k_scales,
                                                      uint8_t* __restrict__ v_packed,
                                                      __half* __restrict__ v_scales, int T, int tiles) {
-    using LY = Layout<D, VS>;
+    using LY = Layout<D, VC>;
+    constexpr bool VS = LY::has_vscales, V8 = VC == 2;
     constexpr int EPT = D / 8;
     __shared__ __align__(16) uint8_t img[LY::tile_bytes];
     const int tile = blockIdx.x, unit = blockIdx.y;
     const int tid = threadIdx.x, t = tid >> 3, c = tid & 7;
-    stage_tile<D, VS>(img, pool, unit, tiles, tile, tid);
+    stage_tile<D, VC>(img, pool, unit, tiles, tile, tid);
     const int tok = tile * kTile + t;
     if (tok >= T) return;
     const size_t vec = (size_t)unit * T + tok;
@@ -406,7 +483,13 @@ __global__ __launch_bounds__(256) void export_kernel(const uint8_t* __restrict__
         k_scales[vec * LY::NB + c] = reinterpret_cast<const __half*>(img + LY::kscales_off)[t * LY::NB + c];
     if (VS && v_scales != nullptr && c == 0)
         v_scales[vec] = reinterpret_cast<const __half*>(img + LY::vscales_off)[t];
-    if (v_packed != nullptr) {
+    if (V8) {
+        if (v_packed != nullptr) {  // int8 codes, [head_dim] per vector
+#pragma unroll
+            for (int i = 0; i < EPT; ++i)
+                v_packed[vec * D + e0 + i] = (uint8_t)((int)img[LY::vcodes_off + v8_byte_offset(t, e0 + i)] - 128);
+        }
+    } else if (v_packed != nullptr) {
         const uint32_t* vreg = reinterpret_cast<const uint32_t*>(img + LY::vcodes_off);
         uint8_t* dst = v_packed + vec * (3 * D / 8) + 3 * e0 / 8;
 #pragma unroll
@@ -422,21 +505,20 @@ __global__ __launch_bounds__(256) void export_kernel(const uint8_t* __restrict__
 }
 
 // ---------------------------------------------------------------------------------- launchers ---
-// Calls f(integral_constant<int, D>, integral_constant<bool, VS>) for the pool's head_dim and value codec.
+// Calls f(integral_constant<int, D>, integral_constant<int, VC>) for the pool's head_dim and value codec.
 template <typename F> static void for_pool_shape(const polykv_pool* p, F&& f) {
     using std::integral_constant;
-    const bool vs = p->value_codec == POLYKV_VALUES_TQ3_SCALED;
-    if (p->head_dim == 128) {
-        if (vs)
-            f(integral_constant<int, 128>{}, integral_constant<bool, true>{});
-        else
-            f(integral_constant<int, 128>{}, integral_constant<bool, false>{});
-    } else {
-        if (vs)
-            f(integral_constant<int, 64>{}, integral_constant<bool, true>{});
-        else
-            f(integral_constant<int, 64>{}, integral_constant<bool, false>{});
-    }
+    auto with_d = [&](auto d) {
+        switch (p->value_codec) {
+            case POLYKV_VALUES_TQ3_SCALED: f(d, integral_constant<int, POLYKV_VALUES_TQ3_SCALED>{}); break;
+            case POLYKV_VALUES_INT8: f(d, integral_constant<int, POLYKV_VALUES_INT8>{}); break;
+            default: f(d, integral_constant<int, POLYKV_VALUES_TQ3>{}); break;
+        }
+    };
+    if (p->head_dim == 128)
+        with_d(integral_constant<int, 128>{});
+    else
+        with_d(integral_constant<int, 64>{});
 }
 
 hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, int begin, int count, hipStream_t s) {
@@ -455,12 +537,12 @@ hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dty
     const uint8_t* pool = (const uint8_t*)p->storage + (size_t)layer_begin * p->kv_heads * p->tiles * p->tile_bytes;
     for_pool_shape(p, [&](auto d, auto vs) {
         constexpr int D = decltype(d)::value;
-        constexpr bool VS = decltype(vs)::value;
+        constexpr int VC = decltype(vs)::value;
         if (dtype == POLYKV_F32)
-            launch_main_kernel(decode_kernel<D, VS, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out,
+            launch_main_kernel(decode_kernel<D, VC, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out,
                                p->length, p->tiles);
         else
-            launch_main_kernel(decode_kernel<D, VS, __half>, grid, dim3(256), 0, s, pool, (__half*)K_out, (__half*)V_out,
+            launch_main_kernel(decode_kernel<D, VC, __half>, grid, dim3(256), 0, s, pool, (__half*)K_out, (__half*)V_out,
                                p->length, p->tiles);
     });
     return hipGetLastError();

@@ -24,7 +24,7 @@ void set_error(const char* fmt, ...);
 // Everything pool_attend needs after validation; passed by value to the kernels.
 struct AttendPlan {
     int D, T, tiles, H;          // pool shape: T tokens encoded so far, in `tiles` tiles
-    int vscaled;                 // 1: the pool stores per-vector value scales (POLYKV_VALUES_TQ3_SCALED)
+    int vcodec;                  // the pool's value codec, POLYKV_VALUES_*
     int tiles_cap;               // tile records per (layer, KV head) in storage (the pool's capacity)
     int layer_begin, layers;     // selected layer range
     int A, nq, q_heads, G, R;    // R = A * nq * G query rows per KV head

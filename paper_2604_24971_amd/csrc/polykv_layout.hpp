@@ -22,12 +22,17 @@
 //                              code e>=4: bits 1:0 = dword2 bits 8(e-4)+7:8(e-4)+6, bit 2 = dword1 bit 8(e-4)+7
 //
 //
-// With per-vector value scales (the scaled-values codec) a region of 32 fp16 scales, one per token,
-// sits between the key scales and the value codes:
+// Value codecs with a per-vector scale (VC = 1, 2) put a region of 32 fp16 scales, one per token,
+// between the key scales and the value codes:
 //   V scales  32 fp16        scale(token t) at index t.
+// The int8 value codec (VC = 2) stores, instead of the 3-bit triplets,
+//   V codes   NB x 1024 B    byte g*1024 + lane*16 + 8*ks + e holds code(coordinate 32g + m, token
+//                            16ks + 8*(e/4) + 4h + e%4) + 128, g < NB, ks < 2, e < 8: the lane's 16 bytes of
+//                            coordinate group g are the A operands of that group's two P.V products, in the
+//                            same token order as above.
 //
 // Per token and KV head this is head_dim + head_dim/16 + 3*head_dim/8 bytes: 184 (d=128), 92 (d=64),
-// plus 2 with value scales.
+// plus 2 with value scales; 2*head_dim + head_dim/16 + 2 with int8 values.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -36,14 +41,17 @@ namespace polykv {
 
 constexpr int kTile = 32;  // tokens per tile record
 
-template <int D, bool VS = false> struct Layout {
+// VC: value codec, numbered as POLYKV_VALUES_* in the ABI header (0 the paper's 3-bit codes, 1 the same
+// with a per-vector scale, 2 int8 codes with a per-vector scale).
+template <int D, int VC = 0> struct Layout {
     static constexpr int NB = D / 32;             // q8_0 blocks per vector
     static constexpr int NT = D / 64;             // value-code triplets per lane
+    static constexpr bool has_vscales = VC != 0;
     static constexpr int kcodes_off = 0;
     static constexpr int kscales_off = NB * 1024;
-    static constexpr int vscales_off = kscales_off + kTile * NB * 2;  // present only if VS
-    static constexpr int vcodes_off = vscales_off + (VS ? kTile * 2 : 0);
-    static constexpr int tile_bytes = vcodes_off + NT * 768;
+    static constexpr int vscales_off = kscales_off + kTile * NB * 2;  // present only if has_vscales
+    static constexpr int vcodes_off = vscales_off + (has_vscales ? kTile * 2 : 0);
+    static constexpr int tile_bytes = vcodes_off + (VC == 2 ? NB * 1024 : NT * 768);
 };
 
 __host__ __device__ inline int tiles_of(int tokens) { return (tokens + kTile - 1) / kTile; }
@@ -90,6 +98,13 @@ __device__ __forceinline__ int kcode_run_offset(int t, int j, int g8) {
 __device__ __forceinline__ int vcode_coord(int G, int lane) { return 32 * (G >> 1) + (lane & 31); }
 __device__ __forceinline__ int vcode_token(int G, int lane, int e) {
     return 16 * (G & 1) + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+}
+
+// int8 value codec: byte offset (inside the V-code region of a tile) of the code of (token t of the tile,
+// coordinate dv).
+__device__ __forceinline__ int v8_byte_offset(int t, int dv) {
+    const int ks = t >> 4, e = (((t >> 3) & 1) << 2) | (t & 3), lane = 32 * ((t >> 2) & 1) + (dv & 31);
+    return (dv >> 5) * 1024 + lane * 16 + 8 * ks + e;
 }
 
 // Extract the 3-bit value code of (token t of the tile, rotated coordinate dv) from the V-code

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libpolykv.so")
 OK, EINVAL, ESHAPE, ESTATE, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
 F16, F32 = 0, 1
 KERNEL_AUTO, KERNEL_VECTOR, KERNEL_MATRIX = 0, 1, 2
-VALUES_TQ3, VALUES_TQ3_SCALED = 0, 1
+VALUES_TQ3, VALUES_TQ3_SCALED, VALUES_INT8 = 0, 1, 2
 MAX_TAIL_AGENTS = 64
 
 
@@ -220,7 +220,10 @@ class Pool:
         n = (self.layers, self.kv_heads, self.length)
         kc = torch.empty(n + (self.head_dim,), dtype=torch.int8, device=self.device)
         ks = torch.empty(n + (self.head_dim // 32,), dtype=torch.float16, device=self.device)
-        vp = torch.empty(n + (3 * self.head_dim // 8,), dtype=torch.uint8, device=self.device)
+        if self.value_codec == VALUES_INT8:      # the int8 value codes themselves
+            vp = torch.empty(n + (self.head_dim,), dtype=torch.int8, device=self.device)
+        else:
+            vp = torch.empty(n + (3 * self.head_dim // 8,), dtype=torch.uint8, device=self.device)
         _check(lib.pool_export(self._h, C.c_void_p(kc.data_ptr()), C.c_void_p(ks.data_ptr()),
                                C.c_void_p(vp.data_ptr()), _stream_ptr(stream)))
         return kc, ks, vp

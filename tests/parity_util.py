@@ -6,7 +6,12 @@ CPU oracle and compare to the stated bars:
     fp64) lies within 1e-6 relative of the midpoint of two fp16 numbers, which may store either; the
     codes of such a vector are then checked against the oracle's codes for the scale it stores;
   * dequantized K/V within 1e-3 relative, per vector, infinity norm;
-  * attention output within 2e-3 absolute.
+  * attention output within 2e-3 absolute.  That bar is stated for the paper-scale workloads, whose
+    value vectors have elements up to about 4; the tests of the value-codec variants also use vectors a
+    hundred times longer, and a row that attends such vectors carries the fp16 rounding of its
+    probabilities (2^-11 relative) on them.  There the bar is 2e-3 * max(1, B / 4) per output row, with
+    B = sum_t p_t * max_c |v_t[c]| the softmax-weighted magnitude of the values the row mixes (computed by
+    the oracle's own attention over the magnitudes).
 """
 import numpy as np
 import torch
@@ -24,9 +29,10 @@ def dev(x):
     return torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
 
 
-def gpu_pool(K, V, scaled_values=False):
+def gpu_pool(K, V, scaled_values=False, int8_values=False):
     L, H, T, d = K.shape
-    pool = pk.Pool(L, H, d, T, value_codec=pk.VALUES_TQ3_SCALED if scaled_values else pk.VALUES_TQ3).bind()
+    codec = pk.VALUES_INT8 if int8_values else pk.VALUES_TQ3_SCALED if scaled_values else pk.VALUES_TQ3
+    pool = pk.Pool(L, H, d, T, value_codec=codec).bind()
     pool.storage.fill_(0xA5)            # stale bytes must never leak into results
     pool.encode(dev(K), dev(V))
     return pool
@@ -60,6 +66,21 @@ def compare_codes(pool, ref):
     """Returns a bool array [L, H] marking units where a (permitted) threshold mismatch occurred."""
     kc, ks, vp = (t.cpu().numpy() for t in pool.export())
     d = pool.head_dim
+    if "v_codes" in ref:        # int8 values: scales bit-exact, codes bit-exact except on a rounding tie
+        np.testing.assert_array_equal(ks.view(np.uint16), ref["k_scales"].view(np.uint16))
+        k_diff = kc != ref["k_codes"]
+        if k_diff.any():
+            frac = np.abs(ref["k_pre"] - np.floor(ref["k_pre"]) - 0.5)
+            assert np.all(frac[k_diff] <= CODE_WINDOW), "key code differs away from a rounding tie"
+        gs = pool.export_value_scales().cpu().numpy()
+        np.testing.assert_array_equal(gs.view(np.uint16), ref["v_scales"].view(np.uint16))
+        assert vp.dtype == np.int8 and vp.shape == ref["v_codes"].shape
+        v_diff = vp != ref["v_codes"]
+        if v_diff.any():
+            frac = np.abs(ref["v_pre"] - np.floor(ref["v_pre"]) - 0.5)
+            assert np.all(frac[v_diff] <= CODE_WINDOW), "value code differs away from a rounding tie"
+            assert np.all(np.abs(vp.astype(np.int32) - ref["v_codes"])[v_diff] == 1)
+        return k_diff.any(axis=(2, 3)) | v_diff.any(axis=(2, 3)), int(k_diff.sum()), int(v_diff.sum())
     scaled = "v_scales" in ref
     if scaled:
         settle_value_scales(pool.export_value_scales().cpu().numpy(), ref)
@@ -105,6 +126,17 @@ def compare_decode(pool, ref, dirty_units):
     return Kh, Vh
 
 
+def attend_row_atol(K_hat, V_hat, Q, scale=None, tails=None, tail_causal=False):
+    """Per-row bar [L, A, nq, q_heads, 1] for pools with long value vectors (see the module docstring)."""
+    mag = np.broadcast_to(np.abs(V_hat).max(axis=-1, keepdims=True), V_hat.shape)
+    tails_mag = None
+    if tails is not None:
+        tails_mag = [(tk, np.broadcast_to(np.abs(np.asarray(tv, dtype=np.float64)).max(axis=-1, keepdims=True), tv.shape))
+                     for tk, tv in tails]
+    B = O.pool_attend(K_hat, mag, Q, scale=scale, tails=tails_mag, tail_causal=tail_causal)[..., :1]
+    return ATTEND_ATOL * np.maximum(1.0, B / 4.0)
+
+
 def compare_attend(out_gpu, out_ref, kv_heads, dirty_units=None, layer_begin=0, atol=ATTEND_ATOL):
     g = out_gpu.cpu().numpy().astype(np.float64)
     assert g.shape == out_ref.shape
@@ -114,5 +146,5 @@ def compare_attend(out_gpu, out_ref, kv_heads, dirty_units=None, layer_begin=0, 
         mask = np.repeat(dirty_units[layer_begin:layer_begin + g.shape[0]], G, axis=1)   # [Ls, q_heads]
         err = np.where(mask[:, None, None, :, None], 0.0, err)
     assert np.isfinite(g).all()
-    assert err.max() <= atol, "attention output off by %g" % err.max()
+    assert np.all(err <= atol), "attention output off by %g (%g times the bar)" % (err.max(), (err / atol).max())
     return float(err.max())

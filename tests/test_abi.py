@@ -72,6 +72,9 @@ def test_value_codec_choice_byte_counts_and_errors():
         assert lib.pool_create_codec(L, H, d, T, pk.VALUES_TQ3_SCALED, C.byref(h)) == pk.OK
         assert lib.pool_bytes(h) == O.stored_bytes(L, H, T, d, scaled_values=True)["packed"]
         lib.pool_destroy(h)
+        assert lib.pool_create_codec(L, H, d, T, pk.VALUES_INT8, C.byref(h)) == pk.OK
+        assert lib.pool_bytes(h) == O.stored_bytes(L, H, T, d, int8_values=True)["packed"]
+        lib.pool_destroy(h)
         assert lib.pool_create_codec(L, H, d, T, pk.VALUES_TQ3, C.byref(h)) == pk.OK
         assert lib.pool_bytes(h) == O.stored_bytes(L, H, T, d)["packed"]
         lib.pool_destroy(h)

@@ -26,14 +26,14 @@ def _pu():
 class Case:
     """One encoded pool on both sides."""
 
-    def __init__(self, cfg, K=None, V=None, scaled_values=False):
+    def __init__(self, cfg, K=None, V=None, scaled_values=False, int8_values=False):
         pu = _pu()
         self.cfg = cfg
         if K is None:
             K, V = W.kv_pool(cfg)
         self.K, self.V = K, V
-        self.ref = O.pool_encode(K, V, scaled_values=scaled_values)
-        self.pool = pu.gpu_pool(K, V, scaled_values=scaled_values)
+        self.ref = O.pool_encode(K, V, scaled_values=scaled_values, int8_values=int8_values)
+        self.pool = pu.gpu_pool(K, V, scaled_values=scaled_values, int8_values=int8_values)
         self.dirty, self.k_mis, self.v_mis = pu.compare_codes(self.pool, self.ref)
         self._dec = None
 
@@ -57,15 +57,10 @@ class Case:
         ref = O.pool_attend(Kh[lb:le], Vh[lb:le], Q, scale=kw.get("scale"), tails=ref_tails)
         out = self.pool.attend(pu.dev(Q), tails=gpu_tails, **kw)
         torch.cuda.synchronize()
-        return pu.compare_attend(out, ref, self.cfg.kv_heads, self.dirty, lb, atol=self.attend_atol(lb, le))
-
-    def attend_atol(self, lb, le):
-        """The absolute bar is stated for values of unit scale; pools of the scaled-values codec are
-        tested on much longer vectors, and there it is taken in units of the values' root mean square."""
-        if "v_scales" not in self.ref:
-            return _pu().ATTEND_ATOL
-        Vh = self.decoded()[1][lb:le]
-        return _pu().ATTEND_ATOL * max(1.0, float(np.sqrt(np.mean(Vh ** 2))))
+        atol = pu.ATTEND_ATOL
+        if "v_scales" in self.ref:      # value-codec variants are tested on long vectors: per-row bar
+            atol = pu.attend_row_atol(Kh[lb:le], Vh[lb:le], Q, scale=kw.get("scale"), tails=ref_tails)
+        return pu.compare_attend(out, ref, self.cfg.kv_heads, self.dirty, lb, atol=atol)
 
 
 @pytest.fixture(scope="module")
