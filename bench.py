@@ -240,7 +240,9 @@ def main():
 
     how = ("; duration = the kernel's own begin/end HIP events (hipExtLaunchKernel start/stop events on the launch "
            "stream), averaged over the timed steps")
-    attend_roof = roof(att_gbps, "attend_mfma_kernel<128,2> (pool_attend)" + how +
+    vc = {"tq3": 0, "tq3-scaled": 1, "int8": 2}[args.value_codec]      # the kernels' value-codec template argument
+    nt = 1 if (cfg.rows_per_kv_head <= 32 or (vc == 2 and d == 128)) else 2
+    attend_roof = roof(att_gbps, "attend_mfma_kernel<%d,%d,%d> (pool_attend)" % (d, nt, vc) + how +
                        "; achieved = algorithmic bytes (packed pool + Q + out) / duration")
     traffic_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
                                 "attend_hbm_traffic_%s.txt" % cfg.name)
@@ -273,8 +275,8 @@ def main():
         "device_copy_GB_per_s": t_copy and 2 * K.numel() * 2 / t_copy / 1e9,
         "append_64_tokens_per_s": append_rate,
         "roofline": attend_roof,
-        "roofline_encode": roof(enc_bytes / k_enc / 1e9, "encode_kernel<128> (pool_encode); dense fp16 K,V in + packed out"),
-        "roofline_decode": roof(dec_bytes / k_dec / 1e9, "decode_kernel<128,half> (pool_decode); packed in + dense fp16 out"),
+        "roofline_encode": roof(enc_bytes / k_enc / 1e9, "encode_kernel<%d,%d> (pool_encode); dense fp16 K,V in + packed out" % (d, vc)),
+        "roofline_decode": roof(dec_bytes / k_dec / 1e9, "decode_kernel<%d,%d,half> (pool_decode); packed in + dense fp16 out" % (d, vc)),
     }
     for key, name in (("roofline_encode", "encode_hbm_bytes_per_launch"), ("roofline_decode", "decode_hbm_bytes_per_launch")):
         if name in vals:
