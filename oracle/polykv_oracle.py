@@ -30,6 +30,9 @@ What it follows (PolyKV paper, section "Compression Scheme" unless noted):
     as an ablation (sections "Discussion" hypothesis and "Future Work"): the key formula applied to
     each value vector with one scale per vector.  See v_encode_int8.
 
+Inputs: float16 arrays, or float32 arrays that stand for bfloat16 tensors (the paper's Llama-3-8B cache
+is bfloat16, section "Experimental Setup") and must hold bfloat16-representable values.
+
 Precision: float64 everywhere, except the steps whose float32/float16 rounding is
 part of the stored format (the fp16 block scale and the code decision of q8_0).
 
@@ -141,19 +144,36 @@ def fwht(x):
 
 
 # --------------------------------------------------------------------------- #
+# Input tensors
+# --------------------------------------------------------------------------- #
+def _as_f32_input(X, name: str):
+    """float16 -> float32 (exact); a float32 array is taken as a bfloat16 tensor and checked for it."""
+    X = np.asarray(X)
+    if X.dtype == np.float16:
+        return X.astype(np.float32)
+    if X.dtype == np.float32:
+        if np.any(np.ascontiguousarray(X).view(np.uint32) & np.uint32(0xFFFF)):
+            raise TypeError("%s: float32 input must hold bfloat16-representable values" % name)
+        return X
+    raise TypeError("%s must be float16, or float32 holding bfloat16 values" % name)
+
+
+FP16_MAX = 65504.0
+
+
+# --------------------------------------------------------------------------- #
 # Keys: q8_0
 # --------------------------------------------------------------------------- #
 def k_encode(K, block: int | None = Q8_BLOCK):
     """K: float16 [..., d].  Returns (codes int8 [..., d], scales float16 [..., d/block],
     pre float32 [..., d]) where pre = k * (1/s) is the value that was rounded.
 
-    Per block:  amax = max|k|;  s = fp16(fp32(amax) / 127)  (stored);  codes are formed with the
+    Per block:  amax = max|k|;  s = fp16(min(fp32(amax) / 127, 65504))  (stored; the minimum only acts
+    on bfloat16 inputs beyond 8.3e6, which then saturate);  codes are formed with the
     STORED scale, inv = fp32(1)/fp32(s), q = clip(rint(fp32(k) * inv), -128, 127), ties to even;
     an all-zero block stores s = 0 and zero codes.  ``block=None``: one block = the whole tensor.
     """
-    K = np.asarray(K)
-    if K.dtype != np.float16:
-        raise TypeError("K must be float16")
+    K = _as_f32_input(K, "K")
     d = K.shape[-1]
     if block is None:
         kb = K.reshape(1, -1)
@@ -163,7 +183,7 @@ def k_encode(K, block: int | None = Q8_BLOCK):
         kb = K.reshape(K.shape[:-1] + (d // block, block))
     k32 = kb.astype(np.float32)
     amax = np.max(np.abs(k32), axis=-1)
-    s16 = (amax / np.float32(127.0)).astype(np.float32).astype(np.float16)
+    s16 = np.minimum((amax / np.float32(127.0)).astype(np.float32), np.float32(FP16_MAX)).astype(np.float16)
     s32 = s16.astype(np.float32)
     with np.errstate(divide="ignore"):
         inv = np.where(s32 > 0, np.float32(1.0) / s32, np.float32(0.0)).astype(np.float32)
@@ -207,9 +227,7 @@ def v_quantize(v_rot):
 
 def v_encode(V):
     """V: float16 [..., d] -> (idx uint8 [..., d] in 0..7, v_rot float64 [..., d])."""
-    V = np.asarray(V)
-    if V.dtype != np.float16:
-        raise TypeError("V must be float16")
+    V = _as_f32_input(V, "V")
     v_rot = v_rotate(V)
     return v_quantize(v_rot), v_rot
 
@@ -275,9 +293,7 @@ def v_quantize_scaled(v_rot, g16):
 def v_encode_scaled(V):
     """V: float16 [..., d] -> (idx uint8 [..., d], g16 float16 [...], v_rot float64 [..., d],
     rms float64 [...])."""
-    V = np.asarray(V)
-    if V.dtype != np.float16:
-        raise TypeError("V must be float16")
+    V = _as_f32_input(V, "V")
     g16, rms = v_scale(V)
     v_rot = v_rotate(V)
     return v_quantize_scaled(v_rot, g16), g16, v_rot, rms
@@ -300,10 +316,7 @@ def v_encode_int8(V):
     vector stores s = 0 and zero codes.  The cap is the same format limit as for the scaled variant:
     only with max|v| > 127 * 128 does the clip act, and elements beyond the range saturate at code
     127 or -128."""
-    V = np.asarray(V)
-    if V.dtype != np.float16:
-        raise TypeError("V must be float16")
-    v32 = V.astype(np.float32)
+    v32 = _as_f32_input(V, "V")
     amax = np.max(np.abs(v32), axis=-1)
     s16 = np.minimum((amax / np.float32(127.0)).astype(np.float32), np.float32(V_SCALE_MAX)).astype(np.float16)
     s32 = s16.astype(np.float32)

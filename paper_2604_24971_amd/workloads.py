@@ -82,6 +82,19 @@ def kv_layer(cfg: PoolConfig, layer: int, tokens: int | None = None, stream: int
     return k.astype(np.float16), v.astype(np.float16)
 
 
+def bf16_round(x):
+    """float32 array rounded to the nearest bfloat16 (ties to even), returned as float32: how the tests
+    and the benchmark make bfloat16 tensors (numpy has no such dtype)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32)
+
+
+def bf16_bits(x):
+    """The 16-bit patterns (uint16) of a float32 array holding bfloat16 values."""
+    return (np.ascontiguousarray(x, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+
 def kv_pool(cfg: PoolConfig):
     """K, V float16 [layers, kv_heads, tokens, head_dim]."""
     K = np.empty((cfg.layers, cfg.kv_heads, cfg.tokens, cfg.head_dim), dtype=np.float16)

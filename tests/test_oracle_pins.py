@@ -547,3 +547,39 @@ def test_int8_values_scale_cap_and_pool_roundtrip():
     qb, sb, _ = O.k_encode(V32)
     np.testing.assert_array_equal(qa, qb)
     np.testing.assert_array_equal(sa, sb[:, 0])
+
+
+# ------------------------------------------------------------ bfloat16 inputs ---
+def test_bfloat16_inputs_same_quantizers_wider_range():
+    from paper_2604_24971_amd import workloads as W
+    rng = np.random.default_rng(41)
+    x = (rng.standard_normal((64, 128)) * np.exp(2.0 * rng.standard_normal((64, 1)))).astype(np.float32)
+    xb = W.bf16_round(x)
+    # the rounding helper: representable, within half a bfloat16 step, idempotent, ties to even
+    assert not np.any(xb.view(np.uint32) & 0xFFFF)
+    assert np.all(np.abs(xb - x) <= np.abs(x) * 2.0 ** -8)
+    np.testing.assert_array_equal(W.bf16_round(xb), xb)
+    tie = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8], dtype=np.float32)      # halfway between neighbours
+    np.testing.assert_array_equal(W.bf16_round(tie), np.array([1.0, 1.0 + 2.0 ** -6], dtype=np.float32))
+    with pytest.raises(TypeError):
+        O.k_encode(x)                                               # float32 that is not bfloat16
+    with pytest.raises(TypeError):
+        O.v_encode(x.astype(np.float64))
+    # values that float16 also holds exactly give the same result through either dtype
+    small = W.bf16_round(rng.standard_normal((8, 128)).astype(np.float32))
+    qa, sa, _ = O.k_encode(small)
+    qb, sb, _ = O.k_encode(small.astype(np.float16))
+    np.testing.assert_array_equal(qa, qb); np.testing.assert_array_equal(sa, sb)
+    np.testing.assert_array_equal(O.v_encode(small)[0], O.v_encode(small.astype(np.float16))[0])
+    # the q8_0 invariants hold on bfloat16 data
+    q, s, _ = O.k_encode(xb)
+    sb_ = np.repeat(s.astype(np.float64), 32, axis=-1)
+    assert np.all(np.abs(O.k_decode(q, s) - xb.astype(np.float64)) <= sb_ / 2 * (1 + 1e-6))
+    assert np.all(np.abs(q.astype(np.int32)).reshape(64, 4, 32).max(-1) == 127)
+    # beyond float16's range: the scale saturates at 65504 and the codes clip
+    big = np.zeros((1, 32), dtype=np.float32); big[0, :3] = [2.0 ** 30, -2.0 ** 30, 3 * 2.0 ** 16]
+    q, s, _ = O.k_encode(big)
+    assert float(s[0, 0]) == 65504.0 and q[0, :3].tolist() == [127, -128, 3]
+    tiny = np.zeros((1, 32), dtype=np.float32); tiny[0, 0] = 2.0 ** -40     # below float16: scale 0, codes 0
+    q, s, _ = O.k_encode(tiny)
+    assert float(s[0, 0]) == 0.0 and not q.any()
