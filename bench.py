@@ -80,6 +80,9 @@ def main():
     ap.add_argument("--value-codec", choices=("tq3", "tq3-scaled", "int8"), default="tq3",
                     help="value codec: tq3 = the paper's (headline configuration); tq3-scaled = the same with a "
                     "per-vector fp16 scale; int8 = uniform int8 without rotation (the paper's proposed ablation)")
+    ap.add_argument("--bf16", action="store_true",
+                    help="dense tensors (K, V, Q, decode output, tails) in bfloat16 instead of fp16: the dtype of the "
+                    "paper's Llama-3-8B cache; not the headline configuration, which BASELINE.json states in fp16")
     ap.add_argument("--phases", default="eda", help="subset of e(ncode) d(ecode) a(ttend) to run per step; "
                     "anything but the default is for profiling one kernel and is marked partial")
     args = ap.parse_args()
@@ -104,6 +107,8 @@ def main():
     V = torch.from_numpy(Vn).cuda()
     del Kn, Vn
     Q = torch.from_numpy(W.queries(cfg)).cuda()
+    io_dtype = torch.bfloat16 if args.bf16 else torch.float16
+    K, V, Q = K.to(io_dtype), V.to(io_dtype), Q.to(io_dtype)
     out = torch.empty(Q.shape, dtype=torch.float32, device="cuda")
     Kd = torch.empty_like(K)
     Vd = torch.empty_like(V)
@@ -112,7 +117,7 @@ def main():
     tails = None
     if args.tail_len > 0:        # every agent has produced tail_len private tokens (fp16, uncompressed)
         cap = max(args.tail_len, cfg.max_tail)
-        tails = pk.Tails(pools[0], [(torch.from_numpy(kt).cuda(), torch.from_numpy(vt).cuda())
+        tails = pk.Tails(pools[0], [(torch.from_numpy(kt).cuda().to(io_dtype), torch.from_numpy(vt).cuda().to(io_dtype))
                                     for kt, vt in W.tails(cfg, [cap] * cfg.agents)], [args.tail_len] * cfg.agents)
     ws = torch.empty(max(pools[0].attend_workspace_bytes(Q, tails=tails), 256), dtype=torch.uint8, device="cuda")
     if args.per_layer:
@@ -141,7 +146,7 @@ def main():
         if "d" in args.phases:
             if kev:
                 pk.time_next_kernel(*kev[1])
-            p.decode(torch.float16, Kd, Vd)
+            p.decode(io_dtype, Kd, Vd)
         if ev:
             ev[2].record()
         if "a" in args.phases:
@@ -259,7 +264,7 @@ def main():
         "config": {"workload": cfg.name, "layers": L, "kv_heads": H, "q_heads": cfg.q_heads, "head_dim": d,
                    "tokens": T, "agents": cfg.agents, "q_per_agent": cfg.q_per_agent,
                    "rows_per_kv_head": cfg.rows_per_kv_head, "pool_bytes": packed, "pool_copies_rotated": len(pools),
-                   "value_codec": args.value_codec,
+                   "value_codec": args.value_codec, "dense_dtype": "bf16" if args.bf16 else "f16",
                    "tail_len": args.tail_len, "tail_bytes": tail_bytes,
                    "attend_calls_per_step": L if args.per_layer else 1},
         "step": "pool_encode -> pool_decode(fp16) -> pool_attend, all layers",

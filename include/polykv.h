@@ -41,7 +41,9 @@ typedef enum {
     POLYKV_EHIP = -5     /* a HIP launch failed                                            */
 } polykv_status;
 
-enum { POLYKV_F16 = 0, POLYKV_F32 = 1 };
+/* Element types of dense tensors.  POLYKV_BF16 is bfloat16, the type of the paper's Llama-3-8B cache (section
+ * "Experimental Setup"); everything is computed exactly as for fp16 after the (exact) widening to fp32. */
+enum { POLYKV_F16 = 0, POLYKV_F32 = 1, POLYKV_BF16 = 2 };
 enum { POLYKV_MAX_TAIL_AGENTS = 64 };
 
 /* Attention kernel selection.  AUTO picks by shape: the matrix-core kernel when it supports the
@@ -88,6 +90,9 @@ int pool_bind(polykv_pool* pool, void* dev_storage, size_t bytes);
  * K_dev, V_dev: fp16 [layers, kv_heads, tokens, head_dim], read-only.  May be called again; it
  * overwrites the pool (the pool is otherwise write-once / read-many). */
 int pool_encode(polykv_pool* pool, const void* K_dev, const void* V_dev, void* stream);
+/* The same for K_dev, V_dev of type in_dtype, POLYKV_F16 or POLYKV_BF16.  A bfloat16 key block whose
+ * max|k| / 127 exceeds the fp16 maximum stores the scale 65504 and saturates. */
+int pool_encode_dtype(polykv_pool* pool, const void* K_dev, const void* V_dev, int in_dtype, void* stream);
 
 /* Incremental fill (an extension: the paper's pool is written once, section "PolyKV Architecture"):
  * compress `count` further tokens, K_dev, V_dev fp16 [layers, kv_heads, count, head_dim], as pool tokens
@@ -97,6 +102,7 @@ int pool_encode(polykv_pool* pool, const void* K_dev, const void* V_dev, void* s
  * POLYKV_ESHAPE if the tokens do not fit.  Calls that fill and calls that read must be ordered by the
  * caller (same stream, or events). */
 int pool_append(polykv_pool* pool, const void* K_dev, const void* V_dev, int count, void* stream);
+int pool_append_dtype(polykv_pool* pool, const void* K_dev, const void* V_dev, int count, int in_dtype, void* stream);
 
 /* Tokens encoded so far (0 .. tokens).  pool_decode, pool_export and pool_attend work on these;
  * their dense tensors have pool_length() tokens per (layer, KV head). */
@@ -104,7 +110,7 @@ int pool_length(const polykv_pool* pool);
 
 /* Decompress the whole pool to dense tensors (the paper's get_kv_for_layer, section
  * "DynamicCache Injection", for all layers): K = code * s, V = H_d c[code] / sqrt(d).
- * out_dtype: POLYKV_F16 or POLYKV_F32; K_out_dev, V_out_dev: [layers, kv_heads, pool_length(), head_dim].
+ * out_dtype: POLYKV_F16, POLYKV_F32 or POLYKV_BF16 (fp32 result rounded once, to nearest even); K_out_dev, V_out_dev: [layers, kv_heads, pool_length(), head_dim].
  * Either output may be NULL to skip it. */
 int pool_decode(const polykv_pool* pool, void* K_out_dev, void* V_out_dev, int out_dtype, void* stream);
 
@@ -160,12 +166,14 @@ typedef struct {
     int splits;       /* token-range splits per KV head; 0 = choose automatically           */
     void* workspace_dev;     /* scratch for split partials, 256-byte aligned                */
     size_t workspace_bytes;  /* >= pool_attend_workspace()                                  */
+    int io_dtype;     /* type of Q and of the tails: POLYKV_F16 (0) or POLYKV_BF16.  bfloat16 queries are
+                         converted to fp16 operands in the matrix-core kernel: |q| must stay below 65504 */
 } polykv_attend_params;
 
 /* Scratch bytes pool_attend needs for these parameters (workspace fields are ignored). */
 size_t pool_attend_workspace(const polykv_pool* pool, const polykv_attend_params* params);
 
-/* Q_dev: fp16 [layer_end-layer_begin, agents, q_per_agent, q_heads, head_dim];
+/* Q_dev: fp16 (or bfloat16, see io_dtype) [layer_end-layer_begin, agents, q_per_agent, q_heads, head_dim];
  * out_dev: fp32, same shape.  Reads the pool only; concurrent calls on different streams are
  * safe if they use different workspaces. */
 int pool_attend(const polykv_pool* pool, const void* Q_dev, void* out_dev,

@@ -96,6 +96,11 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
     p.has_tails = tails ? 1 : 0;
     p.tail_capacity = tails ? prm->tail_capacity : 0;
     p.tail_causal = (tails && prm->tail_causal != 0) ? 1 : 0;
+    if (prm->io_dtype != POLYKV_F16 && prm->io_dtype != POLYKV_BF16) {
+        set_error("pool_attend: io_dtype %d is neither POLYKV_F16 nor POLYKV_BF16", prm->io_dtype);
+        return POLYKV_EINVAL;
+    }
+    p.io_bf16 = prm->io_dtype == POLYKV_BF16 ? 1 : 0;
 
     const bool mat_ok = matrix_kernel_supports(p.D, p.R);
     if (prm->kernel == POLYKV_KERNEL_MATRIX && !mat_ok) {
@@ -240,10 +245,14 @@ static int hip_result(hipError_t e, const char* who) {
     return POLYKV_EHIP;
 }
 
-static int encode_range(polykv_pool* pool, const void* K_dev, const void* V_dev, int begin, int count, void* stream,
-                        const char* who) {
+static int encode_range(polykv_pool* pool, const void* K_dev, const void* V_dev, int in_dtype, int begin, int count,
+                        void* stream, const char* who) {
     if (pool == nullptr || K_dev == nullptr || V_dev == nullptr) {
         set_error("%s: NULL argument", who);
+        return POLYKV_EINVAL;
+    }
+    if (in_dtype != POLYKV_F16 && in_dtype != POLYKV_BF16) {
+        set_error("%s: in_dtype %d is neither POLYKV_F16 nor POLYKV_BF16", who, in_dtype);
         return POLYKV_EINVAL;
     }
     if (pool->storage == nullptr) {
@@ -258,17 +267,25 @@ static int encode_range(polykv_pool* pool, const void* K_dev, const void* V_dev,
         set_error("%s: %d tokens do not fit: %d of the pool's %d are in use", who, count, begin, pool->tokens);
         return POLYKV_ESHAPE;
     }
-    const int rc = hip_result(launch_encode(pool, K_dev, V_dev, begin, count, (hipStream_t)stream), who);
+    const int rc = hip_result(launch_encode(pool, K_dev, V_dev, in_dtype, begin, count, (hipStream_t)stream), who);
     if (rc == POLYKV_OK) pool->length = begin + count;
     return rc;
 }
 
 int pool_encode(polykv_pool* pool, const void* K_dev, const void* V_dev, void* stream) {
-    return encode_range(pool, K_dev, V_dev, 0, pool ? pool->tokens : 0, stream, "pool_encode");
+    return encode_range(pool, K_dev, V_dev, POLYKV_F16, 0, pool ? pool->tokens : 0, stream, "pool_encode");
+}
+
+int pool_encode_dtype(polykv_pool* pool, const void* K_dev, const void* V_dev, int in_dtype, void* stream) {
+    return encode_range(pool, K_dev, V_dev, in_dtype, 0, pool ? pool->tokens : 0, stream, "pool_encode");
 }
 
 int pool_append(polykv_pool* pool, const void* K_dev, const void* V_dev, int count, void* stream) {
-    return encode_range(pool, K_dev, V_dev, pool ? pool->length : 0, count, stream, "pool_append");
+    return encode_range(pool, K_dev, V_dev, POLYKV_F16, pool ? pool->length : 0, count, stream, "pool_append");
+}
+
+int pool_append_dtype(polykv_pool* pool, const void* K_dev, const void* V_dev, int count, int in_dtype, void* stream) {
+    return encode_range(pool, K_dev, V_dev, in_dtype, pool ? pool->length : 0, count, stream, "pool_append");
 }
 
 int pool_length(const polykv_pool* pool) { return pool ? pool->length : 0; }
@@ -277,8 +294,8 @@ int pool_decode_layers(const polykv_pool* pool, void* K_out_dev, void* V_out_dev
                        int layer_end, void* stream) {
     int rc = check_readable(pool, "pool_decode");
     if (rc != POLYKV_OK) return rc;
-    if (out_dtype != POLYKV_F16 && out_dtype != POLYKV_F32) {
-        set_error("pool_decode: out_dtype %d is neither POLYKV_F16 nor POLYKV_F32", out_dtype);
+    if (out_dtype != POLYKV_F16 && out_dtype != POLYKV_F32 && out_dtype != POLYKV_BF16) {
+        set_error("pool_decode: out_dtype %d is not one of POLYKV_F16, POLYKV_F32, POLYKV_BF16", out_dtype);
         return POLYKV_EINVAL;
     }
     if (layer_begin < 0 || layer_end > pool->layers || layer_begin >= layer_end) {

@@ -59,7 +59,9 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
     for (int i = tid; i < kRB * D; i += 256) {
         const int r = i / D, jj = i - r * D;
         float v = 0.0f;
-        if (r0 + r < p.R) v = __half2float(Q[q_row_index(p, ls, kvh, r0 + r) * D + jj]) * p.qscale;
+        if (r0 + r < p.R)
+            v = bits16_to_float(reinterpret_cast<const uint16_t*>(Q)[q_row_index(p, ls, kvh, r0 + r) * D + jj], p.io_bf16) *
+                p.qscale;
         q_s[r][jj] = v;
     }
     if (tid < 8) ctab[tid] = centroid_of(tid);
@@ -258,10 +260,10 @@ __global__ __launch_bounds__(64) void attend_tail_kernel(const __half* __restric
         const int r = i / (D / 8), piece = i - r * (D / 8);
         uint4 raw = make_uint4(0, 0, 0, 0);
         if (r0 + r < r_end) raw = *reinterpret_cast<const uint4*>(Q + q_row_index(p, ls, kvh, r0 + r) * D + 8 * piece);
-        const __half2* h2 = reinterpret_cast<const __half2*>(&raw);
+        const uint32_t* w2 = reinterpret_cast<const uint32_t*>(&raw);
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            const float2 f = __half22float2(h2[b]);
+            const float2 f = pair16_to_float2(w2[b], p.io_bf16);
             q_s[r][8 * piece + 2 * b] = f.x * p.qscale;
             q_s[r][8 * piece + 2 * b + 1] = f.y * p.qscale;
         }
@@ -283,10 +285,10 @@ __global__ __launch_bounds__(64) void attend_tail_kernel(const __half* __restric
         float k[D];
 #pragma unroll
         for (int i = 0; i < D / 8; ++i) {
-            const __half2* h2 = reinterpret_cast<const __half2*>(&kraw[i]);
+            const uint32_t* w2 = reinterpret_cast<const uint32_t*>(&kraw[i]);
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                const float2 f = __half22float2(h2[b]);
+                const float2 f = pair16_to_float2(w2[b], p.io_bf16);
                 k[i * 8 + 2 * b] = f.x;
                 k[i * 8 + 2 * b + 1] = f.y;
             }
@@ -324,7 +326,7 @@ __global__ __launch_bounds__(64) void attend_tail_kernel(const __half* __restric
             for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int i = 0; i < EPL; ++i) {
-                    const float v = __half2float(vraw[t4 + u].h[i]);
+                    const float v = bits16_to_float(__half_as_ushort(vraw[t4 + u].h[i]), p.io_bf16);
 #pragma unroll
                     for (int r = 0; r < kRB; ++r)
                         acc[r][i] = fmaf(u == 0 ? pr[r].x : u == 1 ? pr[r].y : u == 2 ? pr[r].z : pr[r].w, v, acc[r][i]);

@@ -431,6 +431,19 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         const int rr = i / (D / 8), piece = i - rr * (D / 8), r = row0 + rr;
         uint4v raw = {0, 0, 0, 0};
         if (r < p.R) raw = *reinterpret_cast<const uint4v*>(Q + q_row_index(p, ls, kvh, r) * D + 8 * piece);
+        if (p.io_bf16) {  // bfloat16 queries become fp16 operands (exact for magnitudes fp16 holds)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const float2 f = pair16_to_float2(raw[b], true);
+                union {
+                    uint32_t u;
+                    _Float16 h[2];
+                } o;
+                o.h[0] = (_Float16)f.x;
+                o.h[1] = (_Float16)f.y;
+                raw[b] = o.u;
+            }
+        }
         *reinterpret_cast<uint4v*>(q_s + rr * QS + 8 * piece) = raw;
     }
     __syncthreads();

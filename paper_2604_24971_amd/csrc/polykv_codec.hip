@@ -47,7 +47,8 @@ struct CodecThread {
 // VC = 2, int8 values: no rotation; the key formula on the whole vector with one scale per vector,
 // s = fp16(min(max|v|/127, 128)) (the uniform int8 ablation proposed in sections "Discussion" and
 // "Future Work").
-template <int D, int VC>
+// BF: K and V are bfloat16 instead of fp16 (the bit patterns are passed as __half all the same).
+template <int D, int VC, bool BF>
 __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ K,
                                                      const __half* __restrict__ V,
                                                      uint8_t* __restrict__ pool, int in_tokens, int tok_begin,
@@ -121,17 +122,18 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         float k[EPT];
 #pragma unroll
         for (int i = 0; i < EPT / 2; ++i) {
-            Half2Bits b;
-            b.u = reinterpret_cast<const uint32_t*>(kraw)[i];
-            k[2 * i] = (float)b.h[0];
-            k[2 * i + 1] = (float)b.h[1];
+            const float2 f = pair16_to_float2(reinterpret_cast<const uint32_t*>(kraw)[i], BF);
+            k[2 * i] = f.x;
+            k[2 * i + 1] = f.y;
         }
         float amax = 0.0f;
 #pragma unroll
         for (int i = 0; i < EPT; i += 2) amax = fmaxf(fmaxf(fabsf(k[i]), fabsf(k[i + 1])), amax);
         amax = fmaxf(amax, lane_xor<1>(amax));
         if (EPT == 8) amax = fmaxf(amax, lane_xor<2>(amax));
-        const __half s16 = __float2half_rn(__fdiv_rn(amax, 127.0f));
+        // bfloat16 keys can exceed what an fp16 scale holds: it saturates at the fp16 maximum
+        const float sraw = __fdiv_rn(amax, 127.0f);
+        const __half s16 = __float2half_rn(BF ? fminf(sraw, 65504.0f) : sraw);
         const float sf = __half2float(s16);
         const float inv = sf > 0.0f ? __fdiv_rn(1.0f, sf) : 0.0f;
         // round(k * inv) + 128 in the low byte of a float: adding 1.5 * 2^23 + 128 rounds the product
@@ -165,10 +167,9 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         float v[EPT];
 #pragma unroll
         for (int i = 0; i < EPT / 2; ++i) {
-            Half2Bits b;
-            b.u = reinterpret_cast<const uint32_t*>(vraw)[i];
-            v[2 * i] = (float)b.h[0];
-            v[2 * i + 1] = (float)b.h[1];
+            const float2 f = pair16_to_float2(reinterpret_cast<const uint32_t*>(vraw)[i], BF);
+            v[2 * i] = f.x;
+            v[2 * i + 1] = f.y;
         }
         float amax = 0.0f;
 #pragma unroll
@@ -195,10 +196,16 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         float y[EPT];
 #pragma unroll
         for (int i = 0; i < EPT / 2; ++i) {
-            Half2Bits b;
-            b.u = reinterpret_cast<const uint32_t*>(vraw)[i];
-            y[2 * i] = __builtin_fmaf((float)b.h[0], eps, 0.0f);  // conversion and sign in one fma-mix
-            y[2 * i + 1] = __builtin_fmaf((float)b.h[1], eps, 0.0f);
+            if (BF) {
+                const float2 f = pair16_to_float2(reinterpret_cast<const uint32_t*>(vraw)[i], true);
+                y[2 * i] = f.x * eps;
+                y[2 * i + 1] = f.y * eps;
+            } else {
+                Half2Bits b;
+                b.u = reinterpret_cast<const uint32_t*>(vraw)[i];
+                y[2 * i] = __builtin_fmaf((float)b.h[0], eps, 0.0f);  // conversion and sign in one fma-mix
+                y[2 * i + 1] = __builtin_fmaf((float)b.h[1], eps, 0.0f);
+            }
         }
         // y = sqrt(D) * v_rot after the transform; the thresholds are scaled instead of the values.  The
         // code is the number of thresholds below v_rot: 4 + n for positive values, 3 - n otherwise, with
@@ -319,6 +326,27 @@ template <int N> struct RowStore<__half, N> {
                 b.h[1] = (_Float16)x[8 * i + 2 * k + 1];
                 w[k] = b.u;
             }
+            reinterpret_cast<uint4*>(dst)[i] = o;
+        }
+    }
+};
+struct Bf16Out {  // output element type: a bfloat16 bit pattern
+    uint16_t bits;
+};
+template <int N> struct RowStore<Bf16Out, N> {
+    // N fp32 values -> N bfloat16 (round to nearest even; inputs are finite), 16-byte stores
+    static __device__ __forceinline__ uint32_t rne(float x) {
+        const uint32_t u = __float_as_uint(x);
+        return u + 0x7FFFu + ((u >> 16) & 1u);
+    }
+    static __device__ __forceinline__ void store(Bf16Out* dst, const float (&x)[N]) {
+#pragma unroll
+        for (int i = 0; i < N / 8; ++i) {
+            uint4 o;
+            uint32_t* w = reinterpret_cast<uint32_t*>(&o);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)  // high halves of the two rounded words
+                w[k] = __builtin_amdgcn_perm(rne(x[8 * i + 2 * k + 1]), rne(x[8 * i + 2 * k]), 0x07060302u);
             reinterpret_cast<uint4*>(dst)[i] = o;
         }
     }
@@ -521,12 +549,17 @@ template <typename F> static void for_pool_shape(const polykv_pool* p, F&& f) {
         with_d(integral_constant<int, 64>{});
 }
 
-hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, int begin, int count, hipStream_t s) {
+hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, int in_dtype, int begin, int count,
+                         hipStream_t s) {
     const int end = begin + count;
     dim3 grid(tiles_of(end) - begin / kTile, p->layers * p->kv_heads);
     for_pool_shape(p, [&](auto d, auto vs) {
-        launch_main_kernel(encode_kernel<decltype(d)::value, decltype(vs)::value>, grid, dim3(256), 0, s, (const __half*)K,
-                           (const __half*)V, (uint8_t*)p->storage, count, begin, end, p->tiles);
+        if (in_dtype == POLYKV_BF16)
+            launch_main_kernel(encode_kernel<decltype(d)::value, decltype(vs)::value, true>, grid, dim3(256), 0, s,
+                               (const __half*)K, (const __half*)V, (uint8_t*)p->storage, count, begin, end, p->tiles);
+        else
+            launch_main_kernel(encode_kernel<decltype(d)::value, decltype(vs)::value, false>, grid, dim3(256), 0, s,
+                               (const __half*)K, (const __half*)V, (uint8_t*)p->storage, count, begin, end, p->tiles);
     });
     return hipGetLastError();
 }
@@ -538,7 +571,10 @@ hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dty
     for_pool_shape(p, [&](auto d, auto vs) {
         constexpr int D = decltype(d)::value;
         constexpr int VC = decltype(vs)::value;
-        if (dtype == POLYKV_F32)
+        if (dtype == POLYKV_BF16)
+            launch_main_kernel(decode_kernel<D, VC, Bf16Out>, grid, dim3(256), 0, s, pool, (Bf16Out*)K_out, (Bf16Out*)V_out,
+                               p->length, p->tiles);
+        else if (dtype == POLYKV_F32)
             launch_main_kernel(decode_kernel<D, VC, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out,
                                p->length, p->tiles);
         else

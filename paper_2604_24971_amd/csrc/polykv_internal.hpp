@@ -32,6 +32,7 @@ struct AttendPlan {
     int kernel;                  // POLYKV_KERNEL_VECTOR / _MATRIX (resolved)
     int nsplit;                  // token-range splits per KV head
     int has_tails, tail_capacity, tail_causal;
+    int io_bf16;                 // 1: Q and the tails are bfloat16, 0: fp16
     // workspace carving (byte offsets from the 256-aligned workspace base)
     size_t off_ml, off_o, off_tail_ml, off_tail_o, total;
 };
@@ -44,7 +45,8 @@ struct TailPtrs {
 
 // Encodes dense tokens [0, count) of K, V ([layers, kv_heads, count, head_dim]) as pool tokens
 // [begin, begin + count); tokens of the first touched tile that lie before `begin` are kept.
-hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, int begin, int count, hipStream_t s);
+hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, int in_dtype, int begin, int count,
+                         hipStream_t s);
 hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dtype, int layer_begin, int layer_end,
                          hipStream_t s);
 hipError_t launch_export(const polykv_pool* p, void* kc, void* ks, void* vp, void* vs, hipStream_t s);

@@ -118,6 +118,27 @@ __device__ __forceinline__ int vcode_extract(const uint32_t* v, int t, int dv) {
     return ((w[2] >> (8 * (e - 4) + 6)) & 3) | (((w[1] >> (8 * (e - 4) + 7)) & 1) << 2);
 }
 
+// ---- 16-bit floating-point inputs: fp16, or bfloat16 (the top half of an fp32) ------------------
+// Two packed 16-bit values -> fp32; `bf` is uniform over the wave.
+__device__ __forceinline__ float2 pair16_to_float2(uint32_t w, bool bf) {
+    if (bf) return make_float2(__uint_as_float(w << 16), __uint_as_float(w & 0xFFFF0000u));
+    union {
+        uint32_t u;
+        _Float16 h[2];
+    } b;
+    b.u = w;
+    return make_float2((float)b.h[0], (float)b.h[1]);
+}
+__device__ __forceinline__ float bits16_to_float(uint16_t bits, bool bf) {
+    if (bf) return __uint_as_float((uint32_t)bits << 16);
+    union {
+        uint16_t u;
+        _Float16 h;
+    } b;
+    b.u = bits;
+    return (float)b.h;
+}
+
 // ---- register-level dequantization helpers shared by the decode and attention kernels ---------
 // Centroids scaled by 1.6146639585494995 and rounded to fp16.  The factor was searched in [1, 2) so
 // that all four magnitudes land within 1.9e-5 (relative) of an fp16 value -- ten times closer than the

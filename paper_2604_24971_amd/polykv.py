@@ -12,7 +12,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpolykv.so")
 
 OK, EINVAL, ESHAPE, ESTATE, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
-F16, F32 = 0, 1
+F16, F32, BF16 = 0, 1, 2
+_DTYPES = {torch.float16: F16, torch.float32: F32, torch.bfloat16: BF16}
 KERNEL_AUTO, KERNEL_VECTOR, KERNEL_MATRIX = 0, 1, 2
 VALUES_TQ3, VALUES_TQ3_SCALED, VALUES_INT8 = 0, 1, 2
 MAX_TAIL_AGENTS = 64
@@ -32,6 +33,7 @@ class AttendParams(C.Structure):
         ("tail_len", C.POINTER(C.c_int)), ("tail_capacity", C.c_int), ("tail_causal", C.c_int),
         ("kernel", C.c_int), ("splits", C.c_int),
         ("workspace_dev", C.c_void_p), ("workspace_bytes", C.c_size_t),
+        ("io_dtype", C.c_int),
     ]
 
 
@@ -55,6 +57,10 @@ def _load():
     lib.pool_encode.restype = ip
     lib.pool_append.argtypes = [vp, vp, vp, ip, vp]
     lib.pool_append.restype = ip
+    lib.pool_encode_dtype.argtypes = [vp, vp, vp, ip, vp]
+    lib.pool_encode_dtype.restype = ip
+    lib.pool_append_dtype.argtypes = [vp, vp, vp, ip, ip, vp]
+    lib.pool_append_dtype.restype = ip
     lib.pool_length.argtypes = [vp]
     lib.pool_length.restype = ip
     lib.pool_decode_layers.argtypes = [vp, vp, vp, ip, ip, ip, vp]
@@ -125,6 +131,7 @@ class Tails:
         self.v = (C.c_void_p * A)()
         self.len = (C.c_int * A)()
         self.capacity = 0
+        self.dtype = None            # torch.float16 or torch.bfloat16, the same for every tail
         self._keep = []
         for a, ent in enumerate(tensors):
             if ent is None:
@@ -136,8 +143,12 @@ class Tails:
             if self.capacity and self.capacity != Kt.shape[2]:
                 raise ValueError("all tails must share one capacity")
             self.capacity = Kt.shape[2]
-            self.k[a] = _dev_ptr(Kt, torch.float16, "tail K").value
-            self.v[a] = _dev_ptr(Vt, torch.float16, "tail V").value
+            if self.dtype is None:
+                self.dtype = Kt.dtype
+            if self.dtype not in (torch.float16, torch.bfloat16):
+                raise TypeError("tails must be float16 or bfloat16")
+            self.k[a] = _dev_ptr(Kt, self.dtype, "tail K").value
+            self.v[a] = _dev_ptr(Vt, self.dtype, "tail V").value
             self._keep += [Kt, Vt]
             if len(ent) > 2:
                 self.len[a] = int(ent[2])
@@ -186,16 +197,20 @@ class Pool:
         shape = (self.layers, self.kv_heads, self.tokens, self.head_dim)
         if tuple(K.shape) != shape or tuple(V.shape) != shape:
             raise ValueError("K and V must have shape %s" % (shape,))
-        _check(lib.pool_encode(self._h, _dev_ptr(K, torch.float16, "K"), _dev_ptr(V, torch.float16, "V"),
-                               _stream_ptr(stream)))
+        if K.dtype not in (torch.float16, torch.bfloat16):
+            raise TypeError("K and V must be float16 or bfloat16")
+        _check(lib.pool_encode_dtype(self._h, _dev_ptr(K, K.dtype, "K"), _dev_ptr(V, K.dtype, "V"), _DTYPES[K.dtype],
+                                     _stream_ptr(stream)))
 
     # pool_append(K, V, count)
     def append(self, K: torch.Tensor, V: torch.Tensor, stream=None):
         if K.dim() != 4 or tuple(K.shape) != tuple(V.shape) or \
                 tuple(K.shape[:2]) != (self.layers, self.kv_heads) or K.shape[3] != self.head_dim:
             raise ValueError("K and V must be [layers, kv_heads, count, head_dim]")
-        _check(lib.pool_append(self._h, _dev_ptr(K, torch.float16, "K"), _dev_ptr(V, torch.float16, "V"),
-                               int(K.shape[2]), _stream_ptr(stream)))
+        if K.dtype not in (torch.float16, torch.bfloat16):
+            raise TypeError("K and V must be float16 or bfloat16")
+        _check(lib.pool_append_dtype(self._h, _dev_ptr(K, K.dtype, "K"), _dev_ptr(V, K.dtype, "V"),
+                                     int(K.shape[2]), _DTYPES[K.dtype], _stream_ptr(stream)))
 
     @property
     def length(self) -> int:
@@ -205,7 +220,7 @@ class Pool:
     def decode(self, dtype=torch.float32, K_out=None, V_out=None, stream=None, layer_begin=0, layer_end=None):
         layer_end = self.layers if layer_end is None else layer_end
         shape = (max(layer_end - layer_begin, 0), self.kv_heads, self.length, self.head_dim)
-        code = {torch.float16: F16, torch.float32: F32}[dtype]
+        code = _DTYPES[dtype]
         if K_out is None:
             K_out = torch.empty(shape, dtype=dtype, device=self.device)
         if V_out is None:
@@ -244,12 +259,17 @@ class Pool:
         p.agents, p.q_per_agent, p.q_heads = A, nq, qh
         p.layer_begin, p.layer_end, p.scale = layer_begin, layer_end, float(scale or 0.0)
         p.kernel, p.splits = kernel, splits
+        if Q.dtype not in (torch.float16, torch.bfloat16):
+            raise TypeError("Q must be float16 or bfloat16")
+        p.io_dtype = _DTYPES[Q.dtype]
         keep = []
         if tails is not None:
             if not isinstance(tails, Tails):
                 tails = Tails(self, tails)
             if tails.agents != A:
                 raise ValueError("tails must have one entry per agent")
+            if tails.dtype is not None and tails.dtype != Q.dtype:
+                raise TypeError("Q and the tails must have the same dtype")
             p.tail_K = C.cast(tails.k, C.POINTER(C.c_void_p))
             p.tail_V = C.cast(tails.v, C.POINTER(C.c_void_p))
             p.tail_len = C.cast(tails.len, C.POINTER(C.c_int))
@@ -280,6 +300,6 @@ class Pool:
         p.workspace_bytes = workspace.numel()
         if out is None:
             out = torch.empty(Q.shape, dtype=torch.float32, device=self.device)
-        _check(lib.pool_attend(self._h, _dev_ptr(Q, torch.float16, "Q"), _dev_ptr(out, torch.float32, "out"),
+        _check(lib.pool_attend(self._h, _dev_ptr(Q, Q.dtype, "Q"), _dev_ptr(out, torch.float32, "out"),
                                C.byref(p), _stream_ptr(stream)))
         return out

@@ -25,16 +25,18 @@ DEQUANT_RTOL = 1e-3
 ATTEND_ATOL = 2e-3
 
 
-def dev(x):
-    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
+def dev(x, bf16=False):
+    """Host array -> device tensor; bf16: a float32 array holding bfloat16 values becomes a bfloat16 tensor."""
+    t = torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
+    return t.to(torch.bfloat16) if bf16 else t
 
 
-def gpu_pool(K, V, scaled_values=False, int8_values=False):
+def gpu_pool(K, V, scaled_values=False, int8_values=False, bf16=False):
     L, H, T, d = K.shape
     codec = pk.VALUES_INT8 if int8_values else pk.VALUES_TQ3_SCALED if scaled_values else pk.VALUES_TQ3
     pool = pk.Pool(L, H, d, T, value_codec=codec).bind()
     pool.storage.fill_(0xA5)            # stale bytes must never leak into results
-    pool.encode(dev(K), dev(V))
+    pool.encode(dev(K, bf16), dev(V, bf16))
     return pool
 
 

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_function():
     assert {"pool_create", "pool_bytes", "pool_bind", "pool_encode", "pool_decode", "pool_export",
             "pool_attend_workspace", "pool_attend", "pool_destroy", "polykv_codebook",
             "polykv_last_error", "pool_append", "pool_length", "pool_decode_layers", "polykv_time_next_kernel",
-            "pool_create_codec", "pool_export_value_scales"} <= set(names)
+            "pool_create_codec", "pool_export_value_scales", "pool_encode_dtype", "pool_append_dtype"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -98,6 +98,8 @@ def test_state_machine_and_argument_errors_without_gpu():
     assert lib.pool_bind(None, fake, 10) == pk.EINVAL
     assert lib.pool_bind(h, fake, lib.pool_bytes(h)) == pk.OK
     assert lib.pool_encode(h, None, fake, None) == pk.EINVAL
+    assert lib.pool_encode_dtype(h, fake, fake, pk.F32, None) == pk.EINVAL    # fp16 or bfloat16 only
+    assert lib.pool_append_dtype(h, fake, fake, 5, 9, None) == pk.EINVAL
     assert lib.pool_encode(h, C.c_void_p(0x10002), fake, None) == pk.EINVAL   # misaligned input
     # bound but not encoded: reads refuse
     assert lib.pool_decode(h, fake, fake, pk.F32, None) == pk.ESTATE
@@ -134,7 +136,7 @@ def test_attend_plan_validation_and_workspace_size():
     assert lib.pool_attend_workspace(h, C.byref(p)) > need8
     p.splits = 0
     for field, val in [("q_heads", 7), ("agents", 0), ("q_per_agent", 0), ("layer_end", 5),
-                       ("layer_begin", 4), ("kernel", 9), ("splits", -1)]:
+                       ("layer_begin", 4), ("kernel", 9), ("splits", -1), ("io_dtype", pk.F32), ("io_dtype", 7)]:
         q = pk.AttendParams.from_buffer_copy(p)
         setattr(q, field, val)
         assert lib.pool_attend_workspace(h, C.byref(q)) == 0, field
