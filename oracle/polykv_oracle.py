@@ -29,6 +29,10 @@ What it follows (PolyKV paper, section "Compression Scheme" unless noted):
   * Variant "int8 values": the uniform int8 value quantizer without rotation that the paper proposes
     as an ablation (sections "Discussion" hypothesis and "Future Work"): the key formula applied to
     each value vector with one scale per vector.  See v_encode_int8.
+  * Variant "sign diagonal": the rotation is H.D instead of H, D a fixed diagonal of pseudorandom signs
+    (the randomized-Hadamard construction of the rotation-based quantizers the paper discusses in
+    section "Related Work"); it keeps structured vectors, which the bare transform maps to a few large
+    coordinates, from saturating the codebook.  See rotation_signs.
 
 Inputs: float16 arrays, or float32 arrays that stand for bfloat16 tensors (the paper's Llama-3-8B cache
 is bfloat16, section "Experimental Setup") and must hold bfloat16-representable values.
@@ -162,6 +166,30 @@ FP16_MAX = 65504.0
 
 
 # --------------------------------------------------------------------------- #
+# Sign diagonal of the rotation variant
+# --------------------------------------------------------------------------- #
+def splitmix64(seed: int, n: int):
+    """The first n outputs of the SplitMix64 generator started at `seed` (Steele, Lea, Flood 2014): output
+    i is the finalizer of seed + (i+1)*0x9E3779B97F4A7C15, so it can be computed per index."""
+    mask = (1 << 64) - 1
+    out = []
+    for i in range(n):
+        z = (seed + (i + 1) * 0x9E3779B97F4A7C15) & mask
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & mask
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & mask
+        out.append(z ^ (z >> 31))
+    return out
+
+
+def rotation_signs(seed: int, d: int):
+    """Diagonal of D, float64 [d] of +-1: coordinate i is negated iff output i of splitmix64(seed) is odd.
+    seed = 0 means no diagonal (the paper's plain transform)."""
+    if seed == 0:
+        return np.ones(d)
+    return np.array([-1.0 if z & 1 else 1.0 for z in splitmix64(seed, d)])
+
+
+# --------------------------------------------------------------------------- #
 # Keys: q8_0
 # --------------------------------------------------------------------------- #
 def k_encode(K, block: int | None = Q8_BLOCK):
@@ -208,11 +236,15 @@ def k_decode(codes, scales, block: int | None = Q8_BLOCK):
 # --------------------------------------------------------------------------- #
 # Values: FWHT rotation + 3-bit Lloyd-Max
 # --------------------------------------------------------------------------- #
-def v_rotate(V):
-    """V_rot = FWHT(V)/sqrt(d) along head_dim (step 1 of the value quantizer)."""
+def v_rotate(V, signs=None):
+    """V_rot = FWHT(V)/sqrt(d) along head_dim (step 1 of the value quantizer); with a sign diagonal
+    (rotation_signs) V_rot = FWHT(D V)/sqrt(d)."""
     V = np.asarray(V)
     d = V.shape[-1]
-    return fwht(V.astype(np.float64)) / math.sqrt(d)
+    v = V.astype(np.float64)
+    if signs is not None:
+        v = v * signs
+    return fwht(v) / math.sqrt(d)
 
 
 def v_quantize(v_rot):
@@ -225,10 +257,10 @@ def v_quantize(v_rot):
     return idx
 
 
-def v_encode(V):
+def v_encode(V, signs=None):
     """V: float16 [..., d] -> (idx uint8 [..., d] in 0..7, v_rot float64 [..., d])."""
     V = _as_f32_input(V, "V")
-    v_rot = v_rotate(V)
+    v_rot = v_rotate(V, signs)
     return v_quantize(v_rot), v_rot
 
 
@@ -251,12 +283,14 @@ def v_unpack(packed, d: int):
     return (bits << np.arange(V_BITS, dtype=np.uint8)).sum(axis=-1).astype(np.uint8)
 
 
-def v_decode(idx):
-    """V_dequant = H c[idx] / sqrt(d)  (true inverse of the normalized rotation)."""
+def v_decode(idx, signs=None):
+    """V_dequant = H c[idx] / sqrt(d)  (true inverse of the normalized rotation); with a sign diagonal
+    D H c[idx] / sqrt(d), the inverse of H D / sqrt(d)."""
     c, _ = codebook()
     idx = np.asarray(idx)
     d = idx.shape[-1]
-    return fwht(c[idx]) / math.sqrt(d)
+    v = fwht(c[idx]) / math.sqrt(d)
+    return v if signs is None else v * signs
 
 
 # --------------------------------------------------------------------------- #
@@ -290,18 +324,18 @@ def v_quantize_scaled(v_rot, g16):
     return np.where(g > 0, idx, np.uint8(3)).astype(np.uint8)
 
 
-def v_encode_scaled(V):
+def v_encode_scaled(V, signs=None):
     """V: float16 [..., d] -> (idx uint8 [..., d], g16 float16 [...], v_rot float64 [..., d],
     rms float64 [...])."""
     V = _as_f32_input(V, "V")
     g16, rms = v_scale(V)
-    v_rot = v_rotate(V)
+    v_rot = v_rotate(V, signs)
     return v_quantize_scaled(v_rot, g16), g16, v_rot, rms
 
 
-def v_decode_scaled(idx, g16):
-    """V_dequant = g * H c[idx] / sqrt(d)."""
-    return v_decode(idx) * np.asarray(g16).astype(np.float64)[..., None]
+def v_decode_scaled(idx, g16, signs=None):
+    """V_dequant = g * H c[idx] / sqrt(d)  (g * D H c[idx] / sqrt(d) with a sign diagonal)."""
+    return v_decode(idx, signs) * np.asarray(g16).astype(np.float64)[..., None]
 
 
 # --------------------------------------------------------------------------- #
@@ -335,21 +369,28 @@ def v_decode_int8(codes, scales):
 # --------------------------------------------------------------------------- #
 # Pool = encode of a whole [L, H, T, d] cache; decode back
 # --------------------------------------------------------------------------- #
-def pool_encode(K, V, scaled_values: bool = False, int8_values: bool = False):
+def pool_encode(K, V, scaled_values: bool = False, int8_values: bool = False, sign_seed: int = 0):
     """K, V float16 [L, H, T, d] -> dict with the canonical stored arrays and the pre-rounding
-    values a parity test needs to find elements that sit on a decision threshold."""
+    values a parity test needs to find elements that sit on a decision threshold.  sign_seed != 0: the
+    rotation carries the sign diagonal rotation_signs(sign_seed, d) (not with int8 values, which are
+    not rotated)."""
     k_codes, k_scales, k_pre = k_encode(K)
     out = {"k_codes": k_codes, "k_scales": k_scales, "k_pre": k_pre}
     if int8_values:
+        if sign_seed:
+            raise ValueError("int8 values are not rotated")
         v_codes, v_scales, v_pre = v_encode_int8(V)
         out.update(v_codes=v_codes, v_scales=v_scales, v_pre=v_pre)
         return out
+    signs = rotation_signs(sign_seed, np.shape(V)[-1]) if sign_seed else None
     if scaled_values:
-        v_idx, g16, v_rot, rms = v_encode_scaled(V)
+        v_idx, g16, v_rot, rms = v_encode_scaled(V, signs)
         out.update(v_scales=g16, v_rms=rms)
     else:
-        v_idx, v_rot = v_encode(V)
+        v_idx, v_rot = v_encode(V, signs)
     out.update(v_packed=v_pack(v_idx), v_idx=v_idx, v_rot=v_rot)
+    if signs is not None:
+        out["v_signs"] = signs
     return out
 
 
@@ -359,7 +400,8 @@ def pool_decode(pool):
         return K_hat, v_decode_int8(pool["v_codes"], pool["v_scales"])
     d = pool["k_codes"].shape[-1]
     idx = v_unpack(pool["v_packed"], d)
-    V_hat = v_decode_scaled(idx, pool["v_scales"]) if "v_scales" in pool else v_decode(idx)
+    signs = pool.get("v_signs")
+    V_hat = v_decode_scaled(idx, pool["v_scales"], signs) if "v_scales" in pool else v_decode(idx, signs)
     return K_hat, V_hat
 
 

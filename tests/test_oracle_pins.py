@@ -583,3 +583,59 @@ def test_bfloat16_inputs_same_quantizers_wider_range():
     tiny = np.zeros((1, 32), dtype=np.float32); tiny[0, 0] = 2.0 ** -40     # below float16: scale 0, codes 0
     q, s, _ = O.k_encode(tiny)
     assert float(s[0, 0]) == 0.0 and not q.any()
+
+
+# ------------------------------------------------------- rotation with a sign diagonal ---
+def test_sign_diagonal_generator_matches_published_splitmix64_vectors():
+    for row in read_golden_rows("splitmix64_vectors.txt"):
+        seed, want = int(row[0]), [int(x) for x in row[1:]]
+        assert O.splitmix64(seed, len(want)) == want
+    s = O.rotation_signs(1234567, 128)
+    assert s.shape == (128,) and set(s.tolist()) == {-1.0, 1.0}
+    # the first published outputs are odd, odd, odd, odd, odd -> five negated coordinates
+    assert s[:5].tolist() == [-1.0] * 5
+    assert 40 < (s < 0).sum() < 88                                  # about half
+    assert np.all(O.rotation_signs(0, 64) == 1.0)                   # seed 0: the plain transform
+    assert not np.array_equal(O.rotation_signs(1, 128), O.rotation_signs(2, 128))
+
+
+def test_sign_diagonal_rotation_is_orthonormal_and_equals_the_dense_matrix():
+    rng = np.random.default_rng(51)
+    c, _ = O.codebook()
+    for d in (64, 128):
+        s = O.rotation_signs(99, d)
+        x = rng.standard_normal((5, d)).astype(np.float16)
+        R = scipy.linalg.hadamard(d) @ np.diag(s) / math.sqrt(d)    # library matrix: H D / sqrt(d)
+        np.testing.assert_allclose(O.v_rotate(x, s), x.astype(np.float64) @ R.T, atol=1e-12)
+        np.testing.assert_allclose(R @ R.T, np.eye(d), atol=1e-12)
+        # decoding applies the inverse (= transpose): codes whose centroids ARE the rotated vector come back
+        idx = rng.integers(0, 8, size=(4, d)).astype(np.uint8)
+        v = c[idx] @ R                                              # R^T c, row-wise
+        np.testing.assert_allclose(O.v_decode(idx, s), v, atol=1e-12)
+        np.testing.assert_allclose(O.v_rotate(v, s), c[idx], atol=1e-12)
+        g = np.full(4, 0.5, dtype=np.float16)
+        np.testing.assert_allclose(O.v_decode_scaled(idx, g, s), 0.5 * v, atol=1e-12)
+
+
+def test_sign_diagonal_keeps_structured_vectors_from_saturating():
+    # a constant vector: the bare transform piles it onto coordinate 0 (2.15 is the largest centroid),
+    # the signed one spreads it like a random vector
+    d = 128
+    V = np.full((1, d), 1.0, dtype=np.float16)
+    plain = O.v_decode(O.v_encode(V)[0])
+    s = O.rotation_signs(7, d)
+    signed = O.v_decode(O.v_encode(V, s)[0], s)
+    err_plain = np.mean((plain - 1.0) ** 2)
+    err_signed = np.mean((signed - 1.0) ** 2)
+    assert err_plain > 0.5 and err_signed < 0.08
+    # through the pool functions, both rotating codecs
+    rng = np.random.default_rng(52)
+    K = rng.standard_normal((1, 1, 40, 64)).astype(np.float16)
+    Vp = (1.0 + 0.05 * rng.standard_normal((1, 1, 40, 64))).astype(np.float16)
+    for scaled in (False, True):
+        a = O.pool_decode(O.pool_encode(K, Vp, scaled_values=scaled))[1]
+        b = O.pool_decode(O.pool_encode(K, Vp, scaled_values=scaled, sign_seed=7))[1]
+        V64 = Vp.astype(np.float64)
+        assert np.mean((b - V64) ** 2) < 0.2 * np.mean((a - V64) ** 2)
+    with pytest.raises(ValueError):
+        O.pool_encode(K, Vp, int8_values=True, sign_seed=7)
