@@ -70,6 +70,13 @@ enum { POLYKV_VALUES_TQ3 = 0, POLYKV_VALUES_TQ3_SCALED = 1, POLYKV_VALUES_INT8 =
 int pool_create(int layers, int kv_heads, int head_dim, int tokens, polykv_pool** out);
 /* The same with a choice of value codec (POLYKV_VALUES_*); pool_create uses POLYKV_VALUES_TQ3. */
 int pool_create_codec(int layers, int kv_heads, int head_dim, int tokens, int value_codec, polykv_pool** out);
+/* Rotation variant: v_rot = H_d D v / sqrt(d) with D a fixed diagonal of pseudorandom signs (the randomized
+ * Hadamard rotation of the rotation-based quantizers discussed in section "Related Work"), which keeps
+ * structured vectors from piling onto a few rotated coordinates; dequantization applies D H_d / sqrt(d).
+ * Coordinate i is negated iff output i of the SplitMix64 generator started at `seed` is odd; seed 0 (the
+ * default) is the paper's plain transform.  Call before any token is encoded (POLYKV_ESTATE otherwise, and for
+ * a POLYKV_VALUES_INT8 pool, whose values are not rotated). */
+int pool_set_sign_seed(polykv_pool* pool, uint64_t seed);
 void pool_destroy(polykv_pool* pool);
 
 /* Bytes of device storage the packed pool needs (tokens are padded to tiles of 32; per token and

@@ -101,6 +101,7 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
         return POLYKV_EINVAL;
     }
     p.io_bf16 = prm->io_dtype == POLYKV_BF16 ? 1 : 0;
+    p.signs = pool->signs;
 
     const bool mat_ok = matrix_kernel_supports(p.D, p.R);
     if (prm->kernel == POLYKV_KERNEL_MATRIX && !mat_ok) {
@@ -197,7 +198,35 @@ int pool_create_codec(int layers, int kv_heads, int head_dim, int tokens, int va
     p->bytes = (size_t)layers * kv_heads * p->tiles * p->tile_bytes;
     p->storage = nullptr;
     p->length = 0;
+    memset(&p->signs, 0, sizeof(p->signs));
     *out = p;
+    return POLYKV_OK;
+}
+
+int pool_set_sign_seed(polykv_pool* pool, uint64_t seed) {
+    if (pool == nullptr) {
+        set_error("pool_set_sign_seed: pool is NULL");
+        return POLYKV_EINVAL;
+    }
+    if (pool->length != 0) {
+        set_error("pool_set_sign_seed: the pool already holds %d tokens", pool->length);
+        return POLYKV_ESTATE;
+    }
+    if (seed != 0 && pool->value_codec == POLYKV_VALUES_INT8) {
+        set_error("pool_set_sign_seed: int8 values are not rotated");
+        return POLYKV_ESTATE;
+    }
+    memset(&pool->signs, 0, sizeof(pool->signs));
+    if (seed == 0) return POLYKV_OK;
+    for (int i = 0; i < pool->head_dim; ++i) {
+        // output i of SplitMix64 started at `seed`; the coordinate is negated iff it is odd
+        uint64_t z = seed + (uint64_t)(i + 1) * 0x9E3779B97F4A7C15ull;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        z ^= z >> 31;
+        if (z & 1) pool->signs.w[i >> 5] |= 1u << (i & 31);
+    }
+    pool->signs.on = (pool->signs.w[0] | pool->signs.w[1] | pool->signs.w[2] | pool->signs.w[3]) != 0;
     return POLYKV_OK;
 }
 

@@ -434,6 +434,8 @@ __global__ __launch_bounds__(256) void attend_merge_kernel(const float* __restri
         x[i] = wht_lane_stage<32>(x[i], lane);
         x[i] *= (D == 64 ? 0.125f : 0.08838834764831845f);
     }
+    if (p.signs.on && p.vcodec != POLYKV_VALUES_INT8)  // rotation variant H.D: coordinates lane*EPL ..
+        flip_signs<EPL>(x, sign_word(p.signs, (lane * EPL) >> 5) >> ((lane * EPL) & 31));
     if (tail_l > 0.0f) {
         const float M2 = fmaxf(M, tail_m);
         const float wa = exp2f(M - M2) * Lsum, wb = exp2f(tail_m - M2);

@@ -569,6 +569,8 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
             if (VC != 2) {
                 wht_cross_quad<CPL>(x, lane);
                 wht_inlane<CPL>(x);
+                // rotation variant H.D: the lane's CPL coordinates start at qd * CPL
+                if (p.signs.on) flip_signs<CPL>(x, sign_word(p.signs, (qd * CPL) >> 5) >> ((qd * CPL) & 31));
             }
             if (r < p.R) {
                 float4* dst = reinterpret_cast<float4*>(out + q_row_index(p, ls, kvh, r) * D + qd * CPL);

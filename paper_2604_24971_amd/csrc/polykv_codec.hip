@@ -52,7 +52,7 @@ template <int D, int VC, bool BF>
 __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ K,
                                                      const __half* __restrict__ V,
                                                      uint8_t* __restrict__ pool, int in_tokens, int tok_begin,
-                                                     int tok_end, int tiles_cap) {
+                                                     int tok_end, int tiles_cap, SignBits signs) {
     // K, V hold in_tokens = tok_end - tok_begin tokens per (layer, KV head); they become pool tokens
     // [tok_begin, tok_end).  blockIdx.x counts tiles from the first one touched.  Tokens of that tile that
     // lie before tok_begin were encoded earlier and are carried over; tokens from tok_end on are padding
@@ -235,6 +235,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
             }
             if (c == 0 && !old_token) reinterpret_cast<__half*>(kimg + LY::vscales_off)[t] = g16;
         }
+        if (signs.on) flip_signs<EPT>(y, sign_word(signs, e0 >> 5) >> (e0 & 31));  // rotation H.D: D first
         wht_cross_chunks<EPT>(y, lane);
         wht_inlane<EPT>(y);
         uint8_t* dst = vstage + e0 * VST + t;
@@ -365,7 +366,7 @@ template <int N> struct RowStore<float, N> {
 template <int D, int VC, typename OutT>
 __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ pool,
                                                      OutT* __restrict__ K_out, OutT* __restrict__ V_out,
-                                                     int T, int tiles) {
+                                                     int T, int tiles, SignBits signs) {
     using LY = Layout<D, VC>;
     constexpr int EPT = D / 8;
     constexpr int KBYTES = LY::vcodes_off;
@@ -478,6 +479,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
         }
         wht_cross_chunks<EPT>(y, lane);
         wht_inlane<EPT>(y);
+        if (signs.on) flip_signs<EPT>(y, sign_word(signs, e0 >> 5) >> (e0 & 31));  // inverse of H.D: D last
         if (valid) RowStore<OutT, EPT>::store(V_out + row, y);
     }
 }
@@ -556,10 +558,12 @@ hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, int
     for_pool_shape(p, [&](auto d, auto vs) {
         if (in_dtype == POLYKV_BF16)
             launch_main_kernel(encode_kernel<decltype(d)::value, decltype(vs)::value, true>, grid, dim3(256), 0, s,
-                               (const __half*)K, (const __half*)V, (uint8_t*)p->storage, count, begin, end, p->tiles);
+                               (const __half*)K, (const __half*)V, (uint8_t*)p->storage, count, begin, end, p->tiles,
+                               p->signs);
         else
             launch_main_kernel(encode_kernel<decltype(d)::value, decltype(vs)::value, false>, grid, dim3(256), 0, s,
-                               (const __half*)K, (const __half*)V, (uint8_t*)p->storage, count, begin, end, p->tiles);
+                               (const __half*)K, (const __half*)V, (uint8_t*)p->storage, count, begin, end, p->tiles,
+                               p->signs);
     });
     return hipGetLastError();
 }
@@ -573,13 +577,13 @@ hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dty
         constexpr int VC = decltype(vs)::value;
         if (dtype == POLYKV_BF16)
             launch_main_kernel(decode_kernel<D, VC, Bf16Out>, grid, dim3(256), 0, s, pool, (Bf16Out*)K_out, (Bf16Out*)V_out,
-                               p->length, p->tiles);
+                               p->length, p->tiles, p->signs);
         else if (dtype == POLYKV_F32)
             launch_main_kernel(decode_kernel<D, VC, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out,
-                               p->length, p->tiles);
+                               p->length, p->tiles, p->signs);
         else
             launch_main_kernel(decode_kernel<D, VC, __half>, grid, dim3(256), 0, s, pool, (__half*)K_out, (__half*)V_out,
-                               p->length, p->tiles);
+                               p->length, p->tiles, p->signs);
     });
     return hipGetLastError();
 }

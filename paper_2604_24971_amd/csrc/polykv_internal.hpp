@@ -7,6 +7,12 @@
 
 #include "../../include/polykv.h"
 
+// Sign diagonal D of the rotation variant H.D: bit i of w[] set = coordinate i is negated; on = any set.
+struct SignBits {
+    uint32_t w[4];
+    uint32_t on;
+};
+
 struct polykv_pool {
     int layers, kv_heads, head_dim, tokens;
     int value_codec;    // POLYKV_VALUES_*
@@ -15,6 +21,7 @@ struct polykv_pool {
     size_t bytes;       // layers * kv_heads * tiles * tile_bytes
     void* storage;      // device, caller-owned
     int length;         // tokens encoded so far (0 = nothing to read yet), <= tokens
+    SignBits signs;     // all zero: the plain transform
 };
 
 namespace polykv {
@@ -33,6 +40,7 @@ struct AttendPlan {
     int nsplit;                  // token-range splits per KV head
     int has_tails, tail_capacity, tail_causal;
     int io_bf16;                 // 1: Q and the tails are bfloat16, 0: fp16
+    SignBits signs;              // the pool's sign diagonal
     // workspace carving (byte offsets from the 256-aligned workspace base)
     size_t off_ml, off_o, off_tail_ml, off_tail_o, total;
 };

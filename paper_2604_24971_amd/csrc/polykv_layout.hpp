@@ -118,6 +118,22 @@ __device__ __forceinline__ int vcode_extract(const uint32_t* v, int t, int dv) {
     return ((w[2] >> (8 * (e - 4) + 6)) & 3) | (((w[1] >> (8 * (e - 4) + 7)) & 1) << 2);
 }
 
+// ---- sign diagonal of the rotation variant (struct SignBits: bit i set = coordinate i negated) ---
+// The 32-bit word holding coordinates 32*idx .. 32*idx+31; idx may differ between lanes.
+template <typename S> __device__ __forceinline__ uint32_t sign_word(const S& s, int idx) {
+    uint32_t r = s.w[0];
+    r = idx == 1 ? s.w[1] : r;
+    r = idx == 2 ? s.w[2] : r;
+    r = idx == 3 ? s.w[3] : r;
+    return r;
+}
+// Negates y[i] where bit i of `bits` is set (y[i] = coordinate e0 + i, bits = sign_word(e0 / 32) >> (e0 % 32)).
+template <int N> __device__ __forceinline__ void flip_signs(float (&y)[N], uint32_t bits) {
+    static_assert(N <= 32, "");
+#pragma unroll
+    for (int i = 0; i < N; ++i) y[i] = __uint_as_float(__float_as_uint(y[i]) ^ ((bits << (31 - i)) & 0x80000000u));
+}
+
 // ---- 16-bit floating-point inputs: fp16, or bfloat16 (the top half of an fp32) ------------------
 // Two packed 16-bit values -> fp32; `bf` is uniform over the wave.
 __device__ __forceinline__ float2 pair16_to_float2(uint32_t w, bool bf) {

@@ -47,6 +47,8 @@ def _load():
     lib.pool_create.restype = ip
     lib.pool_create_codec.argtypes = [ip, ip, ip, ip, ip, C.POINTER(vp)]
     lib.pool_create_codec.restype = ip
+    lib.pool_set_sign_seed.argtypes = [vp, C.c_uint64]
+    lib.pool_set_sign_seed.restype = ip
     lib.pool_destroy.argtypes = [vp]
     lib.pool_destroy.restype = None
     lib.pool_bytes.argtypes = [vp]
@@ -167,13 +169,15 @@ class Pool:
     """pool_create + pool_bind around a torch-owned storage tensor."""
 
     def __init__(self, layers: int, kv_heads: int, head_dim: int, tokens: int, device="cuda:0",
-                 value_codec: int = VALUES_TQ3):
+                 value_codec: int = VALUES_TQ3, sign_seed: int = 0):
         self.layers, self.kv_heads, self.head_dim, self.tokens = layers, kv_heads, head_dim, tokens
         self.value_codec = value_codec
         self.device = torch.device(device)
         h = C.c_void_p()
         _check(lib.pool_create_codec(layers, kv_heads, head_dim, tokens, value_codec, C.byref(h)))
         self._h = h
+        if sign_seed:
+            _check(lib.pool_set_sign_seed(self._h, sign_seed))
         self.nbytes = lib.pool_bytes(self._h)
         self.storage = None
         self._workspace = None

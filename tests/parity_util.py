@@ -31,10 +31,10 @@ def dev(x, bf16=False):
     return t.to(torch.bfloat16) if bf16 else t
 
 
-def gpu_pool(K, V, scaled_values=False, int8_values=False, bf16=False):
+def gpu_pool(K, V, scaled_values=False, int8_values=False, bf16=False, sign_seed=0):
     L, H, T, d = K.shape
     codec = pk.VALUES_INT8 if int8_values else pk.VALUES_TQ3_SCALED if scaled_values else pk.VALUES_TQ3
-    pool = pk.Pool(L, H, d, T, value_codec=codec).bind()
+    pool = pk.Pool(L, H, d, T, value_codec=codec, sign_seed=sign_seed).bind()
     pool.storage.fill_(0xA5)            # stale bytes must never leak into results
     pool.encode(dev(K, bf16), dev(V, bf16))
     return pool

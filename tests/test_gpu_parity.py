@@ -26,14 +26,14 @@ def _pu():
 class Case:
     """One encoded pool on both sides."""
 
-    def __init__(self, cfg, K=None, V=None, scaled_values=False, int8_values=False):
+    def __init__(self, cfg, K=None, V=None, scaled_values=False, int8_values=False, sign_seed=0):
         pu = _pu()
         self.cfg = cfg
         if K is None:
             K, V = W.kv_pool(cfg)
         self.K, self.V = K, V
-        self.ref = O.pool_encode(K, V, scaled_values=scaled_values, int8_values=int8_values)
-        self.pool = pu.gpu_pool(K, V, scaled_values=scaled_values, int8_values=int8_values)
+        self.ref = O.pool_encode(K, V, scaled_values=scaled_values, int8_values=int8_values, sign_seed=sign_seed)
+        self.pool = pu.gpu_pool(K, V, scaled_values=scaled_values, int8_values=int8_values, sign_seed=sign_seed)
         self.dirty, self.k_mis, self.v_mis = pu.compare_codes(self.pool, self.ref)
         self._dec = None
 
