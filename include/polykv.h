@@ -65,7 +65,7 @@ enum { POLYKV_KERNEL_AUTO = 0, POLYKV_KERNEL_VECTOR = 1, POLYKV_KERNEL_MATRIX = 
 enum { POLYKV_VALUES_TQ3 = 0, POLYKV_VALUES_TQ3_SCALED = 1, POLYKV_VALUES_INT8 = 2 };
 
 /* Host descriptor for a pool of `layers` x `kv_heads` x `tokens` vectors of `head_dim` elements.
- * head_dim must be 64 or 128; all other dimensions >= 1.  (SharedKVPool, section "PolyKV
+ * head_dim must be 64, 128 or 256; all other dimensions >= 1.  (SharedKVPool, section "PolyKV
  * Architecture".)  *out receives the handle; release it with pool_destroy. */
 int pool_create(int layers, int kv_heads, int head_dim, int tokens, polykv_pool** out);
 /* The same with a choice of value codec (POLYKV_VALUES_*); pool_create uses POLYKV_VALUES_TQ3. */

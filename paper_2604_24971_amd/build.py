@@ -32,6 +32,21 @@ def _run(cmd):
     return r.stdout
 
 
+def _check_no_scratch(remarks: str):
+    """The matrix-core attention kernel parks its query operands in accumulation registers; builds in which
+    the register allocator then spilled some of them to scratch memory returned wrong results on the GPU
+    (head_dim 256 and the int8 codec at head_dim 128 with 64-row blocks, both since reshaped).  Refuse such a
+    build: every instantiation that parks (head_dim 64 and 128) must come out without scratch."""
+    name = None
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split()[0]
+        elif "ScratchSize" in line and name and "attend_mfma_kernel" in name and "Li256E" not in name:
+            size = int(line.split("ScratchSize [bytes/lane]:")[1].split()[0])
+            if size:
+                raise RuntimeError("%s spills %d bytes per lane to scratch: reduce its register use" % (name, size))
+
+
 def build_library(verbose: bool = True, extra_flags=()) -> str:
     """Compile every source and link the shared library; always recompiles."""
     hipcc = _hipcc()
@@ -40,7 +55,12 @@ def build_library(verbose: bool = True, extra_flags=()) -> str:
     objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
 
     def compile_one(i):
-        return _run([hipcc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, SOURCES[i]), "-o", objs[i]])
+        cmd = [hipcc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, SOURCES[i]), "-o", objs[i]]
+        if SOURCES[i] == "polykv_attend_mfma.hip":
+            log = _run(cmd + ["-Rpass-analysis=kernel-resource-usage", "-fno-caret-diagnostics"])
+            _check_no_scratch(log)
+            return "\n".join(l for l in log.splitlines() if "kernel-resource-usage" not in l)
+        return _run(cmd)
 
     with ThreadPoolExecutor(max_workers=4) as ex:
         logs = list(ex.map(compile_one, range(len(SOURCES))))

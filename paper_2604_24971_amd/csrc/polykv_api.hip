@@ -128,7 +128,8 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
         // tiles per wave -- below that the per-workgroup prologue, epilogue and the partials written for
         // the merge kernel cost more than the idle CUs (measured on one-layer calls of the Llama shape:
         // 16 splits of 8 tiles 16.8 us, 32 splits of 4 tiles 19.3 us).
-        const int block_rows = (p.vcodec == POLYKV_VALUES_INT8 && p.D == 128) ? 32 : 64;  // rows per workgroup
+        // rows per workgroup: 64, or 32 where 64 rows of accumulators do not fit
+        const int block_rows = (p.D == 256 || (p.vcodec == POLYKV_VALUES_INT8 && p.D == 128)) ? 32 : 64;
         const long groups = (long)units * ((p.R + block_rows - 1) / block_rows);
         long want = (256 + groups - 1) / groups;
         if (want > cap_tiles / 8) want = cap_tiles / 8;
@@ -172,8 +173,8 @@ int pool_create_codec(int layers, int kv_heads, int head_dim, int tokens, int va
         set_error("pool_create: unknown value codec %d", value_codec);
         return POLYKV_EINVAL;
     }
-    if (head_dim != 64 && head_dim != 128) {
-        set_error("pool_create: head_dim=%d not supported (64 or 128)", head_dim);
+    if (head_dim != 64 && head_dim != 128 && head_dim != 256) {
+        set_error("pool_create: head_dim=%d not supported (64, 128 or 256)", head_dim);
         return POLYKV_ESHAPE;
     }
     if (layers < 1 || kv_heads < 1 || tokens < 1 || (long)layers * kv_heads > 65535) {
@@ -194,7 +195,8 @@ int pool_create_codec(int layers, int kv_heads, int head_dim, int tokens, int va
     p->value_codec = value_codec;
     const int tb128[3] = {Layout<128, 0>::tile_bytes, Layout<128, 1>::tile_bytes, Layout<128, 2>::tile_bytes};
     const int tb64[3] = {Layout<64, 0>::tile_bytes, Layout<64, 1>::tile_bytes, Layout<64, 2>::tile_bytes};
-    p->tile_bytes = head_dim == 128 ? tb128[value_codec] : tb64[value_codec];
+    const int tb256[3] = {Layout<256, 0>::tile_bytes, Layout<256, 1>::tile_bytes, Layout<256, 2>::tile_bytes};
+    p->tile_bytes = head_dim == 128 ? tb128[value_codec] : head_dim == 64 ? tb64[value_codec] : tb256[value_codec];
     p->bytes = (size_t)layers * kv_heads * p->tiles * p->tile_bytes;
     p->storage = nullptr;
     p->length = 0;
@@ -226,7 +228,7 @@ int pool_set_sign_seed(polykv_pool* pool, uint64_t seed) {
         z ^= z >> 31;
         if (z & 1) pool->signs.w[i >> 5] |= 1u << (i & 31);
     }
-    pool->signs.on = (pool->signs.w[0] | pool->signs.w[1] | pool->signs.w[2] | pool->signs.w[3]) != 0;
+    for (int k = 0; k < 8; ++k) pool->signs.on |= pool->signs.w[k] != 0;
     return POLYKV_OK;
 }
 

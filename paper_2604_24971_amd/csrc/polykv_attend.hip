@@ -432,7 +432,7 @@ __global__ __launch_bounds__(256) void attend_merge_kernel(const float* __restri
         x[i] = wht_lane_stage<8>(x[i], lane);
         x[i] = wht_lane_stage<16>(x[i], lane);
         x[i] = wht_lane_stage<32>(x[i], lane);
-        x[i] *= (D == 64 ? 0.125f : 0.08838834764831845f);
+        x[i] *= (D == 64 ? 0.125f : D == 128 ? 0.08838834764831845f : 0.0625f);
     }
     if (p.signs.on && p.vcodec != POLYKV_VALUES_INT8)  // rotation variant H.D: coordinates lane*EPL ..
         flip_signs<EPL>(x, sign_word(p.signs, (lane * EPL) >> 5) >> ((lane * EPL) & 31));
@@ -468,10 +468,11 @@ hipError_t launch_attend(const polykv_pool* pool, const AttendPlan& plan, const 
         if (matrix_kernel_direct(plan)) return hipSuccess;
     } else {
         dim3 grid(plan.nsplit / 4, units, (plan.R + kRB - 1) / kRB);
-        decltype(&attend_vector_kernel<128, 0>) table[2][3] = {
+        decltype(&attend_vector_kernel<128, 0>) table[3][3] = {
             {attend_vector_kernel<64, 0>, attend_vector_kernel<64, 1>, attend_vector_kernel<64, 2>},
-            {attend_vector_kernel<128, 0>, attend_vector_kernel<128, 1>, attend_vector_kernel<128, 2>}};
-        auto kern = table[plan.D == 128][plan.vcodec];
+            {attend_vector_kernel<128, 0>, attend_vector_kernel<128, 1>, attend_vector_kernel<128, 2>},
+            {attend_vector_kernel<256, 0>, attend_vector_kernel<256, 1>, attend_vector_kernel<256, 2>}};
+        auto kern = table[plan.D == 64 ? 0 : plan.D == 128 ? 1 : 2][plan.vcodec];
         launch_main_kernel(kern, grid, dim3(256), 0, s, storage, (const __half*)Q, ws_ml, ws_o, plan);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
@@ -479,16 +480,20 @@ hipError_t launch_attend(const polykv_pool* pool, const AttendPlan& plan, const 
         dim3 grid(plan.A, units, (plan.nq * plan.G + kRB - 1) / kRB);
         if (plan.D == 128)
             attend_tail_kernel<128><<<grid, 64, 0, s>>>((const __half*)Q, *tails, tail_ml, tail_o, plan);
-        else
+        else if (plan.D == 64)
             attend_tail_kernel<64><<<grid, 64, 0, s>>>((const __half*)Q, *tails, tail_ml, tail_o, plan);
+        else
+            attend_tail_kernel<256><<<grid, 64, 0, s>>>((const __half*)Q, *tails, tail_ml, tail_o, plan);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     const long nrows = (long)units * plan.R;
     dim3 mgrid((unsigned)((nrows + 3) / 4));
     if (plan.D == 128)
         attend_merge_kernel<128><<<mgrid, 256, 0, s>>>(ws_ml, ws_o, tail_ml, tail_o, (float*)out, plan);
-    else
+    else if (plan.D == 64)
         attend_merge_kernel<64><<<mgrid, 256, 0, s>>>(ws_ml, ws_o, tail_ml, tail_o, (float*)out, plan);
+    else
+        attend_merge_kernel<256><<<mgrid, 256, 0, s>>>(ws_ml, ws_o, tail_ml, tail_o, (float*)out, plan);
     return hipGetLastError();
 }
 

@@ -457,7 +457,9 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
                 qb[nt][j][s] = *reinterpret_cast<const half8*>(q_s + (32 * nt + n) * QS + 32 * j + 16 * s + 8 * h);
                 // The queries are only ever MFMA operands: park them in accumulation registers so that
                 // the vector registers are left for the scores and the dequantization temporaries.
-                asm volatile("" : "+a"(qb[nt][j][s]));
+                // (Not at head_dim 256: there the allocator has to spill, and builds that spilled parked
+                // operands to scratch memory computed wrong results.)
+                if constexpr (D != 256) asm volatile("" : "+a"(qb[nt][j][s]));
             }
 
     float16v O[MG][NT];
@@ -551,7 +553,8 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         // direct: 1/l, the centroid scale, 1/sqrt(D) and the entry sign of the DPP stages in one factor
         // int8 values are accumulated unrotated and unscaled: 1/l is all that is left to do
         const float f = VC == 2 ? (direct ? __builtin_amdgcn_rcpf(l) : 1.0f)
-                        : direct ? quad_entry_sign(lane) * (kInvCentroidScale * (D == 64 ? 0.125f : 0.08838834764831845f)) *
+                        : direct ? quad_entry_sign(lane) *
+                                       (kInvCentroidScale * (D == 64 ? 0.125f : D == 128 ? 0.08838834764831845f : 0.0625f)) *
                                        __builtin_amdgcn_rcpf(l)
                                  : kInvCentroidScale;
         float x[CPL];
@@ -570,7 +573,16 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
                 wht_cross_quad<CPL>(x, lane);
                 wht_inlane<CPL>(x);
                 // rotation variant H.D: the lane's CPL coordinates start at qd * CPL
-                if (p.signs.on) flip_signs<CPL>(x, sign_word(p.signs, (qd * CPL) >> 5) >> ((qd * CPL) & 31));
+                if (p.signs.on) {
+                    if constexpr (CPL <= 32) {
+                        flip_signs<CPL>(x, sign_word(p.signs, (qd * CPL) >> 5) >> ((qd * CPL) & 31));
+                    } else {  // 64 coordinates per lane: two sign words
+                        float(&lo)[32] = *reinterpret_cast<float(*)[32]>(&x[0]);
+                        float(&hi)[32] = *reinterpret_cast<float(*)[32]>(&x[32]);
+                        flip_signs<32>(lo, sign_word(p.signs, 2 * qd));
+                        flip_signs<32>(hi, sign_word(p.signs, 2 * qd + 1));
+                    }
+                }
             }
             if (r < p.R) {
                 float4* dst = reinterpret_cast<float4*>(out + q_row_index(p, ls, kvh, r) * D + qd * CPL);
@@ -591,7 +603,7 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
 }
 
 bool matrix_kernel_supports(int head_dim, int rows_per_kv_head) {
-    return (head_dim == 64 || head_dim == 128) && rows_per_kv_head >= 1;
+    return (head_dim == 64 || head_dim == 128 || head_dim == 256) && rows_per_kv_head >= 1;
 }
 
 bool matrix_kernel_direct(const AttendPlan& plan) { return plan.nsplit == 1 && !plan.has_tails; }
@@ -612,32 +624,36 @@ static hipError_t launch_one(dim3 grid, const uint8_t* storage, const AttendPlan
     return hipGetLastError();
 }
 
-template <int D>
-static hipError_t launch_d(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,
-                           float* ws_o, float* out, hipStream_t s) {
+// Row tiles per workgroup: two (64 rows) where the accumulators, the parked queries and two staged tiles
+// fit the 512 registers of a wave; one (32 rows) at head_dim 256 and for the int8 value codec at head_dim
+// 128, whose staged value codes take 16 registers per tile.
+template <int D, int VC>
+static hipError_t launch_dv(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml, float* ws_o,
+                            float* out, hipStream_t s) {
     const uint8_t* storage = reinterpret_cast<const uint8_t*>(pool->storage);
     const int units = plan.layers * plan.H;
     const int direct = matrix_kernel_direct(plan) ? 1 : 0;
-    const dim3 grid1(plan.nsplit, units, 1), grid2(plan.nsplit, units, (plan.R + 63) / 64);
-    if (plan.vcodec == POLYKV_VALUES_TQ3_SCALED) {
-        if (plan.R <= 32) return launch_one<D, 1, 1>(grid1, storage, plan, Q, ws_ml, ws_o, out, direct, s);
-        return launch_one<D, 2, 1>(grid2, storage, plan, Q, ws_ml, ws_o, out, direct, s);
+    constexpr bool two_tiles_fit = D == 64 || (D == 128 && VC != 2);
+    if constexpr (two_tiles_fit) {
+        if (plan.R > 32)
+            return launch_one<D, 2, VC>(dim3(plan.nsplit, units, (plan.R + 63) / 64), storage, plan, Q, ws_ml, ws_o, out,
+                                        direct, s);
     }
-    if (plan.vcodec == POLYKV_VALUES_INT8) {
-        // At head_dim 128 the staged int8 value codes (16 registers per tile, twice) do not fit beside 64
-        // rows of accumulators: that shape runs blocks of 32 rows.
-        if (D == 128 || plan.R <= 32)
-            return launch_one<D, 1, 2>(dim3(plan.nsplit, units, (plan.R + 31) / 32), storage, plan, Q, ws_ml, ws_o, out,
-                                       direct, s);
-        if constexpr (D != 128) return launch_one<D, 2, 2>(grid2, storage, plan, Q, ws_ml, ws_o, out, direct, s);
-    }
-    if (plan.R <= 32) return launch_one<D, 1, 0>(grid1, storage, plan, Q, ws_ml, ws_o, out, direct, s);
-    return launch_one<D, 2, 0>(grid2, storage, plan, Q, ws_ml, ws_o, out, direct, s);
+    return launch_one<D, 1, VC>(dim3(plan.nsplit, units, (plan.R + 31) / 32), storage, plan, Q, ws_ml, ws_o, out, direct, s);
+}
+
+template <int D>
+static hipError_t launch_d(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,
+                           float* ws_o, float* out, hipStream_t s) {
+    if (plan.vcodec == POLYKV_VALUES_TQ3_SCALED) return launch_dv<D, 1>(pool, plan, Q, ws_ml, ws_o, out, s);
+    if (plan.vcodec == POLYKV_VALUES_INT8) return launch_dv<D, 2>(pool, plan, Q, ws_ml, ws_o, out, s);
+    return launch_dv<D, 0>(pool, plan, Q, ws_ml, ws_o, out, s);
 }
 
 hipError_t launch_attend_matrix(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,
                                 float* ws_o, float* out, hipStream_t s) {
     if (plan.D == 128) return launch_d<128>(pool, plan, Q, ws_ml, ws_o, out, s);
+    if (plan.D == 256) return launch_d<256>(pool, plan, Q, ws_ml, ws_o, out, s);
     return launch_d<64>(pool, plan, Q, ws_ml, ws_o, out, s);
 }
 

@@ -21,10 +21,10 @@
 namespace polykv {
 
 template <int D> __device__ __forceinline__ constexpr float inv_sqrt_d() {
-    return D == 64 ? 0.125f : 0.08838834764831845f;
+    return D == 64 ? 0.125f : D == 128 ? 0.08838834764831845f : 0.0625f;
 }
 template <int D> __device__ __forceinline__ constexpr float sqrt_d() {
-    return D == 64 ? 8.0f : 11.313708498984761f;
+    return D == 64 ? 8.0f : D == 128 ? 11.313708498984761f : 16.0f;
 }
 
 union Half2Bits {
@@ -91,8 +91,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         const uint4* src = reinterpret_cast<const uint4*>(rec);
         for (int i = tid; i < KBYTES / 16; i += 256) reinterpret_cast<uint4*>(kimg)[i] = src[i];
         if (V8) {
-            if (tid < LY::NB * 64) {
-                const int g = tid >> 6;
+            for (int g = tid >> 6; g < LY::NB; g += 4) {
                 const uint4 w = *reinterpret_cast<const uint4*>(rec + LY::vcodes_off + g * 1024 + lane * 16);
                 uint8_t* dst = vstage + (32 * g + (lane & 31)) * VST + 4 * (lane >> 5);  // tokens 4h.., 8+4h.., 16+4h.., 24+4h..
                 *reinterpret_cast<uint32_t*>(dst) = w.x;
@@ -100,7 +99,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
                 *reinterpret_cast<uint32_t*>(dst + 16) = w.z;
                 *reinterpret_cast<uint32_t*>(dst + 24) = w.w;
             }
-        } else if (tid < LY::NT * 64) {
+        } else if (tid < LY::NT * 64) {  // NT <= 4: one wave per triplet
             const int q = tid >> 6;
             const uint32_t* w = reinterpret_cast<const uint32_t*>(rec + LY::vcodes_off + q * 768 + lane * 12);
             const uint32_t w0 = w[0], w1 = w[1], w2 = w[2];
@@ -129,7 +128,8 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         float amax = 0.0f;
 #pragma unroll
         for (int i = 0; i < EPT; i += 2) amax = fmaxf(fmaxf(fabsf(k[i]), fabsf(k[i + 1])), amax);
-        amax = fmaxf(amax, lane_xor<1>(amax));
+        // a q8_0 block of 32 elements spans 32 / EPT lanes
+        if (EPT <= 16) amax = fmaxf(amax, lane_xor<1>(amax));
         if (EPT == 8) amax = fmaxf(amax, lane_xor<2>(amax));
         // bfloat16 keys can exceed what an fp16 scale holds: it saturates at the fp16 maximum
         const float sraw = __fdiv_rn(amax, 127.0f);
@@ -265,8 +265,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
 
     // ---- int8 values: one lane's 16 bytes of a coordinate group per thread, in P.V operand order
     if (V8) {
-        if (tid < LY::NB * 64) {
-            const int g = tid >> 6;
+        for (int g = tid >> 6; g < LY::NB; g += 4) {
             const uint8_t* src = vstage + (32 * g + (lane & 31)) * VST + 4 * (lane >> 5);
             uint4 w;
             w.x = *reinterpret_cast<const uint32_t*>(src);
@@ -392,8 +391,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
         for (int i = tid; i < KBYTES / 16; i += 256) dst[i] = src[i];
     }
     if (V8) {
-        if (V_out != nullptr && tid < LY::NB * 64) {
-            const int g = tid >> 6;
+        for (int g = tid >> 6; V_out != nullptr && g < LY::NB; g += 4) {
             const uint4 w = *reinterpret_cast<const uint4*>(rec + LY::vcodes_off + g * 1024 + lane * 16);
             uint8_t* dst = vbuf + (32 * g + (lane & 31)) * VST + 4 * (lane >> 5);
             *reinterpret_cast<uint32_t*>(dst) = w.x;
@@ -401,9 +399,10 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
             *reinterpret_cast<uint32_t*>(dst + 16) = w.z;
             *reinterpret_cast<uint32_t*>(dst + 24) = w.w;
         }
-    } else if (V_out != nullptr && tid < LY::NT * 128) {
-        // thread (half, q, lane): two of the four coordinate groups of one lane triplet
-        const int half = tid / (LY::NT * 64), ql = tid - half * (LY::NT * 64);
+    } else if (V_out != nullptr) {
+      for (int x = tid; x < LY::NT * 128; x += 256) {
+        // work item (half, q, lane): two of the four coordinate groups of one lane triplet
+        const int half = x / (LY::NT * 64), ql = x - half * (LY::NT * 64);
         const int q = ql >> 6;
         const uint32_t* w = reinterpret_cast<const uint32_t*>(rec + LY::vcodes_off + q * 768 + lane * 12);
         const uint32_t w0 = w[0], w1 = w[1], w2 = w[2];
@@ -428,6 +427,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
             col[10 * CS] = c67.h[0];
             col[11 * CS] = c67.h[1];
         }
+      }
     }
     __syncthreads();
 
@@ -547,8 +547,10 @@ template <typename F> static void for_pool_shape(const polykv_pool* p, F&& f) {
     };
     if (p->head_dim == 128)
         with_d(integral_constant<int, 128>{});
-    else
+    else if (p->head_dim == 64)
         with_d(integral_constant<int, 64>{});
+    else
+        with_d(integral_constant<int, 256>{});
 }
 
 hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, int in_dtype, int begin, int count,

@@ -9,7 +9,7 @@
 
 // Sign diagonal D of the rotation variant H.D: bit i of w[] set = coordinate i is negated; on = any set.
 struct SignBits {
-    uint32_t w[4];
+    uint32_t w[8];
     uint32_t on;
 };
 

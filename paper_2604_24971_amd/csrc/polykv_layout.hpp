@@ -122,9 +122,8 @@ __device__ __forceinline__ int vcode_extract(const uint32_t* v, int t, int dv) {
 // The 32-bit word holding coordinates 32*idx .. 32*idx+31; idx may differ between lanes.
 template <typename S> __device__ __forceinline__ uint32_t sign_word(const S& s, int idx) {
     uint32_t r = s.w[0];
-    r = idx == 1 ? s.w[1] : r;
-    r = idx == 2 ? s.w[2] : r;
-    r = idx == 3 ? s.w[3] : r;
+#pragma unroll
+    for (int k = 1; k < 8; ++k) r = idx == k ? s.w[k] : r;
     return r;
 }
 // Negates y[i] where bit i of `bits` is set (y[i] = coordinate e0 + i, bits = sign_word(e0 / 32) >> (e0 % 32)).

@@ -55,6 +55,9 @@ CONFIGS = {
     3: PoolConfig(3, "llama3-8b-shape-4096", 32, 8, 32, 128, 4096, 15, 1),
     4: PoolConfig(4, "llama3-8b-shape-7194-tails", 32, 8, 32, 128, 7194, 15, 1, max_tail=64),
     5: PoolConfig(5, "llama3-8b-shape-7194-stress", 32, 8, 32, 128, 7194, 64, 4),
+    # not one of the paper's workloads: a head_dim-256 shape (16 query heads over 8 KV heads) for the extra
+    # kernel instantiations
+    6: PoolConfig(6, "head-dim-256-shape-4096", 26, 8, 16, 256, 4096, 15, 1),
 }
 
 

@@ -45,7 +45,7 @@ def _create(L, H, d, T):
 
 
 def test_create_validation_and_byte_counts():
-    for bad in [(1, 1, 96, 10), (1, 1, 256, 10), (0, 1, 64, 10), (1, 0, 64, 10), (1, 1, 64, 0),
+    for bad in [(1, 1, 96, 10), (1, 1, 512, 10), (1, 1, 32, 10), (0, 1, 64, 10), (1, 0, 64, 10), (1, 1, 64, 0),
                 (1, 1, 64, -5), (70000, 1, 64, 10)]:
         rc, h = _create(*bad)
         assert rc == pk.ESHAPE and not h.value
@@ -53,7 +53,7 @@ def test_create_validation_and_byte_counts():
     assert lib.pool_create(1, 1, 64, 1, None) == pk.EINVAL
     assert lib.pool_bytes(None) == 0
     # tile-multiple token counts: exactly the oracle's stored byte count (184 / 92 B per token-head)
-    for (L, H, d, T) in [(32, 8, 128, 4096), (1, 4, 64, 640), (24, 32, 64, 1856)]:
+    for (L, H, d, T) in [(32, 8, 128, 4096), (1, 4, 64, 640), (24, 32, 64, 1856), (2, 4, 256, 320)]:
         rc, h = _create(L, H, d, T)
         assert rc == pk.OK
         assert lib.pool_bytes(h) == O.stored_bytes(L, H, T, d)["packed"]
