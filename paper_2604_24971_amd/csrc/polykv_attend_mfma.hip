@@ -427,10 +427,19 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     // (the merge buffers are idle until the end) and picked up from there in operand order.
     constexpr int QS = D + 8;  // halves per staged row: 16-byte aligned, rotates the banks
     _Float16* q_s = reinterpret_cast<_Float16*>(o_s);
-    for (int i = tid; i < ROWS * (D / 8); i += 256) {
-        const int rr = i / (D / 8), piece = i - rr * (D / 8), r = row0 + rr;
-        uint4v raw = {0, 0, 0, 0};
-        if (r < p.R) raw = *reinterpret_cast<const uint4v*>(Q + q_row_index(p, ls, kvh, r) * D + 8 * piece);
+    constexpr int QP = ROWS * (D / 8) / 256;  // 16-byte pieces per thread; all requested before any is used
+    static_assert(QP * 256 == ROWS * (D / 8), "");
+    uint4v qraw[QP];
+#pragma unroll
+    for (int u = 0; u < QP; ++u) {
+        // rows past the end re-read the last row (no branch between the loads) and are zeroed below
+        const int i = tid + 256 * u, rr = i / (D / 8), piece = i - rr * (D / 8), r = min(row0 + rr, p.R - 1);
+        qraw[u] = *reinterpret_cast<const uint4v*>(Q + q_row_index(p, ls, kvh, r) * D + 8 * piece);
+    }
+#pragma unroll
+    for (int u = 0; u < QP; ++u) {
+        const int i = tid + 256 * u, rr = i / (D / 8), piece = i - rr * (D / 8);
+        uint4v raw = row0 + rr < p.R ? qraw[u] : uint4v{0, 0, 0, 0};
         if (p.io_bf16) {  // bfloat16 queries become fp16 operands (exact for magnitudes fp16 holds)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
@@ -453,14 +462,21 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
 #pragma unroll
         for (int j = 0; j < NB; ++j)
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
+            for (int s = 0; s < 2; ++s)
                 qb[nt][j][s] = *reinterpret_cast<const half8*>(q_s + (32 * nt + n) * QS + 32 * j + 16 * s + 8 * h);
-                // The queries are only ever MFMA operands: park them in accumulation registers so that
-                // the vector registers are left for the scores and the dequantization temporaries.
-                // (Not at head_dim 256: there the allocator has to spill, and builds that spilled parked
-                // operands to scratch memory computed wrong results.)
-                if constexpr (D != 256) asm volatile("" : "+a"(qb[nt][j][s]));
-            }
+    // The queries are only ever MFMA operands: park them in accumulation registers so that the vector
+    // registers are left for the scores and the dequantization temporaries (a second loop, so that the LDS
+    // reads above are all in flight before the first one is waited for).  Not at head_dim 256: there the
+    // allocator has to spill, and builds that spilled parked operands to scratch memory computed wrong
+    // results.
+    if constexpr (D != 256) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) asm volatile("" : "+a"(qb[nt][j][s]));
+    }
 
     float16v O[MG][NT];
     float Lsum[NT], m_ref[NT], m_thr[NT], mneg[NT], mloc[NT];
