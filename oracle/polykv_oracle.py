@@ -369,12 +369,22 @@ def v_decode_int8(codes, scales):
 # --------------------------------------------------------------------------- #
 # Pool = encode of a whole [L, H, T, d] cache; decode back
 # --------------------------------------------------------------------------- #
-def pool_encode(K, V, scaled_values: bool = False, int8_values: bool = False, sign_seed: int = 0):
+def pool_encode(K, V, scaled_values: bool = False, int8_values: bool = False, sign_seed: int = 0,
+                key_per_tensor: bool = False):
     """K, V float16 [L, H, T, d] -> dict with the canonical stored arrays and the pre-rounding
     values a parity test needs to find elements that sit on a decision threshold.  sign_seed != 0: the
     rotation carries the sign diagonal rotation_signs(sign_seed, d) (not with int8 values, which are
-    not rotated)."""
-    k_codes, k_scales, k_pre = k_encode(K)
+    not rotated).  key_per_tensor: one key scale per layer tensor [H, T, d], s = max|K|/127 over the
+    whole tensor -- the key formula exactly as section "Compression Scheme" prints it -- instead of one
+    per block of 32; k_scales is then float16 [L]."""
+    if key_per_tensor:
+        K = np.asarray(K)
+        per_layer = [k_encode(K[l], block=None) for l in range(K.shape[0])]
+        k_codes = np.stack([p[0] for p in per_layer])
+        k_scales = np.array([p[1] for p in per_layer], dtype=np.float16)
+        k_pre = np.stack([p[2] for p in per_layer])
+    else:
+        k_codes, k_scales, k_pre = k_encode(K)
     out = {"k_codes": k_codes, "k_scales": k_scales, "k_pre": k_pre}
     if int8_values:
         if sign_seed:
@@ -395,7 +405,11 @@ def pool_encode(K, V, scaled_values: bool = False, int8_values: bool = False, si
 
 
 def pool_decode(pool):
-    K_hat = k_decode(pool["k_codes"], pool["k_scales"])
+    if pool["k_scales"].ndim == 1:      # one scale per layer tensor
+        K_hat = np.stack([k_decode(pool["k_codes"][l], pool["k_scales"][l], block=None)
+                          for l in range(pool["k_codes"].shape[0])])
+    else:
+        K_hat = k_decode(pool["k_codes"], pool["k_scales"])
     if "v_codes" in pool:
         return K_hat, v_decode_int8(pool["v_codes"], pool["v_scales"])
     d = pool["k_codes"].shape[-1]
@@ -405,11 +419,12 @@ def pool_decode(pool):
     return K_hat, V_hat
 
 
-def stored_bytes(L: int, H: int, T: int, d: int, scaled_values: bool = False, int8_values: bool = False) -> dict:
+def stored_bytes(L: int, H: int, T: int, d: int, scaled_values: bool = False, int8_values: bool = False,
+                 key_per_tensor: bool = False) -> dict:
     """Byte accounting (section "Compression Scheme", paragraph "Compression ratio")."""
     n = L * H * T
     k_codes = n * d
-    k_scales = n * (d // Q8_BLOCK) * 2
+    k_scales = L * 2 if key_per_tensor else n * (d // Q8_BLOCK) * 2
     v_codes = n * d if int8_values else n * d * V_BITS // 8
     v_scales = n * 2 if (scaled_values or int8_values) else 0
     dense16 = 2 * n * d * 2

@@ -639,3 +639,35 @@ def test_sign_diagonal_keeps_structured_vectors_from_saturating():
         assert np.mean((b - V64) ** 2) < 0.2 * np.mean((a - V64) ** 2)
     with pytest.raises(ValueError):
         O.pool_encode(K, Vp, int8_values=True, sign_seed=7)
+
+
+# ------------------------------------------------ keys with one scale per layer tensor ---
+def test_per_tensor_key_scale_pool_form_and_the_papers_ratio():
+    rng = np.random.default_rng(61)
+    L, H, T, d = 3, 2, 50, 64
+    K = (rng.standard_normal((L, H, T, d)) * np.array([0.5, 2.0, 7.0])[:, None, None, None]).astype(np.float16)
+    V = rng.standard_normal((L, H, T, d)).astype(np.float16)
+    ref = O.pool_encode(K, V, key_per_tensor=True)
+    assert ref["k_scales"].shape == (L,) and ref["k_scales"].dtype == np.float16
+    K64 = K.astype(np.float64)
+    for l in range(L):
+        amax = np.abs(K64[l]).max()
+        s = float(ref["k_scales"][l])
+        assert abs(s * 127 / amax - 1) < 2.0 ** -11                   # s = max|K| / 127 over the layer tensor
+        assert np.abs(ref["k_codes"][l].astype(np.int32)).max() == 127
+        # brute force: every code is a nearest multiple of that one scale
+        cand = np.arange(-128, 128, dtype=np.float64) * s
+        best = np.abs(K64[l][..., None] - cand).min(-1)
+        got = np.abs(K64[l] - ref["k_codes"][l] * s)
+        near_tie = np.abs(np.abs(ref["k_pre"][l] - np.floor(ref["k_pre"][l])) - 0.5) < 1e-4
+        assert np.all((got <= best * (1 + 1e-9) + 1e-12) | near_tie)
+    Kh, _ = O.pool_decode(ref)
+    assert np.all(np.abs(Kh - K64) <= ref["k_scales"].astype(np.float64)[:, None, None, None] / 2 * (1 + 1e-6))
+    # layers are independent tensors: encoding one layer alone gives the same codes
+    one = O.pool_encode(K[1:2], V[1:2], key_per_tensor=True)
+    np.testing.assert_array_equal(one["k_codes"][0], ref["k_codes"][1])
+    # without per-block scales the stored bytes give exactly the ratio the paper states, 16 / 5.5
+    consts = {r[0]: float(r[1]) for r in read_golden_rows("paper_constants.txt")}
+    b = O.stored_bytes(32, 8, 7194, 128, key_per_tensor=True)
+    assert b["packed"] == 32 * 8 * 7194 * 176 + 32 * 2
+    assert round(b["ratio_stored"], 2) == consts["compression_ratio"]
