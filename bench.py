@@ -80,6 +80,9 @@ def main():
     ap.add_argument("--value-codec", choices=("tq3", "tq3-scaled", "int8"), default="tq3",
                     help="value codec: tq3 = the paper's (headline configuration); tq3-scaled = the same with a "
                     "per-vector fp16 scale; int8 = uniform int8 without rotation (the paper's proposed ablation)")
+    ap.add_argument("--key-codec", choices=("block32", "tensor"), default="block32",
+                    help="key codec: block32 = q8_0 blocks of 32 (headline configuration); tensor = one scale per layer "
+                    "tensor, the key formula as the paper prints it (two passes over K at encode)")
     ap.add_argument("--bf16", action="store_true",
                     help="dense tensors (K, V, Q, decode output, tails) in bfloat16 instead of fp16: the dtype of the "
                     "paper's Llama-3-8B cache; not the headline configuration, which BASELINE.json states in fp16")
@@ -113,7 +116,8 @@ def main():
     Kd = torch.empty_like(K)
     Vd = torch.empty_like(V)
     codec = {"tq3": pk.VALUES_TQ3, "tq3-scaled": pk.VALUES_TQ3_SCALED, "int8": pk.VALUES_INT8}[args.value_codec]
-    pools = [pk.Pool(L, H, d, T, value_codec=codec).bind() for _ in range(max(1, args.pools))]
+    kcodec = pk.KEYS_Q8_TENSOR if args.key_codec == "tensor" else pk.KEYS_Q8_BLOCK32
+    pools = [pk.Pool(L, H, d, T, value_codec=codec, key_codec=kcodec).bind() for _ in range(max(1, args.pools))]
     tails = None
     if args.tail_len > 0:        # every agent has produced tail_len private tokens (fp16, uncompressed)
         cap = max(args.tail_len, cfg.max_tail)
@@ -212,10 +216,11 @@ def main():
             spare.bind(spare.storage)                      # empties the pool
             for kc, vc in zip(Kc, Vc):
                 spare.append(kc, vc)
-        fill()
-        t_fill = timed(fill, 3)
-        append_rate = len(Kc) * chunk / t_fill
-        spare.encode(K, V)
+        if args.key_codec == "block32":                    # (a per-tensor key scale cannot be appended to)
+            fill()
+            t_fill = timed(fill, 3)
+            append_rate = len(Kc) * chunk / t_fill
+            spare.encode(K, V)
 
     enc = np.array([e[0].elapsed_time(e[1]) for e in events]) * 1e-3
     dec = np.array([e[1].elapsed_time(e[2]) for e in events]) * 1e-3
@@ -227,10 +232,13 @@ def main():
             return fallback
         return max(float(np.mean([k[idx][0].elapsed_time(k[idx][1]) for k in kevents])) * 1e-3, 1e-9)
     k_enc, k_dec, k_att = kernel_time(0, "e", t_enc), kernel_time(1, "d", t_dec), kernel_time(2, "a", t_att)
+    if args.key_codec == "tensor":            # encode is three kernels (zero, max|k|, encode): the stream time covers them
+        k_enc = t_enc
 
     units = L * H
     v_bytes = {"tq3": 3 * d // 8, "tq3-scaled": 3 * d // 8 + 2, "int8": d + 2}[args.value_codec]
-    packed = units * T * (d + d // 16 + v_bytes)                     # algorithmic pool bytes
+    k_bytes = d + (d // 16 if args.key_codec == "block32" else 0)
+    packed = units * T * (k_bytes + v_bytes)                         # algorithmic pool bytes
     enc_bytes = units * T * 4 * d + packed
     dec_bytes = packed + units * T * 4 * d
     tail_bytes = cfg.agents * args.tail_len * units * 4 * d                    # fp16 K and V of every agent's tail
@@ -246,12 +254,13 @@ def main():
     how = ("; duration = the kernel's own begin/end HIP events (hipExtLaunchKernel start/stop events on the launch "
            "stream), averaged over the timed steps")
     vc = {"tq3": 0, "tq3-scaled": 1, "int8": 2}[args.value_codec]      # the kernels' value-codec template argument
-    nt = 1 if (cfg.rows_per_kv_head <= 32 or (vc == 2 and d == 128)) else 2
-    attend_roof = roof(att_gbps, "attend_mfma_kernel<%d,%d,%d> (pool_attend)" % (d, nt, vc) + how +
+    nt = 1 if (cfg.rows_per_kv_head <= 32 or d == 256 or (vc == 2 and d == 128)) else 2
+    kc = 1 if args.key_codec == "tensor" else 0
+    attend_roof = roof(att_gbps, "attend_mfma_kernel<%d,%d,%d,%d> (pool_attend)" % (d, nt, vc, kc) + how +
                        "; achieved = algorithmic bytes (packed pool + Q + out) / duration")
     traffic_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
                                 "attend_hbm_traffic_%s.txt" % cfg.name)
-    if os.path.exists(traffic_file) and args.value_codec == "tq3":     # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel
+    if os.path.exists(traffic_file) and args.value_codec == "tq3" and args.key_codec == "block32":     # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel
         vals = dict(line.split()[:2] for line in open(traffic_file) if line.strip() and not line.startswith("#"))
         attend_roof["traffic"] = float(vals["hbm_bytes_per_launch"])
     else:
@@ -264,7 +273,7 @@ def main():
         "config": {"workload": cfg.name, "layers": L, "kv_heads": H, "q_heads": cfg.q_heads, "head_dim": d,
                    "tokens": T, "agents": cfg.agents, "q_per_agent": cfg.q_per_agent,
                    "rows_per_kv_head": cfg.rows_per_kv_head, "pool_bytes": packed, "pool_copies_rotated": len(pools),
-                   "value_codec": args.value_codec, "dense_dtype": "bf16" if args.bf16 else "f16",
+                   "value_codec": args.value_codec, "key_codec": args.key_codec, "dense_dtype": "bf16" if args.bf16 else "f16",
                    "tail_len": args.tail_len, "tail_bytes": tail_bytes,
                    "attend_calls_per_step": L if args.per_layer else 1},
         "step": "pool_encode -> pool_decode(fp16) -> pool_attend, all layers",
@@ -280,8 +289,8 @@ def main():
         "device_copy_GB_per_s": t_copy and 2 * K.numel() * 2 / t_copy / 1e9,
         "append_64_tokens_per_s": append_rate,
         "roofline": attend_roof,
-        "roofline_encode": roof(enc_bytes / k_enc / 1e9, "encode_kernel<%d,%d> (pool_encode); dense fp16 K,V in + packed out" % (d, vc)),
-        "roofline_decode": roof(dec_bytes / k_dec / 1e9, "decode_kernel<%d,%d,half> (pool_decode); packed in + dense fp16 out" % (d, vc)),
+        "roofline_encode": roof(enc_bytes / k_enc / 1e9, "encode_kernel<%d,%d,%s,%d> (pool_encode); dense 16-bit K,V in + packed out" % (d, vc, "true" if args.bf16 else "false", kc)),
+        "roofline_decode": roof(dec_bytes / k_dec / 1e9, "decode_kernel<%d,%d,%s,%d> (pool_decode); packed in + dense 16-bit out" % (d, vc, "bf16" if args.bf16 else "half", kc)),
     }
     for key, name in (("roofline_encode", "encode_hbm_bytes_per_launch"), ("roofline_decode", "decode_hbm_bytes_per_launch")):
         if name in vals:

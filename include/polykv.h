@@ -64,12 +64,25 @@ enum { POLYKV_KERNEL_AUTO = 0, POLYKV_KERNEL_VECTOR = 1, POLYKV_KERNEL_MATRIX = 
  *                             stored s, V = code * s.  head_dim + 2 bytes per vector. */
 enum { POLYKV_VALUES_TQ3 = 0, POLYKV_VALUES_TQ3_SCALED = 1, POLYKV_VALUES_INT8 = 2 };
 
+/* Key codecs.
+ *   POLYKV_KEYS_Q8_BLOCK32  q8_0: one fp16 scale per block of 32 consecutive head_dim elements (the default).
+ *   POLYKV_KEYS_Q8_TENSOR   the key formula as section "Compression Scheme" prints it: ONE scale per layer tensor
+ *                           [kv_heads, tokens, head_dim], s = fp16(max|K| / 127).  No per-block scales are stored
+ *                           (head_dim + 3*head_dim/8 bytes per token and KV head, the paper's 16/5.5 ratio), and
+ *                           the attention kernel needs no per-block dequantization.  The maximum must be known
+ *                           before any code is formed: such a pool is filled by one pool_encode (two passes over
+ *                           K); pool_append returns POLYKV_ESTATE. */
+enum { POLYKV_KEYS_Q8_BLOCK32 = 0, POLYKV_KEYS_Q8_TENSOR = 1 };
+
 /* Host descriptor for a pool of `layers` x `kv_heads` x `tokens` vectors of `head_dim` elements.
  * head_dim must be 64, 128 or 256; all other dimensions >= 1.  (SharedKVPool, section "PolyKV
  * Architecture".)  *out receives the handle; release it with pool_destroy. */
 int pool_create(int layers, int kv_heads, int head_dim, int tokens, polykv_pool** out);
 /* The same with a choice of value codec (POLYKV_VALUES_*); pool_create uses POLYKV_VALUES_TQ3. */
 int pool_create_codec(int layers, int kv_heads, int head_dim, int tokens, int value_codec, polykv_pool** out);
+/* ... and of key codec (POLYKV_KEYS_*). */
+int pool_create_codecs(int layers, int kv_heads, int head_dim, int tokens, int key_codec, int value_codec,
+                       polykv_pool** out);
 /* Rotation variant: v_rot = H_d D v / sqrt(d) with D a fixed diagonal of pseudorandom signs (the randomized
  * Hadamard rotation of the rotation-based quantizers discussed in section "Related Work"), which keeps
  * structured vectors from piling onto a few rotated coordinates; dequantization applies D H_d / sqrt(d).
@@ -128,7 +141,7 @@ int pool_decode_layers(const polykv_pool* pool, void* K_out_dev, void* V_out_dev
 
 /* Copy the pool out in the canonical format used to compare implementations:
  *   k_codes_dev  int8   [layers, kv_heads, pool_length(), head_dim]
- *   k_scales_dev fp16   [layers, kv_heads, pool_length(), head_dim/32]
+ *   k_scales_dev fp16   [layers, kv_heads, pool_length(), head_dim/32]  ([layers] for POLYKV_KEYS_Q8_TENSOR)
  *   v_packed_dev uint8  [layers, kv_heads, pool_length(), 3*head_dim/8], little-endian bit stream:
  *                code j of a vector occupies stream bits 3j..3j+2, stream bit i is bit (i mod 8)
  *                of byte floor(i/8).

@@ -30,6 +30,13 @@ KernelEvents take_kernel_events() {
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Bytes of one tile record for the given head_dim and codecs.
+template <int D> static int tile_bytes_of(int vc, int kc) {
+    const int t[2][3] = {{Layout<D, 0, 0>::tile_bytes, Layout<D, 1, 0>::tile_bytes, Layout<D, 2, 0>::tile_bytes},
+                         {Layout<D, 0, 1>::tile_bytes, Layout<D, 1, 1>::tile_bytes, Layout<D, 2, 1>::tile_bytes}};
+    return t[kc][vc];
+}
+
 // Resolve every choice pool_attend makes from the pool shape and the caller's parameters, so that
 // pool_attend_workspace() and pool_attend() agree by construction.
 static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, AttendPlan* plan) {
@@ -75,6 +82,10 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
     memset(&p, 0, sizeof(p));
     p.D = pool->head_dim;
     p.vcodec = pool->value_codec;
+    p.kcodec = pool->key_codec;
+    p.kmax = pool->key_codec == POLYKV_KEYS_Q8_TENSOR
+                 ? reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(pool->storage) + pool->kmax_off)
+                 : nullptr;
     p.T = pool->length;
     p.tiles = tiles_of(pool->length);
     p.tiles_cap = pool->tiles;
@@ -164,6 +175,11 @@ int pool_create(int layers, int kv_heads, int head_dim, int tokens, polykv_pool*
 }
 
 int pool_create_codec(int layers, int kv_heads, int head_dim, int tokens, int value_codec, polykv_pool** out) {
+    return pool_create_codecs(layers, kv_heads, head_dim, tokens, POLYKV_KEYS_Q8_BLOCK32, value_codec, out);
+}
+
+int pool_create_codecs(int layers, int kv_heads, int head_dim, int tokens, int key_codec, int value_codec,
+                       polykv_pool** out) {
     if (out == nullptr) {
         set_error("pool_create: out is NULL");
         return POLYKV_EINVAL;
@@ -171,6 +187,10 @@ int pool_create_codec(int layers, int kv_heads, int head_dim, int tokens, int va
     *out = nullptr;
     if (value_codec < POLYKV_VALUES_TQ3 || value_codec > POLYKV_VALUES_INT8) {
         set_error("pool_create: unknown value codec %d", value_codec);
+        return POLYKV_EINVAL;
+    }
+    if (key_codec != POLYKV_KEYS_Q8_BLOCK32 && key_codec != POLYKV_KEYS_Q8_TENSOR) {
+        set_error("pool_create: unknown key codec %d", key_codec);
         return POLYKV_EINVAL;
     }
     if (head_dim != 64 && head_dim != 128 && head_dim != 256) {
@@ -193,11 +213,16 @@ int pool_create_codec(int layers, int kv_heads, int head_dim, int tokens, int va
     p->tokens = tokens;
     p->tiles = tiles_of(tokens);
     p->value_codec = value_codec;
-    const int tb128[3] = {Layout<128, 0>::tile_bytes, Layout<128, 1>::tile_bytes, Layout<128, 2>::tile_bytes};
-    const int tb64[3] = {Layout<64, 0>::tile_bytes, Layout<64, 1>::tile_bytes, Layout<64, 2>::tile_bytes};
-    const int tb256[3] = {Layout<256, 0>::tile_bytes, Layout<256, 1>::tile_bytes, Layout<256, 2>::tile_bytes};
-    p->tile_bytes = head_dim == 128 ? tb128[value_codec] : head_dim == 64 ? tb64[value_codec] : tb256[value_codec];
+    p->key_codec = key_codec;
+    p->tile_bytes = head_dim == 128  ? tile_bytes_of<128>(value_codec, key_codec)
+                    : head_dim == 64 ? tile_bytes_of<64>(value_codec, key_codec)
+                                     : tile_bytes_of<256>(value_codec, key_codec);
     p->bytes = (size_t)layers * kv_heads * p->tiles * p->tile_bytes;
+    p->kmax_off = 0;
+    if (key_codec == POLYKV_KEYS_Q8_TENSOR) {  // the layers' max|k| behind the records, 256-byte aligned
+        p->kmax_off = align_up(p->bytes, 256);
+        p->bytes = p->kmax_off + align_up((size_t)layers * sizeof(uint32_t), 256);
+    }
     p->storage = nullptr;
     p->length = 0;
     memset(&p->signs, 0, sizeof(p->signs));
@@ -312,10 +337,14 @@ int pool_encode_dtype(polykv_pool* pool, const void* K_dev, const void* V_dev, i
 }
 
 int pool_append(polykv_pool* pool, const void* K_dev, const void* V_dev, int count, void* stream) {
-    return encode_range(pool, K_dev, V_dev, POLYKV_F16, pool ? pool->length : 0, count, stream, "pool_append");
+    return pool_append_dtype(pool, K_dev, V_dev, count, POLYKV_F16, stream);
 }
 
 int pool_append_dtype(polykv_pool* pool, const void* K_dev, const void* V_dev, int count, int in_dtype, void* stream) {
+    if (pool != nullptr && pool->key_codec == POLYKV_KEYS_Q8_TENSOR) {
+        set_error("pool_append: a pool with one key scale per layer tensor is filled by one pool_encode");
+        return POLYKV_ESTATE;
+    }
     return encode_range(pool, K_dev, V_dev, in_dtype, pool ? pool->length : 0, count, stream, "pool_append");
 }
 

@@ -38,12 +38,12 @@ template <int N> struct __attribute__((aligned(2 * N))) HalfVecN { __half h[N]; 
 //   PV      lane = (half h, coordinate m) exactly as the value codes are stored: the lane owns the
 //           codes of 16 of the tile's tokens for coordinates 32*g + m and accumulates its share;
 //           the two lane halves are added once at the end.
-template <int D, int VC>
+template <int D, int VC, int KC>
 __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __restrict__ pool,
                                                             const __half* __restrict__ Q,
                                                             float* __restrict__ ws_ml,
                                                             float* __restrict__ ws_o, AttendPlan p) {
-    using LY = Layout<D, VC>;
+    using LY = Layout<D, VC, KC>;
     constexpr bool VS = LY::has_vscales, V8 = VC == 2;
     constexpr int MT = D / 32;
     __shared__ __align__(16) float q_s[kRB][D];
@@ -91,11 +91,12 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
             const uint8_t* tb = unit_base + (size_t)min(tile, p.tiles - 1) * LY::tile_bytes;
             float k[D];
             const __half* sc = reinterpret_cast<const __half*>(tb + LY::kscales_off) + tl * LY::NB;
+            const float s_tensor = KC == 1 ? (float)tensor_key_scale(p.kmax[p.layer_begin + ls]) : 0.0f;
             // codecs with a per-vector value scale: it rides on the token's probability in the P.V sum
             const float vscale = VS ? __half2float(reinterpret_cast<const __half*>(tb + LY::vscales_off)[tl]) : 1.0f;
 #pragma unroll
             for (int j = 0; j < LY::NB; ++j) {
-                const float s = __half2float(sc[j]);
+                const float s = KC == 1 ? s_tensor : __half2float(sc[j]);
 #pragma unroll
                 for (int g8 = 0; g8 < 4; ++g8) {
                     const uint2 raw = *reinterpret_cast<const uint2*>(tb + kcode_run_offset(tl, j, g8));
@@ -468,11 +469,14 @@ hipError_t launch_attend(const polykv_pool* pool, const AttendPlan& plan, const 
         if (matrix_kernel_direct(plan)) return hipSuccess;
     } else {
         dim3 grid(plan.nsplit / 4, units, (plan.R + kRB - 1) / kRB);
-        decltype(&attend_vector_kernel<128, 0>) table[3][3] = {
-            {attend_vector_kernel<64, 0>, attend_vector_kernel<64, 1>, attend_vector_kernel<64, 2>},
-            {attend_vector_kernel<128, 0>, attend_vector_kernel<128, 1>, attend_vector_kernel<128, 2>},
-            {attend_vector_kernel<256, 0>, attend_vector_kernel<256, 1>, attend_vector_kernel<256, 2>}};
-        auto kern = table[plan.D == 64 ? 0 : plan.D == 128 ? 1 : 2][plan.vcodec];
+        decltype(&attend_vector_kernel<128, 0, 0>) table[2][3][3] = {
+            {{attend_vector_kernel<64, 0, 0>, attend_vector_kernel<64, 1, 0>, attend_vector_kernel<64, 2, 0>},
+             {attend_vector_kernel<128, 0, 0>, attend_vector_kernel<128, 1, 0>, attend_vector_kernel<128, 2, 0>},
+             {attend_vector_kernel<256, 0, 0>, attend_vector_kernel<256, 1, 0>, attend_vector_kernel<256, 2, 0>}},
+            {{attend_vector_kernel<64, 0, 1>, attend_vector_kernel<64, 1, 1>, attend_vector_kernel<64, 2, 1>},
+             {attend_vector_kernel<128, 0, 1>, attend_vector_kernel<128, 1, 1>, attend_vector_kernel<128, 2, 1>},
+             {attend_vector_kernel<256, 0, 1>, attend_vector_kernel<256, 1, 1>, attend_vector_kernel<256, 2, 1>}}};
+        auto kern = table[plan.kcodec][plan.D == 64 ? 0 : plan.D == 128 ? 1 : 2][plan.vcodec];
         launch_main_kernel(kern, grid, dim3(256), 0, s, storage, (const __half*)Q, ws_ml, ws_o, plan);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }

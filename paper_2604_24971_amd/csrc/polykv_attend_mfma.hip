@@ -69,7 +69,7 @@ __device__ __forceinline__ float xor32_sum(float x) {
 // fully coalesced run across the wave (the record is stored in exactly this order).
 template <int D> struct RawK {
     uint4v k[D / 32];      // [j]: codes of token m, block j: elements 8h..8h+7 (x, y) and 16+8h.. (z, w)
-    uint32_t sc[D / 64];   // fp16 scales of token m, blocks 0..NB-1
+    uint32_t sc[D / 64];   // fp16 scales of token m, blocks 0..NB-1 (unused with one scale per layer tensor)
 };
 template <int D, int VC> struct RawV {
     uint32_t w[VC == 2 ? 1 : D / 64][3];  // 3-bit codecs: the lane's code triplets
@@ -81,27 +81,30 @@ template <int D, int VC> struct RawV {
 
 // `tile` is wave-uniform and the lane's share sits at a 32-bit offset from it, so every load can use
 // the scalar-base + vector-offset addressing form and no per-lane 64-bit address is ever computed.
-template <int D> __device__ __forceinline__ void load_rawk(RawK<D>& r, const uint8_t* tile, int lane) {
+template <int D, int KC> __device__ __forceinline__ void load_rawk(RawK<D>& r, const uint8_t* tile, int lane) {
     const uint32_t soff = Layout<D>::kscales_off + (uint32_t)(lane & 31) * (D / 32) * 2, koff = (uint32_t)lane * 16;
+    if (KC == 0) {
 #pragma unroll
-    for (int x = 0; x < D / 64; ++x) r.sc[x] = *reinterpret_cast<const uint32_t*>(tile + soff + 4 * x);
+        for (int x = 0; x < D / 64; ++x) r.sc[x] = *reinterpret_cast<const uint32_t*>(tile + soff + 4 * x);
+    }
 #pragma unroll
     for (int j = 0; j < D / 32; ++j) r.k[j] = *reinterpret_cast<const uint4v*>(tile + koff + j * 1024);
 }
-template <int D, int VC> __device__ __forceinline__ void load_rawv(RawV<D, VC>& r, const uint8_t* tile, int lane) {
+template <int D, int VC, int KC> __device__ __forceinline__ void load_rawv(RawV<D, VC>& r, const uint8_t* tile, int lane) {
+    using LY = Layout<D, VC, KC>;
     if (VC == 2) {
-        const uint32_t voff = Layout<D, VC>::vcodes_off + (uint32_t)lane * 16;
+        const uint32_t voff = LY::vcodes_off + (uint32_t)lane * 16;
 #pragma unroll
         for (int g = 0; g < D / 32; ++g) r.c[g] = *reinterpret_cast<const uint4v*>(tile + voff + g * 1024);
     } else {
-        const uint32_t voff = Layout<D, VC>::vcodes_off + (uint32_t)lane * 12;
+        const uint32_t voff = LY::vcodes_off + (uint32_t)lane * 12;
 #pragma unroll
         for (int q = 0; q < D / 64; ++q)
 #pragma unroll
             for (int w = 0; w < 3; ++w) r.w[q][w] = *reinterpret_cast<const uint32_t*>(tile + voff + q * 768 + 4 * w);
     }
     if (VC != 0) {
-        const uint32_t goff = Layout<D, VC>::vscales_off + (uint32_t)(lane >> 5) * 8;
+        const uint32_t goff = LY::vscales_off + (uint32_t)(lane >> 5) * 8;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             const uint2 two = *reinterpret_cast<const uint2*>(tile + goff + 16 * b);
@@ -111,13 +114,19 @@ template <int D, int VC> __device__ __forceinline__ void load_rawv(RawV<D, VC>& 
     }
 }
 
-// Half block (j, s) of a lane's key codes -> the exact two-term fp16 split of code * scale.
-template <int D>
+// Half block (j, s) of a lane's key codes -> the exact two-term fp16 split of code * scale.  With one scale
+// per layer tensor (KC = 1) the scale is folded into the softmax scale instead: hi is the code itself, an
+// exact fp16 integer, and there is no second term.
+template <int D, int KC>
 __device__ __forceinline__ void key_split(const RawK<D>& rk, int j, int s, half8& hi, half8& lo) {
     H8 a;
     codes4_to_half(s == 0 ? rk.k[j].x : rk.k[j].z, a.u[0], a.u[1]);
     codes4_to_half(s == 0 ? rk.k[j].y : rk.k[j].w, a.u[2], a.u[3]);
     a.h = a.h - (_Float16)1152.0f;
+    if (KC == 1) {
+        hi = a.h;
+        return;
+    }
     union {
         uint32_t u;
         _Float16 h[2];
@@ -179,7 +188,7 @@ __device__ __forceinline__ void exp4(const float16v& S, int c, float qscale, flo
 
 // The pool's last tile when it crosses the end of the pool, read straight from memory: scores, softmax
 // and PV one after the other, tokens >= T masked out.  Runs at most once per KV head.
-template <int D, int NT, int VC>
+template <int D, int NT, int VC, int KC>
 __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile, int T, float qscale, float raise_thr,
                                                  int lane, const half8 (&qb)[NT][D / 32][2], float16v (&O)[D / 32][NT],
                                                  float (&Lsum)[NT], float (&m_ref)[NT], float (&m_thr)[NT],
@@ -188,8 +197,8 @@ __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile,
     const int h = lane >> 5;
     RawK<D> rk;
     RawV<D, VC> rv;
-    load_rawk<D>(rk, lt, lane);
-    load_rawv<D, VC>(rv, lt, lane);
+    load_rawk<D, KC>(rk, lt, lane);
+    load_rawv<D, VC, KC>(rv, lt, lane);
     float16v S[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
@@ -200,11 +209,11 @@ __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile,
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             half8 hi, lo;
-            key_split<D>(rk, j, s, hi, lo);
+            key_split<D, KC>(rk, j, s, hi, lo);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 S[nt] = mfma32(hi, qb[nt][j][s], S[nt]);
-                S[nt] = mfma32(lo, qb[nt][j][s], S[nt]);
+                if (KC == 0) S[nt] = mfma32(lo, qb[nt][j][s], S[nt]);
             }
         }
 #pragma unroll
@@ -249,7 +258,7 @@ __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile,
 //   Sa         scores of tile A on entry, of tile B on exit; mloc / raise: per-lane row maxima of the
 //              same tile and whether some row outgrew the reference
 // Only full tiles go through here; a ragged last tile is handled by process_ragged_tile.
-template <int D, int NT, int VC, bool HAS_A, bool HAS_B>
+template <int D, int NT, int VC, int KC, bool HAS_A, bool HAS_B>
 __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<D>& rk, RawV<D, VC>& rvN, RawK<D>& rkN,
                                               const uint8_t* nextK, const uint8_t* nextV, float qscale,
                                               float raise_thr, int lane, const half8 (&qb)[NT][D / 32][2],
@@ -307,21 +316,23 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
 
     // The next step's bytes are requested first thing, into the other set of registers, so that every
     // load has the whole step (and more, for all but the first key block) to land.
-    if (HAS_B) load_rawk<D>(rkN, nextK, lane);
-    load_rawv<D, VC>(rvN, nextV, lane);
+    if (HAS_B) load_rawk<D, KC>(rkN, nextK, lane);
+    load_rawv<D, VC, KC>(rvN, nextV, lane);
     __builtin_amdgcn_sched_barrier(0);
 
     H8 pb[NT][2];      // probabilities of tile A: B operands of the P.V products, [row tile][k slice]
     half8 khi[2], klo[2];
     H8 va[2];
     auto exp_chunk = [&](int c) { exp4<VC != 0>(Sa[c >> 2], c & 3, qscale, mneg[c >> 2], pb[c >> 2], Lsum[c >> 2], rv.g); };
-    auto kdeq = [&](int k) { key_split<D>(rk, k >> 1, k & 1, khi[k & 1], klo[k & 1]); };
+    auto kdeq = [&](int k) { key_split<D, KC>(rk, k >> 1, k & 1, khi[k & 1], klo[k & 1]); };
     auto qk = [&](int k) {
         const int j = k >> 1, s = k & 1;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) Sb[nt] = mfma32(khi[k & 1], qb[nt][j][s], Sb[nt]);
+        if (KC == 0) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) Sb[nt] = mfma32(klo[k & 1], qb[nt][j][s], Sb[nt]);
+            for (int nt = 0; nt < NT; ++nt) Sb[nt] = mfma32(klo[k & 1], qb[nt][j][s], Sb[nt]);
+        }
     };
     auto vdeq = [&](int G) { value_group<D, VC>(rv, G, va[G & 1]); };
     auto pv = [&](int G) {
@@ -353,7 +364,7 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
                 for (int c = c0; c < c1; ++c) exp_chunk(c);
                 if (k + 1 == NQK) vdeq(0);
             }
-            slice_end(integral_constant<int, 2 * NT>{}, integral_constant<int, (HAS_A ? 30 : 16)>{});
+            slice_end(integral_constant<int, (KC == 0 ? 2 : 1) * NT>{}, integral_constant<int, (HAS_A ? 30 : 16)>{});
         }
     } else if (HAS_A) {
 #pragma unroll
@@ -383,12 +394,12 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
     }
 }
 
-template <int D, int NT, int VC>
+template <int D, int NT, int VC, int KC>
 __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restrict__ pool,
                                                           const __half* __restrict__ Q,
                                                           float* __restrict__ ws_ml, float* __restrict__ ws_o,
                                                           float* __restrict__ out, AttendPlan p, int direct) {
-    using LY = Layout<D, VC>;
+    using LY = Layout<D, VC, KC>;
     constexpr int NB = D / 32, MG = D / 32, ROWS = 32 * NT;
     constexpr int OSTRIDE = D + 4;
     constexpr int TB = LY::tile_bytes;
@@ -405,7 +416,13 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     const int tps = (p.tiles + p.nsplit - 1) / p.nsplit;
     const int t_begin = split * tps, t_end = min(p.tiles, t_begin + tps);
     const uint8_t* unit_base = pool + (size_t)((p.layer_begin + ls) * p.H + kvh) * p.tiles_cap * TB;
-    const float qscale = p.qscale;
+    // One key scale per layer tensor: the keys enter the products as their integer codes and the scale
+    // rides on the softmax scale (an all-zero layer has only zero codes: any positive scale will do).
+    float qscale = p.qscale;
+    if (KC == 1) {
+        const float s_tensor = (float)tensor_key_scale(p.kmax[p.layer_begin + ls]);
+        qscale *= s_tensor > 0.0f ? s_tensor : 1.0f;
+    }
 
     // this wave's tiles: t_begin + wave, +4, +8, ...; local index k <-> tile my_first + 4k
     const int my_first = t_begin + wave;
@@ -418,8 +435,8 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     RawK<D> rk;
     RawV<D, VC> rv;
     if (my_count > 0) {
-        load_rawk<D>(rk, tile_ptr(0), lane);
-        load_rawv<D, VC>(rv, tile_ptr(0), lane);
+        load_rawk<D, KC>(rk, tile_ptr(0), lane);
+        load_rawv<D, VC, KC>(rv, tile_ptr(0), lane);
     }
 
     // ---- query rows as MFMA B operands: lane (n, h) holds q[row 32nt+n][32j + 16s + 8h .. +7].
@@ -505,27 +522,27 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         RawK<D> rk2;
         RawV<D, VC> rv2;
         // prologue: scores of tile 0 from rk; requests K of tile 1 and (again) V of tile 0 into set 2
-        pipeline_step<D, NT, VC, false, true>(rv, rk, rv2, rk2, tile_ptr(1), tile_ptr(0), qscale, raise_thr, lane, qb, O, Lsum,
+        pipeline_step<D, NT, VC, KC, false, true>(rv, rk, rv2, rk2, tile_ptr(1), tile_ptr(0), qscale, raise_thr, lane, qb, O, Lsum,
                                           m_ref, m_thr, mneg, S, mloc, raise);
         int s = 0;
         for (; s + 1 < full_count - 1; s += 2) {  // two steps per trip: the sets swap roles without copies
-            pipeline_step<D, NT, VC, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
-            pipeline_step<D, NT, VC, true, true>(rv, rk, rv2, rk2, tile_ptr(s + 3), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, true, true>(rv, rk, rv2, rk2, tile_ptr(s + 3), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         }
         if (s < full_count - 1) {  // one step with a B tile left: current = set 2
-            pipeline_step<D, NT, VC, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
-            pipeline_step<D, NT, VC, true, false>(rv, rk, rv2, rk2, tile_ptr(s + 2), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, true, false>(rv, rk, rv2, rk2, tile_ptr(s + 2), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
                                               O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         } else {
-            pipeline_step<D, NT, VC, true, false>(rv2, rk2, rv, rk, tile_ptr(s + 1), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, true, false>(rv2, rk2, rv, rk, tile_ptr(s + 1), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
                                               O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         }
     }
     if (last_ragged)
-        process_ragged_tile<D, NT, VC>(tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
+        process_ragged_tile<D, NT, VC, KC>(tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
                                    Lsum, m_ref, m_thr, mneg);
 
     // ---- merge the four waves through LDS: every wave stores its accumulators, rescaled to the
@@ -624,11 +641,11 @@ bool matrix_kernel_supports(int head_dim, int rows_per_kv_head) {
 
 bool matrix_kernel_direct(const AttendPlan& plan) { return plan.nsplit == 1 && !plan.has_tails; }
 
-template <int D, int NT, int VC>
+template <int D, int NT, int VC, int KC>
 static hipError_t launch_one(dim3 grid, const uint8_t* storage, const AttendPlan& plan, const void* Q, float* ws_ml,
                              float* ws_o, float* out, int direct, hipStream_t s) {
     constexpr int kMergeBytes = 4 * 32 * NT * (D + 4) * (int)sizeof(float);
-    auto kern = attend_mfma_kernel<D, NT, VC>;
+    auto kern = attend_mfma_kernel<D, NT, VC, KC>;
     static bool configured = false;  // per instantiation: the limit is a property of the function
     if (!configured && kMergeBytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -643,7 +660,7 @@ static hipError_t launch_one(dim3 grid, const uint8_t* storage, const AttendPlan
 // Row tiles per workgroup: two (64 rows) where the accumulators, the parked queries and two staged tiles
 // fit the 512 registers of a wave; one (32 rows) at head_dim 256 and for the int8 value codec at head_dim
 // 128, whose staged value codes take 16 registers per tile.
-template <int D, int VC>
+template <int D, int VC, int KC>
 static hipError_t launch_dv(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml, float* ws_o,
                             float* out, hipStream_t s) {
     const uint8_t* storage = reinterpret_cast<const uint8_t*>(pool->storage);
@@ -652,18 +669,24 @@ static hipError_t launch_dv(const polykv_pool* pool, const AttendPlan& plan, con
     constexpr bool two_tiles_fit = D == 64 || (D == 128 && VC != 2);
     if constexpr (two_tiles_fit) {
         if (plan.R > 32)
-            return launch_one<D, 2, VC>(dim3(plan.nsplit, units, (plan.R + 63) / 64), storage, plan, Q, ws_ml, ws_o, out,
-                                        direct, s);
+            return launch_one<D, 2, VC, KC>(dim3(plan.nsplit, units, (plan.R + 63) / 64), storage, plan, Q, ws_ml, ws_o,
+                                            out, direct, s);
     }
-    return launch_one<D, 1, VC>(dim3(plan.nsplit, units, (plan.R + 31) / 32), storage, plan, Q, ws_ml, ws_o, out, direct, s);
+    return launch_one<D, 1, VC, KC>(dim3(plan.nsplit, units, (plan.R + 31) / 32), storage, plan, Q, ws_ml, ws_o, out, direct,
+                                    s);
 }
 
 template <int D>
 static hipError_t launch_d(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,
                            float* ws_o, float* out, hipStream_t s) {
-    if (plan.vcodec == POLYKV_VALUES_TQ3_SCALED) return launch_dv<D, 1>(pool, plan, Q, ws_ml, ws_o, out, s);
-    if (plan.vcodec == POLYKV_VALUES_INT8) return launch_dv<D, 2>(pool, plan, Q, ws_ml, ws_o, out, s);
-    return launch_dv<D, 0>(pool, plan, Q, ws_ml, ws_o, out, s);
+    if (plan.kcodec == POLYKV_KEYS_Q8_TENSOR) {
+        if (plan.vcodec == POLYKV_VALUES_TQ3_SCALED) return launch_dv<D, 1, 1>(pool, plan, Q, ws_ml, ws_o, out, s);
+        if (plan.vcodec == POLYKV_VALUES_INT8) return launch_dv<D, 2, 1>(pool, plan, Q, ws_ml, ws_o, out, s);
+        return launch_dv<D, 0, 1>(pool, plan, Q, ws_ml, ws_o, out, s);
+    }
+    if (plan.vcodec == POLYKV_VALUES_TQ3_SCALED) return launch_dv<D, 1, 0>(pool, plan, Q, ws_ml, ws_o, out, s);
+    if (plan.vcodec == POLYKV_VALUES_INT8) return launch_dv<D, 2, 0>(pool, plan, Q, ws_ml, ws_o, out, s);
+    return launch_dv<D, 0, 0>(pool, plan, Q, ws_ml, ws_o, out, s);
 }
 
 hipError_t launch_attend_matrix(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,

@@ -48,19 +48,22 @@ struct CodecThread {
 // s = fp16(min(max|v|/127, 128)) (the uniform int8 ablation proposed in sections "Discussion" and
 // "Future Work").
 // BF: K and V are bfloat16 instead of fp16 (the bit patterns are passed as __half all the same).
-template <int D, int VC, bool BF>
+// KC = 1: one key scale per layer tensor, from the layer's max|k| in kmax[] (found by kamax_kernel); H = KV
+// heads per layer.
+template <int D, int VC, bool BF, int KC>
 __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ K,
                                                      const __half* __restrict__ V,
                                                      uint8_t* __restrict__ pool, int in_tokens, int tok_begin,
-                                                     int tok_end, int tiles_cap, SignBits signs) {
+                                                     int tok_end, int tiles_cap, SignBits signs,
+                                                     const uint32_t* __restrict__ kmax, int H) {
     // K, V hold in_tokens = tok_end - tok_begin tokens per (layer, KV head); they become pool tokens
     // [tok_begin, tok_end).  blockIdx.x counts tiles from the first one touched.  Tokens of that tile that
     // lie before tok_begin were encoded earlier and are carried over; tokens from tok_end on are padding
     // and are encoded as zeros.
-    using LY = Layout<D, VC>;
+    using LY = Layout<D, VC, KC>;
     constexpr bool VS = VC == 1, V8 = VC == 2;
     constexpr int EPT = D / 8;
-    constexpr int KBYTES = LY::vcodes_off;  // key codes + key scales (+ value scales)
+    constexpr int KBYTES = LY::vcodes_off;  // key codes (+ key scales) (+ value scales)
     constexpr int VST = kTile + 4;          // bytes per rotated coordinate in the code staging area
     __shared__ __align__(16) uint8_t kimg[KBYTES];
     __shared__ __align__(16) uint8_t vstage[D * VST];  // value codes as bytes, [coordinate][token]
@@ -133,7 +136,8 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         if (EPT == 8) amax = fmaxf(amax, lane_xor<2>(amax));
         // bfloat16 keys can exceed what an fp16 scale holds: it saturates at the fp16 maximum
         const float sraw = __fdiv_rn(amax, 127.0f);
-        const __half s16 = __float2half_rn(BF ? fminf(sraw, 65504.0f) : sraw);
+        __half s16 = __float2half_rn(BF ? fminf(sraw, 65504.0f) : sraw);
+        if (KC == 1) s16 = (__half)tensor_key_scale(kmax[unit / H]);
         const float sf = __half2float(s16);
         const float inv = sf > 0.0f ? __fdiv_rn(1.0f, sf) : 0.0f;
         // round(k * inv) + 128 in the low byte of a float: adding 1.5 * 2^23 + 128 rounds the product
@@ -158,7 +162,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
             w.y = b01 | b23;
             *reinterpret_cast<uint2*>(kimg + LY::kcodes_off + kcode_run_offset(t, j, g8 + rr)) = w;
         }
-        if ((e0 & 31) == 0 && !old_token)
+        if (KC == 0 && (e0 & 31) == 0 && !old_token)
             reinterpret_cast<__half*>(kimg + LY::kscales_off)[t * LY::NB + j] = s16;
     }
 
@@ -301,10 +305,10 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------ decode ---
-template <int D, int VC>
+template <int D, int VC, int KC>
 __device__ __forceinline__ void stage_tile(uint8_t* img, const uint8_t* pool, int unit, int tiles,
                                            int tile, int tid) {
-    using LY = Layout<D, VC>;
+    using LY = Layout<D, VC, KC>;
     const uint4* src = reinterpret_cast<const uint4*>(pool + ((size_t)unit * tiles + tile) * LY::tile_bytes);
     uint4* dst = reinterpret_cast<uint4*>(img);
     for (int i = tid; i < LY::tile_bytes / 16; i += 256) dst[i] = src[i];
@@ -362,11 +366,12 @@ template <int N> struct RowStore<float, N> {
 // K = code * s and V = H c[code] / sqrt(d)  (sections "Compression Scheme" and "TurboQuant",
 // dequantization; the inverse of the normalized rotation is the same normalized transform); times the
 // vector's scale in the scaled-values codec (VC = 1).  Int8 values (VC = 2): V = code * s, no rotation.
-template <int D, int VC, typename OutT>
+template <int D, int VC, typename OutT, int KC>
 __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ pool,
                                                      OutT* __restrict__ K_out, OutT* __restrict__ V_out,
-                                                     int T, int tiles, SignBits signs) {
-    using LY = Layout<D, VC>;
+                                                     int T, int tiles, SignBits signs,
+                                                     const uint32_t* __restrict__ kmax, int H) {
+    using LY = Layout<D, VC, KC>;
     constexpr int EPT = D / 8;
     constexpr int KBYTES = LY::vcodes_off;
     constexpr bool VS = LY::has_vscales, V8 = VC == 2;
@@ -437,7 +442,8 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
     const int e0 = c * EPT, j = e0 >> 5, g8 = (e0 >> 3) & 3;
 
     if (K_out != nullptr) {
-        const _Float16 s16 = reinterpret_cast<const _Float16*>(kimg + LY::kscales_off)[t * LY::NB + j];
+        const _Float16 s16 = KC == 1 ? tensor_key_scale(kmax[unit / H])
+                                     : reinterpret_cast<const _Float16*>(kimg + LY::kscales_off)[t * LY::NB + j];
         float k[EPT];
 #pragma unroll
         for (int rr = 0; rr < EPT / 8; ++rr) {
@@ -485,19 +491,22 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
 }
 
 // ------------------------------------------------------------------------------------ export ---
-template <int D, int VC>
+template <int D, int VC, int KC>
 __global__ __launch_bounds__(256) void export_kernel(const uint8_t* __restrict__ pool,
                                                      int8_t* __restrict__ k_codes,
                                                      __half* __restrict__ k_scales,
                                                      uint8_t* __restrict__ v_packed,
-                                                     __half* __restrict__ v_scales, int T, int tiles) {
-    using LY = Layout<D, VC>;
+                                                     __half* __restrict__ v_scales, int T, int tiles,
+                                                     const uint32_t* __restrict__ kmax, int H) {
+    using LY = Layout<D, VC, KC>;
     constexpr bool VS = LY::has_vscales, V8 = VC == 2;
     constexpr int EPT = D / 8;
     __shared__ __align__(16) uint8_t img[LY::tile_bytes];
     const int tile = blockIdx.x, unit = blockIdx.y;
     const int tid = threadIdx.x, t = tid >> 3, c = tid & 7;
-    stage_tile<D, VC>(img, pool, unit, tiles, tile, tid);
+    stage_tile<D, VC, KC>(img, pool, unit, tiles, tile, tid);
+    if (KC == 1 && k_scales != nullptr && tile == 0 && unit % H == 0 && tid == 0)  // one scale per layer
+        k_scales[unit / H] = (__half)tensor_key_scale(kmax[unit / H]);
     const int tok = tile * kTile + t;
     if (tok >= T) return;
     const size_t vec = (size_t)unit * T + tok;
@@ -509,7 +518,7 @@ __global__ __launch_bounds__(256) void export_kernel(const uint8_t* __restrict__
             k_codes[vec * D + e0 + i] = (int8_t)((int)codes[i & 7] - 128);
         }
     }
-    if (k_scales != nullptr && c < LY::NB)
+    if (KC == 0 && k_scales != nullptr && c < LY::NB)
         k_scales[vec * LY::NB + c] = reinterpret_cast<const __half*>(img + LY::kscales_off)[t * LY::NB + c];
     if (VS && v_scales != nullptr && c == 0)
         v_scales[vec] = reinterpret_cast<const __half*>(img + LY::vscales_off)[t];
@@ -534,15 +543,62 @@ __global__ __launch_bounds__(256) void export_kernel(const uint8_t* __restrict__
     }
 }
 
+// ---------------------------------------------------------------- per-tensor key scale: max|k| ---
+__global__ void zero_u32_kernel(uint32_t* __restrict__ p, int n) {
+    for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0u;
+}
+
+// max|k| of every layer tensor, first pass of the key formula with one scale per tensor (section
+// "Compression Scheme", key quantization).  Same thread -> (token, chunk) map as the encode kernel; a
+// workgroup strides over the tiles of its KV head and issues one atomic at the end (non-negative floats
+// order like their bit patterns), so a layer's maximum sees a few thousand atomics, not one per tile.
+template <int D, bool BF>
+__global__ __launch_bounds__(256) void kamax_kernel(const __half* __restrict__ K, uint32_t* __restrict__ kmax, int T,
+                                                    int H) {
+    constexpr int EPT = D / 8;
+    __shared__ float wmax[4];
+    const int unit = blockIdx.y, tid = threadIdx.x;
+    const CodecThread th(tid);
+    float amax = 0.0f;
+    for (int tok = blockIdx.x * kTile + th.t; tok < T; tok += gridDim.x * kTile) {
+        const uint4* src = reinterpret_cast<const uint4*>(K + ((size_t)unit * T + tok) * D + th.c * EPT);
+#pragma unroll
+        for (int i = 0; i < EPT / 8; ++i) {
+            const uint4 raw = src[i];
+            const uint32_t* w = reinterpret_cast<const uint32_t*>(&raw);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float2 f = pair16_to_float2(w[k], BF);
+                amax = fmaxf(amax, fmaxf(fabsf(f.x), fabsf(f.y)));
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) amax = fmaxf(amax, __shfl_xor(amax, m, 64));
+    if ((tid & 63) == 0) wmax[tid >> 6] = amax;
+    __syncthreads();
+    if (tid == 0) {
+        const float m = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+        atomicMax(&kmax[unit / H], __float_as_uint(m));
+    }
+}
+
 // ---------------------------------------------------------------------------------- launchers ---
-// Calls f(integral_constant<int, D>, integral_constant<int, VC>) for the pool's head_dim and value codec.
+// Calls f(integral_constant<int, D>, integral_constant<int, VC>, integral_constant<int, KC>) for the pool's
+// head_dim, value codec and key codec.
 template <typename F> static void for_pool_shape(const polykv_pool* p, F&& f) {
     using std::integral_constant;
+    auto with_dv = [&](auto d, auto vc) {
+        if (p->key_codec == POLYKV_KEYS_Q8_TENSOR)
+            f(d, vc, integral_constant<int, POLYKV_KEYS_Q8_TENSOR>{});
+        else
+            f(d, vc, integral_constant<int, POLYKV_KEYS_Q8_BLOCK32>{});
+    };
     auto with_d = [&](auto d) {
         switch (p->value_codec) {
-            case POLYKV_VALUES_TQ3_SCALED: f(d, integral_constant<int, POLYKV_VALUES_TQ3_SCALED>{}); break;
-            case POLYKV_VALUES_INT8: f(d, integral_constant<int, POLYKV_VALUES_INT8>{}); break;
-            default: f(d, integral_constant<int, POLYKV_VALUES_TQ3>{}); break;
+            case POLYKV_VALUES_TQ3_SCALED: with_dv(d, integral_constant<int, POLYKV_VALUES_TQ3_SCALED>{}); break;
+            case POLYKV_VALUES_INT8: with_dv(d, integral_constant<int, POLYKV_VALUES_INT8>{}); break;
+            default: with_dv(d, integral_constant<int, POLYKV_VALUES_TQ3>{}); break;
         }
     };
     if (p->head_dim == 128)
@@ -553,19 +609,35 @@ template <typename F> static void for_pool_shape(const polykv_pool* p, F&& f) {
         with_d(integral_constant<int, 256>{});
 }
 
+// The layers' max|k| inside the pool's storage (POLYKV_KEYS_Q8_TENSOR), else nullptr.
+static uint32_t* kmax_of(const polykv_pool* p) {
+    return p->key_codec == POLYKV_KEYS_Q8_TENSOR ? reinterpret_cast<uint32_t*>((char*)p->storage + p->kmax_off) : nullptr;
+}
+
 hipError_t launch_encode(const polykv_pool* p, const void* K, const void* V, int in_dtype, int begin, int count,
                          hipStream_t s) {
     const int end = begin + count;
-    dim3 grid(tiles_of(end) - begin / kTile, p->layers * p->kv_heads);
-    for_pool_shape(p, [&](auto d, auto vs) {
+    const int units = p->layers * p->kv_heads;
+    dim3 grid(tiles_of(end) - begin / kTile, units);
+    uint32_t* kmax = kmax_of(p);
+    for_pool_shape(p, [&](auto d, auto vs, auto kc) {
+        constexpr int D = decltype(d)::value, VC = decltype(vs)::value, KC = decltype(kc)::value;
+        if (KC == 1) {  // first pass of the per-tensor key formula: the layers' max|k| (begin is 0 here)
+            zero_u32_kernel<<<1, 256, 0, s>>>(kmax, p->layers);
+            const dim3 mgrid(min(tiles_of(count), 8), units);
+            if (in_dtype == POLYKV_BF16)
+                kamax_kernel<D, true><<<mgrid, 256, 0, s>>>((const __half*)K, kmax, count, p->kv_heads);
+            else
+                kamax_kernel<D, false><<<mgrid, 256, 0, s>>>((const __half*)K, kmax, count, p->kv_heads);
+        }
         if (in_dtype == POLYKV_BF16)
-            launch_main_kernel(encode_kernel<decltype(d)::value, decltype(vs)::value, true>, grid, dim3(256), 0, s,
-                               (const __half*)K, (const __half*)V, (uint8_t*)p->storage, count, begin, end, p->tiles,
-                               p->signs);
+            launch_main_kernel(encode_kernel<D, VC, true, KC>, grid, dim3(256), 0, s, (const __half*)K, (const __half*)V,
+                               (uint8_t*)p->storage, count, begin, end, p->tiles, p->signs, (const uint32_t*)kmax,
+                               p->kv_heads);
         else
-            launch_main_kernel(encode_kernel<decltype(d)::value, decltype(vs)::value, false>, grid, dim3(256), 0, s,
-                               (const __half*)K, (const __half*)V, (uint8_t*)p->storage, count, begin, end, p->tiles,
-                               p->signs);
+            launch_main_kernel(encode_kernel<D, VC, false, KC>, grid, dim3(256), 0, s, (const __half*)K, (const __half*)V,
+                               (uint8_t*)p->storage, count, begin, end, p->tiles, p->signs, (const uint32_t*)kmax,
+                               p->kv_heads);
     });
     return hipGetLastError();
 }
@@ -574,28 +646,29 @@ hipError_t launch_decode(const polykv_pool* p, void* K_out, void* V_out, int dty
                          hipStream_t s) {
     dim3 grid(tiles_of(p->length), (layer_end - layer_begin) * p->kv_heads);  // the tokens encoded so far
     const uint8_t* pool = (const uint8_t*)p->storage + (size_t)layer_begin * p->kv_heads * p->tiles * p->tile_bytes;
-    for_pool_shape(p, [&](auto d, auto vs) {
-        constexpr int D = decltype(d)::value;
-        constexpr int VC = decltype(vs)::value;
+    const uint32_t* kmax = kmax_of(p) ? kmax_of(p) + layer_begin : nullptr;
+    for_pool_shape(p, [&](auto d, auto vs, auto kc) {
+        constexpr int D = decltype(d)::value, VC = decltype(vs)::value, KC = decltype(kc)::value;
         if (dtype == POLYKV_BF16)
-            launch_main_kernel(decode_kernel<D, VC, Bf16Out>, grid, dim3(256), 0, s, pool, (Bf16Out*)K_out, (Bf16Out*)V_out,
-                               p->length, p->tiles, p->signs);
+            launch_main_kernel(decode_kernel<D, VC, Bf16Out, KC>, grid, dim3(256), 0, s, pool, (Bf16Out*)K_out,
+                               (Bf16Out*)V_out, p->length, p->tiles, p->signs, kmax, p->kv_heads);
         else if (dtype == POLYKV_F32)
-            launch_main_kernel(decode_kernel<D, VC, float>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out,
-                               p->length, p->tiles, p->signs);
+            launch_main_kernel(decode_kernel<D, VC, float, KC>, grid, dim3(256), 0, s, pool, (float*)K_out, (float*)V_out,
+                               p->length, p->tiles, p->signs, kmax, p->kv_heads);
         else
-            launch_main_kernel(decode_kernel<D, VC, __half>, grid, dim3(256), 0, s, pool, (__half*)K_out, (__half*)V_out,
-                               p->length, p->tiles, p->signs);
+            launch_main_kernel(decode_kernel<D, VC, __half, KC>, grid, dim3(256), 0, s, pool, (__half*)K_out,
+                               (__half*)V_out, p->length, p->tiles, p->signs, kmax, p->kv_heads);
     });
     return hipGetLastError();
 }
 
-hipError_t launch_export(const polykv_pool* p, void* kc, void* ks, void* vp, void* vs_out, hipStream_t s) {
+hipError_t launch_export(const polykv_pool* p, void* kc_out, void* ks, void* vp, void* vs_out, hipStream_t s) {
     dim3 grid(tiles_of(p->length), p->layers * p->kv_heads);  // the tokens encoded so far
     const uint8_t* pool = (const uint8_t*)p->storage;
-    for_pool_shape(p, [&](auto d, auto vs) {
-        export_kernel<decltype(d)::value, decltype(vs)::value>
-            <<<grid, 256, 0, s>>>(pool, (int8_t*)kc, (__half*)ks, (uint8_t*)vp, (__half*)vs_out, p->length, p->tiles);
+    const uint32_t* kmax = kmax_of(p);
+    for_pool_shape(p, [&](auto d, auto vs, auto kc) {
+        export_kernel<decltype(d)::value, decltype(vs)::value, decltype(kc)::value><<<grid, 256, 0, s>>>(
+            pool, (int8_t*)kc_out, (__half*)ks, (uint8_t*)vp, (__half*)vs_out, p->length, p->tiles, kmax, p->kv_heads);
     });
     return hipGetLastError();
 }

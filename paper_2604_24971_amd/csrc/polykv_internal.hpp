@@ -16,6 +16,8 @@ struct SignBits {
 struct polykv_pool {
     int layers, kv_heads, head_dim, tokens;
     int value_codec;    // POLYKV_VALUES_*
+    int key_codec;      // POLYKV_KEYS_*
+    size_t kmax_off;    // POLYKV_KEYS_Q8_TENSOR: byte offset in storage of the layers' max|k| (uint32 fp32 bits each)
     int tiles;          // ceil(tokens / 32): tile records per (layer, KV head), the record stride
     size_t tile_bytes;  // bytes of one tile record
     size_t bytes;       // layers * kv_heads * tiles * tile_bytes
@@ -32,6 +34,8 @@ void set_error(const char* fmt, ...);
 struct AttendPlan {
     int D, T, tiles, H;          // pool shape: T tokens encoded so far, in `tiles` tiles
     int vcodec;                  // the pool's value codec, POLYKV_VALUES_*
+    int kcodec;                  // the pool's key codec, POLYKV_KEYS_*
+    const uint32_t* kmax;        // POLYKV_KEYS_Q8_TENSOR: the layers' max|k| (device), indexed by pool layer
     int tiles_cap;               // tile records per (layer, KV head) in storage (the pool's capacity)
     int layer_begin, layers;     // selected layer range
     int A, nq, q_heads, G, R;    // R = A * nq * G query rows per KV head

@@ -31,8 +31,11 @@
 //                            coordinate group g are the A operands of that group's two P.V products, in the
 //                            same token order as above.
 //
+// With one key scale per layer tensor (KC = 1) the K-scales region is absent; the layer maxima live in a
+// small array behind all records (see polykv_pool::kmax_off).
+//
 // Per token and KV head this is head_dim + head_dim/16 + 3*head_dim/8 bytes: 184 (d=128), 92 (d=64),
-// plus 2 with value scales; 2*head_dim + head_dim/16 + 2 with int8 values.
+// plus 2 with value scales; 2*head_dim + head_dim/16 + 2 with int8 values; head_dim/16 less with KC = 1.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -43,13 +46,15 @@ constexpr int kTile = 32;  // tokens per tile record
 
 // VC: value codec, numbered as POLYKV_VALUES_* in the ABI header (0 the paper's 3-bit codes, 1 the same
 // with a per-vector scale, 2 int8 codes with a per-vector scale).
-template <int D, int VC = 0> struct Layout {
+// KC: key codec, POLYKV_KEYS_* (0 q8_0 blocks of 32 with a scale each, 1 one scale per layer tensor).
+template <int D, int VC = 0, int KC = 0> struct Layout {
     static constexpr int NB = D / 32;             // q8_0 blocks per vector
     static constexpr int NT = D / 64;             // value-code triplets per lane
     static constexpr bool has_vscales = VC != 0;
+    static constexpr bool has_kscales = KC == 0;
     static constexpr int kcodes_off = 0;
-    static constexpr int kscales_off = NB * 1024;
-    static constexpr int vscales_off = kscales_off + kTile * NB * 2;  // present only if has_vscales
+    static constexpr int kscales_off = NB * 1024;                     // present only if has_kscales
+    static constexpr int vscales_off = kscales_off + (has_kscales ? kTile * NB * 2 : 0);  // only if has_vscales
     static constexpr int vcodes_off = vscales_off + (has_vscales ? kTile * 2 : 0);
     static constexpr int tile_bytes = vcodes_off + (VC == 2 ? NB * 1024 : NT * 768);
 };
@@ -116,6 +121,12 @@ __device__ __forceinline__ int vcode_extract(const uint32_t* v, int t, int dv) {
     if (gi < 3) return (w[gi] >> (8 * (e & 3) + 3 * (e >> 2))) & 7;
     if (e < 4) return ((w[0] >> (8 * e + 6)) & 3) | (((w[1] >> (8 * e + 6)) & 1) << 2);
     return ((w[2] >> (8 * (e - 4) + 6)) & 3) | (((w[1] >> (8 * (e - 4) + 7)) & 1) << 2);
+}
+
+// One key scale per layer tensor: the layer's max|k| (fp32 bits, kept behind the records) -> the fp16
+// scale max|k| / 127, saturating at the fp16 maximum; the same expression in every kernel.
+__device__ __forceinline__ _Float16 tensor_key_scale(uint32_t amax_bits) {
+    return (_Float16)fminf(__fdiv_rn(__uint_as_float(amax_bits), 127.0f), 65504.0f);
 }
 
 // ---- sign diagonal of the rotation variant (struct SignBits: bit i set = coordinate i negated) ---

@@ -16,6 +16,7 @@ F16, F32, BF16 = 0, 1, 2
 _DTYPES = {torch.float16: F16, torch.float32: F32, torch.bfloat16: BF16}
 KERNEL_AUTO, KERNEL_VECTOR, KERNEL_MATRIX = 0, 1, 2
 VALUES_TQ3, VALUES_TQ3_SCALED, VALUES_INT8 = 0, 1, 2
+KEYS_Q8_BLOCK32, KEYS_Q8_TENSOR = 0, 1
 MAX_TAIL_AGENTS = 64
 
 
@@ -47,6 +48,8 @@ def _load():
     lib.pool_create.restype = ip
     lib.pool_create_codec.argtypes = [ip, ip, ip, ip, ip, C.POINTER(vp)]
     lib.pool_create_codec.restype = ip
+    lib.pool_create_codecs.argtypes = [ip, ip, ip, ip, ip, ip, C.POINTER(vp)]
+    lib.pool_create_codecs.restype = ip
     lib.pool_set_sign_seed.argtypes = [vp, C.c_uint64]
     lib.pool_set_sign_seed.restype = ip
     lib.pool_destroy.argtypes = [vp]
@@ -169,12 +172,13 @@ class Pool:
     """pool_create + pool_bind around a torch-owned storage tensor."""
 
     def __init__(self, layers: int, kv_heads: int, head_dim: int, tokens: int, device="cuda:0",
-                 value_codec: int = VALUES_TQ3, sign_seed: int = 0):
+                 value_codec: int = VALUES_TQ3, sign_seed: int = 0, key_codec: int = KEYS_Q8_BLOCK32):
         self.layers, self.kv_heads, self.head_dim, self.tokens = layers, kv_heads, head_dim, tokens
         self.value_codec = value_codec
+        self.key_codec = key_codec
         self.device = torch.device(device)
         h = C.c_void_p()
-        _check(lib.pool_create_codec(layers, kv_heads, head_dim, tokens, value_codec, C.byref(h)))
+        _check(lib.pool_create_codecs(layers, kv_heads, head_dim, tokens, key_codec, value_codec, C.byref(h)))
         self._h = h
         if sign_seed:
             _check(lib.pool_set_sign_seed(self._h, sign_seed))
@@ -238,7 +242,10 @@ class Pool:
     def export(self, stream=None):
         n = (self.layers, self.kv_heads, self.length)
         kc = torch.empty(n + (self.head_dim,), dtype=torch.int8, device=self.device)
-        ks = torch.empty(n + (self.head_dim // 32,), dtype=torch.float16, device=self.device)
+        if self.key_codec == KEYS_Q8_TENSOR:     # one scale per layer tensor
+            ks = torch.empty((self.layers,), dtype=torch.float16, device=self.device)
+        else:
+            ks = torch.empty(n + (self.head_dim // 32,), dtype=torch.float16, device=self.device)
         if self.value_codec == VALUES_INT8:      # the int8 value codes themselves
             vp = torch.empty(n + (self.head_dim,), dtype=torch.int8, device=self.device)
         else:

@@ -31,10 +31,11 @@ def dev(x, bf16=False):
     return t.to(torch.bfloat16) if bf16 else t
 
 
-def gpu_pool(K, V, scaled_values=False, int8_values=False, bf16=False, sign_seed=0):
+def gpu_pool(K, V, scaled_values=False, int8_values=False, bf16=False, sign_seed=0, key_per_tensor=False):
     L, H, T, d = K.shape
     codec = pk.VALUES_INT8 if int8_values else pk.VALUES_TQ3_SCALED if scaled_values else pk.VALUES_TQ3
-    pool = pk.Pool(L, H, d, T, value_codec=codec, sign_seed=sign_seed).bind()
+    pool = pk.Pool(L, H, d, T, value_codec=codec, sign_seed=sign_seed,
+                   key_codec=pk.KEYS_Q8_TENSOR if key_per_tensor else pk.KEYS_Q8_BLOCK32).bind()
     pool.storage.fill_(0xA5)            # stale bytes must never leak into results
     pool.encode(dev(K, bf16), dev(V, bf16))
     return pool

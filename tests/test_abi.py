@@ -26,7 +26,7 @@ def test_library_exports_every_declared_function():
     assert {"pool_create", "pool_bytes", "pool_bind", "pool_encode", "pool_decode", "pool_export",
             "pool_attend_workspace", "pool_attend", "pool_destroy", "polykv_codebook",
             "polykv_last_error", "pool_append", "pool_length", "pool_decode_layers", "polykv_time_next_kernel",
-            "pool_create_codec", "pool_export_value_scales", "pool_encode_dtype", "pool_append_dtype", "pool_set_sign_seed"} <= set(names)
+            "pool_create_codec", "pool_export_value_scales", "pool_encode_dtype", "pool_append_dtype", "pool_set_sign_seed", "pool_create_codecs"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -83,6 +83,13 @@ def test_value_codec_choice_byte_counts_and_errors():
     assert lib.pool_export_value_scales(h, fake, None) == pk.ESTATE   # nothing bound / encoded
     assert lib.pool_set_sign_seed(h, 12345) == pk.OK and lib.pool_set_sign_seed(h, 0) == pk.OK
     assert lib.pool_set_sign_seed(None, 1) == pk.EINVAL
+    lib.pool_destroy(h)
+    # one key scale per layer tensor: no per-block scales, the layers' maxima behind the records; no append
+    assert lib.pool_create_codecs(1, 1, 64, 10, 5, pk.VALUES_TQ3, C.byref(h)) == pk.EINVAL
+    assert lib.pool_create_codecs(32, 8, 128, 4096, pk.KEYS_Q8_TENSOR, pk.VALUES_TQ3, C.byref(h)) == pk.OK
+    assert lib.pool_bytes(h) == 32 * 8 * 4096 * 176 + 256
+    assert lib.pool_bind(h, fake, lib.pool_bytes(h)) == pk.OK
+    assert lib.pool_append(h, fake, fake, 5, None) == pk.ESTATE
     lib.pool_destroy(h)
     assert lib.pool_create_codec(1, 1, 64, 10, pk.VALUES_INT8, C.byref(h)) == pk.OK
     assert lib.pool_set_sign_seed(h, 12345) == pk.ESTATE              # int8 values are not rotated
