@@ -54,7 +54,7 @@ import math
 import numpy as np
 
 Q8_BLOCK = 32          # elements per q8_0 block
-V_BITS = 3             # bits per value code
+V_BITS = 3             # bits per value code: the paper's choice; 2 and 4 are variants
 V_LEVELS = 1 << V_BITS
 
 
@@ -96,14 +96,15 @@ def lloyd_max_gaussian(levels: int = V_LEVELS, tol: float = 1e-15, max_iter: int
     return c, t
 
 
-_CODEBOOK = None
+_CODEBOOKS = {}
 
 
-def codebook():
-    global _CODEBOOK
-    if _CODEBOOK is None:
-        _CODEBOOK = lloyd_max_gaussian()
-    return _CODEBOOK
+def codebook(bits: int = V_BITS):
+    """(centroids, thresholds) of the 2^bits-level quantizer (section "TurboQuant": b bits per coordinate;
+    the paper uses b = 3)."""
+    if bits not in _CODEBOOKS:
+        _CODEBOOKS[bits] = lloyd_max_gaussian(1 << bits)
+    return _CODEBOOKS[bits]
 
 
 def lloyd_max_mse(c, t) -> float:
@@ -247,46 +248,46 @@ def v_rotate(V, signs=None):
     return fwht(v) / math.sqrt(d)
 
 
-def v_quantize(v_rot):
+def v_quantize(v_rot, bits: int = V_BITS):
     """Nearest-centroid index; a tie goes to the lower index, i.e. idx = #{k : v_rot > t_k}
     (step 2 of the value quantizer)."""
-    _, t = codebook()
+    _, t = codebook(bits)
     idx = np.zeros(np.shape(v_rot), dtype=np.uint8)
     for tk in t:
         idx += (v_rot > tk).astype(np.uint8)
     return idx
 
 
-def v_encode(V, signs=None):
-    """V: float16 [..., d] -> (idx uint8 [..., d] in 0..7, v_rot float64 [..., d])."""
+def v_encode(V, signs=None, bits: int = V_BITS):
+    """V: float16 [..., d] -> (idx uint8 [..., d] in 0..2^bits-1, v_rot float64 [..., d])."""
     V = _as_f32_input(V, "V")
     v_rot = v_rotate(V, signs)
-    return v_quantize(v_rot), v_rot
+    return v_quantize(v_rot, bits), v_rot
 
 
-def v_pack(idx):
-    """Canonical bit-packing: code j occupies stream bits 3j..3j+2 (LSB first); stream bit i is
-    bit (i mod 8) of byte floor(i/8).  [..., d] -> uint8 [..., 3d/8]."""
+def v_pack(idx, bits: int = V_BITS):
+    """Canonical bit-packing: code j occupies stream bits b*j..b*j+b-1 (LSB first); stream bit i is
+    bit (i mod 8) of byte floor(i/8).  [..., d] -> uint8 [..., b*d/8]."""
     idx = np.asarray(idx, dtype=np.uint8)
     d = idx.shape[-1]
-    if (d * V_BITS) % 8:
-        raise ValueError("3*d must be a multiple of 8")
-    bits = ((idx[..., :, None] >> np.arange(V_BITS, dtype=np.uint8)) & 1).astype(np.uint8)
-    bits = bits.reshape(idx.shape[:-1] + (d * V_BITS,))
-    return np.packbits(bits, axis=-1, bitorder="little")
+    if (d * bits) % 8:
+        raise ValueError("bits*d must be a multiple of 8")
+    stream = ((idx[..., :, None] >> np.arange(bits, dtype=np.uint8)) & 1).astype(np.uint8)
+    stream = stream.reshape(idx.shape[:-1] + (d * bits,))
+    return np.packbits(stream, axis=-1, bitorder="little")
 
 
-def v_unpack(packed, d: int):
+def v_unpack(packed, d: int, bits: int = V_BITS):
     packed = np.asarray(packed, dtype=np.uint8)
-    bits = np.unpackbits(packed, axis=-1, bitorder="little")[..., : d * V_BITS]
-    bits = bits.reshape(packed.shape[:-1] + (d, V_BITS)).astype(np.uint8)
-    return (bits << np.arange(V_BITS, dtype=np.uint8)).sum(axis=-1).astype(np.uint8)
+    stream = np.unpackbits(packed, axis=-1, bitorder="little")[..., : d * bits]
+    stream = stream.reshape(packed.shape[:-1] + (d, bits)).astype(np.uint8)
+    return (stream << np.arange(bits, dtype=np.uint8)).sum(axis=-1).astype(np.uint8)
 
 
-def v_decode(idx, signs=None):
+def v_decode(idx, signs=None, bits: int = V_BITS):
     """V_dequant = H c[idx] / sqrt(d)  (true inverse of the normalized rotation); with a sign diagonal
     D H c[idx] / sqrt(d), the inverse of H D / sqrt(d)."""
-    c, _ = codebook()
+    c, _ = codebook(bits)
     idx = np.asarray(idx)
     d = idx.shape[-1]
     v = fwht(c[idx]) / math.sqrt(d)
@@ -312,30 +313,30 @@ def v_scale(V):
     return np.minimum(rms, V_SCALE_MAX).astype(np.float16), rms
 
 
-def v_quantize_scaled(v_rot, g16):
+def v_quantize_scaled(v_rot, g16, bits: int = V_BITS):
     """idx = #{k : v_rot > t_k * g}: the quantizer of v_quantize applied to v_rot / g, written without
     the division.  A vector whose scale is stored as zero decodes to the zero vector whatever its
-    codes; it gets the codes of the zero vector, 3 (as v_quantize gives for 0)."""
-    _, t = codebook()
+    codes; it gets the codes of the zero vector, 2^(bits-1) - 1 (as v_quantize gives for 0; 3 at 3 bits)."""
+    _, t = codebook(bits)
     g = np.asarray(g16).astype(np.float64)[..., None]
     idx = np.zeros(np.shape(v_rot), dtype=np.uint8)
     for tk in t:
         idx += (v_rot > tk * g).astype(np.uint8)
-    return np.where(g > 0, idx, np.uint8(3)).astype(np.uint8)
+    return np.where(g > 0, idx, np.uint8((1 << bits) // 2 - 1)).astype(np.uint8)
 
 
-def v_encode_scaled(V, signs=None):
+def v_encode_scaled(V, signs=None, bits: int = V_BITS):
     """V: float16 [..., d] -> (idx uint8 [..., d], g16 float16 [...], v_rot float64 [..., d],
     rms float64 [...])."""
     V = _as_f32_input(V, "V")
     g16, rms = v_scale(V)
     v_rot = v_rotate(V, signs)
-    return v_quantize_scaled(v_rot, g16), g16, v_rot, rms
+    return v_quantize_scaled(v_rot, g16, bits), g16, v_rot, rms
 
 
-def v_decode_scaled(idx, g16, signs=None):
+def v_decode_scaled(idx, g16, signs=None, bits: int = V_BITS):
     """V_dequant = g * H c[idx] / sqrt(d)  (g * D H c[idx] / sqrt(d) with a sign diagonal)."""
-    return v_decode(idx, signs) * np.asarray(g16).astype(np.float64)[..., None]
+    return v_decode(idx, signs, bits) * np.asarray(g16).astype(np.float64)[..., None]
 
 
 # --------------------------------------------------------------------------- #
@@ -370,13 +371,14 @@ def v_decode_int8(codes, scales):
 # Pool = encode of a whole [L, H, T, d] cache; decode back
 # --------------------------------------------------------------------------- #
 def pool_encode(K, V, scaled_values: bool = False, int8_values: bool = False, sign_seed: int = 0,
-                key_per_tensor: bool = False):
+                key_per_tensor: bool = False, value_bits: int = V_BITS):
     """K, V float16 [L, H, T, d] -> dict with the canonical stored arrays and the pre-rounding
     values a parity test needs to find elements that sit on a decision threshold.  sign_seed != 0: the
     rotation carries the sign diagonal rotation_signs(sign_seed, d) (not with int8 values, which are
     not rotated).  key_per_tensor: one key scale per layer tensor [H, T, d], s = max|K|/127 over the
     whole tensor -- the key formula exactly as section "Compression Scheme" prints it -- instead of one
-    per block of 32; k_scales is then float16 [L]."""
+    per block of 32; k_scales is then float16 [L].  value_bits: bits per value code (the paper's 3, or 2 or 4
+    with the Lloyd-Max codebook of that size)."""
     if key_per_tensor:
         K = np.asarray(K)
         per_layer = [k_encode(K[l], block=None) for l in range(K.shape[0])]
@@ -394,11 +396,11 @@ def pool_encode(K, V, scaled_values: bool = False, int8_values: bool = False, si
         return out
     signs = rotation_signs(sign_seed, np.shape(V)[-1]) if sign_seed else None
     if scaled_values:
-        v_idx, g16, v_rot, rms = v_encode_scaled(V, signs)
+        v_idx, g16, v_rot, rms = v_encode_scaled(V, signs, value_bits)
         out.update(v_scales=g16, v_rms=rms)
     else:
-        v_idx, v_rot = v_encode(V, signs)
-    out.update(v_packed=v_pack(v_idx), v_idx=v_idx, v_rot=v_rot)
+        v_idx, v_rot = v_encode(V, signs, value_bits)
+    out.update(v_packed=v_pack(v_idx, value_bits), v_idx=v_idx, v_rot=v_rot, v_bits=value_bits)
     if signs is not None:
         out["v_signs"] = signs
     return out
@@ -413,19 +415,20 @@ def pool_decode(pool):
     if "v_codes" in pool:
         return K_hat, v_decode_int8(pool["v_codes"], pool["v_scales"])
     d = pool["k_codes"].shape[-1]
-    idx = v_unpack(pool["v_packed"], d)
+    bits = pool.get("v_bits", V_BITS)
+    idx = v_unpack(pool["v_packed"], d, bits)
     signs = pool.get("v_signs")
-    V_hat = v_decode_scaled(idx, pool["v_scales"], signs) if "v_scales" in pool else v_decode(idx, signs)
+    V_hat = v_decode_scaled(idx, pool["v_scales"], signs, bits) if "v_scales" in pool else v_decode(idx, signs, bits)
     return K_hat, V_hat
 
 
 def stored_bytes(L: int, H: int, T: int, d: int, scaled_values: bool = False, int8_values: bool = False,
-                 key_per_tensor: bool = False) -> dict:
+                 key_per_tensor: bool = False, value_bits: int = V_BITS) -> dict:
     """Byte accounting (section "Compression Scheme", paragraph "Compression ratio")."""
     n = L * H * T
     k_codes = n * d
     k_scales = L * 2 if key_per_tensor else n * (d // Q8_BLOCK) * 2
-    v_codes = n * d if int8_values else n * d * V_BITS // 8
+    v_codes = n * d if int8_values else n * d * value_bits // 8
     v_scales = n * 2 if (scaled_values or int8_values) else 0
     dense16 = 2 * n * d * 2
     packed = k_codes + k_scales + v_codes + v_scales

@@ -671,3 +671,63 @@ def test_per_tensor_key_scale_pool_form_and_the_papers_ratio():
     b = O.stored_bytes(32, 8, 7194, 128, key_per_tensor=True)
     assert b["packed"] == 32 * 8 * 7194 * 176 + 32 * 2
     assert round(b["ratio_stored"], 2) == consts["compression_ratio"]
+
+
+# ------------------------------------------------------- other value bit widths ---
+def test_codebooks_of_2_3_4_bits_match_the_published_table_and_the_bound():
+    for row in read_golden_rows("max1960_table.txt"):
+        levels, mse, want = int(row[0]), float(row[1]), np.array([float(x) for x in row[2:]])
+        bits = levels.bit_length() - 1
+        c, t = O.codebook(bits)
+        assert c.shape == (levels,) and t.shape == (levels - 1,)
+        np.testing.assert_allclose(c[levels // 2:], want, rtol=6e-4)      # four printed digits
+        np.testing.assert_allclose(c, -c[::-1], atol=1e-15)
+        assert abs(O.lloyd_max_mse(c, t) / mse - 1) < 1e-3
+        assert O.lloyd_max_mse(c, t) < O.turboquant_mse_bound(bits)
+        # fixed point, by numerical integration
+        pdf = scipy.stats.norm.pdf
+        edges = [-np.inf, *t, np.inf]
+        for k in range(levels):
+            mass = scipy.integrate.quad(pdf, edges[k], edges[k + 1])[0]
+            mean = scipy.integrate.quad(lambda x: x * pdf(x), edges[k], edges[k + 1])[0] / mass
+            assert abs(mean - c[k]) < 1e-8
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_value_codec_at_other_bit_widths(bits):
+    c, t = O.codebook(bits)
+    rng = np.random.default_rng(70 + bits)
+    x = rng.standard_normal(20000) * 1.5
+    np.testing.assert_array_equal(O.v_quantize(x, bits), np.argmin(np.abs(x[:, None] - c[None, :]), axis=1))
+    assert O.v_quantize(np.array([0.0]), bits)[0] == (1 << bits) // 2 - 1    # a tie goes to the lower index
+    # exhaustive pack / unpack of one byte-aligned group, and a hand-computed byte
+    per = 8 // bits
+    allc = np.array(list(itertools.product(range(1 << bits), repeat=per)), dtype=np.uint8)
+    packed = O.v_pack(allc, bits)
+    assert packed.shape == (allc.shape[0], 1)
+    np.testing.assert_array_equal(O.v_unpack(packed, per, bits), allc)
+    if bits == 4:
+        assert O.v_pack(np.array([[0x3, 0xA]], dtype=np.uint8), 4)[0, 0] == 0xA3      # code 0 in the low nibble
+    else:
+        assert O.v_pack(np.array([[1, 2, 3, 0]], dtype=np.uint8), 2)[0, 0] == 0b00111001
+    # statistics on Gaussian data: per-coordinate MSE = the codebook's, carried through the rotation
+    d = 128
+    V = rng.standard_normal((4096, d)).astype(np.float16)
+    idx, v_rot = O.v_encode(V, bits=bits)
+    assert idx.max() == (1 << bits) - 1
+    mse = np.mean((O.v_decode(idx, bits=bits) - V.astype(np.float64)) ** 2)
+    assert abs(mse / O.lloyd_max_mse(c, t) - 1) < 0.02
+    # scaled variant and pool functions
+    sig = np.exp(rng.standard_normal((4096, 1)))
+    Vw = (V.astype(np.float64) * sig).astype(np.float16)
+    idx, g16, _, _ = O.v_encode_scaled(Vw, bits=bits)
+    rel = np.sum((O.v_decode_scaled(idx, g16, bits=bits) - Vw.astype(np.float64)) ** 2, -1) / np.sum(Vw.astype(np.float64) ** 2, -1)
+    assert abs(rel.mean() / O.lloyd_max_mse(c, t) - 1) < 0.03
+    assert np.all(O.v_encode_scaled(np.zeros((1, d), np.float16), bits=bits)[0] == (1 << bits) // 2 - 1)
+    K = rng.standard_normal((1, 2, 40, 64)).astype(np.float16)
+    Vp = rng.standard_normal((1, 2, 40, 64)).astype(np.float16)
+    ref = O.pool_encode(K, Vp, value_bits=bits)
+    assert ref["v_packed"].shape == (1, 2, 40, 64 * bits // 8) and ref["v_bits"] == bits
+    _, Vh = O.pool_decode(ref)
+    np.testing.assert_array_equal(Vh, O.v_decode(ref["v_idx"], bits=bits))
+    assert O.stored_bytes(32, 8, 4096, 128, value_bits=bits)["packed"] == 32 * 8 * 4096 * (136 + 16 * bits)
