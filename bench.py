@@ -58,6 +58,11 @@ def cpu_baseline(cfg, W, layers=None):
     }
 
 
+# name -> (codec id of the C ABI, bits per value code, per-vector scale stored)
+VALUE_CODECS = {"tq3": (0, 3, False), "tq3-scaled": (1, 3, True), "int8": (2, 8, True), "tq2": (3, 2, False),
+                "tq2-scaled": (4, 2, True), "tq4": (5, 4, False), "tq4-scaled": (6, 4, True)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -77,9 +82,10 @@ def main():
     ap.add_argument("--extras", action="store_true",
                     help="after the timed region also time a plain device copy and pool_attend launched back to back "
                          "(context only; off by default so that a profile of the default run holds the timed steps only)")
-    ap.add_argument("--value-codec", choices=("tq3", "tq3-scaled", "int8"), default="tq3",
-                    help="value codec: tq3 = the paper's (headline configuration); tq3-scaled = the same with a "
-                    "per-vector fp16 scale; int8 = uniform int8 without rotation (the paper's proposed ablation)")
+    ap.add_argument("--value-codec", choices=tuple(VALUE_CODECS), default="tq3",
+                    help="value codec: tq3 = the paper's (headline configuration); tqB-scaled = with a per-vector fp16 "
+                    "scale; tq2 / tq4 = 2 / 4 bits per coordinate; int8 = uniform int8 without rotation (the paper's "
+                    "proposed ablation)")
     ap.add_argument("--key-codec", choices=("block32", "tensor"), default="block32",
                     help="key codec: block32 = q8_0 blocks of 32 (headline configuration); tensor = one scale per layer "
                     "tensor, the key formula as the paper prints it (two passes over K at encode)")
@@ -115,7 +121,7 @@ def main():
     out = torch.empty(Q.shape, dtype=torch.float32, device="cuda")
     Kd = torch.empty_like(K)
     Vd = torch.empty_like(V)
-    codec = {"tq3": pk.VALUES_TQ3, "tq3-scaled": pk.VALUES_TQ3_SCALED, "int8": pk.VALUES_INT8}[args.value_codec]
+    codec = VALUE_CODECS[args.value_codec][0]
     kcodec = pk.KEYS_Q8_TENSOR if args.key_codec == "tensor" else pk.KEYS_Q8_BLOCK32
     pools = [pk.Pool(L, H, d, T, value_codec=codec, key_codec=kcodec).bind() for _ in range(max(1, args.pools))]
     tails = None
@@ -236,7 +242,8 @@ def main():
         k_enc = t_enc
 
     units = L * H
-    v_bytes = {"tq3": 3 * d // 8, "tq3-scaled": 3 * d // 8 + 2, "int8": d + 2}[args.value_codec]
+    v_bits, v_scaled = VALUE_CODECS[args.value_codec][1:]
+    v_bytes = v_bits * d // 8 + (2 if v_scaled else 0)
     k_bytes = d + (d // 16 if args.key_codec == "block32" else 0)
     packed = units * T * (k_bytes + v_bytes)                         # algorithmic pool bytes
     enc_bytes = units * T * 4 * d + packed
@@ -253,7 +260,7 @@ def main():
 
     how = ("; duration = the kernel's own begin/end HIP events (hipExtLaunchKernel start/stop events on the launch "
            "stream), averaged over the timed steps")
-    vc = {"tq3": 0, "tq3-scaled": 1, "int8": 2}[args.value_codec]      # the kernels' value-codec template argument
+    vc = codec                                                          # the kernels' value-codec template argument
     nt = 1 if (cfg.rows_per_kv_head <= 32 or d == 256 or (vc == 2 and d == 128)) else 2
     kc = 1 if args.key_codec == "tensor" else 0
     attend_roof = roof(att_gbps, "attend_mfma_kernel<%d,%d,%d,%d> (pool_attend)" % (d, nt, vc, kc) + how +

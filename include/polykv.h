@@ -61,8 +61,20 @@ enum { POLYKV_KERNEL_AUTO = 0, POLYKV_KERNEL_VECTOR = 1, POLYKV_KERNEL_MATRIX = 
  *   POLYKV_VALUES_INT8        uniform int8 without rotation, the ablation proposed in sections "Discussion" and
  *                             "Future Work": the key formula on each value vector with one scale per vector,
  *                             s = fp16(min(max|v| / 127, 128)), code = clip(rint(v / s), -128, 127) formed with the
- *                             stored s, V = code * s.  head_dim + 2 bytes per vector. */
-enum { POLYKV_VALUES_TQ3 = 0, POLYKV_VALUES_TQ3_SCALED = 1, POLYKV_VALUES_INT8 = 2 };
+ *                             stored s, V = code * s.  head_dim + 2 bytes per vector.
+ *   POLYKV_VALUES_TQ2, _TQ4   the paper's codec at 2 and 4 bits per coordinate (section "TurboQuant" states the
+ *   (and their _SCALED forms) quantizer for b bits; the paper uses b = 3): the Lloyd-Max codebook of N(0,1) with
+ *                             4 and 16 levels, code = number of thresholds strictly below v_rot, head_dim/4 and
+ *                             head_dim/2 bytes per vector. */
+enum {
+    POLYKV_VALUES_TQ3 = 0,
+    POLYKV_VALUES_TQ3_SCALED = 1,
+    POLYKV_VALUES_INT8 = 2,
+    POLYKV_VALUES_TQ2 = 3,
+    POLYKV_VALUES_TQ2_SCALED = 4,
+    POLYKV_VALUES_TQ4 = 5,
+    POLYKV_VALUES_TQ4_SCALED = 6
+};
 
 /* Key codecs.
  *   POLYKV_KEYS_Q8_BLOCK32  q8_0: one fp16 scale per block of 32 consecutive head_dim elements (the default).
@@ -146,14 +158,15 @@ int pool_decode_layers(const polykv_pool* pool, void* K_out_dev, void* V_out_dev
  *                code j of a vector occupies stream bits 3j..3j+2, stream bit i is bit (i mod 8)
  *                of byte floor(i/8).
  *                A POLYKV_VALUES_INT8 pool writes int8 [layers, kv_heads, pool_length(), head_dim] here,
- *                the value codes themselves.
+ *                the value codes themselves; the 2- and 4-bit codecs the same stream with 2 / 4 bits per code
+ *                (head_dim/4 and head_dim/2 bytes per vector).
  * (The in-HBM layout is tiled for the attention kernel and is not part of the ABI.)  Any of the
  * three may be NULL. */
 int pool_export(const polykv_pool* pool, void* k_codes_dev, void* k_scales_dev, void* v_packed_dev,
                 void* stream);
 
-/* The per-vector value scales of a POLYKV_VALUES_TQ3_SCALED or POLYKV_VALUES_INT8 pool: v_scales_dev fp16
- * [layers, kv_heads, pool_length()].  POLYKV_ESTATE for a pool of the paper's codec, which has none. */
+/* The per-vector value scales of a pool whose value codec stores them (the _SCALED codecs and POLYKV_VALUES_INT8):
+ * v_scales_dev fp16 [layers, kv_heads, pool_length()].  POLYKV_ESTATE for the other codecs. */
 int pool_export_value_scales(const polykv_pool* pool, void* v_scales_dev, void* stream);
 
 /* Decode attention of N agents directly over the packed pool (replaces the paper's per-agent
@@ -202,6 +215,8 @@ int pool_attend(const polykv_pool* pool, const void* Q_dev, void* out_dev,
 /* The value codebook the library uses: 8 ascending centroids and the 7 decision thresholds
  * (midpoints), as fp32 (section "TurboQuant", Lloyd-Max quantization).  Host call. */
 void polykv_codebook(float* centroids8, float* thresholds7);
+/* The same for bits = 2, 3 or 4: 2^bits ascending centroids and 2^bits - 1 thresholds.  POLYKV_EINVAL otherwise. */
+int polykv_codebook_bits(int bits, float* centroids, float* thresholds);
 
 /* Measurement hook (for benchmarks and profilers; not an operation of the method).  Arms the calling
  * thread: the NEXT pool_encode, pool_decode or pool_attend call of this thread that launches has the HIP runtime

@@ -32,8 +32,11 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Bytes of one tile record for the given head_dim and codecs.
 template <int D> static int tile_bytes_of(int vc, int kc) {
-    const int t[2][3] = {{Layout<D, 0, 0>::tile_bytes, Layout<D, 1, 0>::tile_bytes, Layout<D, 2, 0>::tile_bytes},
-                         {Layout<D, 0, 1>::tile_bytes, Layout<D, 1, 1>::tile_bytes, Layout<D, 2, 1>::tile_bytes}};
+    const int t[2][kNumValueCodecs] = {
+        {Layout<D, 0, 0>::tile_bytes, Layout<D, 1, 0>::tile_bytes, Layout<D, 2, 0>::tile_bytes, Layout<D, 3, 0>::tile_bytes,
+         Layout<D, 4, 0>::tile_bytes, Layout<D, 5, 0>::tile_bytes, Layout<D, 6, 0>::tile_bytes},
+        {Layout<D, 0, 1>::tile_bytes, Layout<D, 1, 1>::tile_bytes, Layout<D, 2, 1>::tile_bytes, Layout<D, 3, 1>::tile_bytes,
+         Layout<D, 4, 1>::tile_bytes, Layout<D, 5, 1>::tile_bytes, Layout<D, 6, 1>::tile_bytes}};
     return t[kc][vc];
 }
 
@@ -185,7 +188,7 @@ int pool_create_codecs(int layers, int kv_heads, int head_dim, int tokens, int k
         return POLYKV_EINVAL;
     }
     *out = nullptr;
-    if (value_codec < POLYKV_VALUES_TQ3 || value_codec > POLYKV_VALUES_INT8) {
+    if (value_codec < POLYKV_VALUES_TQ3 || value_codec > POLYKV_VALUES_TQ4_SCALED) {
         set_error("pool_create: unknown value codec %d", value_codec);
         return POLYKV_EINVAL;
     }
@@ -386,7 +389,7 @@ int pool_export(const polykv_pool* pool, void* k_codes_dev, void* k_scales_dev, 
 int pool_export_value_scales(const polykv_pool* pool, void* v_scales_dev, void* stream) {
     int rc = check_readable(pool, "pool_export_value_scales");
     if (rc != POLYKV_OK) return rc;
-    if (pool->value_codec == POLYKV_VALUES_TQ3) {
+    if (!vc_has_scale(pool->value_codec)) {
         set_error("pool_export_value_scales: the pool's value codec stores no scales");
         return POLYKV_ESTATE;
     }
@@ -460,6 +463,27 @@ void polykv_codebook(float* centroids8, float* thresholds7) {
             thresholds7[2 - i] = -t[i];
         }
     }
+}
+
+int polykv_codebook_bits(int bits, float* centroids, float* thresholds) {
+    if (bits < 2 || bits > 4) {
+        set_error("polykv_codebook_bits: bits=%d (2, 3 or 4)", bits);
+        return POLYKV_EINVAL;
+    }
+    const int half = 1 << (bits - 1);
+    if (centroids != nullptr)
+        for (int i = 0; i < half; ++i) {
+            centroids[half + i] = centroid_mag(bits, i);
+            centroids[half - 1 - i] = -centroid_mag(bits, i);
+        }
+    if (thresholds != nullptr) {
+        thresholds[half - 1] = 0.0f;
+        for (int i = 0; i < half - 1; ++i) {
+            thresholds[half + i] = threshold_mag(bits, i);
+            thresholds[half - 2 - i] = -threshold_mag(bits, i);
+        }
+    }
+    return POLYKV_OK;
 }
 
 int polykv_time_next_kernel(void* start_event, void* stop_event) {

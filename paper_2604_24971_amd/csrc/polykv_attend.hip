@@ -44,11 +44,12 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
                                                             float* __restrict__ ws_ml,
                                                             float* __restrict__ ws_o, AttendPlan p) {
     using LY = Layout<D, VC, KC>;
-    constexpr bool VS = LY::has_vscales, V8 = VC == 2;
+    constexpr int VB = vc_bits(VC);
+    constexpr bool VS = LY::has_vscales, V8 = VB == 8;
     constexpr int MT = D / 32;
     __shared__ __align__(16) float q_s[kRB][D];
     __shared__ __align__(16) float p_s[4][kRB][64];
-    __shared__ float ctab[8];
+    __shared__ float ctab[16];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int usel = blockIdx.y;  // selected unit: ls * H + kvh
@@ -64,7 +65,8 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
                 p.qscale;
         q_s[r][jj] = v;
     }
-    if (tid < 8) ctab[tid] = centroid_of(tid);
+    if (VB == 3 && tid < 8) ctab[tid] = centroid_of(tid);
+    if ((VB == 2 || VB == 4) && tid < (1 << VB)) ctab[tid] = centroid_signmag(VB, tid);  // sign-magnitude codes
     __syncthreads();
 
     const int nchunks = (p.tiles + 1) / 2;
@@ -145,6 +147,32 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
 #pragma unroll
                         for (int e3 = 0; e3 < 4; ++e3) cv[e3] = (float)((int)((w[x] >> (8 * e3)) & 0xFF) - 128);
                         const int tk = sub * 32 + 8 * x + 4 * vh;  // tokens tk .. tk+3
+#pragma unroll
+                        for (int r = 0; r < kRB; ++r) {
+                            const float4 pv = *reinterpret_cast<const float4*>(&p_s[wave][r][tk]);
+                            acc[r][g] = fmaf(pv.x, cv[0], acc[r][g]);
+                            acc[r][g] = fmaf(pv.y, cv[1], acc[r][g]);
+                            acc[r][g] = fmaf(pv.z, cv[2], acc[r][g]);
+                            acc[r][g] = fmaf(pv.w, cv[3], acc[r][g]);
+                        }
+                    }
+                }
+                continue;
+            }
+            if (VB == 2 || VB == 4) {
+#pragma unroll
+                for (int G = 0; G < D / 16; ++G) {
+                    const uint32_t w = VB == 4 ? vreg[lane * (D / 16) + G] : vreg[lane * (D / 32) + (G >> 1)];
+                    const int g = G >> 1;
+#pragma unroll
+                    for (int e4 = 0; e4 < 2; ++e4) {
+                        float cv[4];
+#pragma unroll
+                        for (int e3 = 0; e3 < 4; ++e3) {
+                            const int code = VB == 4 ? (w >> (8 * e3 + 4 * e4)) & 15 : (w >> (8 * e3 + 2 * (2 * (G & 1) + e4))) & 3;
+                            cv[e3] = ctab[code];
+                        }
+                        const int tk = sub * 32 + vcode_token(G, lane, 4 * e4);  // tokens tk .. tk+3
 #pragma unroll
                         for (int r = 0; r < kRB; ++r) {
                             const float4 pv = *reinterpret_cast<const float4*>(&p_s[wave][r][tk]);
@@ -469,13 +497,15 @@ hipError_t launch_attend(const polykv_pool* pool, const AttendPlan& plan, const 
         if (matrix_kernel_direct(plan)) return hipSuccess;
     } else {
         dim3 grid(plan.nsplit / 4, units, (plan.R + kRB - 1) / kRB);
-        decltype(&attend_vector_kernel<128, 0, 0>) table[2][3][3] = {
-            {{attend_vector_kernel<64, 0, 0>, attend_vector_kernel<64, 1, 0>, attend_vector_kernel<64, 2, 0>},
-             {attend_vector_kernel<128, 0, 0>, attend_vector_kernel<128, 1, 0>, attend_vector_kernel<128, 2, 0>},
-             {attend_vector_kernel<256, 0, 0>, attend_vector_kernel<256, 1, 0>, attend_vector_kernel<256, 2, 0>}},
-            {{attend_vector_kernel<64, 0, 1>, attend_vector_kernel<64, 1, 1>, attend_vector_kernel<64, 2, 1>},
-             {attend_vector_kernel<128, 0, 1>, attend_vector_kernel<128, 1, 1>, attend_vector_kernel<128, 2, 1>},
-             {attend_vector_kernel<256, 0, 1>, attend_vector_kernel<256, 1, 1>, attend_vector_kernel<256, 2, 1>}}};
+        using Kern = decltype(&attend_vector_kernel<128, 0, 0>);
+#define POLYKV_VEC_ROW(D, KC)                                                                                   \
+    {attend_vector_kernel<D, 0, KC>, attend_vector_kernel<D, 1, KC>, attend_vector_kernel<D, 2, KC>,            \
+     attend_vector_kernel<D, 3, KC>, attend_vector_kernel<D, 4, KC>, attend_vector_kernel<D, 5, KC>,            \
+     attend_vector_kernel<D, 6, KC>}
+        static const Kern table[2][3][kNumValueCodecs] = {
+            {POLYKV_VEC_ROW(64, 0), POLYKV_VEC_ROW(128, 0), POLYKV_VEC_ROW(256, 0)},
+            {POLYKV_VEC_ROW(64, 1), POLYKV_VEC_ROW(128, 1), POLYKV_VEC_ROW(256, 1)}};
+#undef POLYKV_VEC_ROW
         auto kern = table[plan.kcodec][plan.D == 64 ? 0 : plan.D == 128 ? 1 : 2][plan.vcodec];
         launch_main_kernel(kern, grid, dim3(256), 0, s, storage, (const __half*)Q, ws_ml, ws_o, plan);
         if ((err = hipGetLastError()) != hipSuccess) return err;

@@ -72,11 +72,13 @@ template <int D> struct RawK {
     uint32_t sc[D / 64];   // fp16 scales of token m, blocks 0..NB-1 (unused with one scale per layer tensor)
 };
 template <int D, int VC> struct RawV {
-    uint32_t w[VC == 2 ? 1 : D / 64][3];  // 3-bit codecs: the lane's code triplets
-    uint4v c[VC == 2 ? D / 32 : 1];       // int8 codec: the lane's 16 code bytes of every coordinate group
+    uint32_t w[vc_bits(VC) == 3 ? D / 64 : 1][3];  // 3-bit codecs: the lane's code triplets
+    uint4v c[vc_bits(VC) == 8 ? D / 32 : 1];       // int8 codec: the lane's 16 code bytes of every coordinate group
+    // 4-bit codecs: one dword per coordinate group; 2-bit codecs: one per pair of groups
+    uint32_t n[vc_bits(VC) == 4 ? D / 16 : vc_bits(VC) == 2 ? D / 32 : 1];
     // codecs with value scales: the scales of the lane's 16 tokens as fp16 pairs, in the order in which
     // the lane holds their probabilities (tokens 8b + 4h + {0,1} in g[2b], + {2,3} in g[2b+1])
-    uint32_t g[VC != 0 ? 8 : 1];
+    uint32_t g[vc_has_scale(VC) ? 8 : 1];
 };
 
 // `tile` is wave-uniform and the lane's share sits at a 32-bit offset from it, so every load can use
@@ -92,7 +94,13 @@ template <int D, int KC> __device__ __forceinline__ void load_rawk(RawK<D>& r, c
 }
 template <int D, int VC, int KC> __device__ __forceinline__ void load_rawv(RawV<D, VC>& r, const uint8_t* tile, int lane) {
     using LY = Layout<D, VC, KC>;
-    if (VC == 2) {
+    constexpr int VB = vc_bits(VC);
+    if (VB == 4 || VB == 2) {
+        constexpr int ND = VB == 4 ? D / 16 : D / 32;  // dwords per lane, contiguous
+        const uint32_t voff = LY::vcodes_off + (uint32_t)lane * (ND * 4);
+#pragma unroll
+        for (int i = 0; i < ND; ++i) r.n[i] = *reinterpret_cast<const uint32_t*>(tile + voff + 4 * i);
+    } else if (VB == 8) {
         const uint32_t voff = LY::vcodes_off + (uint32_t)lane * 16;
 #pragma unroll
         for (int g = 0; g < D / 32; ++g) r.c[g] = *reinterpret_cast<const uint4v*>(tile + voff + g * 1024);
@@ -103,7 +111,7 @@ template <int D, int VC, int KC> __device__ __forceinline__ void load_rawv(RawV<
 #pragma unroll
             for (int w = 0; w < 3; ++w) r.w[q][w] = *reinterpret_cast<const uint32_t*>(tile + voff + q * 768 + 4 * w);
     }
-    if (VC != 0) {
+    if (vc_has_scale(VC)) {
         const uint32_t goff = LY::vscales_off + (uint32_t)(lane >> 5) * 8;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
@@ -139,7 +147,15 @@ __device__ __forceinline__ void key_split(const RawK<D>& rk, int j, int s, half8
 
 // Value group G of a lane: eight 3-bit codes -> fp16 centroids, the A operand of one P.V product.
 template <int D, int VC> __device__ __forceinline__ void value_group(const RawV<D, VC>& rv, int G, H8& va) {
-    if (VC == 2) {
+    if (vc_bits(VC) == 4) {
+        group8_b4(rv.n[G], va.u);
+        return;
+    }
+    if (vc_bits(VC) == 2) {
+        group8_b2(rv.n[G >> 1], G & 1, va.u);
+        return;
+    }
+    if (vc_bits(VC) == 8) {
         // int8 codes of coordinate group G/2, token half G%2 -> exact fp16 integers (the scale rides on P)
         const uint4v& c = rv.c[G >> 1];
         codes4_to_half((G & 1) == 0 ? c.x : c.z, va.u[0], va.u[1]);
@@ -235,7 +251,7 @@ __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile,
 #pragma unroll
         for (int g = 0; g < D / 32; ++g) O[g][nt] *= alpha;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) exp4<VC != 0>(S[nt], c, qscale, mneg[nt], pb[nt], Lsum[nt], rv.g);
+        for (int c = 0; c < 4; ++c) exp4<vc_has_scale(VC)>(S[nt], c, qscale, mneg[nt], pb[nt], Lsum[nt], rv.g);
     }
 #pragma unroll
     for (int G = 0; G < NG; ++G) {
@@ -323,7 +339,7 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
     H8 pb[NT][2];      // probabilities of tile A: B operands of the P.V products, [row tile][k slice]
     half8 khi[2], klo[2];
     H8 va[2];
-    auto exp_chunk = [&](int c) { exp4<VC != 0>(Sa[c >> 2], c & 3, qscale, mneg[c >> 2], pb[c >> 2], Lsum[c >> 2], rv.g); };
+    auto exp_chunk = [&](int c) { exp4<vc_has_scale(VC)>(Sa[c >> 2], c & 3, qscale, mneg[c >> 2], pb[c >> 2], Lsum[c >> 2], rv.g); };
     auto kdeq = [&](int k) { key_split<D, KC>(rk, k >> 1, k & 1, khi[k & 1], klo[k & 1]); };
     auto qk = [&](int k) {
         const int j = k >> 1, s = k & 1;
@@ -585,11 +601,11 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         const float l = (l_s[rr] + l_s[ROWS + rr]) + (l_s[2 * ROWS + rr] + l_s[3 * ROWS + rr]);
         // direct: 1/l, the centroid scale, 1/sqrt(D) and the entry sign of the DPP stages in one factor
         // int8 values are accumulated unrotated and unscaled: 1/l is all that is left to do
+        constexpr float kCS = inv_centroid_scale<vc_bits(VC)>();
         const float f = VC == 2 ? (direct ? __builtin_amdgcn_rcpf(l) : 1.0f)
-                        : direct ? quad_entry_sign(lane) *
-                                       (kInvCentroidScale * (D == 64 ? 0.125f : D == 128 ? 0.08838834764831845f : 0.0625f)) *
+                        : direct ? quad_entry_sign(lane) * (kCS * (D == 64 ? 0.125f : D == 128 ? 0.08838834764831845f : 0.0625f)) *
                                        __builtin_amdgcn_rcpf(l)
-                                 : kInvCentroidScale;
+                                 : kCS;
         float x[CPL];
         const float4* a4 = reinterpret_cast<const float4*>(&o_s[rr * OSTRIDE + qd * CPL]);
         constexpr int BUF4 = ROWS * OSTRIDE / 4;  // one wave's buffer, in float4 units
@@ -676,17 +692,25 @@ static hipError_t launch_dv(const polykv_pool* pool, const AttendPlan& plan, con
                                     s);
 }
 
+template <int D, int KC>
+static hipError_t launch_dk(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml, float* ws_o,
+                            float* out, hipStream_t s) {
+    switch (plan.vcodec) {
+        case 1: return launch_dv<D, 1, KC>(pool, plan, Q, ws_ml, ws_o, out, s);
+        case 2: return launch_dv<D, 2, KC>(pool, plan, Q, ws_ml, ws_o, out, s);
+        case 3: return launch_dv<D, 3, KC>(pool, plan, Q, ws_ml, ws_o, out, s);
+        case 4: return launch_dv<D, 4, KC>(pool, plan, Q, ws_ml, ws_o, out, s);
+        case 5: return launch_dv<D, 5, KC>(pool, plan, Q, ws_ml, ws_o, out, s);
+        case 6: return launch_dv<D, 6, KC>(pool, plan, Q, ws_ml, ws_o, out, s);
+        default: return launch_dv<D, 0, KC>(pool, plan, Q, ws_ml, ws_o, out, s);
+    }
+}
+
 template <int D>
 static hipError_t launch_d(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,
                            float* ws_o, float* out, hipStream_t s) {
-    if (plan.kcodec == POLYKV_KEYS_Q8_TENSOR) {
-        if (plan.vcodec == POLYKV_VALUES_TQ3_SCALED) return launch_dv<D, 1, 1>(pool, plan, Q, ws_ml, ws_o, out, s);
-        if (plan.vcodec == POLYKV_VALUES_INT8) return launch_dv<D, 2, 1>(pool, plan, Q, ws_ml, ws_o, out, s);
-        return launch_dv<D, 0, 1>(pool, plan, Q, ws_ml, ws_o, out, s);
-    }
-    if (plan.vcodec == POLYKV_VALUES_TQ3_SCALED) return launch_dv<D, 1, 0>(pool, plan, Q, ws_ml, ws_o, out, s);
-    if (plan.vcodec == POLYKV_VALUES_INT8) return launch_dv<D, 2, 0>(pool, plan, Q, ws_ml, ws_o, out, s);
-    return launch_dv<D, 0, 0>(pool, plan, Q, ws_ml, ws_o, out, s);
+    if (plan.kcodec == POLYKV_KEYS_Q8_TENSOR) return launch_dk<D, 1>(pool, plan, Q, ws_ml, ws_o, out, s);
+    return launch_dk<D, 0>(pool, plan, Q, ws_ml, ws_o, out, s);
 }
 
 hipError_t launch_attend_matrix(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,

@@ -61,7 +61,8 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
     // lie before tok_begin were encoded earlier and are carried over; tokens from tok_end on are padding
     // and are encoded as zeros.
     using LY = Layout<D, VC, KC>;
-    constexpr bool VS = VC == 1, V8 = VC == 2;
+    constexpr int VB = vc_bits(VC);  // bits per value code
+    constexpr bool V8 = VB == 8, VS = vc_has_scale(VC) && !V8;
     constexpr int EPT = D / 8;
     constexpr int KBYTES = LY::vcodes_off;  // key codes (+ key scales) (+ value scales)
     constexpr int VST = kTile + 4;          // bytes per rotated coordinate in the code staging area
@@ -101,6 +102,27 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
                 *reinterpret_cast<uint32_t*>(dst + 8) = w.y;
                 *reinterpret_cast<uint32_t*>(dst + 16) = w.z;
                 *reinterpret_cast<uint32_t*>(dst + 24) = w.w;
+            }
+        } else if (VB == 4 || VB == 2) {
+            if (tid < LY::NT * 64) {  // work item (q, lane): groups 4q .. 4q+3
+                const int q = tid >> 6;
+#pragma unroll
+                for (int gi = 0; gi < 4; ++gi) {
+                    const int G = 4 * q + gi;
+                    uint32_t lo, hi;
+                    if (VB == 4) {
+                        const uint32_t w = reinterpret_cast<const uint32_t*>(rec + LY::vcodes_off)[lane * (D / 16) + G];
+                        lo = w & 0x0F0F0F0Fu;
+                        hi = (w >> 4) & 0x0F0F0F0Fu;
+                    } else {
+                        const uint32_t w = reinterpret_cast<const uint32_t*>(rec + LY::vcodes_off)[lane * (D / 32) + (G >> 1)];
+                        lo = (w >> (4 * (G & 1))) & 0x03030303u;
+                        hi = (w >> (4 * (G & 1) + 2)) & 0x03030303u;
+                    }
+                    uint8_t* dst = vstage + vcode_coord(G, lane) * VST + vcode_token(G, lane, 0);
+                    *reinterpret_cast<uint32_t*>(dst) = lo;
+                    *reinterpret_cast<uint32_t*>(dst + 8) = hi;
+                }
             }
         } else if (tid < LY::NT * 64) {  // NT <= 4: one wave per triplet
             const int q = tid >> 6;
@@ -216,6 +238,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         // n the number of positive thresholds below |v_rot|.
         float t1 = POLYKV_T1 * sqrt_d<D>(), t2 = POLYKV_T2 * sqrt_d<D>(), t3 = POLYKV_T3 * sqrt_d<D>();
         float zref = 0.0f;  // what "positive" is measured against
+        float tscale = sqrt_d<D>();  // factor on the thresholds (2- and 4-bit codes)
         if (VS) {
             // |v|^2 over the 8 lanes of the token (the signs do not matter); every lane gets the same sum
             float ss = 0.0f;
@@ -231,11 +254,13 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
             t1 = t1 * g;
             t2 = t2 * g;
             t3 = t3 * g;
-            // a scale of zero stores the zero vector, code 3 everywhere: nothing counts as positive and no
-            // magnitude exceeds a threshold
+            tscale = tscale * g;
+            // a scale of zero stores the zero vector, the code of zero everywhere: nothing counts as positive
+            // and no magnitude exceeds a threshold
             if (!(g > 0.0f)) {
                 zref = INFINITY;
                 t1 = t2 = t3 = INFINITY;
+                tscale = INFINITY;
             }
             if (c == 0 && !old_token) reinterpret_cast<__half*>(kimg + LY::vscales_off)[t] = g16;
         }
@@ -243,8 +268,24 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         wht_cross_chunks<EPT>(y, lane);
         wht_inlane<EPT>(y);
         uint8_t* dst = vstage + e0 * VST + t;
+        if (VB != 3) {
+            // 2 and 4 bits: sign and magnitude, magnitude = number of positive thresholds below |v_rot|
+            constexpr int NTH = (1 << (VB - 1)) - 1;
+            float th[NTH];
 #pragma unroll
-        for (int i = 0; i < EPT; ++i) {
+            for (int k = 0; k < NTH; ++k) th[k] = threshold_mag(VB, k) * tscale;  // inf * t = inf for a zero scale
+#pragma unroll
+            for (int i = 0; i < EPT; ++i) {
+                const float ay = fabsf(y[i]);
+                int n = 0;
+#pragma unroll
+                for (int k = 0; k < NTH; ++k) n += ay > th[k];
+                const int code = (y[i] > zref ? 0 : (1 << (VB - 1))) | n;
+                if (!old_token) dst[i * VST] = (uint8_t)code;
+            }
+        }
+#pragma unroll
+        for (int i = 0; VB == 3 && i < EPT; ++i) {
             // Four compares into scalar masks, then a select and an add-with-carry chain.  On this target a
             // vector instruction may read a scalar mask only two or more instructions after the compare
             // that wrote it; the order below keeps that distance without padding.
@@ -277,6 +318,27 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
             w.z = *reinterpret_cast<const uint32_t*>(src + 16);
             w.w = *reinterpret_cast<const uint32_t*>(src + 24);
             *reinterpret_cast<uint4*>(rec + LY::vcodes_off + g * 1024 + lane * 16) = w;
+        }
+    } else if (VB == 4 || VB == 2) {
+        // ---- 4 / 2 bits: work item (q, lane) packs groups 4q .. 4q+3 into four / two dwords
+        if (tid < LY::NT * 64) {
+            const int q = tid >> 6;
+            uint32_t lo[4], hi[4];
+#pragma unroll
+            for (int gi = 0; gi < 4; ++gi) {
+                const int G = 4 * q + gi;
+                const uint8_t* src = vstage + vcode_coord(G, lane) * VST + vcode_token(G, lane, 0);
+                lo[gi] = *reinterpret_cast<const uint32_t*>(src);
+                hi[gi] = *reinterpret_cast<const uint32_t*>(src + 8);
+            }
+            if (VB == 4) {
+                uint4 w = make_uint4(lo[0] | (hi[0] << 4), lo[1] | (hi[1] << 4), lo[2] | (hi[2] << 4), lo[3] | (hi[3] << 4));
+                *reinterpret_cast<uint4*>(rec + LY::vcodes_off + lane * (D / 4) + 16 * q) = w;
+            } else {
+                uint2 w = make_uint2(lo[0] | (hi[0] << 2) | (lo[1] << 4) | (hi[1] << 6),
+                                     lo[2] | (hi[2] << 2) | (lo[3] << 4) | (hi[3] << 6));
+                *reinterpret_cast<uint2*>(rec + LY::vcodes_off + lane * (D / 8) + 8 * q) = w;
+            }
         }
     } else if (tid < LY::NT * 64) {
         // ---- bit-pack the value codes: one lane triplet (three dwords, four coordinate groups) per thread
@@ -374,7 +436,8 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
     using LY = Layout<D, VC, KC>;
     constexpr int EPT = D / 8;
     constexpr int KBYTES = LY::vcodes_off;
-    constexpr bool VS = LY::has_vscales, V8 = VC == 2;
+    constexpr int VB = vc_bits(VC);
+    constexpr bool VS = LY::has_vscales, V8 = VB == 8;
     constexpr int CS = D + 8;  // halves per token row of the centroid staging area (16-byte aligned rows)
     constexpr int VST = kTile + 4;  // int8 values: bytes per coordinate of the code staging area
     __shared__ __align__(16) uint8_t kimg[KBYTES];
@@ -409,19 +472,31 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
         // work item (half, q, lane): two of the four coordinate groups of one lane triplet
         const int half = x / (LY::NT * 64), ql = x - half * (LY::NT * 64);
         const int q = ql >> 6;
-        const uint32_t* w = reinterpret_cast<const uint32_t*>(rec + LY::vcodes_off + q * 768 + lane * 12);
-        const uint32_t w0 = w[0], w1 = w[1], w2 = w[2];
+        uint32_t w0 = 0, w1 = 0, w2 = 0;
+        if (VB == 3) {
+            const uint32_t* w = reinterpret_cast<const uint32_t*>(rec + LY::vcodes_off + q * 768 + lane * 12);
+            w0 = w[0], w1 = w[1], w2 = w[2];
+        }
 #pragma unroll
         for (int gg = 0; gg < 2; ++gg) {
-            uint32_t sel_a, sel_b;
-            if (half == 0)
-                vcode_selectors(w0, w1, w2, gg, sel_a, sel_b);
-            else
-                vcode_selectors(w0, w1, w2, 2 + gg, sel_a, sel_b);
-            Half2Bits c01, c23, c45, c67;
-            lookup4(sel_a, c01.u, c23.u);
-            lookup4(sel_b, c45.u, c67.u);
             const int G = 4 * q + 2 * half + gg;
+            Half2Bits c01, c23, c45, c67;
+            if (VB == 3) {
+                uint32_t sel_a, sel_b;
+                if (half == 0)
+                    vcode_selectors(w0, w1, w2, gg, sel_a, sel_b);
+                else
+                    vcode_selectors(w0, w1, w2, 2 + gg, sel_a, sel_b);
+                lookup4(sel_a, c01.u, c23.u);
+                lookup4(sel_b, c45.u, c67.u);
+            } else {
+                uint32_t o[4];
+                if (VB == 4)
+                    group8_b4(reinterpret_cast<const uint32_t*>(rec + LY::vcodes_off)[lane * (D / 16) + G], o);
+                else
+                    group8_b2(reinterpret_cast<const uint32_t*>(rec + LY::vcodes_off)[lane * (D / 32) + (G >> 1)], G & 1, o);
+                c01.u = o[0], c23.u = o[1], c45.u = o[2], c67.u = o[3];
+            }
             _Float16* col = cent + vcode_token(G, lane, 0) * CS + vcode_coord(G, lane);  // codes e: rows +0..3, +8..11
             col[0 * CS] = c01.h[0];
             col[1 * CS] = c01.h[1];
@@ -469,7 +544,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
         }
     } else if (V_out != nullptr) {
         // the centroid scale, 1/sqrt(D) and the entry sign of the cross-lane stages ride on the conversion
-        const float f = codec_entry_sign(lane) * (kInvCentroidScale * inv_sqrt_d<D>()) * vscale;
+        const float f = codec_entry_sign(lane) * (inv_centroid_scale<VB>() * inv_sqrt_d<D>()) * vscale;
         float y[EPT];
 #pragma unroll
         for (int i = 0; i < EPT / 8; ++i) {
@@ -499,7 +574,8 @@ __global__ __launch_bounds__(256) void export_kernel(const uint8_t* __restrict__
                                                      __half* __restrict__ v_scales, int T, int tiles,
                                                      const uint32_t* __restrict__ kmax, int H) {
     using LY = Layout<D, VC, KC>;
-    constexpr bool VS = LY::has_vscales, V8 = VC == 2;
+    constexpr int VB = vc_bits(VC);
+    constexpr bool VS = LY::has_vscales, V8 = VB == 8;
     constexpr int EPT = D / 8;
     __shared__ __align__(16) uint8_t img[LY::tile_bytes];
     const int tile = blockIdx.x, unit = blockIdx.y;
@@ -527,6 +603,23 @@ __global__ __launch_bounds__(256) void export_kernel(const uint8_t* __restrict__
 #pragma unroll
             for (int i = 0; i < EPT; ++i)
                 v_packed[vec * D + e0 + i] = (uint8_t)((int)img[LY::vcodes_off + v8_byte_offset(t, e0 + i)] - 128);
+        }
+    } else if (VB != 3) {
+        if (v_packed != nullptr) {  // canonical codes (ascending over all centroids), VB bits each, LSB first
+            const uint32_t* vreg = reinterpret_cast<const uint32_t*>(img + LY::vcodes_off);
+            constexpr int half = 1 << (VB - 1), PER = 8 / VB;
+            uint8_t* dst = v_packed + vec * (VB * D / 8) + VB * e0 / 8;
+#pragma unroll
+            for (int b = 0; b < EPT / PER; ++b) {
+                uint32_t byte = 0;
+#pragma unroll
+                for (int i = 0; i < PER; ++i) {
+                    const int sm = VB == 4 ? vcode_extract_b4(vreg, D, t, e0 + b * PER + i) : vcode_extract_b2(vreg, D, t, e0 + b * PER + i);
+                    const int code = (sm & half) ? half - 1 - (sm & (half - 1)) : half + sm;
+                    byte |= (uint32_t)code << (VB * i);
+                }
+                dst[b] = (uint8_t)byte;
+            }
         }
     } else if (v_packed != nullptr) {
         const uint32_t* vreg = reinterpret_cast<const uint32_t*>(img + LY::vcodes_off);
@@ -596,9 +689,13 @@ template <typename F> static void for_pool_shape(const polykv_pool* p, F&& f) {
     };
     auto with_d = [&](auto d) {
         switch (p->value_codec) {
-            case POLYKV_VALUES_TQ3_SCALED: with_dv(d, integral_constant<int, POLYKV_VALUES_TQ3_SCALED>{}); break;
-            case POLYKV_VALUES_INT8: with_dv(d, integral_constant<int, POLYKV_VALUES_INT8>{}); break;
-            default: with_dv(d, integral_constant<int, POLYKV_VALUES_TQ3>{}); break;
+            case 1: with_dv(d, integral_constant<int, 1>{}); break;
+            case 2: with_dv(d, integral_constant<int, 2>{}); break;
+            case 3: with_dv(d, integral_constant<int, 3>{}); break;
+            case 4: with_dv(d, integral_constant<int, 4>{}); break;
+            case 5: with_dv(d, integral_constant<int, 5>{}); break;
+            case 6: with_dv(d, integral_constant<int, 6>{}); break;
+            default: with_dv(d, integral_constant<int, 0>{}); break;
         }
     };
     if (p->head_dim == 128)

@@ -44,19 +44,36 @@ namespace polykv {
 
 constexpr int kTile = 32;  // tokens per tile record
 
-// VC: value codec, numbered as POLYKV_VALUES_* in the ABI header (0 the paper's 3-bit codes, 1 the same
-// with a per-vector scale, 2 int8 codes with a per-vector scale).
+// Value codecs, numbered as POLYKV_VALUES_* in the ABI header: 0 the paper's 3-bit codes, 1 the same with a
+// per-vector scale, 2 int8 codes with a per-vector scale, 3 / 4 two-bit codes without / with the scale,
+// 5 / 6 four-bit codes without / with it.
+constexpr int vc_bits(int vc) { return vc == 2 ? 8 : (vc == 3 || vc == 4) ? 2 : (vc == 5 || vc == 6) ? 4 : 3; }
+constexpr bool vc_has_scale(int vc) { return vc == 1 || vc == 2 || vc == 4 || vc == 6; }
+constexpr int kNumValueCodecs = 7;
+
+// The 2-bit and 4-bit codes are stored as sign and magnitude: top bit set = negative, the other bits = the
+// number of positive thresholds below |v_rot| (the canonical code, ascending over all centroids, is
+// half - 1 - magnitude for negative and half + magnitude for positive values, half = 2^(bits-1)).  Per lane
+// and coordinate group G (as for the 3-bit codes: coordinate 32*(G/2) + m, code e = token
+// 16*(G%2) + 8*(e/4) + 4h + e%4):
+//   4 bits   one dword per G, the lane's D/16 dwords contiguous at byte lane*(D/4) + 4G: code e < 4 in the low
+//            nibble of byte e, code e >= 4 in the high nibble of byte e - 4;
+//   2 bits   half a dword per G, the lane's D/32 dwords contiguous at byte lane*(D/8) + 4*(G/2): code e of
+//            group G at bit 8*(e%4) + 2*(2*(G%2) + e/4).
+// VC: value codec.
 // KC: key codec, POLYKV_KEYS_* (0 q8_0 blocks of 32 with a scale each, 1 one scale per layer tensor).
 template <int D, int VC = 0, int KC = 0> struct Layout {
     static constexpr int NB = D / 32;             // q8_0 blocks per vector
     static constexpr int NT = D / 64;             // value-code triplets per lane
-    static constexpr bool has_vscales = VC != 0;
+    static constexpr bool has_vscales = vc_has_scale(VC);
+    static constexpr int vbits = vc_bits(VC);
     static constexpr bool has_kscales = KC == 0;
     static constexpr int kcodes_off = 0;
     static constexpr int kscales_off = NB * 1024;                     // present only if has_kscales
     static constexpr int vscales_off = kscales_off + (has_kscales ? kTile * NB * 2 : 0);  // only if has_vscales
     static constexpr int vcodes_off = vscales_off + (has_vscales ? kTile * 2 : 0);
-    static constexpr int tile_bytes = vcodes_off + (VC == 2 ? NB * 1024 : NT * 768);
+    static constexpr int tile_bytes =
+        vcodes_off + (vbits == 8 ? NB * 1024 : vbits == 3 ? NT * 768 : vbits == 4 ? D * 16 : D * 8);
 };
 
 __host__ __device__ inline int tiles_of(int tokens) { return (tokens + kTile - 1) / kTile; }
@@ -186,6 +203,72 @@ __device__ __forceinline__ void lookup4(uint32_t sel, uint32_t& out01, uint32_t&
 __device__ __forceinline__ void codes4_to_half(uint32_t w, uint32_t& out01, uint32_t& out23) {
     out01 = __builtin_amdgcn_perm(0x64646464u, w, 0x04010400u);
     out23 = __builtin_amdgcn_perm(0x64646464u, w, 0x04030402u);
+}
+
+// ---- 2-bit and 4-bit codebooks (Lloyd-Max for N(0,1), positive half; rounded to fp32) -------------------
+__device__ __host__ inline float centroid_mag(int bits, int i) {
+    constexpr float c2[2] = {0.452780038f, 1.51041758f};
+    constexpr float c3[4] = {POLYKV_C0, POLYKV_C1, POLYKV_C2, POLYKV_C3};
+    constexpr float c4[8] = {0.128395036f, 0.388048291f, 0.656759143f, 0.942340434f,
+                             1.25623119f,  1.6180464f,   2.06901717f,  2.73258948f};
+    return bits == 2 ? c2[i] : bits == 4 ? c4[i] : c3[i];
+}
+__device__ __host__ inline float threshold_mag(int bits, int i) {  // the i-th positive threshold
+    constexpr float t2[1] = {0.981598794f};
+    constexpr float t3[3] = {POLYKV_T1, POLYKV_T2, POLYKV_T3};
+    constexpr float t4[7] = {0.258221656f, 0.522403717f, 0.799549758f, 1.09928584f, 1.4371388f, 1.84353185f, 2.40080333f};
+    return bits == 2 ? t2[i] : bits == 4 ? t4[i] : t3[i];
+}
+// Centroid of a sign-magnitude code (2 or 4 bits).
+__device__ __forceinline__ float centroid_signmag(int bits, int code) {
+    const int half = 1 << (bits - 1);
+    const float c = centroid_mag(bits, code & (half - 1));
+    return (code & half) ? -c : c;
+}
+// As for the 3-bit table: magnitudes times a factor searched in [1, 2) so that they land close to fp16 values
+// (4 bits: 1.3338515, within 9.3e-5; 2 bits: 1.9810335, within 2.7e-7); the inverse goes on the output row.
+template <int BITS> __device__ __host__ constexpr float inv_centroid_scale() {
+    return BITS == 4 ? 0.7497086444780398f : BITS == 2 ? 0.5047870215218471f : kInvCentroidScale;
+}
+// fp16 patterns of the scaled magnitudes, byte planes.  4 bits: 317B 3824 3B02 3D07 3EB4 4051 4185 434A.
+constexpr uint32_t kTab4LoA = 0x0702247Bu, kTab4LoB = 0x4A8551B4u, kTab4HiA = 0x3D3B3831u, kTab4HiB = 0x4341403Eu;
+// 2 bits: 3B2D 41FC.
+constexpr uint32_t kTab2Lo = 0x0000FC2Du, kTab2Hi = 0x0000413Bu;
+
+// Four 4-bit sign-magnitude codes: magnitudes in the bytes of `sel` (0..7), `sign` = 0x80 in the bytes of the
+// negative ones -> four fp16 centroids.
+__device__ __forceinline__ void lookup4_b4(uint32_t sel, uint32_t sign, uint32_t& out01, uint32_t& out23) {
+    const uint32_t lo = __builtin_amdgcn_perm(kTab4LoB, kTab4LoA, sel);
+    const uint32_t hi = __builtin_amdgcn_perm(kTab4HiB, kTab4HiA, sel) | sign;
+    out01 = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
+    out23 = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
+}
+// The same for 2-bit codes: magnitudes 0..1 in the bytes of `sel`.
+__device__ __forceinline__ void lookup4_b2(uint32_t sel, uint32_t sign, uint32_t& out01, uint32_t& out23) {
+    const uint32_t lo = __builtin_amdgcn_perm(0u, kTab2Lo, sel);
+    const uint32_t hi = __builtin_amdgcn_perm(0u, kTab2Hi, sel) | sign;
+    out01 = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
+    out23 = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
+}
+// Eight codes of coordinate group G from the lane's dword `w` -> eight fp16 centroids (four dwords, codes e
+// in order).  4 bits: w is the group's dword; 2 bits: w is the dword of the pair G/2 and `odd` = G % 2.
+__device__ __forceinline__ void group8_b4(uint32_t w, uint32_t (&out)[4]) {
+    lookup4_b4(w & 0x07070707u, (w << 4) & 0x80808080u, out[0], out[1]);
+    lookup4_b4((w >> 4) & 0x07070707u, w & 0x80808080u, out[2], out[3]);
+}
+__device__ __forceinline__ void group8_b2(uint32_t w, int odd, uint32_t (&out)[4]) {
+    const uint32_t v = odd ? w >> 4 : w;   // slots 2*odd and 2*odd + 1 now sit at bits 0..1 and 2..3 of every byte
+    lookup4_b2(v & 0x01010101u, (v << 6) & 0x80808080u, out[0], out[1]);
+    lookup4_b2((v >> 2) & 0x01010101u, (v << 4) & 0x80808080u, out[2], out[3]);
+}
+// The sign-magnitude code of (token t of the tile, rotated coordinate dv) from the V-code region (dword view).
+__device__ __forceinline__ int vcode_extract_b4(const uint32_t* v, int D, int t, int dv) {
+    const int G = 2 * (dv >> 5) + (t >> 4), e = (((t >> 3) & 1) << 2) | (t & 3), lane = 32 * ((t >> 2) & 1) + (dv & 31);
+    return (v[lane * (D / 16) + G] >> (8 * (e & 3) + 4 * (e >> 2))) & 15;
+}
+__device__ __forceinline__ int vcode_extract_b2(const uint32_t* v, int D, int t, int dv) {
+    const int G = 2 * (dv >> 5) + (t >> 4), e = (((t >> 3) & 1) << 2) | (t & 3), lane = 32 * ((t >> 2) & 1) + (dv & 31);
+    return (v[lane * (D / 32) + (G >> 1)] >> (8 * (e & 3) + 2 * (2 * (G & 1) + (e >> 2)))) & 3;
 }
 
 // Value-code selectors of one lane's triplet (w0, w1, w2): group gi (0..3) -> the codes of its eight

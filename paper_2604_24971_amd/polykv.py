@@ -16,6 +16,8 @@ F16, F32, BF16 = 0, 1, 2
 _DTYPES = {torch.float16: F16, torch.float32: F32, torch.bfloat16: BF16}
 KERNEL_AUTO, KERNEL_VECTOR, KERNEL_MATRIX = 0, 1, 2
 VALUES_TQ3, VALUES_TQ3_SCALED, VALUES_INT8 = 0, 1, 2
+VALUES_TQ2, VALUES_TQ2_SCALED, VALUES_TQ4, VALUES_TQ4_SCALED = 3, 4, 5, 6
+VALUE_BITS = {0: 3, 1: 3, 2: 8, 3: 2, 4: 2, 5: 4, 6: 4}
 KEYS_Q8_BLOCK32, KEYS_Q8_TENSOR = 0, 1
 MAX_TAIL_AGENTS = 64
 
@@ -82,6 +84,8 @@ def _load():
     lib.pool_attend.restype = ip
     lib.polykv_codebook.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_float)]
     lib.polykv_codebook.restype = None
+    lib.polykv_codebook_bits.argtypes = [ip, C.POINTER(C.c_float), C.POINTER(C.c_float)]
+    lib.polykv_codebook_bits.restype = ip
     lib.polykv_time_next_kernel.argtypes = [vp, vp]
     lib.polykv_time_next_kernel.restype = ip
     lib.polykv_last_error.argtypes = []
@@ -97,10 +101,10 @@ def _check(rc: int):
         raise PolyKVError(rc, lib.polykv_last_error().decode())
 
 
-def codebook():
-    c = (C.c_float * 8)()
-    t = (C.c_float * 7)()
-    lib.polykv_codebook(c, t)
+def codebook(bits: int = 3):
+    c = (C.c_float * (1 << bits))()
+    t = (C.c_float * ((1 << bits) - 1))()
+    _check(lib.polykv_codebook_bits(bits, c, t))
     return list(c), list(t)
 
 
@@ -249,7 +253,7 @@ class Pool:
         if self.value_codec == VALUES_INT8:      # the int8 value codes themselves
             vp = torch.empty(n + (self.head_dim,), dtype=torch.int8, device=self.device)
         else:
-            vp = torch.empty(n + (3 * self.head_dim // 8,), dtype=torch.uint8, device=self.device)
+            vp = torch.empty(n + (VALUE_BITS[self.value_codec] * self.head_dim // 8,), dtype=torch.uint8, device=self.device)
         _check(lib.pool_export(self._h, C.c_void_p(kc.data_ptr()), C.c_void_p(ks.data_ptr()),
                                C.c_void_p(vp.data_ptr()), _stream_ptr(stream)))
         return kc, ks, vp

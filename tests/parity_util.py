@@ -31,9 +31,16 @@ def dev(x, bf16=False):
     return t.to(torch.bfloat16) if bf16 else t
 
 
-def gpu_pool(K, V, scaled_values=False, int8_values=False, bf16=False, sign_seed=0, key_per_tensor=False):
+def value_codec_id(scaled_values=False, int8_values=False, value_bits=3):
+    if int8_values:
+        return pk.VALUES_INT8
+    return {(3, False): pk.VALUES_TQ3, (3, True): pk.VALUES_TQ3_SCALED, (2, False): pk.VALUES_TQ2,
+            (2, True): pk.VALUES_TQ2_SCALED, (4, False): pk.VALUES_TQ4, (4, True): pk.VALUES_TQ4_SCALED}[(value_bits, scaled_values)]
+
+
+def gpu_pool(K, V, scaled_values=False, int8_values=False, bf16=False, sign_seed=0, key_per_tensor=False, value_bits=3):
     L, H, T, d = K.shape
-    codec = pk.VALUES_INT8 if int8_values else pk.VALUES_TQ3_SCALED if scaled_values else pk.VALUES_TQ3
+    codec = value_codec_id(scaled_values, int8_values, value_bits)
     pool = pk.Pool(L, H, d, T, value_codec=codec, sign_seed=sign_seed,
                    key_codec=pk.KEYS_Q8_TENSOR if key_per_tensor else pk.KEYS_Q8_BLOCK32).bind()
     pool.storage.fill_(0xA5)            # stale bytes must never leak into results
@@ -60,8 +67,8 @@ def settle_value_scales(gs, ref):
     ref["v_scales"] = g_ref.copy()
     ref["v_scales"][diff] = alt
     ref["v_idx"] = ref["v_idx"].copy()
-    ref["v_idx"][diff] = O.v_quantize_scaled(ref["v_rot"][diff], alt)
-    ref["v_packed"] = O.v_pack(ref["v_idx"])
+    ref["v_idx"][diff] = O.v_quantize_scaled(ref["v_rot"][diff], alt, ref.get("v_bits", 3))
+    ref["v_packed"] = O.v_pack(ref["v_idx"], ref.get("v_bits", 3))
     return int(diff.sum())
 
 
@@ -96,10 +103,11 @@ def compare_codes(pool, ref):
         assert np.all(frac[k_diff] <= CODE_WINDOW), "key code differs away from a rounding tie"
         assert np.all(np.abs(kc.astype(np.int32) - ref["k_codes"])[k_diff] == 1)
     # value codes
-    v_idx = O.v_unpack(vp, d)
+    bits = ref.get("v_bits", 3)
+    v_idx = O.v_unpack(vp, d, bits)
     v_diff = v_idx != ref["v_idx"]
     if v_diff.any():
-        _, t = O.codebook()
+        _, t = O.codebook(bits)
         if scaled:   # thresholds and window in units of the vector's scale
             g = np.broadcast_to(ref["v_scales"].astype(np.float64)[..., None], v_idx.shape)[v_diff]
             assert np.all(g > 0)

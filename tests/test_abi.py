@@ -26,16 +26,22 @@ def test_library_exports_every_declared_function():
     assert {"pool_create", "pool_bytes", "pool_bind", "pool_encode", "pool_decode", "pool_export",
             "pool_attend_workspace", "pool_attend", "pool_destroy", "polykv_codebook",
             "polykv_last_error", "pool_append", "pool_length", "pool_decode_layers", "polykv_time_next_kernel",
-            "pool_create_codec", "pool_export_value_scales", "pool_encode_dtype", "pool_append_dtype", "pool_set_sign_seed", "pool_create_codecs"} <= set(names)
+            "pool_create_codec", "pool_export_value_scales", "pool_encode_dtype", "pool_append_dtype", "pool_set_sign_seed", "pool_create_codecs", "polykv_codebook_bits"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
 
 def test_codebook_literals_equal_oracle_codebook_in_fp32():
-    c, t = pk.codebook()
-    oc, ot = O.codebook()
-    np.testing.assert_array_equal(np.array(c, np.float32), oc.astype(np.float32))
-    np.testing.assert_array_equal(np.array(t, np.float32), ot.astype(np.float32))
+    c8, t7 = (C.c_float * 8)(), (C.c_float * 7)()
+    lib.polykv_codebook(c8, t7)
+    for bits in (2, 3, 4):
+        c, t = pk.codebook(bits)
+        oc, ot = O.codebook(bits)
+        np.testing.assert_array_equal(np.array(c, np.float32), oc.astype(np.float32))
+        np.testing.assert_array_equal(np.array(t, np.float32), ot.astype(np.float32))
+        if bits == 3:
+            assert list(c8) == c and list(t7) == t
+    assert lib.polykv_codebook_bits(5, None, None) == pk.EINVAL
 
 
 def _create(L, H, d, T):
@@ -68,6 +74,12 @@ def test_create_validation_and_byte_counts():
 def test_value_codec_choice_byte_counts_and_errors():
     h = C.c_void_p()
     assert lib.pool_create_codec(1, 1, 64, 10, 7, C.byref(h)) == pk.EINVAL and not h.value
+    for codec, bits, scaled in [(pk.VALUES_TQ2, 2, False), (pk.VALUES_TQ2_SCALED, 2, True), (pk.VALUES_TQ4, 4, False),
+                                (pk.VALUES_TQ4_SCALED, 4, True)]:
+        for (L, H, d, T) in [(32, 8, 128, 4096), (1, 4, 64, 640), (2, 2, 256, 64)]:
+            assert lib.pool_create_codec(L, H, d, T, codec, C.byref(h)) == pk.OK
+            assert lib.pool_bytes(h) == O.stored_bytes(L, H, T, d, scaled_values=scaled, value_bits=bits)["packed"]
+            lib.pool_destroy(h)
     for (L, H, d, T) in [(32, 8, 128, 4096), (1, 4, 64, 640)]:
         assert lib.pool_create_codec(L, H, d, T, pk.VALUES_TQ3_SCALED, C.byref(h)) == pk.OK
         assert lib.pool_bytes(h) == O.stored_bytes(L, H, T, d, scaled_values=True)["packed"]

@@ -26,16 +26,17 @@ def _pu():
 class Case:
     """One encoded pool on both sides."""
 
-    def __init__(self, cfg, K=None, V=None, scaled_values=False, int8_values=False, sign_seed=0, key_per_tensor=False):
+    def __init__(self, cfg, K=None, V=None, scaled_values=False, int8_values=False, sign_seed=0, key_per_tensor=False,
+                 value_bits=3):
         pu = _pu()
         self.cfg = cfg
         if K is None:
             K, V = W.kv_pool(cfg)
         self.K, self.V = K, V
         self.ref = O.pool_encode(K, V, scaled_values=scaled_values, int8_values=int8_values, sign_seed=sign_seed,
-                                 key_per_tensor=key_per_tensor)
+                                 key_per_tensor=key_per_tensor, value_bits=value_bits)
         self.pool = pu.gpu_pool(K, V, scaled_values=scaled_values, int8_values=int8_values, sign_seed=sign_seed,
-                                key_per_tensor=key_per_tensor)
+                                key_per_tensor=key_per_tensor, value_bits=value_bits)
         self.dirty, self.k_mis, self.v_mis = pu.compare_codes(self.pool, self.ref)
         self._dec = None
 
