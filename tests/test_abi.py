@@ -193,3 +193,20 @@ def test_python_binding_rejects_wrong_tensors_before_any_launch():
     pool.close()
     with pytest.raises(pk.PolyKVError):
         pk.Pool(1, 2, 80, 50)
+
+
+def test_header_is_valid_c99(tmp_path):
+    # the boundary is a C ABI: the header must compile as plain C, on its own
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_polykv.c"
+    src.write_text('#include "polykv.h"\n'
+                   "int use(void) { polykv_attend_params p = {0}; polykv_pool* h = 0;\n"
+                   "  return pool_create_codecs(1, 1, 64, 1, POLYKV_KEYS_Q8_BLOCK32, POLYKV_VALUES_TQ3, &h) + p.agents\n"
+                   "         + (int)sizeof(polykv_status) + POLYKV_BF16 + POLYKV_KERNEL_AUTO; }\n")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                        "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
