@@ -267,6 +267,10 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         if (signs.on) flip_signs<EPT>(y, sign_word(signs, e0 >> 5) >> (e0 & 31));  // rotation H.D: D first
         wht_cross_chunks<EPT>(y, lane);
         wht_inlane<EPT>(y);
+        // the thresholds are operands of every element's compare block: pin them to registers once (as
+        // constants the compiler would load them again in front of each block)
+        asm volatile("" : "+v"(t1), "+v"(t2), "+v"(t3), "+v"(zref), "+v"(tscale));
+        uint8_t codes[EPT];
         uint8_t* dst = vstage + e0 * VST + t;
         if (VB != 3) {
             // 2 and 4 bits: sign and magnitude, magnitude = number of positive thresholds below |v_rot|
@@ -276,12 +280,43 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
             for (int k = 0; k < NTH; ++k) th[k] = threshold_mag(VB, k) * tscale;  // inf * t = inf for a zero scale
 #pragma unroll
             for (int i = 0; i < EPT; ++i) {
-                const float ay = fabsf(y[i]);
-                int n = 0;
+                int code;
+                if constexpr (VB == 4) {
+                    // eight compares into scalar masks first, then a select and an add-with-carry chain: as in
+                    // the 3-bit quantizer below, every mask is read two or more instructions after its compare
+                    int n, m;
+                    unsigned long long sp, s1, s2, s3, s4, s5, s6, s7;
+                    asm("v_cmp_lt_f32_e64 %2, %18, %10\n\t"
+                        "v_cmp_gt_f32_e64 %3, |%10|, %11\n\t"
+                        "v_cmp_gt_f32_e64 %4, |%10|, %12\n\t"
+                        "v_cmp_gt_f32_e64 %5, |%10|, %13\n\t"
+                        "v_cmp_gt_f32_e64 %6, |%10|, %14\n\t"
+                        "v_cmp_gt_f32_e64 %7, |%10|, %15\n\t"
+                        "v_cmp_gt_f32_e64 %8, |%10|, %16\n\t"
+                        "v_cmp_gt_f32_e64 %9, |%10|, %17\n\t"
+                        "v_cndmask_b32_e64 %1, 8, 0, %2\n\t"
+                        "v_addc_co_u32_e64 %0, vcc, 0, 0, %3\n\t"
+                        "v_addc_co_u32_e64 %0, vcc, 0, %0, %4\n\t"
+                        "v_addc_co_u32_e64 %0, vcc, 0, %0, %5\n\t"
+                        "v_addc_co_u32_e64 %0, vcc, 0, %0, %6\n\t"
+                        "v_addc_co_u32_e64 %0, vcc, 0, %0, %7\n\t"
+                        "v_addc_co_u32_e64 %0, vcc, 0, %0, %8\n\t"
+                        "v_addc_co_u32_e64 %0, vcc, 0, %0, %9\n\t"
+                        "v_or_b32_e32 %0, %0, %1"
+                        : "=&v"(n), "=&v"(m), "=&s"(sp), "=&s"(s1), "=&s"(s2), "=&s"(s3), "=&s"(s4), "=&s"(s5), "=&s"(s6),
+                          "=&s"(s7)
+                        : "v"(y[i]), "v"(th[0]), "v"(th[1]), "v"(th[2]), "v"(th[3]), "v"(th[4]), "v"(th[5]), "v"(th[6]),
+                          "v"(zref)
+                        : "vcc");
+                    code = n;
+                } else {
+                    const float ay = fabsf(y[i]);
+                    int n = 0;
 #pragma unroll
-                for (int k = 0; k < NTH; ++k) n += ay > th[k];
-                const int code = (y[i] > zref ? 0 : (1 << (VB - 1))) | n;
-                if (!old_token) dst[i * VST] = (uint8_t)code;
+                    for (int k = 0; k < NTH; ++k) n += ay > th[k];
+                    code = (y[i] > zref ? 0 : (1 << (VB - 1))) | n;
+                }
+                codes[i] = (uint8_t)code;
             }
         }
 #pragma unroll
@@ -303,7 +338,11 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
                 : "=&v"(n), "=&v"(m), "=&s"(sp), "=&s"(s1), "=&s"(s2), "=&s"(s3)
                 : "v"(y[i]), "v"(t1), "v"(t2), "v"(t3), "v"(zref)
                 : "vcc");
-            if (!old_token) dst[i * VST] = (uint8_t)n;
+            codes[i] = (uint8_t)n;
+        }
+        if (!old_token) {
+#pragma unroll
+            for (int i = 0; i < EPT; ++i) dst[i * VST] = codes[i];
         }
     }
     __syncthreads();
