@@ -143,16 +143,23 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
 
     // ---- keys: block absmax -> fp16 scale -> codes with the stored scale
     {
-        float k[EPT];
+        // max|k| on the raw 16-bit patterns: magnitudes of fp16 (and of bfloat16) order like unsigned integers
+        typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+        union {
+            uint32_t u;
+            ushort2v v;
+        } mx;
+        mx.u = 0;
 #pragma unroll
         for (int i = 0; i < EPT / 2; ++i) {
-            const float2 f = pair16_to_float2(reinterpret_cast<const uint32_t*>(kraw)[i], BF);
-            k[2 * i] = f.x;
-            k[2 * i + 1] = f.y;
+            union {
+                uint32_t u;
+                ushort2v v;
+            } w;
+            w.u = reinterpret_cast<const uint32_t*>(kraw)[i] & 0x7FFF7FFFu;
+            mx.v = __builtin_elementwise_max(mx.v, w.v);
         }
-        float amax = 0.0f;
-#pragma unroll
-        for (int i = 0; i < EPT; i += 2) amax = fmaxf(fmaxf(fabsf(k[i]), fabsf(k[i + 1])), amax);
+        float amax = bits16_to_float((uint16_t)max(mx.u & 0xFFFFu, mx.u >> 16), BF);
         // a q8_0 block of 32 elements spans 32 / EPT lanes
         if (EPT <= 16) amax = fmaxf(amax, lane_xor<1>(amax));
         if (EPT == 8) amax = fmaxf(amax, lane_xor<2>(amax));
@@ -169,7 +176,18 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         uint32_t r[EPT];
 #pragma unroll
         for (int i = 0; i < EPT; ++i) {
-            const float q = k[i] * inv + kMagic;  // two roundings (contraction is off in this file)
+            // two roundings, product then sum (contraction is off in this file); for fp16 input the
+            // conversion rides on the multiply (one fma-mix instruction, the product rounded once)
+            const uint32_t pair = reinterpret_cast<const uint32_t*>(kraw)[i >> 1];
+            float prod;
+            if (BF) {
+                prod = __uint_as_float((i & 1) ? pair & 0xFFFF0000u : pair << 16) * inv;
+            } else {
+                Half2Bits hb;
+                hb.u = pair;
+                prod = __builtin_fmaf((float)hb.h[i & 1], inv, 0.0f);
+            }
+            const float q = prod + kMagic;
             r[i] = __float_as_uint(__builtin_amdgcn_fmed3f(q, kMagic - 128.0f, kMagic + 127.0f));
         }
 #pragma unroll
