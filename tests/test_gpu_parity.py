@@ -417,3 +417,29 @@ def test_append_in_chunks_equals_one_encode_of_the_concatenation(d, chunks):
     pool.encode(pu.dev(Kc), pu.dev(Vc))
     assert pool.length == cap
     pu.compare_codes(pool, O.pool_encode(Kc, Vc))
+
+
+# ------------------------------------------------------------------------ extreme shapes ---
+def test_one_long_head_and_very_many_short_units():
+    pu = _pu()
+    pk = _pk()
+    rng = np.random.default_rng(31)
+    # one KV head with 50,001 tokens (1,563 tiles, a ragged last one): many splits, long rows of partials
+    T, d = 50001, 64
+    K = (rng.standard_normal((1, 1, T, d)) * 0.5).astype(np.float16)
+    V = rng.standard_normal((1, 1, T, d)).astype(np.float16)
+    case = Case(W.PoolConfig(0, "long", 1, 1, 4, d, T, 3, 1), K, V)
+    pu.compare_decode(case.pool, case.ref, case.dirty)
+    Q = rng.standard_normal((1, 3, 1, 4, d)).astype(np.float16)
+    case.attend_check(Q)
+    case.attend_check(Q, splits=1)
+    case.attend_check(Q, splits=300)
+    # 4,000 (layer, KV head) units of 33 tokens: the unit index fills the grid's second dimension
+    L, H, T2 = 500, 8, 33
+    K2 = rng.standard_normal((L, H, T2, d)).astype(np.float16)
+    V2 = rng.standard_normal((L, H, T2, d)).astype(np.float16)
+    case2 = Case(W.PoolConfig(0, "wide", L, H, 8, d, T2, 1, 1), K2, V2)
+    pu.compare_decode(case2.pool, case2.ref, case2.dirty)
+    Q2 = rng.standard_normal((L, 1, 1, 8, d)).astype(np.float16)
+    case2.attend_check(Q2)
+    case2.attend_check(Q2[490:], layer_begin=490, layer_end=500, kernel=pk.KERNEL_VECTOR)
