@@ -91,13 +91,13 @@ def main():
                     "tensor, the key formula as the paper prints it (two passes over K at encode)")
     ap.add_argument("--bf16", action="store_true",
                     help="dense tensors (K, V, Q, decode output, tails) in bfloat16 instead of fp16: the dtype of the "
-                    "paper's Llama-3-8B cache; not the headline configuration, which BASELINE.json states in fp16")
+                    "paper's Llama-3-8B cache; the headline configuration is stated in fp16")
     ap.add_argument("--phases", default="eda", help="subset of e(ncode) d(ecode) a(ttend) to run per step; "
                     "anything but the default is for profiling one kernel and is marked partial")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the pool path shards by layer / KV head "
-              "with no exchange, see DESIGN.md", file=sys.stderr)
+              "with no exchange between GPUs", file=sys.stderr)
         sys.exit(2)
 
     import torch
