@@ -87,8 +87,10 @@ enum {
 enum { POLYKV_KEYS_Q8_BLOCK32 = 0, POLYKV_KEYS_Q8_TENSOR = 1 };
 
 /* Host descriptor for a pool of `layers` x `kv_heads` x `tokens` vectors of `head_dim` elements.
- * head_dim must be 64, 128 or 256; all other dimensions >= 1.  (SharedKVPool, section "PolyKV
- * Architecture".)  *out receives the handle; release it with pool_destroy. */
+ * head_dim must be 64, 128 or 256; all other dimensions >= 1, layers * kv_heads <= 65535, and the packed
+ * records of one KV head (pool_bytes / (layers * kv_heads)) at most 4 GiB, about 23 million tokens at
+ * head_dim 128; POLYKV_ESHAPE otherwise.  (SharedKVPool, section "PolyKV Architecture".)  *out receives the
+ * handle; release it with pool_destroy. */
 int pool_create(int layers, int kv_heads, int head_dim, int tokens, polykv_pool** out);
 /* The same with a choice of value codec (POLYKV_VALUES_*); pool_create uses POLYKV_VALUES_TQ3. */
 int pool_create_codec(int layers, int kv_heads, int head_dim, int tokens, int value_codec, polykv_pool** out);

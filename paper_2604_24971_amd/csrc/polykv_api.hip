@@ -205,6 +205,14 @@ int pool_create_codecs(int layers, int kv_heads, int head_dim, int tokens, int k
                   layers, kv_heads, tokens);
         return POLYKV_ESHAPE;
     }
+    const int tile_bytes = head_dim == 128  ? tile_bytes_of<128>(value_codec, key_codec)
+                           : head_dim == 64 ? tile_bytes_of<64>(value_codec, key_codec)
+                                            : tile_bytes_of<256>(value_codec, key_codec);
+    // the kernels address a tile within its KV head's records with 32-bit byte offsets
+    if (((long long)tokens + kTile - 1) / kTile * tile_bytes > 0xFFFFFFFFll) {
+        set_error("pool_create: tokens=%d: the records of one KV head would exceed 4 GiB", tokens);
+        return POLYKV_ESHAPE;
+    }
     polykv_pool* p = new (std::nothrow) polykv_pool();
     if (p == nullptr) {
         set_error("pool_create: out of host memory");
@@ -217,9 +225,7 @@ int pool_create_codecs(int layers, int kv_heads, int head_dim, int tokens, int k
     p->tiles = tiles_of(tokens);
     p->value_codec = value_codec;
     p->key_codec = key_codec;
-    p->tile_bytes = head_dim == 128  ? tile_bytes_of<128>(value_codec, key_codec)
-                    : head_dim == 64 ? tile_bytes_of<64>(value_codec, key_codec)
-                                     : tile_bytes_of<256>(value_codec, key_codec);
+    p->tile_bytes = tile_bytes;
     p->bytes = (size_t)layers * kv_heads * p->tiles * p->tile_bytes;
     p->kmax_off = 0;
     if (key_codec == POLYKV_KEYS_Q8_TENSOR) {  // the layers' max|k| behind the records, 256-byte aligned

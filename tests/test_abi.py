@@ -52,11 +52,14 @@ def _create(L, H, d, T):
 
 def test_create_validation_and_byte_counts():
     for bad in [(1, 1, 96, 10), (1, 1, 512, 10), (1, 1, 32, 10), (0, 1, 64, 10), (1, 0, 64, 10), (1, 1, 64, 0),
-                (1, 1, 64, -5), (70000, 1, 64, 10)]:
+                (1, 1, 64, -5), (70000, 1, 64, 10), (1, 1, 128, 24_000_000), (1, 1, 64, 2**31 - 1)]:
         rc, h = _create(*bad)
         assert rc == pk.ESHAPE and not h.value
         assert lib.polykv_last_error()
     assert lib.pool_create(1, 1, 64, 1, None) == pk.EINVAL
+    rc, h = _create(1, 1, 128, 23_000_000)         # the largest KV heads stay under 4 GiB of records
+    assert rc == pk.OK and lib.pool_bytes(h) == 23_000_000 // 32 * 32 * 184
+    lib.pool_destroy(h)
     assert lib.pool_bytes(None) == 0
     # tile-multiple token counts: exactly the oracle's stored byte count (184 / 92 B per token-head)
     for (L, H, d, T) in [(32, 8, 128, 4096), (1, 4, 64, 640), (24, 32, 64, 1856), (2, 4, 256, 320)]:
