@@ -568,18 +568,25 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
     }
     __syncthreads();
 
+    // A thread's share of its token's row is every eighth 8-element piece: piece p = 8 * rr + c for rr = 0 ..
+    // EPT/8 - 1.  The eight threads of a token then write one contiguous run per store instruction, and the
+    // rotation does not care which index bits are in-lane and which are cross-lane.
     const int tok = tile * kTile + t;
     const bool valid = tok < T;
-    const size_t row = ((size_t)unit * T + (valid ? tok : 0)) * D + c * EPT;
-    const int e0 = c * EPT, j = e0 >> 5, g8 = (e0 >> 3) & 3;
+    const size_t row = ((size_t)unit * T + (valid ? tok : 0)) * D;
+    constexpr int NP = EPT / 8;
+    auto piece_of = [&](const float (&x)[EPT], int rr) -> const float(&)[8] {
+        return *reinterpret_cast<const float(*)[8]>(&x[8 * rr]);
+    };
 
     if (K_out != nullptr) {
-        const _Float16 s16 = KC == 1 ? tensor_key_scale(kmax[unit / H])
-                                     : reinterpret_cast<const _Float16*>(kimg + LY::kscales_off)[t * LY::NB + j];
         float k[EPT];
 #pragma unroll
-        for (int rr = 0; rr < EPT / 8; ++rr) {
-            const uint2 raw = *reinterpret_cast<const uint2*>(kimg + LY::kcodes_off + kcode_run_offset(t, j, g8 + rr));
+        for (int rr = 0; rr < NP; ++rr) {
+            const int p = 8 * rr + c, j = p >> 2, g8 = p & 3;
+            const _Float16 s16 = KC == 1 ? tensor_key_scale(kmax[unit / H])
+                                         : reinterpret_cast<const _Float16*>(kimg + LY::kscales_off)[t * LY::NB + j];
+            const uint2 raw = *reinterpret_cast<const uint2*>(kimg + LY::kcodes_off + kcode_run_offset(t, j, g8));
             Half2Bits h[4];
             codes4_to_half(raw.x, h[0].u, h[1].u);
             codes4_to_half(raw.y, h[2].u, h[3].u);
@@ -590,35 +597,52 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
                 k[8 * rr + 2 * i + 1] = (float)(h[i].h[1] - (_Float16)1152.0f) * (float)s16;
             }
         }
-        if (valid) RowStore<OutT, EPT>::store(K_out + row, k);
+        if (valid) {
+#pragma unroll
+            for (int rr = 0; rr < NP; ++rr) RowStore<OutT, 8>::store(K_out + row + 8 * (8 * rr + c), piece_of(k, rr));
+        }
     }
     if (V8) {
         if (V_out != nullptr) {
             float y[EPT];
 #pragma unroll
-            for (int i = 0; i < EPT; ++i) y[i] = (float)((int)vbuf[(e0 + i) * VST + t] - 128) * vscale;  // exact in fp32
-            if (valid) RowStore<OutT, EPT>::store(V_out + row, y);
+            for (int i = 0; i < EPT; ++i)  // exact in fp32
+                y[i] = (float)((int)vbuf[(8 * (8 * (i >> 3) + c) + (i & 7)) * VST + t] - 128) * vscale;
+            if (valid) {
+#pragma unroll
+                for (int rr = 0; rr < NP; ++rr) RowStore<OutT, 8>::store(V_out + row + 8 * (8 * rr + c), piece_of(y, rr));
+            }
         }
     } else if (V_out != nullptr) {
         // the centroid scale, 1/sqrt(D) and the entry sign of the cross-lane stages ride on the conversion
         const float f = codec_entry_sign(lane) * (inv_centroid_scale<VB>() * inv_sqrt_d<D>()) * vscale;
         float y[EPT];
 #pragma unroll
-        for (int i = 0; i < EPT / 8; ++i) {
-            const uint4 raw = *reinterpret_cast<const uint4*>(cent + t * CS + e0 + 8 * i);
+        for (int rr = 0; rr < NP; ++rr) {
+            const uint4 raw = *reinterpret_cast<const uint4*>(cent + t * CS + 8 * (8 * rr + c));
             const uint32_t* w = reinterpret_cast<const uint32_t*>(&raw);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 Half2Bits b;
                 b.u = w[k];
-                y[8 * i + 2 * k] = __builtin_fmaf((float)b.h[0], f, 0.0f);
-                y[8 * i + 2 * k + 1] = __builtin_fmaf((float)b.h[1], f, 0.0f);
+                y[8 * rr + 2 * k] = __builtin_fmaf((float)b.h[0], f, 0.0f);
+                y[8 * rr + 2 * k + 1] = __builtin_fmaf((float)b.h[1], f, 0.0f);
             }
         }
         wht_cross_chunks<EPT>(y, lane);
         wht_inlane<EPT>(y);
-        if (signs.on) flip_signs<EPT>(y, sign_word(signs, e0 >> 5) >> (e0 & 31));  // inverse of H.D: D last
-        if (valid) RowStore<OutT, EPT>::store(V_out + row, y);
+        if (signs.on) {  // inverse of H.D: D last
+#pragma unroll
+            for (int rr = 0; rr < NP; ++rr) {
+                const int p = 8 * rr + c;
+                float(&y8)[8] = *reinterpret_cast<float(*)[8]>(&y[8 * rr]);
+                flip_signs<8>(y8, sign_word(signs, p >> 2) >> (8 * (p & 3)));
+            }
+        }
+        if (valid) {
+#pragma unroll
+            for (int rr = 0; rr < NP; ++rr) RowStore<OutT, 8>::store(V_out + row + 8 * (8 * rr + c), piece_of(y, rr));
+        }
     }
 }
 
