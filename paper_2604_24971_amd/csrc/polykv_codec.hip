@@ -296,45 +296,57 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
             float th[NTH];
 #pragma unroll
             for (int k = 0; k < NTH; ++k) th[k] = threshold_mag(VB, k) * tscale;  // inf * t = inf for a zero scale
+            if constexpr (VB == 4) {
+                // Sign, then a three-level binary search over the seven thresholds: per element four compares
+                // into scalar masks, four selects of the next threshold and four add-with-carry steps that
+                // shift the decisions into the code (code = 2 code + decision).  Two elements go in lockstep
+                // so that every mask is read two or more instructions after the compare that wrote it.
 #pragma unroll
-            for (int i = 0; i < EPT; ++i) {
-                int code;
-                if constexpr (VB == 4) {
-                    // eight compares into scalar masks first, then a select and an add-with-carry chain: as in
-                    // the 3-bit quantizer below, every mask is read two or more instructions after its compare
-                    int n, m;
-                    unsigned long long sp, s1, s2, s3, s4, s5, s6, s7;
-                    asm("v_cmp_lt_f32_e64 %2, %18, %10\n\t"
-                        "v_cmp_gt_f32_e64 %3, |%10|, %11\n\t"
-                        "v_cmp_gt_f32_e64 %4, |%10|, %12\n\t"
-                        "v_cmp_gt_f32_e64 %5, |%10|, %13\n\t"
-                        "v_cmp_gt_f32_e64 %6, |%10|, %14\n\t"
-                        "v_cmp_gt_f32_e64 %7, |%10|, %15\n\t"
-                        "v_cmp_gt_f32_e64 %8, |%10|, %16\n\t"
-                        "v_cmp_gt_f32_e64 %9, |%10|, %17\n\t"
-                        "v_cndmask_b32_e64 %1, 8, 0, %2\n\t"
-                        "v_addc_co_u32_e64 %0, vcc, 0, 0, %3\n\t"
-                        "v_addc_co_u32_e64 %0, vcc, 0, %0, %4\n\t"
-                        "v_addc_co_u32_e64 %0, vcc, 0, %0, %5\n\t"
-                        "v_addc_co_u32_e64 %0, vcc, 0, %0, %6\n\t"
-                        "v_addc_co_u32_e64 %0, vcc, 0, %0, %7\n\t"
-                        "v_addc_co_u32_e64 %0, vcc, 0, %0, %8\n\t"
-                        "v_addc_co_u32_e64 %0, vcc, 0, %0, %9\n\t"
-                        "v_or_b32_e32 %0, %0, %1"
-                        : "=&v"(n), "=&v"(m), "=&s"(sp), "=&s"(s1), "=&s"(s2), "=&s"(s3), "=&s"(s4), "=&s"(s5), "=&s"(s6),
-                          "=&s"(s7)
-                        : "v"(y[i]), "v"(th[0]), "v"(th[1]), "v"(th[2]), "v"(th[3]), "v"(th[4]), "v"(th[5]), "v"(th[6]),
-                          "v"(zref)
+                for (int i = 0; i < EPT; i += 2) {
+                    int n0, n1;
+                    float ta, tb, aa, ab, ba, bb;
+                    unsigned long long ma0, ma1, mb0, mb1;
+                    asm("v_cmp_nlt_f32_e64 %8, %21, %12\n\t"
+                        "v_cmp_nlt_f32_e64 %9, %21, %13\n\t"
+                        "v_cmp_gt_f32_e64 %10, |%12|, %17\n\t"
+                        "v_cmp_gt_f32_e64 %11, |%13|, %17\n\t"
+                        "v_addc_co_u32_e64 %0, vcc, 0, 0, %8\n\t"
+                        "v_addc_co_u32_e64 %1, vcc, 0, 0, %9\n\t"
+                        "v_cndmask_b32_e64 %2, %15, %19, %10\n\t"
+                        "v_cndmask_b32_e64 %3, %15, %19, %11\n\t"
+                        "v_cndmask_b32_e64 %4, %14, %18, %10\n\t"
+                        "v_cndmask_b32_e64 %5, %14, %18, %11\n\t"
+                        "v_cndmask_b32_e64 %6, %16, %20, %10\n\t"
+                        "v_cndmask_b32_e64 %7, %16, %20, %11\n\t"
+                        "v_cmp_gt_f32_e64 %8, |%12|, %2\n\t"
+                        "v_cmp_gt_f32_e64 %9, |%13|, %3\n\t"
+                        "v_addc_co_u32_e64 %0, vcc, %0, %0, %10\n\t"
+                        "v_addc_co_u32_e64 %1, vcc, %1, %1, %11\n\t"
+                        "v_cndmask_b32_e64 %2, %4, %6, %8\n\t"
+                        "v_cndmask_b32_e64 %3, %5, %7, %9\n\t"
+                        "v_cmp_gt_f32_e64 %10, |%12|, %2\n\t"
+                        "v_cmp_gt_f32_e64 %11, |%13|, %3\n\t"
+                        "v_addc_co_u32_e64 %0, vcc, %0, %0, %8\n\t"
+                        "v_addc_co_u32_e64 %1, vcc, %1, %1, %9\n\t"
+                        "v_addc_co_u32_e64 %0, vcc, %0, %0, %10\n\t"
+                        "v_addc_co_u32_e64 %1, vcc, %1, %1, %11"
+                        : "=&v"(n0), "=&v"(n1), "=&v"(ta), "=&v"(tb), "=&v"(aa), "=&v"(ab), "=&v"(ba), "=&v"(bb),
+                          "=&s"(ma0), "=&s"(ma1), "=&s"(mb0), "=&s"(mb1)
+                        : "v"(y[i]), "v"(y[i + 1]), "v"(th[0]), "v"(th[1]), "v"(th[2]), "v"(th[3]), "v"(th[4]), "v"(th[5]),
+                          "v"(th[6]), "v"(zref)
                         : "vcc");
-                    code = n;
-                } else {
+                    codes[i] = (uint8_t)n0;
+                    codes[i + 1] = (uint8_t)n1;
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < EPT; ++i) {
                     const float ay = fabsf(y[i]);
                     int n = 0;
 #pragma unroll
                     for (int k = 0; k < NTH; ++k) n += ay > th[k];
-                    code = (y[i] > zref ? 0 : (1 << (VB - 1))) | n;
+                    codes[i] = (uint8_t)((y[i] > zref ? 0 : (1 << (VB - 1))) | n);
                 }
-                codes[i] = (uint8_t)code;
             }
         }
 #pragma unroll
