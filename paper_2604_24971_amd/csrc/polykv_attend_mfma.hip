@@ -591,8 +591,10 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     }
     __syncthreads();
 
-    // ---- final pass: every wave finishes ROWS/4 rows, four lanes to a row, D/4 consecutive
-    // coordinates to a lane: the rotation is then log2(D/4) in-register stages and two DPP stages.
+    // ---- final pass: every wave finishes ROWS/4 rows, four lanes to a row.  Lane qd of a row takes every
+    // fourth 4-coordinate piece (piece 4i + qd), so that the four lanes read and write 64 contiguous bytes per
+    // instruction; the rotation is then log2(D/4) in-register stages and two DPP stages, whichever index bits
+    // sit in the lane.
     constexpr int CPL = D / 4, RPW = ROWS / 4;
     const int ri = lane >> 2, qd = lane & 3;
     if (ri < RPW) {
@@ -606,12 +608,12 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
                         : direct ? quad_entry_sign(lane) * (kCS * (D == 64 ? 0.125f : D == 128 ? 0.08838834764831845f : 0.0625f)) *
                                        __builtin_amdgcn_rcpf(l)
                                  : kCS;
-        float x[CPL];
-        const float4* a4 = reinterpret_cast<const float4*>(&o_s[rr * OSTRIDE + qd * CPL]);
+        float x[CPL];  // x[4i + k] = coordinate 16i + 4qd + k
+        const float4* a4 = reinterpret_cast<const float4*>(&o_s[rr * OSTRIDE]) + qd;
         constexpr int BUF4 = ROWS * OSTRIDE / 4;  // one wave's buffer, in float4 units
 #pragma unroll
         for (int i = 0; i < CPL / 4; ++i) {
-            const float4 a = a4[i], b = a4[BUF4 + i], c = a4[2 * BUF4 + i], d = a4[3 * BUF4 + i];
+            const float4 a = a4[4 * i], b = a4[BUF4 + 4 * i], c = a4[2 * BUF4 + 4 * i], d = a4[3 * BUF4 + 4 * i];
             x[4 * i + 0] = ((a.x + b.x) + (c.x + d.x)) * f;
             x[4 * i + 1] = ((a.y + b.y) + (c.y + d.y)) * f;
             x[4 * i + 2] = ((a.z + b.z) + (c.z + d.z)) * f;
@@ -621,28 +623,25 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
             if (VC != 2) {
                 wht_cross_quad<CPL>(x, lane);
                 wht_inlane<CPL>(x);
-                // rotation variant H.D: the lane's CPL coordinates start at qd * CPL
+                // rotation variant H.D: piece i holds coordinates 16i + 4qd ..
                 if (p.signs.on) {
-                    if constexpr (CPL <= 32) {
-                        flip_signs<CPL>(x, sign_word(p.signs, (qd * CPL) >> 5) >> ((qd * CPL) & 31));
-                    } else {  // 64 coordinates per lane: two sign words
-                        float(&lo)[32] = *reinterpret_cast<float(*)[32]>(&x[0]);
-                        float(&hi)[32] = *reinterpret_cast<float(*)[32]>(&x[32]);
-                        flip_signs<32>(lo, sign_word(p.signs, 2 * qd));
-                        flip_signs<32>(hi, sign_word(p.signs, 2 * qd + 1));
+#pragma unroll
+                    for (int i = 0; i < CPL / 4; ++i) {
+                        float(&x4)[4] = *reinterpret_cast<float(*)[4]>(&x[4 * i]);
+                        flip_signs<4>(x4, sign_word(p.signs, i >> 1) >> (16 * (i & 1) + 4 * qd));
                     }
                 }
             }
             if (r < p.R) {
-                float4* dst = reinterpret_cast<float4*>(out + q_row_index(p, ls, kvh, r) * D + qd * CPL);
+                float4* dst = reinterpret_cast<float4*>(out + q_row_index(p, ls, kvh, r) * D) + qd;
 #pragma unroll
-                for (int i = 0; i < CPL / 4; ++i) dst[i] = make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
+                for (int i = 0; i < CPL / 4; ++i) dst[4 * i] = make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
             }
         } else if (r < p.R) {
             const size_t prow = ((size_t)usel * p.nsplit + split) * p.R + r;
-            float4* dst = reinterpret_cast<float4*>(ws_o + prow * D + qd * CPL);
+            float4* dst = reinterpret_cast<float4*>(ws_o + prow * D) + qd;
 #pragma unroll
-            for (int i = 0; i < CPL / 4; ++i) dst[i] = make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
+            for (int i = 0; i < CPL / 4; ++i) dst[4 * i] = make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
             if (qd == 0) {
                 ws_ml[prow * 2] = Mr * qscale;
                 ws_ml[prow * 2 + 1] = l;
