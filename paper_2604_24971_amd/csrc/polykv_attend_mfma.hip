@@ -389,21 +389,36 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
         __builtin_amdgcn_sched_barrier(0);
     }
 
+    // The per-lane row maxima of tile B (for the next step's vote; no cross-lane reduction is needed for the
+    // vote) are taken while the P.V products of tile A run: that phase is bound by the matrix cores, so the
+    // accumulator reads and the maxima ride along for free.
+    constexpr bool kMaxInPV = HAS_A && HAS_B && NG >= 4;
+    constexpr int SPS = kMaxInPV ? 16 * NT / NG : 0;  // scores per P.V slice (a multiple of 2)
+    if (kMaxInPV) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) mloc[nt] = -INFINITY;
+    }
     if (HAS_A) {
 #pragma unroll
         for (int G = 0; G < NG; ++G) {
             pv(G);
             if (G + 1 < NG) vdeq(G + 1);
-            slice_end(integral_constant<int, NT>{}, integral_constant<int, 12>{});
+            if (kMaxInPV) {
+#pragma unroll
+                for (int x = G * SPS; x < (G + 1) * SPS; x += 2) {
+                    const int nt = x / 16, i = x % 16;
+                    mloc[nt] = fmaxf(fmaxf(mloc[nt], Sb[nt][i]), Sb[nt][i + 1]);
+                }
+            }
+            slice_end(integral_constant<int, NT>{}, integral_constant<int, (kMaxInPV ? 12 + 3 * SPS / 2 : 12)>{});
         }
     }
 
-    // ---- row maxima of tile B for the next step's vote (no cross-lane reduction needed for the vote)
     if (HAS_B) {
         raise = false;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            mloc[nt] = max16(Sb[nt]);
+            if (!kMaxInPV) mloc[nt] = max16(Sb[nt]);
             raise |= mloc[nt] > m_thr[nt];  // also true while the reference is -inf
             Sa[nt] = Sb[nt];
         }
