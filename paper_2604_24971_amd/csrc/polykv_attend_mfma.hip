@@ -330,11 +330,17 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
     };
     using std::integral_constant;
 
-    // The next step's bytes are requested first thing, into the other set of registers, so that every
-    // load has the whole step (and more, for all but the first key block) to land.
-    if (HAS_B) load_rawk<D, KC>(rkN, nextK, lane);
-    load_rawv<D, VC, KC>(rvN, nextV, lane);
-    __builtin_amdgcn_sched_barrier(0);
+    // The next step's bytes are requested into the other set of registers as soon as the first score
+    // products are on the matrix cores (right here when the step has none): every load still has nearly the
+    // whole step to land, and the stretch in which the matrix cores wait for vector work stays short.
+    auto request_next = [&]() {
+        if (HAS_B) load_rawk<D, KC>(rkN, nextK, lane);
+        load_rawv<D, VC, KC>(rvN, nextV, lane);
+    };
+    if (!HAS_B) {
+        request_next();
+        __builtin_amdgcn_sched_barrier(0);
+    }
 
     H8 pb[NT][2];      // probabilities of tile A: B operands of the P.V products, [row tile][k slice]
     half8 khi[2], klo[2];
@@ -361,17 +367,14 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int i = 0; i < 16; ++i) Sb[nt][i] = 0.0f;
-        // lead-in: vector work only
-        constexpr int lead = NCH / NQK > 0 ? NCH / NQK : 1;
-        if (HAS_A) {
-#pragma unroll
-            for (int c = 0; c < lead; ++c) exp_chunk(c);
-        }
+        // lead-in: only the vector work that the first products need
+        constexpr int lead = 0;
         kdeq(0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int k = 0; k < NQK; ++k) {
             qk(k);
+            if (k == 0) request_next();
             if (k + 1 < NQK) kdeq(k + 1);
             if (HAS_A) {
                 // spread the remaining probability chunks over the score slices
