@@ -383,7 +383,7 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
                 for (int c = c0; c < c1; ++c) exp_chunk(c);
                 if (k + 1 == NQK) vdeq(0);
             }
-            slice_end(integral_constant<int, (KC == 0 ? 2 : 1) * NT>{}, integral_constant<int, (HAS_A ? 30 : 16)>{});
+            slice_end(integral_constant<int, (KC == 0 ? 2 : 1) * NT>{}, integral_constant<int, (HAS_A ? 28 : 16)>{});
         }
     } else if (HAS_A) {
 #pragma unroll
