@@ -81,43 +81,67 @@ template <int D, int VC> struct RawV {
     uint32_t g[vc_has_scale(VC) ? 8 : 1];
 };
 
-// `tile` is wave-uniform and the lane's share sits at a 32-bit offset from it, so every load can use
-// the scalar-base + vector-offset addressing form and no per-lane 64-bit address is ever computed.
-template <int D, int KC> __device__ __forceinline__ void load_rawk(RawK<D>& r, const uint8_t* tile, int lane) {
+// The records of a KV head are read through a buffer resource: every load is "resource + wave-uniform byte
+// offset of the tile (a scalar register) + the lane's constant offset (a vector register that never changes)
+// + an immediate", so a step spends no vector instruction on addresses, and a load beyond the KV head's records
+// would return zeros instead of touching memory.
+typedef __amdgpu_buffer_rsrc_t TileRsrc;
+__device__ __forceinline__ TileRsrc make_tile_rsrc(const uint8_t* unit_base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(unit_base), 0, bytes, 0x00020000);
+}
+template <int D, int KC> __device__ __forceinline__ void load_rawk(RawK<D>& r, TileRsrc rs, uint32_t tile, int lane) {
     const uint32_t soff = Layout<D>::kscales_off + (uint32_t)(lane & 31) * (D / 32) * 2, koff = (uint32_t)lane * 16;
     if (KC == 0) {
+        if (D == 64) {
+            r.sc[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, soff, tile, 0);
+        } else {
 #pragma unroll
-        for (int x = 0; x < D / 64; ++x) r.sc[x] = *reinterpret_cast<const uint32_t*>(tile + soff + 4 * x);
+            for (int x = 0; x < D / 128; ++x) {
+                const auto two = __builtin_amdgcn_raw_buffer_load_b64(rs, soff + 8 * x, tile, 0);
+                r.sc[2 * x] = two[0];
+                r.sc[2 * x + 1] = two[1];
+            }
+        }
     }
 #pragma unroll
-    for (int j = 0; j < D / 32; ++j) r.k[j] = *reinterpret_cast<const uint4v*>(tile + koff + j * 1024);
+    for (int j = 0; j < D / 32; ++j) r.k[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, koff + j * 1024, tile, 0);
 }
-template <int D, int VC, int KC> __device__ __forceinline__ void load_rawv(RawV<D, VC>& r, const uint8_t* tile, int lane) {
+template <int D, int VC, int KC>
+__device__ __forceinline__ void load_rawv(RawV<D, VC>& r, TileRsrc rs, uint32_t tile, int lane) {
     using LY = Layout<D, VC, KC>;
     constexpr int VB = vc_bits(VC);
     if (VB == 4 || VB == 2) {
         constexpr int ND = VB == 4 ? D / 16 : D / 32;  // dwords per lane, contiguous
         const uint32_t voff = LY::vcodes_off + (uint32_t)lane * (ND * 4);
+        if constexpr (ND % 4 == 0) {
 #pragma unroll
-        for (int i = 0; i < ND; ++i) r.n[i] = *reinterpret_cast<const uint32_t*>(tile + voff + 4 * i);
+            for (int i = 0; i < ND; i += 4) {
+                const uint4v w = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 4 * i, tile, 0);
+                r.n[i] = w.x, r.n[i + 1] = w.y, r.n[i + 2] = w.z, r.n[i + 3] = w.w;
+            }
+        } else {
+            const auto w = __builtin_amdgcn_raw_buffer_load_b64(rs, voff, tile, 0);  // ND == 2
+            r.n[0] = w[0], r.n[1] = w[1];
+        }
     } else if (VB == 8) {
         const uint32_t voff = LY::vcodes_off + (uint32_t)lane * 16;
 #pragma unroll
-        for (int g = 0; g < D / 32; ++g) r.c[g] = *reinterpret_cast<const uint4v*>(tile + voff + g * 1024);
+        for (int g = 0; g < D / 32; ++g) r.c[g] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + g * 1024, tile, 0);
     } else {
         const uint32_t voff = LY::vcodes_off + (uint32_t)lane * 12;
 #pragma unroll
-        for (int q = 0; q < D / 64; ++q)
-#pragma unroll
-            for (int w = 0; w < 3; ++w) r.w[q][w] = *reinterpret_cast<const uint32_t*>(tile + voff + q * 768 + 4 * w);
+        for (int q = 0; q < D / 64; ++q) {
+            const auto w = __builtin_amdgcn_raw_buffer_load_b96(rs, voff + q * 768, tile, 0);
+            r.w[q][0] = w[0], r.w[q][1] = w[1], r.w[q][2] = w[2];
+        }
     }
     if (vc_has_scale(VC)) {
         const uint32_t goff = LY::vscales_off + (uint32_t)(lane >> 5) * 8;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            const uint2 two = *reinterpret_cast<const uint2*>(tile + goff + 16 * b);
-            r.g[2 * b] = two.x;
-            r.g[2 * b + 1] = two.y;
+            const auto two = __builtin_amdgcn_raw_buffer_load_b64(rs, goff + 16 * b, tile, 0);
+            r.g[2 * b] = two[0];
+            r.g[2 * b + 1] = two[1];
         }
     }
 }
@@ -205,7 +229,7 @@ __device__ __forceinline__ void exp4(const float16v& S, int c, float qscale, flo
 // The pool's last tile when it crosses the end of the pool, read straight from memory: scores, softmax
 // and PV one after the other, tokens >= T masked out.  Runs at most once per KV head.
 template <int D, int NT, int VC, int KC>
-__device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile, int T, float qscale, float raise_thr,
+__device__ __forceinline__ void process_ragged_tile(TileRsrc rs, uint32_t lt, int tile, int T, float qscale, float raise_thr,
                                                  int lane, const half8 (&qb)[NT][D / 32][2], float16v (&O)[D / 32][NT],
                                                  float (&Lsum)[NT], float (&m_ref)[NT], float (&m_thr)[NT],
                                                  float (&mneg)[NT]) {
@@ -213,8 +237,8 @@ __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile,
     const int h = lane >> 5;
     RawK<D> rk;
     RawV<D, VC> rv;
-    load_rawk<D, KC>(rk, lt, lane);
-    load_rawv<D, VC, KC>(rv, lt, lane);
+    load_rawk<D, KC>(rk, rs, lt, lane);
+    load_rawv<D, VC, KC>(rv, rs, lt, lane);
     float16v S[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
@@ -276,7 +300,7 @@ __device__ __forceinline__ void process_ragged_tile(const uint8_t* lt, int tile,
 // Only full tiles go through here; a ragged last tile is handled by process_ragged_tile.
 template <int D, int NT, int VC, int KC, bool HAS_A, bool HAS_B>
 __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<D>& rk, RawV<D, VC>& rvN, RawK<D>& rkN,
-                                              const uint8_t* nextK, const uint8_t* nextV, float qscale,
+                                              TileRsrc rs, uint32_t nextK, uint32_t nextV, float qscale,
                                               float raise_thr, int lane, const half8 (&qb)[NT][D / 32][2],
                                               float16v (&O)[D / 32][NT], float (&Lsum)[NT], float (&m_ref)[NT],
                                               float (&m_thr)[NT], float (&mneg)[NT], float16v (&Sa)[NT],
@@ -334,8 +358,8 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
     // products are on the matrix cores (right here when the step has none): every load still has nearly the
     // whole step to land, and the stretch in which the matrix cores wait for vector work stays short.
     auto request_next = [&]() {
-        if (HAS_B) load_rawk<D, KC>(rkN, nextK, lane);
-        load_rawv<D, VC, KC>(rvN, nextV, lane);
+        if (HAS_B) load_rawk<D, KC>(rkN, rs, nextK, lane);
+        load_rawv<D, VC, KC>(rvN, rs, nextV, lane);
     };
     if (!HAS_B) {
         request_next();
@@ -463,14 +487,15 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     const int my_count = my_first < t_end ? (t_end - my_first + 3) / 4 : 0;
     // pointer to local tile k; k past the end is clamped (the refill loads of the last steps then
     // fetch the wave's own last tile again, harmlessly, instead of needing a branch per load)
-    const uint8_t* wave_base = unit_base + (size_t)my_first * TB;
+    // (byte offsets from the KV head's first record; pool_create keeps a KV head's records under 4 GiB)
+    const TileRsrc rs = make_tile_rsrc(unit_base, (uint32_t)p.tiles_cap * (uint32_t)TB);
     const int last_k = max(my_count - 1, 0);
-    auto tile_ptr = [&](int k) { return wave_base + (uint32_t)min(k, last_k) * (uint32_t)(4 * TB); };
+    auto tile_ptr = [&](int k) { return (uint32_t)(my_first + 4 * min(k, last_k)) * (uint32_t)TB; };
     RawK<D> rk;
     RawV<D, VC> rv;
     if (my_count > 0) {
-        load_rawk<D, KC>(rk, tile_ptr(0), lane);
-        load_rawv<D, VC, KC>(rv, tile_ptr(0), lane);
+        load_rawk<D, KC>(rk, rs, tile_ptr(0), lane);
+        load_rawv<D, VC, KC>(rv, rs, tile_ptr(0), lane);
     }
 
     // ---- query rows as MFMA B operands: lane (n, h) holds q[row 32nt+n][32j + 16s + 8h .. +7].
@@ -556,27 +581,27 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         RawK<D> rk2;
         RawV<D, VC> rv2;
         // prologue: scores of tile 0 from rk; requests K of tile 1 and (again) V of tile 0 into set 2
-        pipeline_step<D, NT, VC, KC, false, true>(rv, rk, rv2, rk2, tile_ptr(1), tile_ptr(0), qscale, raise_thr, lane, qb, O, Lsum,
+        pipeline_step<D, NT, VC, KC, false, true>(rv, rk, rv2, rk2, rs, tile_ptr(1), tile_ptr(0), qscale, raise_thr, lane, qb, O, Lsum,
                                           m_ref, m_thr, mneg, S, mloc, raise);
         int s = 0;
         for (; s + 1 < full_count - 1; s += 2) {  // two steps per trip: the sets swap roles without copies
-            pipeline_step<D, NT, VC, KC, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, true, true>(rv2, rk2, rv, rk, rs, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
-            pipeline_step<D, NT, VC, KC, true, true>(rv, rk, rv2, rk2, tile_ptr(s + 3), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, true, true>(rv, rk, rv2, rk2, rs, tile_ptr(s + 3), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         }
         if (s < full_count - 1) {  // one step with a B tile left: current = set 2
-            pipeline_step<D, NT, VC, KC, true, true>(rv2, rk2, rv, rk, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, true, true>(rv2, rk2, rv, rk, rs, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
-            pipeline_step<D, NT, VC, KC, true, false>(rv, rk, rv2, rk2, tile_ptr(s + 2), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, true, false>(rv, rk, rv2, rk2, rs, tile_ptr(s + 2), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
                                               O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         } else {
-            pipeline_step<D, NT, VC, KC, true, false>(rv2, rk2, rv, rk, tile_ptr(s + 1), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, true, false>(rv2, rk2, rv, rk, rs, tile_ptr(s + 1), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
                                               O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         }
     }
     if (last_ragged)
-        process_ragged_tile<D, NT, VC, KC>(tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
+        process_ragged_tile<D, NT, VC, KC>(rs, tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
                                    Lsum, m_ref, m_thr, mneg);
 
     // ---- merge the four waves through LDS: every wave stores its accumulators, rescaled to the
