@@ -420,7 +420,8 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
     // vote) are taken while the P.V products of tile A run: that phase is bound by the matrix cores, so the
     // accumulator reads and the maxima ride along for free.
     constexpr bool kMaxInPV = HAS_A && HAS_B && NG >= 4;
-    constexpr int SPS = kMaxInPV ? 16 * NT / NG : 0;  // scores per P.V slice (a multiple of 2)
+    constexpr int SPS = kMaxInPV ? 16 * NT / NG : 0;  // scores per P.V slice: 16 NT scores over NG slices
+    static_assert(!kMaxInPV || (SPS >= 1 && SPS * NG == 16 * NT), "");
     if (kMaxInPV) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) mloc[nt] = -INFINITY;
@@ -434,10 +435,13 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
 #pragma unroll
                 for (int x = G * SPS; x < (G + 1) * SPS; x += 2) {
                     const int nt = x / 16, i = x % 16;
-                    mloc[nt] = fmaxf(fmaxf(mloc[nt], Sb[nt][i]), Sb[nt][i + 1]);
+                    if (x + 1 < (G + 1) * SPS)
+                        mloc[nt] = fmaxf(fmaxf(mloc[nt], Sb[nt][i]), Sb[nt][i + 1]);
+                    else  // an odd count (one score per slice at head_dim 256)
+                        mloc[nt] = fmaxf(mloc[nt], Sb[nt][i]);
                 }
             }
-            slice_end(integral_constant<int, NT>{}, integral_constant<int, (kMaxInPV ? 12 + 3 * SPS / 2 : 12)>{});
+            slice_end(integral_constant<int, NT>{}, integral_constant<int, (kMaxInPV ? 12 + (3 * SPS + 1) / 2 : 12)>{});
         }
     }
 
