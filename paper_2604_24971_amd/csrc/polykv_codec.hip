@@ -1,8 +1,9 @@
 // Encode / decode / export kernels of the packed pool (gfx950).
 //
-// One workgroup of 256 threads handles one tile (32 tokens) of one KV head.  Thread (t, c) owns the
-// D/8 consecutive head_dim elements c*D/8 .. of token t, so a dense fp16 row is read (or written) by
-// 8 lanes with 16- or 32-byte accesses and a wave covers 8 whole rows.  The Walsh-Hadamard transform
+// One workgroup of 256 threads handles one tile (32 tokens) of one KV head.  Thread (t, c) owns D/8
+// head_dim elements of token t -- in encode the consecutive ones c*D/8 .., in decode every eighth 8-element
+// piece (8i + c), which makes every store instruction of the dense output write whole cache lines -- so a
+// dense row is read or written by 8 lanes and a wave covers 8 whole rows.  The Walsh-Hadamard transform
 // is log2(D/8) in-register stages plus three one-instruction DPP stages across those 8 lanes.  Both
 // kernels are written to stay under the HBM time in vector instructions: conversions are fused with
 // multiplies, the key codes are rounded with one magic-number add, the value quantizer compares the
