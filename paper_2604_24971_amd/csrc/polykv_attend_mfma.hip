@@ -516,6 +516,16 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         const int i = tid + 256 * u, rr = i / (D / 8), piece = i - rr * (D / 8), r = min(row0 + rr, p.R - 1);
         qraw[u] = *reinterpret_cast<const uint4v*>(Q + q_row_index(p, ls, kvh, r) * D + 8 * piece);
     }
+    // the accumulators are cleared while the queries and the first tiles are on their way
+    float16v O[MG][NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int g = 0; g < MG; ++g) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[g][nt][i] = 0.0f;
+            asm volatile("" : "+a"(O[g][nt]));  // now, not where the first product needs them
+        }
 #pragma unroll
     for (int u = 0; u < QP; ++u) {
         const int i = tid + 256 * u, rr = i / (D / 8), piece = i - rr * (D / 8);
@@ -558,7 +568,6 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
                 for (int s = 0; s < 2; ++s) asm volatile("" : "+a"(qb[nt][j][s]));
     }
 
-    float16v O[MG][NT];
     float Lsum[NT], m_ref[NT], m_thr[NT], mneg[NT], mloc[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
@@ -567,10 +576,6 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         mneg[nt] = 0.0f;
         mloc[nt] = -INFINITY;
         Lsum[nt] = 0.0f;
-#pragma unroll
-        for (int g = 0; g < MG; ++g)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) O[g][nt][i] = 0.0f;
     }
     const float raise_thr = 8.0f / qscale;  // raise the reference only when a row exceeds it by 2^8
     bool raise = false;
