@@ -554,6 +554,7 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
 #pragma unroll
             for (int s = 0; s < 2; ++s)
                 qb[nt][j][s] = *reinterpret_cast<const half8*>(q_s + (32 * nt + n) * QS + 32 * j + 16 * s + 8 * h);
+    __syncthreads();  // every wave has picked up its queries: the merge at the end reuses this memory
     // The queries are only ever MFMA operands: park them in accumulation registers so that the vector
     // registers are left for the scores and the dequantization temporaries (a second loop, so that the LDS
     // reads above are all in flight before the first one is waited for).  Not at head_dim 256: there the
@@ -613,31 +614,26 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         process_ragged_tile<D, NT, VC, KC>(rs, tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
                                    Lsum, m_ref, m_thr, mneg);
 
-    // ---- merge the four waves through LDS: every wave stores its accumulators, rescaled to the
-    // common row maximum, into a buffer of its own; the final pass adds the four buffers in a fixed
-    // order, so the result is reproducible.
-    if (h == 0) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) m_s[wave][32 * nt + n] = m_ref[nt];
-    }
-    __syncthreads();  // also: every wave has picked up its queries, the buffers may be overwritten
+    // ---- merge the four waves through LDS: every wave stores its row maxima, denominators and accumulators
+    // as they are into buffers of its own; the final pass rescales them to the common row maximum and adds
+    // them in a fixed order, so the result is reproducible.
     {
         float* obuf = o_s + wave * (ROWS * OSTRIDE);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int r = 32 * nt + n;
-            const float M = fmaxf(fmaxf(m_s[0][r], m_s[1][r]), fmaxf(m_s[2][r], m_s[3][r]));
-            const float f = m_ref[nt] == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f((m_ref[nt] - M) * qscale);
             const float l = xor32_sum(Lsum[nt]);  // the lane pair (n, h) shares a row
-            if (h == 0) l_s[wave * ROWS + r] = l * f;
+            if (h == 0) {
+                m_s[wave][r] = m_ref[nt];
+                l_s[wave * ROWS + r] = l;
+            }
 #pragma unroll
             for (int g = 0; g < MG; ++g)
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
                     // registers 4b..4b+3 hold coordinates 32g + 8b + 4h + 0..3 of row r
                     float4* dst = reinterpret_cast<float4*>(&obuf[r * OSTRIDE + 32 * g + 8 * b + 4 * h]);
-                    *dst = make_float4(O[g][nt][4 * b + 0] * f, O[g][nt][4 * b + 1] * f, O[g][nt][4 * b + 2] * f,
-                                       O[g][nt][4 * b + 3] * f);
+                    *dst = make_float4(O[g][nt][4 * b + 0], O[g][nt][4 * b + 1], O[g][nt][4 * b + 2], O[g][nt][4 * b + 3]);
                 }
         }
     }
@@ -652,7 +648,11 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     if (ri < RPW) {
         const int rr = wave + 4 * ri, r = row0 + rr;
         const float Mr = fmaxf(fmaxf(m_s[0][rr], m_s[1][rr]), fmaxf(m_s[2][rr], m_s[3][rr]));
-        const float l = (l_s[rr] + l_s[ROWS + rr]) + (l_s[2 * ROWS + rr] + l_s[3 * ROWS + rr]);
+        float fw[4];  // a wave's weight: 2^(its maximum - the common one); 0 if it saw no tile
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            fw[w] = m_s[w][rr] == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f((m_s[w][rr] - Mr) * qscale);
+        const float l = (l_s[rr] * fw[0] + l_s[ROWS + rr] * fw[1]) + (l_s[2 * ROWS + rr] * fw[2] + l_s[3 * ROWS + rr] * fw[3]);
         // direct: 1/l, the centroid scale, 1/sqrt(D) and the entry sign of the DPP stages in one factor
         // int8 values are accumulated unrotated and unscaled: 1/l is all that is left to do
         constexpr float kCS = inv_centroid_scale<vc_bits(VC)>();
@@ -660,16 +660,18 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
                         : direct ? quad_entry_sign(lane) * (kCS * (D == 64 ? 0.125f : D == 128 ? 0.08838834764831845f : 0.0625f)) *
                                        __builtin_amdgcn_rcpf(l)
                                  : kCS;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) fw[w] *= f;
         float x[CPL];  // x[4i + k] = coordinate 16i + 4qd + k
         const float4* a4 = reinterpret_cast<const float4*>(&o_s[rr * OSTRIDE]) + qd;
         constexpr int BUF4 = ROWS * OSTRIDE / 4;  // one wave's buffer, in float4 units
 #pragma unroll
         for (int i = 0; i < CPL / 4; ++i) {
             const float4 a = a4[4 * i], b = a4[BUF4 + 4 * i], c = a4[2 * BUF4 + 4 * i], d = a4[3 * BUF4 + 4 * i];
-            x[4 * i + 0] = ((a.x + b.x) + (c.x + d.x)) * f;
-            x[4 * i + 1] = ((a.y + b.y) + (c.y + d.y)) * f;
-            x[4 * i + 2] = ((a.z + b.z) + (c.z + d.z)) * f;
-            x[4 * i + 3] = ((a.w + b.w) + (c.w + d.w)) * f;
+            x[4 * i + 0] = (a.x * fw[0] + b.x * fw[1]) + (c.x * fw[2] + d.x * fw[3]);
+            x[4 * i + 1] = (a.y * fw[0] + b.y * fw[1]) + (c.y * fw[2] + d.y * fw[3]);
+            x[4 * i + 2] = (a.z * fw[0] + b.z * fw[1]) + (c.z * fw[2] + d.z * fw[3]);
+            x[4 * i + 3] = (a.w * fw[0] + b.w * fw[1]) + (c.w * fw[2] + d.w * fw[3]);
         }
         if (direct) {
             if (VC != 2) {
