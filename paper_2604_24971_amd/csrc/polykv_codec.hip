@@ -78,15 +78,22 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
     const bool old_token = tok < tok_begin;              // keep what the record holds
     const bool valid = !old_token && tok < tok_end;      // read from K, V
     const bool has_old = tile * kTile < tok_begin;       // uniform over the workgroup
-    const size_t row = ((size_t)unit * in_tokens + (valid ? tok - tok_begin : 0)) * D + c * EPT;
-    const int e0 = c * EPT, j = e0 >> 5, g8 = (e0 >> 3) & 3;
+    // At head_dim 256 a thread's share is every eighth 8-element piece (8 rr + c, as in decode_kernel): with
+    // four pieces per thread the 8 lanes of a token then read whole cache lines per load instruction, which is
+    // worth a tenth of the kernel's time there (and nothing at 128, where the consecutive share stays).
+    constexpr bool PIECES = D == 256;
+    const size_t row = ((size_t)unit * in_tokens + (valid ? tok - tok_begin : 0)) * D + (PIECES ? 0 : c * EPT);
+    const int e0 = c * EPT, j = e0 >> 5, g8 = (e0 >> 3) & 3;  // (consecutive share)
+    // element i of the thread's share is head_dim coordinate coord(i)
+    auto coord = [&](int i) { return PIECES ? 8 * (8 * (i >> 3) + c) + (i & 7) : e0 + i; };
     uint8_t* rec = pool + ((size_t)unit * tiles_cap + tile) * LY::tile_bytes;
 
     uint4 kraw[EPT / 8], vraw[EPT / 8];
 #pragma unroll
     for (int i = 0; i < EPT / 8; ++i) {
-        kraw[i] = valid ? reinterpret_cast<const uint4*>(K + row)[i] : make_uint4(0, 0, 0, 0);
-        vraw[i] = valid ? reinterpret_cast<const uint4*>(V + row)[i] : make_uint4(0, 0, 0, 0);
+        const int piece = PIECES ? 8 * i + c : i;
+        kraw[i] = valid ? reinterpret_cast<const uint4*>(K + row)[piece] : make_uint4(0, 0, 0, 0);
+        vraw[i] = valid ? reinterpret_cast<const uint4*>(V + row)[piece] : make_uint4(0, 0, 0, 0);
     }
 
     if (has_old) {
@@ -143,7 +150,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
     }
 
     // ---- keys: block absmax -> fp16 scale -> codes with the stored scale
-    {
+    if constexpr (!PIECES) {
         // max|k| on the raw 16-bit patterns: magnitudes of fp16 (and of bfloat16) order like unsigned integers
         typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
         union {
@@ -205,6 +212,76 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         }
         if (KC == 0 && (e0 & 31) == 0 && !old_token)
             reinterpret_cast<__half*>(kimg + LY::kscales_off)[t * LY::NB + j] = s16;
+    } else {
+        // Interleaved pieces: piece rr of the thread lies in block 2 rr + c / 4, which the four lanes of a quad
+        // share (c % 4 = the piece's place in the block).  Lane q of the quad works out the scale of piece q's
+        // block; a quad broadcast hands every lane the four scales.
+        typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+        constexpr int NP = EPT / 8;
+        static_assert(NP == 4, "one piece per lane of a quad");
+        float amax_p[NP];
+#pragma unroll
+        for (int rr = 0; rr < NP; ++rr) {
+            union {
+                uint32_t u;
+                ushort2v v;
+            } mx, w;
+            mx.u = 0;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                w.u = reinterpret_cast<const uint32_t*>(&kraw[rr])[x] & 0x7FFF7FFFu;
+                mx.v = __builtin_elementwise_max(mx.v, w.v);
+            }
+            float am = bits16_to_float((uint16_t)max(mx.u & 0xFFFFu, mx.u >> 16), BF);
+            am = fmaxf(am, lane_xor<1>(am));
+            amax_p[rr] = fmaxf(am, lane_xor<2>(am));
+        }
+        const int q = c & 3;
+        const float amax = q == 0 ? amax_p[0] : q == 1 ? amax_p[1] : q == 2 ? amax_p[2] : amax_p[3];
+        const float sraw = __fdiv_rn(amax, 127.0f);
+        __half s16 = __float2half_rn(BF ? fminf(sraw, 65504.0f) : sraw);
+        if (KC == 1) s16 = (__half)tensor_key_scale(kmax[unit / H]);
+        const float sf = __half2float(s16);
+        const float inv = sf > 0.0f ? __fdiv_rn(1.0f, sf) : 0.0f;
+        float sf_p[NP], inv_p[NP];
+        {
+            const int si = __float_as_int(sf), ii = __float_as_int(inv);
+            sf_p[0] = __int_as_float(__builtin_amdgcn_update_dpp(si, si, 0x00, 0xF, 0xF, false));   // quad_perm [0,0,0,0]
+            sf_p[1] = __int_as_float(__builtin_amdgcn_update_dpp(si, si, 0x55, 0xF, 0xF, false));   // [1,1,1,1]
+            sf_p[2] = __int_as_float(__builtin_amdgcn_update_dpp(si, si, 0xAA, 0xF, 0xF, false));   // [2,2,2,2]
+            sf_p[3] = __int_as_float(__builtin_amdgcn_update_dpp(si, si, 0xFF, 0xF, 0xF, false));   // [3,3,3,3]
+            inv_p[0] = __int_as_float(__builtin_amdgcn_update_dpp(ii, ii, 0x00, 0xF, 0xF, false));
+            inv_p[1] = __int_as_float(__builtin_amdgcn_update_dpp(ii, ii, 0x55, 0xF, 0xF, false));
+            inv_p[2] = __int_as_float(__builtin_amdgcn_update_dpp(ii, ii, 0xAA, 0xF, 0xF, false));
+            inv_p[3] = __int_as_float(__builtin_amdgcn_update_dpp(ii, ii, 0xFF, 0xF, 0xF, false));
+        }
+        constexpr float kMagic = 12582912.0f + 128.0f;  // as above: the low byte is round(k * inv) + 128
+#pragma unroll
+        for (int rr = 0; rr < NP; ++rr) {
+            uint32_t r[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t pair = reinterpret_cast<const uint32_t*>(&kraw[rr])[i >> 1];
+                float prod;
+                if (BF) {
+                    prod = __uint_as_float((i & 1) ? pair & 0xFFFF0000u : pair << 16) * inv_p[rr];
+                } else {
+                    Half2Bits hb;
+                    hb.u = pair;
+                    prod = __builtin_fmaf((float)hb.h[i & 1], inv_p[rr], 0.0f);
+                }
+                const float qv = prod + kMagic;
+                r[i] = __float_as_uint(__builtin_amdgcn_fmed3f(qv, kMagic - 128.0f, kMagic + 127.0f));
+            }
+            if (!old_token) {
+                uint2 w;
+                w.x = __builtin_amdgcn_perm(r[1], r[0], 0x0c0c0400u) | __builtin_amdgcn_perm(r[3], r[2], 0x04000c0cu);
+                w.y = __builtin_amdgcn_perm(r[5], r[4], 0x0c0c0400u) | __builtin_amdgcn_perm(r[7], r[6], 0x04000c0cu);
+                *reinterpret_cast<uint2*>(kimg + LY::kcodes_off + kcode_run_offset(t, 2 * rr + (c >> 2), q)) = w;
+                if (KC == 0 && q == 0)  // exact: the value is an fp16 number
+                    reinterpret_cast<__half*>(kimg + LY::kscales_off)[t * LY::NB + 2 * rr + (c >> 2)] = __float2half_rn(sf_p[rr]);
+            }
+        }
     }
 
     // ---- values, int8 codec: vector absmax -> fp16 scale -> codes with the stored scale, staged as bytes
@@ -226,12 +303,11 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         const float sf = __half2float(s16);
         const float inv = sf > 0.0f ? __fdiv_rn(1.0f, sf) : 0.0f;
         constexpr float kMagic = 12582912.0f + 128.0f;  // as for the keys: the low byte is round(v * inv) + 128
-        uint8_t* dst = vstage + e0 * VST + t;
 #pragma unroll
         for (int i = 0; i < EPT; ++i) {
             const float q = v[i] * inv + kMagic;
             const uint32_t r = __float_as_uint(__builtin_amdgcn_fmed3f(q, kMagic - 128.0f, kMagic + 127.0f));
-            if (!old_token) dst[i * VST] = (uint8_t)r;
+            if (!old_token) vstage[coord(i) * VST + t] = (uint8_t)r;
         }
         if (c == 0 && !old_token) reinterpret_cast<__half*>(kimg + LY::vscales_off)[t] = s16;
     }
@@ -283,14 +359,24 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
             }
             if (c == 0 && !old_token) reinterpret_cast<__half*>(kimg + LY::vscales_off)[t] = g16;
         }
-        if (signs.on) flip_signs<EPT>(y, sign_word(signs, e0 >> 5) >> (e0 & 31));  // rotation H.D: D first
+        if (signs.on) {  // rotation H.D: D first
+            if constexpr (PIECES) {
+#pragma unroll
+                for (int rr = 0; rr < EPT / 8; ++rr) {
+                    const int p = 8 * rr + c;
+                    float(&y8)[8] = *reinterpret_cast<float(*)[8]>(&y[8 * rr]);
+                    flip_signs<8>(y8, sign_word(signs, p >> 2) >> (8 * (p & 3)));
+                }
+            } else {
+                flip_signs<EPT>(y, sign_word(signs, e0 >> 5) >> (e0 & 31));
+            }
+        }
         wht_cross_chunks<EPT>(y, lane);
         wht_inlane<EPT>(y);
         // the thresholds are operands of every element's compare block: pin them to registers once (as
         // constants the compiler would load them again in front of each block)
         asm volatile("" : "+v"(t1), "+v"(t2), "+v"(t3), "+v"(zref), "+v"(tscale));
         uint8_t codes[EPT];
-        uint8_t* dst = vstage + e0 * VST + t;
         if (VB != 3) {
             // 2 and 4 bits: sign and magnitude, magnitude = number of positive thresholds below |v_rot|
             constexpr int NTH = (1 << (VB - 1)) - 1;
@@ -373,7 +459,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const __half* __restrict__ 
         }
         if (!old_token) {
 #pragma unroll
-            for (int i = 0; i < EPT; ++i) dst[i * VST] = codes[i];
+            for (int i = 0; i < EPT; ++i) vstage[coord(i) * VST + t] = codes[i];
         }
     }
     __syncthreads();
