@@ -1,8 +1,9 @@
 // Encode / decode / export kernels of the packed pool (gfx950).
 //
 // One workgroup of 256 threads handles one tile (32 tokens) of one KV head.  Thread (t, c) owns D/8
-// head_dim elements of token t -- in encode the consecutive ones c*D/8 .., in decode every eighth 8-element
-// piece (8i + c), which makes every store instruction of the dense output write whole cache lines -- so a
+// head_dim elements of token t -- in decode, and in encode at head_dim 256, every eighth 8-element piece
+// (8i + c), which makes every access instruction to the dense tensors cover whole cache lines; in encode
+// at head_dim 64 and 128 the consecutive ones c*D/8 .., where that does not pay -- so a
 // dense row is read or written by 8 lanes and a wave covers 8 whole rows.  The Walsh-Hadamard transform
 // is log2(D/8) in-register stages plus three one-instruction DPP stages across those 8 lanes.  Both
 // kernels are written to stay under the HBM time in vector instructions: conversions are fused with
