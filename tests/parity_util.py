@@ -8,10 +8,14 @@ CPU oracle and compare to the stated bars:
   * dequantized K/V within 1e-3 relative, per vector, infinity norm;
   * attention output within 2e-3 absolute.  That bar is stated for the paper-scale workloads, whose
     value vectors have elements up to about 4; the tests of the value-codec variants also use vectors a
-    hundred times longer, and a row that attends such vectors carries the fp16 rounding of its
-    probabilities (2^-11 relative) on them.  There the bar is 2e-3 * max(1, B / 4) per output row, with
-    B = sum_t p_t * max_c |v_t[c]| the softmax-weighted magnitude of the values the row mixes (computed by
-    the oracle's own attention over the magnitudes).
+    hundred times longer.  The matrix kernel rounds a probability to fp16 (2^-11 relative: as a perturbed
+    softmax weight that moves the output by at most 2 * 2^-11 * B) and, in the codecs whose value scale
+    rides on the probability, rounds the product with the scale once more (2^-11 * B), where
+    B = sum_t p_t * max_c |v_t[c]| is the softmax-weighted magnitude of the values the row mixes (computed
+    by the oracle's own attention over the magnitudes).  For those pools the bar is, per output row,
+    max(2e-3, 3 * 2^-11 * B): what the arithmetic can lose at worst.  Measured on 200 tiny pools, where
+    nothing averages out: at most 0.9 * 2^-11 * B with such a scale, 0.3 * 2^-11 * B without, and
+    0.002 * 2^-11 * B in the fp32 vector kernel.
 """
 import numpy as np
 import torch
@@ -145,7 +149,7 @@ def attend_row_atol(K_hat, V_hat, Q, scale=None, tails=None, tail_causal=False):
         tails_mag = [(tk, np.broadcast_to(np.abs(np.asarray(tv, dtype=np.float64)).max(axis=-1, keepdims=True), tv.shape))
                      for tk, tv in tails]
     B = O.pool_attend(K_hat, mag, Q, scale=scale, tails=tails_mag, tail_causal=tail_causal)[..., :1]
-    return ATTEND_ATOL * np.maximum(1.0, B / 4.0)
+    return np.maximum(ATTEND_ATOL, 3.0 * 2.0 ** -11 * B)
 
 
 def compare_attend(out_gpu, out_ref, kv_heads, dirty_units=None, layer_begin=0, atol=ATTEND_ATOL):
