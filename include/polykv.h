@@ -214,6 +214,19 @@ size_t pool_attend_workspace(const polykv_pool* pool, const polykv_attend_params
 int pool_attend(const polykv_pool* pool, const void* Q_dev, void* out_dev,
                 const polykv_attend_params* params, void* stream);
 
+/* pool_attend for callers that cannot allocate device memory -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: the same operation, kernels and results, but the split partials live
+ * in a buffer of POLYKV_STATIC_WORKSPACE_BYTES that is part of the library's code object (every GPU the library
+ * runs on holds one until the process ends); params->workspace_dev / workspace_bytes are ignored.  The call
+ * allocates nothing on the host or the device.  POLYKV_ENOMEM, with the sizes in polykv_last_error(), if the
+ * call needs more scratch than that (pool_attend_workspace() says how much).  All calls on one GPU share that
+ * GPU's buffer: two calls that may run at the same time on one GPU (different streams) race -- order them, or
+ * use pool_attend with workspaces of the caller's.  Nothing in the buffer has to be cleared between calls:
+ * every call writes all the partials it later reads. */
+#define POLYKV_STATIC_WORKSPACE_BYTES (32u << 20)
+int pool_attend_static(const polykv_pool* pool, const void* Q_dev, void* out_dev,
+                       const polykv_attend_params* params, void* stream);
+
 /* The value codebook the library uses: 8 ascending centroids and the 7 decision thresholds
  * (midpoints), as fp32 (section "TurboQuant", Lloyd-Max quantization).  Host call. */
 void polykv_codebook(float* centroids8, float* thresholds7);

@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "polykv_internal.hpp"
@@ -413,6 +414,10 @@ size_t pool_attend_workspace(const polykv_pool* pool, const polykv_attend_params
     return plan.total;
 }
 
+// pool_attend with the workspace already resolved: `workspace` holds at least plan.total bytes.
+static int attend_with_workspace(const polykv_pool* pool, const AttendPlan& plan, const void* Q_dev, void* out_dev,
+                                 const polykv_attend_params* params, void* workspace, void* stream);
+
 int pool_attend(const polykv_pool* pool, const void* Q_dev, void* out_dev, const polykv_attend_params* params,
                 void* stream) {
     int rc = check_readable(pool, "pool_attend");
@@ -420,10 +425,6 @@ int pool_attend(const polykv_pool* pool, const void* Q_dev, void* out_dev, const
     AttendPlan plan;
     rc = make_plan(pool, params, &plan);
     if (rc != POLYKV_OK) return rc;
-    if (Q_dev == nullptr || out_dev == nullptr) {
-        set_error("pool_attend: NULL Q or out");
-        return POLYKV_EINVAL;
-    }
     if (params->workspace_dev == nullptr || ((uintptr_t)params->workspace_dev & 255) != 0) {
         set_error("pool_attend: workspace must be a 256-byte aligned device pointer");
         return POLYKV_EINVAL;
@@ -431,6 +432,66 @@ int pool_attend(const polykv_pool* pool, const void* Q_dev, void* out_dev, const
     if (params->workspace_bytes < plan.total) {
         set_error("pool_attend: workspace has %zu bytes, %zu needed", params->workspace_bytes, plan.total);
         return POLYKV_ENOMEM;
+    }
+    return attend_with_workspace(pool, plan, Q_dev, out_dev, params, params->workspace_dev, stream);
+}
+
+// ---- pool_attend_static: the split partials live in an array that is part of the library's code object.
+// Each GPU holds its own copy at its own address; the address is looked up once per device, with that device
+// current, and only that pointer -- never the array's name -- is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[POLYKV_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+// Device address of `scratch` on the current device (nullptr and an error message on failure).
+static void* static_scratch_for_current_device() {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        set_error("pool_attend_static: cannot identify the current device (HIP error %d, device %d)", (int)e, dev);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || ptr == nullptr) {
+            set_error("pool_attend_static: hipGetSymbolAddress failed on device %d: HIP error %d (%s)", dev, (int)e,
+                      hipGetErrorString(e));
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+int pool_attend_static(const polykv_pool* pool, const void* Q_dev, void* out_dev, const polykv_attend_params* params,
+                       void* stream) {
+    int rc = check_readable(pool, "pool_attend_static");
+    if (rc != POLYKV_OK) return rc;
+    AttendPlan plan;
+    rc = make_plan(pool, params, &plan);
+    if (rc != POLYKV_OK) return rc;
+    if (plan.total > (size_t)POLYKV_STATIC_WORKSPACE_BYTES) {
+        set_error("pool_attend_static: this call needs %zu bytes of scratch, the built-in buffer holds %zu; use "
+                  "pool_attend with a workspace of the caller's",
+                  plan.total, (size_t)POLYKV_STATIC_WORKSPACE_BYTES);
+        return POLYKV_ENOMEM;
+    }
+    void* ws = static_scratch_for_current_device();
+    if (ws == nullptr) return POLYKV_EHIP;
+    return attend_with_workspace(pool, plan, Q_dev, out_dev, params, ws, stream);
+}
+
+static int attend_with_workspace(const polykv_pool* pool, const AttendPlan& plan, const void* Q_dev, void* out_dev,
+                                 const polykv_attend_params* params, void* workspace, void* stream) {
+    if (Q_dev == nullptr || out_dev == nullptr) {
+        set_error("pool_attend: NULL Q or out");
+        return POLYKV_EINVAL;
     }
     if (((uintptr_t)Q_dev & 15) != 0 || ((uintptr_t)out_dev & 15) != 0) {
         set_error("pool_attend: Q and out must be 16-byte aligned");
@@ -449,8 +510,8 @@ int pool_attend(const polykv_pool* pool, const void* Q_dev, void* out_dev, const
             }
         }
     }
-    return hip_result(launch_attend(pool, plan, Q_dev, out_dev, plan.has_tails ? &tails : nullptr,
-                                    params->workspace_dev, (hipStream_t)stream),
+    return hip_result(launch_attend(pool, plan, Q_dev, out_dev, plan.has_tails ? &tails : nullptr, workspace,
+                                    (hipStream_t)stream),
                       "pool_attend");
 }
 

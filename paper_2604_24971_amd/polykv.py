@@ -20,6 +20,7 @@ VALUES_TQ2, VALUES_TQ2_SCALED, VALUES_TQ4, VALUES_TQ4_SCALED = 3, 4, 5, 6
 VALUE_BITS = {0: 3, 1: 3, 2: 8, 3: 2, 4: 2, 5: 4, 6: 4}
 KEYS_Q8_BLOCK32, KEYS_Q8_TENSOR = 0, 1
 MAX_TAIL_AGENTS = 64
+STATIC_WORKSPACE_BYTES = 32 << 20
 
 
 class PolyKVError(RuntimeError):
@@ -82,6 +83,8 @@ def _load():
     lib.pool_attend_workspace.restype = sz
     lib.pool_attend.argtypes = [vp, vp, vp, C.POINTER(AttendParams), vp]
     lib.pool_attend.restype = ip
+    lib.pool_attend_static.argtypes = [vp, vp, vp, C.POINTER(AttendParams), vp]
+    lib.pool_attend_static.restype = ip
     lib.polykv_codebook.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_float)]
     lib.polykv_codebook.restype = None
     lib.polykv_codebook_bits.argtypes = [ip, C.POINTER(C.c_float), C.POINTER(C.c_float)]
@@ -317,4 +320,12 @@ class Pool:
             out = torch.empty(Q.shape, dtype=torch.float32, device=self.device)
         _check(lib.pool_attend(self._h, _dev_ptr(Q, Q.dtype, "Q"), _dev_ptr(out, torch.float32, "out"),
                                C.byref(p), _stream_ptr(stream)))
+        return out
+
+    # pool_attend_static(Q[agents], out): no workspace, nothing allocated by the library
+    def attend_static(self, Q: torch.Tensor, out: torch.Tensor, *, q_heads=None, layer_begin=0, layer_end=None,
+                      scale=None, tails=None, kernel=KERNEL_AUTO, splits=0, stream=None, tail_causal=False):
+        p, _keep = self._params(Q, q_heads, layer_begin, layer_end, scale, tails, kernel, splits, tail_causal)
+        _check(lib.pool_attend_static(self._h, _dev_ptr(Q, Q.dtype, "Q"), _dev_ptr(out, torch.float32, "out"),
+                                      C.byref(p), _stream_ptr(stream)))
         return out
