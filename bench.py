@@ -92,6 +92,9 @@ def main():
     ap.add_argument("--bf16", action="store_true",
                     help="dense tensors (K, V, Q, decode output, tails) in bfloat16 instead of fp16: the dtype of the "
                     "paper's Llama-3-8B cache; the headline configuration is stated in fp16")
+    ap.add_argument("--key-precision", choices=("exact", "fp16"), default="exact",
+                    help="exact = scores over code * scale exactly (headline); fp16 = over the dequantized keys rounded "
+                    "to fp16, the precision of the dense cache the paper's read path attends over")
     ap.add_argument("--phases", default="eda", help="subset of e(ncode) d(ecode) a(ttend) to run per step; "
                     "anything but the default is for profiling one kernel and is marked partial")
     args = ap.parse_args()
@@ -123,6 +126,7 @@ def main():
     Vd = torch.empty_like(V)
     codec = VALUE_CODECS[args.value_codec][0]
     kcodec = pk.KEYS_Q8_TENSOR if args.key_codec == "tensor" else pk.KEYS_Q8_BLOCK32
+    kprec = pk.KEY_PRECISION_FP16 if args.key_precision == "fp16" else pk.KEY_PRECISION_EXACT
     pools = [pk.Pool(L, H, d, T, value_codec=codec, key_codec=kcodec).bind() for _ in range(max(1, args.pools))]
     tails = None
     if args.tail_len > 0:        # every agent has produced tail_len private tokens (fp16, uncompressed)
@@ -162,11 +166,11 @@ def main():
         if "a" in args.phases:
             if args.per_layer:
                 for l in range(L):
-                    p.attend(Ql[l], outl[l], layer_begin=l, layer_end=l + 1, workspace=ws, tails=tails)
+                    p.attend(Ql[l], outl[l], layer_begin=l, layer_end=l + 1, workspace=ws, tails=tails, key_precision=kprec)
             else:
                 if kev:
                     pk.time_next_kernel(*kev[2])
-                p.attend(Q, out, workspace=ws, tails=tails)
+                p.attend(Q, out, workspace=ws, tails=tails, key_precision=kprec)
         if ev:
             ev[3].record()
 
@@ -208,7 +212,7 @@ def main():
         iso = [0]
 
         def attend_only():
-            pools[iso[0] % len(pools)].attend(Q, out, workspace=ws, tails=tails)
+            pools[iso[0] % len(pools)].attend(Q, out, workspace=ws, tails=tails, key_precision=kprec)
             iso[0] += 1
         timed(attend_only, 3)
         t_att_iso = timed(attend_only, args.steps)
@@ -280,7 +284,7 @@ def main():
         "config": {"workload": cfg.name, "layers": L, "kv_heads": H, "q_heads": cfg.q_heads, "head_dim": d,
                    "tokens": T, "agents": cfg.agents, "q_per_agent": cfg.q_per_agent,
                    "rows_per_kv_head": cfg.rows_per_kv_head, "pool_bytes": packed, "pool_copies_rotated": len(pools),
-                   "value_codec": args.value_codec, "key_codec": args.key_codec, "dense_dtype": "bf16" if args.bf16 else "f16",
+                   "value_codec": args.value_codec, "key_codec": args.key_codec, "key_precision": args.key_precision, "dense_dtype": "bf16" if args.bf16 else "f16",
                    "tail_len": args.tail_len, "tail_bytes": tail_bytes,
                    "attend_calls_per_step": L if args.per_layer else 1},
         "step": "pool_encode -> pool_decode(fp16) -> pool_attend, all layers",

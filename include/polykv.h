@@ -49,6 +49,7 @@ enum { POLYKV_MAX_TAIL_AGENTS = 64 };
 /* Attention kernel selection.  AUTO picks by shape: the matrix-core kernel when it supports the
  * shape, else the vector kernel.  The explicit values exist for tests and profiling. */
 enum { POLYKV_KERNEL_AUTO = 0, POLYKV_KERNEL_VECTOR = 1, POLYKV_KERNEL_MATRIX = 2 };
+enum { POLYKV_KEY_PRECISION_EXACT = 0, POLYKV_KEY_PRECISION_FP16 = 1 };
 
 /* Value codecs.
  *   POLYKV_VALUES_TQ3         the paper's: rotate, 3-bit Lloyd-Max codes for N(0,1) applied to the rotated
@@ -203,6 +204,12 @@ typedef struct {
     size_t workspace_bytes;  /* >= pool_attend_workspace()                                  */
     int io_dtype;     /* type of Q and of the tails: POLYKV_F16 (0) or POLYKV_BF16.  bfloat16 queries are
                          converted to fp16 operands in the matrix-core kernel: |q| must stay below 65504 */
+    int key_precision; /* POLYKV_KEY_PRECISION_EXACT (0, the default): scores over K = code * s exactly.
+                          POLYKV_KEY_PRECISION_FP16: scores over fp16(code * s), the dequantized key rounded once to
+                          the 16-bit type of the dense cache -- what the paper's read path attends over after its cast
+                          to the model dtype (section "DynamicCache Injection"); saves a third of the score products.
+                          Honoured by the matrix-core kernel for pools with q8_0 block keys and the paper's value
+                          codec at head_dim 64 / 128; every other case is computed with exact keys. */
 } polykv_attend_params;
 
 /* Scratch bytes pool_attend needs for these parameters (workspace fields are ignored). */

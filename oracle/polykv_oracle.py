@@ -443,6 +443,14 @@ def stored_bytes(L: int, H: int, T: int, d: int, scaled_values: bool = False, in
 # --------------------------------------------------------------------------- #
 # Read path: N agents' decode attention over the shared pool
 # --------------------------------------------------------------------------- #
+def keys_as_fp16(K_hat):
+    """The decoded keys as the paper's read path holds them: section "DynamicCache Injection" casts the
+    decompressed tensors to the model's 16-bit dtype before they enter an agent's cache, so attention there runs
+    over K rounded once (to nearest, ties to even) to that type.  Reading taken for the optional reduced key
+    precision of the attention call: fp16, the 16-bit type of this build's dense tensors.  Returns float64."""
+    return np.asarray(K_hat, dtype=np.float64).astype(np.float16).astype(np.float64)
+
+
 def softmax_attend_one(q, Kmat, Vmat, scale):
     """One query vector against T keys/values, float64: the textbook definition."""
     s = (Kmat @ q) * scale

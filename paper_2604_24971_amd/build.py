@@ -33,17 +33,16 @@ def _run(cmd):
 
 
 def _check_no_scratch(remarks: str):
-    """The matrix-core attention kernel parks its query operands in accumulation registers; builds in which
-    the register allocator then spilled some of them to scratch memory returned wrong results on the GPU
-    (head_dim 256 and the int8 codec at head_dim 128 with 64-row blocks, both since reshaped).  Refuse such a
-    build: every instantiation that parks (head_dim 64 and 128) must come out without scratch."""
+    """The matrix-core attention kernel keeps its accumulators, parked query operands and score tiles in all 512
+    registers of a wave; builds in which the register allocator spilled part of that to scratch memory returned
+    wrong results on the GPU.  Refuse such a build: every instantiation must come out without scratch."""
     name = None
     for line in remarks.splitlines():
         if "Function Name:" in line:
             name = line.split("Function Name:")[1].split()[0]
-        elif "ScratchSize" in line and name and "attend_mfma_kernel" in name and "Li256E" not in name:
+        elif "ScratchSize" in line and name and "attend_mfma_kernel" in name:
             size = int(line.split("ScratchSize [bytes/lane]:")[1].split()[0])
-            if size:
+            if size and not os.environ.get("POLYKV_BUILD_ALLOW_SCRATCH"):   # (the variable is for timing experiments only)
                 raise RuntimeError("%s spills %d bytes per lane to scratch: reduce its register use" % (name, size))
 
 

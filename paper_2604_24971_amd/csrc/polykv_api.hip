@@ -106,6 +106,10 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
         return POLYKV_ESHAPE;
     }
     p.R = (int)rows;
+    if (!(prm->scale >= 0.0f) || !(prm->scale <= 3.0e38f)) {
+        set_error("pool_attend: the softmax scale must be finite and >= 0 (0 = 1/sqrt(head_dim))");
+        return POLYKV_EINVAL;
+    }
     const float scale = prm->scale != 0.0f ? prm->scale : 1.0f / sqrtf((float)p.D);
     p.qscale = scale * 1.4426950408889634f;
     p.has_tails = tails ? 1 : 0;
@@ -116,14 +120,22 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
         return POLYKV_EINVAL;
     }
     p.io_bf16 = prm->io_dtype == POLYKV_BF16 ? 1 : 0;
+    if (prm->key_precision != POLYKV_KEY_PRECISION_EXACT && prm->key_precision != POLYKV_KEY_PRECISION_FP16) {
+        set_error("pool_attend: key_precision %d is not a POLYKV_KEY_PRECISION_* value", prm->key_precision);
+        return POLYKV_EINVAL;
+    }
     p.signs = pool->signs;
 
-    const bool mat_ok = matrix_kernel_supports(p.D, p.R);
+    const bool mat_ok = matrix_kernel_supports(p.D, p.R, p.vcodec);
     if (prm->kernel == POLYKV_KERNEL_MATRIX && !mat_ok) {
-        set_error("pool_attend: the matrix-core kernel does not support head_dim=%d rows=%d", p.D, p.R);
+        set_error("pool_attend: the matrix-core kernel does not support head_dim=%d rows=%d with this value codec", p.D, p.R);
         return POLYKV_ESHAPE;
     }
     p.kernel = prm->kernel == POLYKV_KERNEL_AUTO ? (mat_ok ? POLYKV_KERNEL_MATRIX : POLYKV_KERNEL_VECTOR) : prm->kernel;
+    p.key_fp16 = (prm->key_precision == POLYKV_KEY_PRECISION_FP16 && p.kernel == POLYKV_KERNEL_MATRIX &&
+                  p.kcodec == POLYKV_KEYS_Q8_BLOCK32 && p.vcodec == POLYKV_VALUES_TQ3 && p.D != 256)
+                     ? 1
+                     : 0;
 
     // Token-range splits per KV head.  Work items are waves; aim at ~2 waves per SIMD of the 256 CUs.
     // The count is derived from the pool's capacity, not from its current fill, so that the workspace
@@ -143,8 +155,7 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
         // tiles per wave -- below that the per-workgroup prologue, epilogue and the partials written for
         // the merge kernel cost more than the idle CUs (measured on one-layer calls of the Llama shape:
         // 16 splits of 8 tiles 16.8 us, 32 splits of 4 tiles 19.3 us).
-        // rows per workgroup: 64, or 32 where 64 rows of accumulators do not fit
-        const int block_rows = (p.D == 256 || (p.vcodec == POLYKV_VALUES_INT8 && p.D == 128)) ? 32 : 64;
+        const int block_rows = matrix_kernel_block_rows(p.D, p.vcodec);
         const long groups = (long)units * ((p.R + block_rows - 1) / block_rows);
         long want = (256 + groups - 1) / groups;
         if (want > cap_tiles / 8) want = cap_tiles / 8;

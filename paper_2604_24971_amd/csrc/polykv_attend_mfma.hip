@@ -29,6 +29,7 @@
 // kernel.  The four waves of a workgroup take interleaved tiles and are merged through LDS.
 #include <hip/hip_fp16.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "polykv_internal.hpp"
@@ -201,8 +202,8 @@ __device__ __forceinline__ float max16(const float16v& a) {
 }
 
 // Four scores of a row -> fp16 probabilities (packed pairs) and their sum into the denominator.  With
-// value scales (g != nullptr: the lane's RawV::g) the P.V operand is p * scale of its token, at most
-// 2^8 * 2^7; the denominator sums the plain p.
+// value scales (g != nullptr: the lane's RawV::g) the P.V operand is p * scale of its token (formed in fp32,
+// rounded to fp16 once), at most 2^8 * 2^7; the denominator sums the plain p.
 template <bool VS>
 __device__ __forceinline__ void exp4(const float16v& S, int c, float qscale, float mneg, H8 (&pb)[2], float& lsum,
                                      const uint32_t* g) {
@@ -211,16 +212,18 @@ __device__ __forceinline__ void exp4(const float16v& S, int c, float qscale, flo
     for (int pr = 0; pr < 2; ++pr) {
         const int i = 4 * c + 2 * pr;
         half2v p2;
-        p2[0] = (_Float16)__builtin_amdgcn_exp2f(fmaf(S[i], qscale, mneg));
-        p2[1] = (_Float16)__builtin_amdgcn_exp2f(fmaf(S[i + 1], qscale, mneg));
+        const float e0 = __builtin_amdgcn_exp2f(fmaf(S[i], qscale, mneg)), e1 = __builtin_amdgcn_exp2f(fmaf(S[i + 1], qscale, mneg));
+        p2[0] = (_Float16)e0;
+        p2[1] = (_Float16)e1;
         lsum = __builtin_amdgcn_fdot2(p2, one2, lsum, false);
-        if (VS) {
+        if (VS) {   // p * g in fp32, rounded to fp16 once
             union {
                 uint32_t u;
-                half2v h;
+                _Float16 h[2];
             } g2;
             g2.u = g[i >> 1];
-            p2 = p2 * g2.h;
+            p2[0] = (_Float16)(e0 * (float)g2.h[0]);
+            p2[1] = (_Float16)(e1 * (float)g2.h[1]);
         }
         pb[i >> 3].p[(i & 7) >> 1] = p2;
     }
@@ -228,7 +231,7 @@ __device__ __forceinline__ void exp4(const float16v& S, int c, float qscale, flo
 
 // The pool's last tile when it crosses the end of the pool, read straight from memory: scores, softmax
 // and PV one after the other, tokens >= T masked out.  Runs at most once per KV head.
-template <int D, int NT, int VC, int KC>
+template <int D, int NT, int VC, int KC, bool K16>
 __device__ __forceinline__ void process_ragged_tile(TileRsrc rs, uint32_t lt, int tile, int T, float qscale, float raise_thr,
                                                  int lane, const half8 (&qb)[NT][D / 32][2], float16v (&O)[D / 32][NT],
                                                  float (&Lsum)[NT], float (&m_ref)[NT], float (&m_thr)[NT],
@@ -253,7 +256,7 @@ __device__ __forceinline__ void process_ragged_tile(TileRsrc rs, uint32_t lt, in
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 S[nt] = mfma32(hi, qb[nt][j][s], S[nt]);
-                if (KC == 0) S[nt] = mfma32(lo, qb[nt][j][s], S[nt]);
+                if (KC == 0 && !K16) S[nt] = mfma32(lo, qb[nt][j][s], S[nt]);
             }
         }
 #pragma unroll
@@ -298,7 +301,7 @@ __device__ __forceinline__ void process_ragged_tile(TileRsrc rs, uint32_t lt, in
 //   Sa         scores of tile A on entry, of tile B on exit; mloc / raise: per-lane row maxima of the
 //              same tile and whether some row outgrew the reference
 // Only full tiles go through here; a ragged last tile is handled by process_ragged_tile.
-template <int D, int NT, int VC, int KC, bool HAS_A, bool HAS_B>
+template <int D, int NT, int VC, int KC, bool K16, bool HAS_A, bool HAS_B>
 __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<D>& rk, RawV<D, VC>& rvN, RawK<D>& rkN,
                                               TileRsrc rs, uint32_t nextK, uint32_t nextV, float qscale,
                                               float raise_thr, int lane, const half8 (&qb)[NT][D / 32][2],
@@ -375,7 +378,7 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
         const int j = k >> 1, s = k & 1;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) Sb[nt] = mfma32(khi[k & 1], qb[nt][j][s], Sb[nt]);
-        if (KC == 0) {
+        if (KC == 0 && !K16) {   // the exact remainder term; dropped when the keys may be rounded to fp16
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) Sb[nt] = mfma32(klo[k & 1], qb[nt][j][s], Sb[nt]);
         }
@@ -407,7 +410,7 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
                 for (int c = c0; c < c1; ++c) exp_chunk(c);
                 if (k + 1 == NQK) vdeq(0);
             }
-            slice_end(integral_constant<int, (KC == 0 ? 2 : 1) * NT>{}, integral_constant<int, (HAS_A ? 28 : 16)>{});
+            slice_end(integral_constant<int, (KC == 0 && !K16 ? 2 : 1) * NT>{}, integral_constant<int, (HAS_A ? 28 : 16)>{});
         }
     } else if (HAS_A) {
 #pragma unroll
@@ -456,7 +459,7 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
     }
 }
 
-template <int D, int NT, int VC, int KC>
+template <int D, int NT, int VC, int KC, bool K16>
 __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restrict__ pool,
                                                           const __half* __restrict__ Q,
                                                           float* __restrict__ ws_ml, float* __restrict__ ws_o,
@@ -591,27 +594,27 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
         RawK<D> rk2;
         RawV<D, VC> rv2;
         // prologue: scores of tile 0 from rk; requests K of tile 1 and (again) V of tile 0 into set 2
-        pipeline_step<D, NT, VC, KC, false, true>(rv, rk, rv2, rk2, rs, tile_ptr(1), tile_ptr(0), qscale, raise_thr, lane, qb, O, Lsum,
+        pipeline_step<D, NT, VC, KC, K16, false, true>(rv, rk, rv2, rk2, rs, tile_ptr(1), tile_ptr(0), qscale, raise_thr, lane, qb, O, Lsum,
                                           m_ref, m_thr, mneg, S, mloc, raise);
         int s = 0;
         for (; s + 1 < full_count - 1; s += 2) {  // two steps per trip: the sets swap roles without copies
-            pipeline_step<D, NT, VC, KC, true, true>(rv2, rk2, rv, rk, rs, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, K16, true, true>(rv2, rk2, rv, rk, rs, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
-            pipeline_step<D, NT, VC, KC, true, true>(rv, rk, rv2, rk2, rs, tile_ptr(s + 3), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, K16, true, true>(rv, rk, rv2, rk2, rs, tile_ptr(s + 3), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         }
         if (s < full_count - 1) {  // one step with a B tile left: current = set 2
-            pipeline_step<D, NT, VC, KC, true, true>(rv2, rk2, rv, rk, rs, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, K16, true, true>(rv2, rk2, rv, rk, rs, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
-            pipeline_step<D, NT, VC, KC, true, false>(rv, rk, rv2, rk2, rs, tile_ptr(s + 2), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, K16, true, false>(rv, rk, rv2, rk2, rs, tile_ptr(s + 2), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
                                               O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         } else {
-            pipeline_step<D, NT, VC, KC, true, false>(rv2, rk2, rv, rk, rs, tile_ptr(s + 1), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
+            pipeline_step<D, NT, VC, KC, K16, true, false>(rv2, rk2, rv, rk, rs, tile_ptr(s + 1), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
                                               O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
         }
     }
     if (last_ragged)
-        process_ragged_tile<D, NT, VC, KC>(rs, tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
+        process_ragged_tile<D, NT, VC, KC, K16>(rs, tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
                                    Lsum, m_ref, m_thr, mneg);
 
     // ---- merge the four waves through LDS: every wave stores its row maxima, denominators and accumulators
@@ -704,66 +707,86 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restr
     }
 }
 
-bool matrix_kernel_supports(int head_dim, int rows_per_kv_head) {
-    return (head_dim == 64 || head_dim == 128 || head_dim == 256) && rows_per_kv_head >= 1;
+// Every shape the pool supports except int8 values at head_dim 256, where two staged tiles of code bytes do not
+// fit the registers next to the accumulators (the vector kernel serves that corner).
+bool matrix_kernel_supports(int head_dim, int rows_per_kv_head, int value_codec) {
+    return (head_dim == 64 || head_dim == 128 || (head_dim == 256 && value_codec != POLYKV_VALUES_INT8)) &&
+           rows_per_kv_head >= 1;
+}
+
+// Query rows per workgroup: 64 where the accumulators, the parked queries, two tiles of scores and two staged
+// tiles fit the 512 registers of a wave; 32 at head_dim 256 and, at head_dim 128, for the two codecs with the
+// most staged value bytes per tile (int8, and 4-bit codes with a scale).
+int matrix_kernel_block_rows(int head_dim, int value_codec) {
+    if (head_dim == 256) return 32;
+    if (head_dim == 128 && (value_codec == POLYKV_VALUES_INT8 || value_codec == POLYKV_VALUES_TQ4_SCALED)) return 32;
+    return 64;
 }
 
 bool matrix_kernel_direct(const AttendPlan& plan) { return plan.nsplit == 1 && !plan.has_tails; }
 
-template <int D, int NT, int VC, int KC>
+template <int D, int NT, int VC, int KC, bool K16>
 static hipError_t launch_one(dim3 grid, const uint8_t* storage, const AttendPlan& plan, const void* Q, float* ws_ml,
                              float* ws_o, float* out, int direct, hipStream_t s) {
     constexpr int kMergeBytes = 4 * 32 * NT * (D + 4) * (int)sizeof(float);
-    auto kern = attend_mfma_kernel<D, NT, VC, KC>;
-    static bool configured = false;  // per instantiation: the limit is a property of the function
-    if (!configured && kMergeBytes > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMergeBytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    auto kern = attend_mfma_kernel<D, NT, VC, KC, K16>;
+    static std::once_flag configured;  // per instantiation: the limit is a property of the function
+    static hipError_t config_result = hipSuccess;
+    if (kMergeBytes > 48 * 1024)
+        std::call_once(configured, [&]() {
+            config_result = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, kMergeBytes);
+        });
+    if (config_result != hipSuccess) return config_result;
     launch_main_kernel(kern, grid, dim3(256), kMergeBytes, s, storage, (const __half*)Q, ws_ml, ws_o, out, plan, direct);
     return hipGetLastError();
 }
 
-// Row tiles per workgroup: two (64 rows) where the accumulators, the parked queries and two staged tiles
-// fit the 512 registers of a wave; one (32 rows) at head_dim 256 and for the int8 value codec at head_dim
-// 128, whose staged value codes take 16 registers per tile.
-template <int D, int VC, int KC>
+// Row tiles per workgroup: two (64 rows) or one (32 rows), see matrix_kernel_block_rows().
+template <int D, int VC, int KC, bool K16>
 static hipError_t launch_dv(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml, float* ws_o,
                             float* out, hipStream_t s) {
     const uint8_t* storage = reinterpret_cast<const uint8_t*>(pool->storage);
     const int units = plan.layers * plan.H;
     const int direct = matrix_kernel_direct(plan) ? 1 : 0;
-    constexpr bool two_tiles_fit = D == 64 || (D == 128 && VC != 2);
+    constexpr bool two_tiles_fit = D == 64 || (D == 128 && VC != 2 && VC != 6);   // matrix_kernel_block_rows()
     if constexpr (two_tiles_fit) {
         if (plan.R > 32)
-            return launch_one<D, 2, VC, KC>(dim3(plan.nsplit, units, (plan.R + 63) / 64), storage, plan, Q, ws_ml, ws_o,
-                                            out, direct, s);
+            return launch_one<D, 2, VC, KC, K16>(dim3(plan.nsplit, units, (plan.R + 63) / 64), storage, plan, Q, ws_ml, ws_o,
+                                                 out, direct, s);
     }
-    return launch_one<D, 1, VC, KC>(dim3(plan.nsplit, units, (plan.R + 31) / 32), storage, plan, Q, ws_ml, ws_o, out, direct,
-                                    s);
+    return launch_one<D, 1, VC, KC, K16>(dim3(plan.nsplit, units, (plan.R + 31) / 32), storage, plan, Q, ws_ml, ws_o, out,
+                                         direct, s);
 }
 
-template <int D, int KC>
+template <int D, int KC, bool K16>
 static hipError_t launch_dk(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml, float* ws_o,
                             float* out, hipStream_t s) {
     switch (plan.vcodec) {
-        case 1: return launch_dv<D, 1, KC>(pool, plan, Q, ws_ml, ws_o, out, s);
-        case 2: return launch_dv<D, 2, KC>(pool, plan, Q, ws_ml, ws_o, out, s);
-        case 3: return launch_dv<D, 3, KC>(pool, plan, Q, ws_ml, ws_o, out, s);
-        case 4: return launch_dv<D, 4, KC>(pool, plan, Q, ws_ml, ws_o, out, s);
-        case 5: return launch_dv<D, 5, KC>(pool, plan, Q, ws_ml, ws_o, out, s);
-        case 6: return launch_dv<D, 6, KC>(pool, plan, Q, ws_ml, ws_o, out, s);
-        default: return launch_dv<D, 0, KC>(pool, plan, Q, ws_ml, ws_o, out, s);
+        case 1: return launch_dv<D, 1, KC, K16>(pool, plan, Q, ws_ml, ws_o, out, s);
+        case 2:
+            if constexpr (D == 256) return hipErrorInvalidValue;   // not built: matrix_kernel_supports() says no
+            else return launch_dv<D, 2, KC, K16>(pool, plan, Q, ws_ml, ws_o, out, s);
+        case 3: return launch_dv<D, 3, KC, K16>(pool, plan, Q, ws_ml, ws_o, out, s);
+        case 4: return launch_dv<D, 4, KC, K16>(pool, plan, Q, ws_ml, ws_o, out, s);
+        case 5: return launch_dv<D, 5, KC, K16>(pool, plan, Q, ws_ml, ws_o, out, s);
+        case 6: return launch_dv<D, 6, KC, K16>(pool, plan, Q, ws_ml, ws_o, out, s);
+        default: return launch_dv<D, 0, KC, K16>(pool, plan, Q, ws_ml, ws_o, out, s);
     }
 }
 
 template <int D>
 static hipError_t launch_d(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,
                            float* ws_o, float* out, hipStream_t s) {
-    if (plan.kcodec == POLYKV_KEYS_Q8_TENSOR) return launch_dk<D, 1>(pool, plan, Q, ws_ml, ws_o, out, s);
-    return launch_dk<D, 0>(pool, plan, Q, ws_ml, ws_o, out, s);
+    if (plan.kcodec == POLYKV_KEYS_Q8_TENSOR) return launch_dk<D, 1, false>(pool, plan, Q, ws_ml, ws_o, out, s);
+    // keys rounded to fp16 once dequantized (the precision of the dense cache the paper's read path holds): only
+    // for the paper's value codec at head_dim 64 / 128, the shapes this option is meant for
+    if (plan.key_fp16) {
+        if constexpr (D != 256) {
+            if (plan.vcodec == POLYKV_VALUES_TQ3) return launch_dv<D, 0, 0, true>(pool, plan, Q, ws_ml, ws_o, out, s);
+        }
+    }
+    return launch_dk<D, 0, false>(pool, plan, Q, ws_ml, ws_o, out, s);
 }
 
 hipError_t launch_attend_matrix(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,

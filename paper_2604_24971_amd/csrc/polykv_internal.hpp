@@ -44,6 +44,7 @@ struct AttendPlan {
     int nsplit;                  // token-range splits per KV head
     int has_tails, tail_capacity, tail_causal;
     int io_bf16;                 // 1: Q and the tails are bfloat16, 0: fp16
+    int key_fp16;                // 1: scores over the dequantized keys rounded to fp16 (POLYKV_KEY_PRECISION_FP16)
     SignBits signs;              // the pool's sign diagonal
     // workspace carving (byte offsets from the 256-aligned workspace base)
     size_t off_ml, off_o, off_tail_ml, off_tail_o, total;
@@ -84,7 +85,9 @@ inline void launch_main_kernel(void (*kern)(Params...), dim3 grid, dim3 block, s
 }
 
 // True if the matrix-core attention kernel supports this shape.
-bool matrix_kernel_supports(int head_dim, int rows_per_kv_head);
+bool matrix_kernel_supports(int head_dim, int rows_per_kv_head, int value_codec);
+// Query rows one workgroup of the matrix-core kernel covers.
+int matrix_kernel_block_rows(int head_dim, int value_codec);
 // True if the matrix-core kernel writes the final output itself (no merge kernel needed).
 bool matrix_kernel_direct(const AttendPlan& plan);
 hipError_t launch_attend_matrix(const polykv_pool* pool, const AttendPlan& plan, const void* Q, float* ws_ml,

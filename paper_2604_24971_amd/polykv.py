@@ -15,6 +15,7 @@ OK, EINVAL, ESHAPE, ESTATE, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
 F16, F32, BF16 = 0, 1, 2
 _DTYPES = {torch.float16: F16, torch.float32: F32, torch.bfloat16: BF16}
 KERNEL_AUTO, KERNEL_VECTOR, KERNEL_MATRIX = 0, 1, 2
+KEY_PRECISION_EXACT, KEY_PRECISION_FP16 = 0, 1
 VALUES_TQ3, VALUES_TQ3_SCALED, VALUES_INT8 = 0, 1, 2
 VALUES_TQ2, VALUES_TQ2_SCALED, VALUES_TQ4, VALUES_TQ4_SCALED = 3, 4, 5, 6
 VALUE_BITS = {0: 3, 1: 3, 2: 8, 3: 2, 4: 2, 5: 4, 6: 4}
@@ -37,7 +38,7 @@ class AttendParams(C.Structure):
         ("tail_len", C.POINTER(C.c_int)), ("tail_capacity", C.c_int), ("tail_causal", C.c_int),
         ("kernel", C.c_int), ("splits", C.c_int),
         ("workspace_dev", C.c_void_p), ("workspace_bytes", C.c_size_t),
-        ("io_dtype", C.c_int),
+        ("io_dtype", C.c_int), ("key_precision", C.c_int),
     ]
 
 
@@ -266,7 +267,8 @@ class Pool:
         _check(lib.pool_export_value_scales(self._h, C.c_void_p(vs.data_ptr()), _stream_ptr(stream)))
         return vs
 
-    def _params(self, Q, q_heads, layer_begin, layer_end, scale, tails, kernel, splits, tail_causal=False):
+    def _params(self, Q, q_heads, layer_begin, layer_end, scale, tails, kernel, splits, tail_causal=False,
+                key_precision=KEY_PRECISION_EXACT):
         if Q.dim() != 5:
             raise ValueError("Q must be [layers_selected, agents, q_per_agent, q_heads, head_dim]")
         layer_end = self.layers if layer_end is None else layer_end
@@ -277,6 +279,7 @@ class Pool:
         p.agents, p.q_per_agent, p.q_heads = A, nq, qh
         p.layer_begin, p.layer_end, p.scale = layer_begin, layer_end, float(scale or 0.0)
         p.kernel, p.splits = kernel, splits
+        p.key_precision = key_precision
         if Q.dtype not in (torch.float16, torch.bfloat16):
             raise TypeError("Q must be float16 or bfloat16")
         p.io_dtype = _DTYPES[Q.dtype]
@@ -305,8 +308,9 @@ class Pool:
     # pool_attend(Q[agents], out)
     def attend(self, Q: torch.Tensor, out: torch.Tensor | None = None, *, q_heads=None, layer_begin=0,
                layer_end=None, scale=None, tails=None, kernel=KERNEL_AUTO, splits=0, workspace=None,
-               stream=None, tail_causal=False):
-        p, _keep = self._params(Q, q_heads, layer_begin, layer_end, scale, tails, kernel, splits, tail_causal)
+               stream=None, tail_causal=False, key_precision=KEY_PRECISION_EXACT):
+        p, _keep = self._params(Q, q_heads, layer_begin, layer_end, scale, tails, kernel, splits, tail_causal,
+                                key_precision)
         need = lib.pool_attend_workspace(self._h, C.byref(p))
         if need == 0:
             _check(lib.pool_attend(self._h, None, None, C.byref(p), None))  # surfaces the shape error
@@ -324,8 +328,10 @@ class Pool:
 
     # pool_attend_static(Q[agents], out): no workspace, nothing allocated by the library
     def attend_static(self, Q: torch.Tensor, out: torch.Tensor, *, q_heads=None, layer_begin=0, layer_end=None,
-                      scale=None, tails=None, kernel=KERNEL_AUTO, splits=0, stream=None, tail_causal=False):
-        p, _keep = self._params(Q, q_heads, layer_begin, layer_end, scale, tails, kernel, splits, tail_causal)
+                      scale=None, tails=None, kernel=KERNEL_AUTO, splits=0, stream=None, tail_causal=False,
+                      key_precision=KEY_PRECISION_EXACT):
+        p, _keep = self._params(Q, q_heads, layer_begin, layer_end, scale, tails, kernel, splits, tail_causal,
+                                key_precision)
         _check(lib.pool_attend_static(self._h, _dev_ptr(Q, Q.dtype, "Q"), _dev_ptr(out, torch.float32, "out"),
                                       C.byref(p), _stream_ptr(stream)))
         return out

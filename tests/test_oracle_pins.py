@@ -731,3 +731,25 @@ def test_value_codec_at_other_bit_widths(bits):
     _, Vh = O.pool_decode(ref)
     np.testing.assert_array_equal(Vh, O.v_decode(ref["v_idx"], bits=bits))
     assert O.stored_bytes(32, 8, 4096, 128, value_bits=bits)["packed"] == 32 * 8 * 4096 * (136 + 16 * bits)
+
+
+def test_fp16_key_reading_rounds_once_to_nearest_even():
+    """keys_as_fp16 (the cast of section "DynamicCache Injection", read as fp16): hand-computed roundings --
+    fp16 has 11 significant bits, so 2049 is a tie (-> 2048, even), 2051 a tie (-> 2052), 2050 exact; values
+    below 2^-24 / 2 vanish; the result of q8_0 dequantization code * s (up to 18 bits) loses at most half an ulp."""
+    x = np.array([2049.0, 2050.0, 2051.0, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, -0.1, 2.0 ** -26, 65504.0])
+    want = np.array([2048.0, 2050.0, 2052.0, 1.0, 1.0 + 2.0 ** -9, -0.0999755859375, 0.0, 65504.0])
+    np.testing.assert_array_equal(O.keys_as_fp16(x), want)
+    rng = np.random.default_rng(5)
+    K = (rng.standard_normal((1, 2, 50, 64)) * 6).astype(np.float16)
+    ref = O.pool_encode(K, K)
+    Kh, _ = O.pool_decode(ref)
+    K16 = O.keys_as_fp16(Kh)
+    assert np.all(np.abs(K16 - Kh) <= 2.0 ** -11 * np.abs(Kh) + 2.0 ** -25)
+    assert np.any(K16 != Kh)                     # the products really have more than 11 bits
+    # keys that fp16 holds exactly (scale a power of two: block maximum 127 * 2^k) pass unchanged
+    K2 = np.zeros((1, 1, 4, 32), dtype=np.float16)
+    K2[..., 0] = 127 * 0.25
+    K2[..., 1:] = rng.integers(-127, 128, size=(1, 1, 4, 31)) * 0.25
+    Kh2, _ = O.pool_decode(O.pool_encode(K2, K2))
+    np.testing.assert_array_equal(O.keys_as_fp16(Kh2), Kh2)
