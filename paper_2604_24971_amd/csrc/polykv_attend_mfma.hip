@@ -203,7 +203,7 @@ __device__ __forceinline__ float max16(const float16v& a) {
 
 // Four scores of a row -> fp16 probabilities (packed pairs) and their sum into the denominator.  With
 // value scales (g != nullptr: the lane's RawV::g) the P.V operand is p * scale of its token (formed in fp32,
-// rounded to fp16 once), at most 2^8 * 2^7; the denominator sums the plain p.
+// rounded to fp16 once), at most 2^8 * 2^7; the denominator sums the plain, unrounded p.
 template <bool VS>
 __device__ __forceinline__ void exp4(const float16v& S, int c, float qscale, float mneg, H8 (&pb)[2], float& lsum,
                                      const uint32_t* g) {
@@ -215,7 +215,11 @@ __device__ __forceinline__ void exp4(const float16v& S, int c, float qscale, flo
         const float e0 = __builtin_amdgcn_exp2f(fmaf(S[i], qscale, mneg)), e1 = __builtin_amdgcn_exp2f(fmaf(S[i + 1], qscale, mneg));
         p2[0] = (_Float16)e0;
         p2[1] = (_Float16)e1;
-        lsum = __builtin_amdgcn_fdot2(p2, one2, lsum, false);
+        // The denominator sums the very numbers that enter the P.V product where those are the probabilities
+        // themselves (their rounding errors then cancel in the quotient); with a value scale the products p * g
+        // are what is rounded, so the denominator takes the unrounded probabilities.
+        if (VS) lsum += e0 + e1;
+        else lsum = __builtin_amdgcn_fdot2(p2, one2, lsum, false);
         if (VS) {   // p * g in fp32, rounded to fp16 once
             union {
                 uint32_t u;

@@ -6,16 +6,16 @@ CPU oracle and compare to the stated bars:
     fp64) lies within 1e-6 relative of the midpoint of two fp16 numbers, which may store either; the
     codes of such a vector are then checked against the oracle's codes for the scale it stores;
   * dequantized K/V within 1e-3 relative, per vector, infinity norm;
-  * attention output within 2e-3 absolute.  That bar is stated for the paper-scale workloads, whose
-    value vectors have elements up to about 4; the tests of the value-codec variants also use vectors a
-    hundred times longer.  The matrix kernel rounds a probability to fp16 (2^-11 relative: as a perturbed
-    softmax weight that moves the output by at most 2 * 2^-11 * B) and, in the codecs whose value scale
-    rides on the probability, rounds the product with the scale once more (2^-11 * B), where
-    B = sum_t p_t * max_c |v_t[c]| is the softmax-weighted magnitude of the values the row mixes (computed
-    by the oracle's own attention over the magnitudes).  For those pools the bar is, per output row,
-    max(2e-3, 3 * 2^-11 * B): what the arithmetic can lose at worst.  Measured on 200 tiny pools, where
-    nothing averages out: at most 0.9 * 2^-11 * B with such a scale, 0.3 * 2^-11 * B without, and
-    0.002 * 2^-11 * B in the fp32 vector kernel.
+  * attention output within 2e-3 absolute for every pool that uses the paper's codec on data of the paper's
+    scale (the BASELINE distributions of configs 1-5, fp16 or bfloat16 inputs).  The tests of the value-codec
+    variants (per-vector scale, int8) also use value vectors a hundred times longer; there the bar is relative to
+    what a row mixes: per output row 2e-3 * max(1, B / 4), B = sum_t p_t * max_c |v_t[c]| the softmax-weighted
+    magnitude of the row's values (by the oracle's own attention over the magnitudes) -- 2e-3 for elements up to
+    4 as in the paper-scale data, growing in proportion beyond.  The coefficient is a requirement, not a
+    measurement of the kernel.
+Where the library's stored code differs from the oracle's on a permitted tie, the reference is switched to the
+neighbouring code the library stores (after checking that it IS the neighbour and the tie is real), so that
+dequantization and attention are compared on every vector and every row, with no unit masked out.
 """
 import numpy as np
 import torch
@@ -76,17 +76,19 @@ def settle_value_scales(gs, ref):
     return int(diff.sum())
 
 
-def compare_codes(pool, ref):
-    """Returns a bool array [L, H] marking units where a (permitted) threshold mismatch occurred."""
-    kc, ks, vp = (t.cpu().numpy() for t in pool.export())
-    d = pool.head_dim
+def settle_codes(ref, kc, ks, vp, gs=None):
+    """Checks the library's exported codes (kc int8, ks fp16, vp packed / int8 values, gs value scales or None)
+    against the oracle's encoding `ref` (same leading shape) bit for bit; a code may differ only where the
+    oracle's pre-rounding value lies within CODE_WINDOW of a decision threshold, and then only by one step.
+    Such elements are switched, in `ref`, to the code the library stores.  Returns (key, value) mismatch counts."""
+    np.testing.assert_array_equal(ks.view(np.uint16), ref["k_scales"].view(np.uint16))
+    k_diff = kc != ref["k_codes"]
+    if k_diff.any():
+        frac = np.abs(ref["k_pre"] - np.floor(ref["k_pre"]) - 0.5)
+        assert np.all(frac[k_diff] <= CODE_WINDOW), "key code differs away from a rounding tie"
+        assert np.all(np.abs(kc.astype(np.int32) - ref["k_codes"])[k_diff] == 1)
+        ref["k_codes"] = np.where(k_diff, kc, ref["k_codes"])
     if "v_codes" in ref:        # int8 values: scales bit-exact, codes bit-exact except on a rounding tie
-        np.testing.assert_array_equal(ks.view(np.uint16), ref["k_scales"].view(np.uint16))
-        k_diff = kc != ref["k_codes"]
-        if k_diff.any():
-            frac = np.abs(ref["k_pre"] - np.floor(ref["k_pre"]) - 0.5)
-            assert np.all(frac[k_diff] <= CODE_WINDOW), "key code differs away from a rounding tie"
-        gs = pool.export_value_scales().cpu().numpy()
         np.testing.assert_array_equal(gs.view(np.uint16), ref["v_scales"].view(np.uint16))
         assert vp.dtype == np.int8 and vp.shape == ref["v_codes"].shape
         v_diff = vp != ref["v_codes"]
@@ -94,20 +96,13 @@ def compare_codes(pool, ref):
             frac = np.abs(ref["v_pre"] - np.floor(ref["v_pre"]) - 0.5)
             assert np.all(frac[v_diff] <= CODE_WINDOW), "value code differs away from a rounding tie"
             assert np.all(np.abs(vp.astype(np.int32) - ref["v_codes"])[v_diff] == 1)
-        return k_diff.any(axis=(2, 3)) | v_diff.any(axis=(2, 3)), int(k_diff.sum()), int(v_diff.sum())
+            ref["v_codes"] = np.where(v_diff, vp, ref["v_codes"])
+        return int(k_diff.sum()), int(v_diff.sum())
     scaled = "v_scales" in ref
     if scaled:
-        settle_value_scales(pool.export_value_scales().cpu().numpy(), ref)
-    # scales: bit-exact
-    np.testing.assert_array_equal(ks.view(np.uint16), ref["k_scales"].view(np.uint16))
-    # key codes
-    k_diff = kc != ref["k_codes"]
-    if k_diff.any():
-        frac = np.abs(ref["k_pre"] - np.floor(ref["k_pre"]) - 0.5)
-        assert np.all(frac[k_diff] <= CODE_WINDOW), "key code differs away from a rounding tie"
-        assert np.all(np.abs(kc.astype(np.int32) - ref["k_codes"])[k_diff] == 1)
-    # value codes
+        settle_value_scales(gs, ref)
     bits = ref.get("v_bits", 3)
+    d = ref["v_idx"].shape[-1]
     v_idx = O.v_unpack(vp, d, bits)
     v_diff = v_idx != ref["v_idx"]
     if v_diff.any():
@@ -120,10 +115,21 @@ def compare_codes(pool, ref):
             dist = np.min(np.abs(ref["v_rot"][v_diff][:, None] - t[None, :]), axis=1)
         assert np.all(dist <= CODE_WINDOW), "value code differs away from a threshold (max dist %g)" % dist.max()
         assert np.all(np.abs(v_idx.astype(np.int32) - ref["v_idx"])[v_diff] == 1)
-    # packed stream identical wherever the codes are
-    if not v_diff.any():
-        np.testing.assert_array_equal(vp, ref["v_packed"])
-    return k_diff.any(axis=(2, 3)) | v_diff.any(axis=(2, 3)), int(k_diff.sum()), int(v_diff.sum())
+        ref["v_idx"] = np.where(v_diff, v_idx, ref["v_idx"]).astype(ref["v_idx"].dtype)
+        ref["v_packed"] = O.v_pack(ref["v_idx"], bits)
+    # with the ties settled the packed stream is identical
+    np.testing.assert_array_equal(vp, ref["v_packed"])
+    return int(k_diff.sum()), int(v_diff.sum())
+
+
+def compare_codes(pool, ref):
+    """Exports the pool and settles it against `ref` (see settle_codes).  Returns (mask, key mismatches, value
+    mismatches); the mask [L, H] is all False -- no unit is excluded from the later comparisons -- and is kept
+    for the callers that pass it on."""
+    kc, ks, vp = (t.cpu().numpy() for t in pool.export())
+    gs = pool.export_value_scales().cpu().numpy() if ("v_scales" in ref) else None
+    k_mis, v_mis = settle_codes(ref, kc, ks, vp, gs)
+    return np.zeros(kc.shape[:2], dtype=bool), k_mis, v_mis
 
 
 def compare_decode(pool, ref, dirty_units):
@@ -149,7 +155,7 @@ def attend_row_atol(K_hat, V_hat, Q, scale=None, tails=None, tail_causal=False):
         tails_mag = [(tk, np.broadcast_to(np.abs(np.asarray(tv, dtype=np.float64)).max(axis=-1, keepdims=True), tv.shape))
                      for tk, tv in tails]
     B = O.pool_attend(K_hat, mag, Q, scale=scale, tails=tails_mag, tail_causal=tail_causal)[..., :1]
-    return np.maximum(ATTEND_ATOL, 3.0 * 2.0 ** -11 * B)
+    return ATTEND_ATOL * np.maximum(1.0, B / 4.0)
 
 
 def compare_attend(out_gpu, out_ref, kv_heads, dirty_units=None, layer_begin=0, atol=ATTEND_ATOL):
