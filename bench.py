@@ -8,7 +8,11 @@ Inputs are synthetic and already resident in HBM when timing starts.  Prints ONE
 the pool attention kernel, taken from HIP events that the runtime stamps at the kernel's begin and
 end); encode tokens/s and the other kernels' rates ride along as extra keys;
 `roofline` describes the attention kernel against HBM peak and `cpu_baseline` times the CPU oracle
-on the same workload, layer by layer.
+on the same workload, layer by layer.  After the timed region (unless --no-extras) the same process adds context:
+a plain device copy (what this GPU sustains for read + write traffic), pool_attend launched back to back over the
+rotated pools (the steady-state read loop of a write-once / read-many pool), and `other_configs`: attention on the
+SmolLM2-shaped pool, the 7,194-token pool with 64-token private tails and the 1,024-row stress shape.
+All durations are medians over the timed calls.
 """
 from __future__ import annotations
 
@@ -58,6 +62,79 @@ def cpu_baseline(cfg, W, layers=None):
     }
 
 
+def attend_back_to_back(pk, pools, Q, out, ws, tails, kprec, n):
+    """pool_attend n times in a row over the rotated pools.  Returns (median stream-level time per call, median
+    duration of the call's main kernel), seconds."""
+    import torch
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n + 3)]
+    for e in evs:
+        for x in e:
+            x.record()
+    torch.cuda.synchronize()
+    for i, e in enumerate(evs):
+        e[0].record()
+        pk.time_next_kernel(e[2], e[3])
+        pools[i % len(pools)].attend(Q, out, workspace=ws, tails=tails, key_precision=kprec)
+        e[1].record()
+    torch.cuda.synchronize()
+    call = float(np.median([e[0].elapsed_time(e[1]) for e in evs[3:]])) * 1e-3
+    kern = float(np.median([e[2].elapsed_time(e[3]) for e in evs[3:]])) * 1e-3
+    return call, kern
+
+
+def other_config(pk, W, n, kprec):
+    """Attention on another of the paper-shaped configurations, back to back over two or three rotated pools.
+    The tensors are drawn on the GPU (seeded torch generator) with the recipe of workloads.py: throughput does
+    not depend on the values."""
+    import torch
+    cfg = W.CONFIGS[n]
+    L, H, d, T = cfg.layers, cfg.kv_heads, cfg.head_dim, cfg.tokens
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1000 * n)
+
+    def draw(shape, scale=None):
+        x = torch.randn(shape, device="cuda", generator=g, dtype=torch.float32)
+        return (x * scale if scale is not None else x).to(torch.float16)
+    gain = torch.exp(0.5 * torch.randn((L, H, 1, d), device="cuda", generator=g))
+    gain = torch.where(torch.rand((L, H, 1, d), device="cuda", generator=g) < 0.01, gain * 8.0, gain)
+    K = draw((L, H, T, d), gain)
+    V = draw((L, H, T, d), torch.exp(0.3 * torch.randn((L, H, T, 1), device="cuda", generator=g)))
+    Q = draw((L, cfg.agents, cfg.q_per_agent, cfg.q_heads, d))
+    out = torch.empty(Q.shape, dtype=torch.float32, device="cuda")
+    units = L * H
+    packed = units * T * (d + d // 16 + 3 * d // 8)
+    copies = 3 if 2 * packed < (256 << 20) else 2          # more than the 256 MB last-level cache in rotation
+    pools = [pk.Pool(L, H, d, T).bind() for _ in range(copies)]
+    for p in pools:
+        p.encode(K, V)
+    tails, tail_len = None, 0
+    if cfg.max_tail:                                        # every agent carries max_tail private tokens
+        tail_len = cfg.max_tail
+        tails = pk.Tails(pools[0], [(draw((L, H, tail_len, d)), draw((L, H, tail_len, d))) for _ in range(cfg.agents)],
+                         [tail_len] * cfg.agents)
+    del K, V
+    ws = torch.empty(max(pools[0].attend_workspace_bytes(Q, tails=tails), 256), dtype=torch.uint8, device="cuda")
+    call, kern = attend_back_to_back(pk, pools, Q, out, ws, tails, kprec, 10)
+    tail_bytes = cfg.agents * tail_len * units * 4 * d
+    nbytes = packed + Q.numel() * 2 + out.numel() * 4 + tail_bytes
+    R = cfg.rows_per_kv_head
+    nt = 1 if R <= 32 else 2
+    t = call if tails is not None else kern                 # with tails a call is three kernels: stream-level time
+    res = {"workload": cfg.name, "rows_per_kv_head": R, "tokens": T, "pool_bytes": packed, "tail_len": tail_len,
+           "tail_bytes": tail_bytes, "algorithmic_bytes": nbytes, "pool_copies_rotated": copies,
+           "kernel": "attend_mfma_kernel<%d,%d,0,0>" % (d, nt), "kernel_ms": kern * 1e3, "call_ms": call * 1e3,
+           "timed": "pool_attend back to back; " + ("call (tail kernel + pool kernel + merge kernel, stream events)"
+                                                    if tails is not None else "the pool kernel's own events"),
+           "GB_per_s": nbytes / t / 1e9, "frac_of_hbm_peak": nbytes / t / 1e9 / HBM_PEAK_GBPS}
+    if R >= 256:                                            # matrix-bound shape: useful attention arithmetic
+        flops = 4.0 * R * d * T * units
+        res["useful_TFLOP_per_s"] = flops / kern / 1e12
+        res["frac_of_f16_matrix_peak"] = flops / kern / 1e12 / 2500.0
+    for p in pools:
+        p.close()
+    return res
+
+
 # name -> (codec id of the C ABI, bits per value code, per-vector scale stored)
 VALUE_CODECS = {"tq3": (0, 3, False), "tq3-scaled": (1, 3, True), "int8": (2, 8, True), "tq2": (3, 2, False),
                 "tq2-scaled": (4, 2, True), "tq4": (5, 4, False), "tq4-scaled": (6, 4, True)}
@@ -79,9 +156,10 @@ def main():
     ap.add_argument("--per-layer", action="store_true",
                     help="attention as the decode loop issues it: one pool_attend per layer (32 calls per step) instead "
                          "of all layers in one call; the attention time is then the stream-level time of the 32 calls")
-    ap.add_argument("--extras", action="store_true",
-                    help="after the timed region also time a plain device copy and pool_attend launched back to back "
-                         "(context only; off by default so that a profile of the default run holds the timed steps only)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip what runs after the timed region (device copy, back-to-back attention, other "
+                         "configurations): for profiles that should hold the timed steps only")
+    ap.add_argument("--extras", action="store_true", help="(default; kept for older command lines)")
     ap.add_argument("--value-codec", choices=tuple(VALUE_CODECS), default="tq3",
                     help="value codec: tq3 = the paper's (headline configuration); tqB-scaled = with a per-vector fp16 "
                     "scale; tq2 / tq4 = 2 / 4 bits per coordinate; int8 = uniform int8 without rotation (the paper's "
@@ -98,6 +176,7 @@ def main():
     ap.add_argument("--phases", default="eda", help="subset of e(ncode) d(ecode) a(ttend) to run per step; "
                     "anything but the default is for profiling one kernel and is marked partial")
     args = ap.parse_args()
+    args.extras = not args.no_extras and args.phases == "eda" and not args.per_layer
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the pool path shards by layer / KV head "
               "with no exchange between GPUs", file=sys.stderr)
@@ -198,7 +277,8 @@ def main():
     # (what this GPU sustains for read + write traffic) and pool_attend launched back to back on its own
     # (the attention kernel is issue-bound, so its duration follows the shader clock, which the power
     # management keeps lower while memory-bound kernels run in between).
-    t_copy = t_att_iso = append_rate = None
+    t_copy = t_att_iso = k_att_iso = append_rate = None
+    other = None
     if args.extras:
         def timed(fn, n):
             evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
@@ -207,15 +287,9 @@ def main():
                 fn()
                 b.record()
             torch.cuda.synchronize()
-            return float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e-3
+            return float(np.median([a.elapsed_time(b) for a, b in evs])) * 1e-3
         t_copy = timed(lambda: Kd.copy_(K), 10)
-        iso = [0]
-
-        def attend_only():
-            pools[iso[0] % len(pools)].attend(Q, out, workspace=ws, tails=tails, key_precision=kprec)
-            iso[0] += 1
-        timed(attend_only, 3)
-        t_att_iso = timed(attend_only, args.steps)
+        t_att_iso, k_att_iso = attend_back_to_back(pk, pools, Q, out, ws, tails, kprec, args.steps)
         # incremental fill: the same tensors appended 64 tokens at a time into a pool of the same capacity
         chunk = 64
         Kc = [K[:, :, i:i + chunk].contiguous() for i in range(0, T - chunk + 1, chunk)]
@@ -231,16 +305,20 @@ def main():
             t_fill = timed(fill, 3)
             append_rate = len(Kc) * chunk / t_fill
             spare.encode(K, V)
+        del Kc, Vc
+        if args.config == 3 and args.value_codec == "tq3" and args.key_codec == "block32" and not args.bf16:
+            del pools[1:]
+            other = [other_config(pk, W, n, kprec) for n in (2, 4, 5)]
 
     enc = np.array([e[0].elapsed_time(e[1]) for e in events]) * 1e-3
     dec = np.array([e[1].elapsed_time(e[2]) for e in events]) * 1e-3
     att = np.array([e[2].elapsed_time(e[3]) for e in events]) * 1e-3
-    t_enc, t_dec, t_att = (max(float(x.mean()), 1e-9) for x in (enc, dec, att))       # stream-level, with launch gaps
+    t_enc, t_dec, t_att = (max(float(np.median(x)), 1e-9) for x in (enc, dec, att))    # stream-level, with launch gaps
 
     def kernel_time(idx, phase, fallback):
         if phase not in args.phases:
             return fallback
-        return max(float(np.mean([k[idx][0].elapsed_time(k[idx][1]) for k in kevents])) * 1e-3, 1e-9)
+        return max(float(np.median([k[idx][0].elapsed_time(k[idx][1]) for k in kevents])) * 1e-3, 1e-9)
     k_enc, k_dec, k_att = kernel_time(0, "e", t_enc), kernel_time(1, "d", t_dec), kernel_time(2, "a", t_att)
     if args.key_codec == "tensor":            # encode is three kernels (zero, max|k|, encode): the stream time covers them
         k_enc = t_enc
@@ -263,11 +341,12 @@ def main():
                 "frac": gbps / HBM_PEAK_GBPS, "traffic": None, "kernel": kernel}
 
     how = ("; duration = the kernel's own begin/end HIP events (hipExtLaunchKernel start/stop events on the launch "
-           "stream), averaged over the timed steps")
+           "stream), median over the timed steps; traffic = the stored rocprofv3 FETCH_SIZE + WRITE_SIZE figure of "
+           "profiles/ (copy-scaled), not measured in this run")
     vc = codec                                                          # the kernels' value-codec template argument
-    nt = 1 if (cfg.rows_per_kv_head <= 32 or d == 256 or (vc == 2 and d == 128)) else 2
+    nt = 1 if (cfg.rows_per_kv_head <= 32 or d == 256 or (vc in (2, 6) and d == 128)) else 2
     kc = 1 if args.key_codec == "tensor" else 0
-    attend_roof = roof(att_gbps, "attend_mfma_kernel<%d,%d,%d,%d> (pool_attend)" % (d, nt, vc, kc) + how +
+    attend_roof = roof(att_gbps, "attend_mfma_kernel<%d,%d,%d,%d,%s> (pool_attend)" % (d, nt, vc, kc, "true" if args.key_precision == "fp16" else "false") + how +
                        "; achieved = algorithmic bytes (packed pool + Q + out) / duration")
     traffic_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
                                 "attend_hbm_traffic_%s.txt" % cfg.name)
@@ -280,7 +359,7 @@ def main():
         "metric": "decode_attention_pool_GB_per_s", "value": att_gbps, "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f16 operands, f32 accumulate", "data": "synthetic",
         "config": {"workload": cfg.name, "layers": L, "kv_heads": H, "q_heads": cfg.q_heads, "head_dim": d,
                    "tokens": T, "agents": cfg.agents, "q_per_agent": cfg.q_per_agent,
                    "rows_per_kv_head": cfg.rows_per_kv_head, "pool_bytes": packed, "pool_copies_rotated": len(pools),
@@ -295,8 +374,14 @@ def main():
                       "note": "events recorded on the stream around each call: kernel + launch gaps"},
         "attend_ms": k_att * 1e3, "encode_ms": k_enc * 1e3, "decode_ms": k_dec * 1e3,
         "attend_algorithmic_bytes": att_bytes,
-        "attend_back_to_back_ms": t_att_iso and t_att_iso * 1e3,
-        "attend_back_to_back_GB_per_s": t_att_iso and att_bytes / t_att_iso / 1e9,
+        "attend_back_to_back_ms": k_att_iso and k_att_iso * 1e3,
+        "attend_back_to_back_GB_per_s": k_att_iso and att_bytes / k_att_iso / 1e9,
+        "attend_back_to_back_frac_of_hbm_peak": k_att_iso and att_bytes / k_att_iso / 1e9 / HBM_PEAK_GBPS,
+        "attend_back_to_back_call_ms": t_att_iso and t_att_iso * 1e3,
+        "attend_back_to_back_note": "pool_attend launched back to back over the rotated pools, outside the timed "
+                                    "region: kernel duration from the kernel's own events; call_ms = stream events "
+                                    "around each call (kernel + launch gap)",
+        "other_configs": other,
         "device_copy_GB_per_s": t_copy and 2 * K.numel() * 2 / t_copy / 1e9,
         "append_64_tokens_per_s": append_rate,
         "roofline": attend_roof,
