@@ -463,8 +463,13 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
     }
 }
 
+// Waves per SIMD the kernel is compiled for: one where it needs all 512 registers; three for 32-row blocks at
+// head_dim 64 (the small-row shape of the SmolLM2-sized pool: 768 workgroups, all resident at once on 256 CUs,
+// so that one workgroup's query fetch, pipeline ramp and merge overlap the others' main loops).
+constexpr int kernel_waves_per_simd(int D, int NT, int VC) { return (D == 64 && NT == 1 && vc_bits(VC) == 3 && !vc_has_scale(VC)) ? 3 : 1; }
+
 template <int D, int NT, int VC, int KC, bool K16>
-__global__ __launch_bounds__(256) void attend_mfma_kernel(const uint8_t* __restrict__ pool,
+__global__ __launch_bounds__(256, kernel_waves_per_simd(D, NT, VC)) void attend_mfma_kernel(const uint8_t* __restrict__ pool,
                                                           const __half* __restrict__ Q,
                                                           float* __restrict__ ws_ml, float* __restrict__ ws_o,
                                                           float* __restrict__ out, AttendPlan p, int direct) {
