@@ -238,15 +238,40 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
 }
 
 // ------------------------------------------------------------------------------ tail kernel ---
-// Dense fp16 attention of one agent's rows over its private, uncompressed continuation.
-// One wave per (selected layer, kv head, agent, row block); emits (m, l, o) in the original domain.
-template <int D>
-__global__ __launch_bounds__(64) void attend_tail_kernel(const __half* __restrict__ Q, TailPtrs tails,
-                                                         float* __restrict__ tail_ml,
-                                                         float* __restrict__ tail_o, AttendPlan p) {
-    constexpr int EPL = D / 64;
-    __shared__ __align__(16) float q_s[kRB][D];
-    __shared__ __align__(16) float p_s[kRB][64];
+// Dense 16-bit attention of one agent's rows over its private, uncompressed continuation.
+// One wave per (selected layer, kv head, agent, block of kRB rows); emits (m, l, o) in the original domain.
+// Written for many waves per SIMD (under 128 registers): the tails are small and scattered, so what hides
+// the memory latency is other waves, not a deep pipeline inside one.  Per block of 64 tokens:
+//   scores  the 64 key rows are fetched with coalesced loads and staged in LDS; lane = token then walks its
+//           row in 16-byte pieces; the products with the raw 16-bit queries (LDS broadcast) are packed dot
+//           products with fp32 accumulation, the softmax scale is applied to the sum;
+//   P.V     lane = (token slot, 8 coordinates): one 16-byte load covers a lane's 8 coordinates of a token,
+//           D/8 lanes a whole value row, so a wave load covers 512/D tokens of consecutive rows; every lane
+//           accumulates its slot's tokens, the slots are added once at the very end.
+typedef _Float16 tail_h2 __attribute__((ext_vector_type(2)));
+typedef short tail_s2 __attribute__((ext_vector_type(2)));
+template <bool BF> __device__ __forceinline__ float tail_dot2(uint32_t a, uint32_t b, float c) {
+    if constexpr (BF) {
+        union { uint32_t u; tail_s2 v; } x, y;
+        x.u = a, y.u = b;
+        return __builtin_amdgcn_fdot2_f32_bf16(x.v, y.v, c, false);
+    } else {
+        union { uint32_t u; tail_h2 v; } x, y;
+        x.u = a, y.u = b;
+        return __builtin_amdgcn_fdot2(x.v, y.v, c, false);
+    }
+}
+
+template <int D, bool BF>
+__global__ __launch_bounds__(64, 4) void attend_tail_kernel(const __half* __restrict__ Q, TailPtrs tails,
+                                                            float* __restrict__ tail_ml,
+                                                            float* __restrict__ tail_o, AttendPlan p) {
+    constexpr int LPR = D / 8;       // lanes per value row
+    constexpr int TPL = 64 / LPR;    // tokens per wave load (token slots)
+    constexpr int NLD = 64 / TPL;    // wave loads per 64 tokens
+    __shared__ __align__(16) uint16_t q_s[kRB][D];     // the raw 16-bit queries
+    __shared__ __align__(16) float p_s[64][kRB];       // probabilities, [token][row]
+    __shared__ uint4 k_s[64][LPR + 1];                 // 64 key rows (one spare piece per row rotates the banks)
     const int lane = threadIdx.x;
     const int usel = blockIdx.y, ls = usel / p.H, kvh = usel - ls * p.H;
     const int a = blockIdx.x;
@@ -263,112 +288,128 @@ __global__ __launch_bounds__(64) void attend_tail_kernel(const __half* __restric
         const int qi = (r0 + r - a * rows_a) / p.G;
         len_r[r] = p.tail_causal ? max(0, len - (p.nq - 1 - min(qi, p.nq - 1))) : len;
     }
-
     const size_t head_off = ((size_t)(p.layer_begin + ls) * p.H + kvh) * p.tail_capacity * D;
-    const __half* Kt = reinterpret_cast<const __half*>(tails.K[a]) + head_off;
-    const __half* Vt = reinterpret_cast<const __half*>(tails.V[a]) + head_off;
+    const uint16_t* Kt = reinterpret_cast<const uint16_t*>(tails.K[a]) + head_off;
+    const uint16_t* Vt = reinterpret_cast<const uint16_t*>(tails.V[a]) + head_off;
 
-    // Everything a block of 64 tokens needs is requested before anything is used: the lane's key row
-    // (lane = token) and, for the second phase (lane = coordinates), its EPL values of all 64 value rows.
-    // The first block's requests go out together with the query loads: one memory latency in all.
-    uint4 kraw[D / 8];
-    HalfVecN<EPL> vraw[64];
-    auto request = [&](int t0) {
-        const int cnt = min(64, len - t0);
-        const uint4* krow = reinterpret_cast<const uint4*>(Kt + (size_t)(t0 + min(lane, cnt - 1)) * D);
-#pragma unroll
-        for (int i = 0; i < D / 8; ++i) kraw[i] = krow[i];
-#pragma unroll
-        for (int t = 0; t < 64; ++t)
-            vraw[t] = *reinterpret_cast<const HalfVecN<EPL>*>(Vt + (size_t)(t0 + min(t, cnt - 1)) * D + lane * EPL);
-    };
-    if (len > 0) request(0);
-
-    // queries: 16-byte loads, D/8 lanes to a row
-    for (int i = lane; i < kRB * (D / 8); i += 64) {
-        const int r = i / (D / 8), piece = i - r * (D / 8);
+    // queries: 16-byte loads, D/8 lanes to a row; rows past the agent's last are zero
+    for (int i = lane; i < kRB * LPR; i += 64) {
+        const int r = i / LPR, piece = i - r * LPR;
         uint4 raw = make_uint4(0, 0, 0, 0);
         if (r0 + r < r_end) raw = *reinterpret_cast<const uint4*>(Q + q_row_index(p, ls, kvh, r0 + r) * D + 8 * piece);
-        const uint32_t* w2 = reinterpret_cast<const uint32_t*>(&raw);
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const float2 f = pair16_to_float2(w2[b], p.io_bf16);
-            q_s[r][8 * piece + 2 * b] = f.x * p.qscale;
-            q_s[r][8 * piece + 2 * b + 1] = f.y * p.qscale;
-        }
+        *reinterpret_cast<uint4*>(&q_s[r][8 * piece]) = raw;
     }
     __syncthreads();
 
-    float m_run[kRB], l_run[kRB], acc[kRB][EPL];
+    const int slot = lane / LPR, piece = lane - slot * LPR;
+    float m_run[kRB], l_run[kRB], acc[kRB][8];
 #pragma unroll
     for (int r = 0; r < kRB; ++r) {
         m_run[r] = -INFINITY;
         l_run[r] = 0.0f;
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) acc[r][i] = 0.0f;
+        for (int c = 0; c < 8; ++c) acc[r][c] = 0.0f;
     }
 
     for (int t0 = 0; t0 < len; t0 += 64) {
-        const int tok = t0 + lane;
-        if (t0 > 0) request(t0);
-        float k[D];
+        const int cnt = min(64, len - t0);
+        // ---- the 64 key rows come in with fully coalesced loads (lane = (token slot, piece), as for the
+        // values below) and go through LDS, where every lane then walks the row of its own token
+        // (rows past the end are copies of the last token; their scores become -inf)
 #pragma unroll
-        for (int i = 0; i < D / 8; ++i) {
-            const uint32_t* w2 = reinterpret_cast<const uint32_t*>(&kraw[i]);
+        for (int b0 = 0; b0 < NLD; b0 += 8) {
+            uint4 kin[8];
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const float2 f = pair16_to_float2(w2[b], p.io_bf16);
-                k[i * 8 + 2 * b] = f.x;
-                k[i * 8 + 2 * b + 1] = f.y;
-            }
-        }
+            for (int u = 0; u < 8; ++u)
+                kin[u] = *reinterpret_cast<const uint4*>(Kt + (size_t)(t0 + min((b0 + u) * TPL + slot, cnt - 1)) * D + 8 * piece);
 #pragma unroll
-        for (int r = 0; r < kRB; ++r) {
-            float s = 0.0f;
-#pragma unroll
-            for (int jj = 0; jj < D; jj += 4) {
-                const float4 qv = *reinterpret_cast<const float4*>(&q_s[r][jj]);
-                s = fmaf(qv.x, k[jj], s);
-                s = fmaf(qv.y, k[jj + 1], s);
-                s = fmaf(qv.z, k[jj + 2], s);
-                s = fmaf(qv.w, k[jj + 3], s);
-            }
-            s = tok < len_r[r] ? s : -INFINITY;
-            const float m_new = fmaxf(m_run[r], wave_max(s));
-            // a row that has seen no token yet keeps m = -inf: nothing to rescale, every weight 0
-            const float alpha = m_new == -INFINITY ? 1.0f : exp2f(m_run[r] - m_new);
-            const float pr = m_new == -INFINITY ? 0.0f : exp2f(s - m_new);
-            l_run[r] = l_run[r] * alpha + wave_sum(pr);
-            m_run[r] = m_new;
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) acc[r][i] *= alpha;
-            p_s[r][lane] = pr;
+            for (int u = 0; u < 8; ++u) k_s[(b0 + u) * TPL + slot][piece] = kin[u];
         }
         __syncthreads();
-        // rows past the tail were re-reads of the last valid one; their weight exp2(-inf) is 0
+        const uint4* krow = &k_s[lane][0];
+        float sc[kRB];
 #pragma unroll
-        for (int t4 = 0; t4 < 64; t4 += 4) {
-            float4 pr[kRB];
+        for (int r = 0; r < kRB; ++r) sc[r] = 0.0f;
 #pragma unroll
-            for (int r = 0; r < kRB; ++r) pr[r] = *reinterpret_cast<const float4*>(&p_s[r][t4]);
+        for (int i0 = 0; i0 < LPR; i0 += 4) {   // four 16-byte pieces of the key row at a time
+            uint4 kraw[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) kraw[u] = krow[i0 + u];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll
-                for (int i = 0; i < EPL; ++i) {
-                    const float v = bits16_to_float(__half_as_ushort(vraw[t4 + u].h[i]), p.io_bf16);
-#pragma unroll
-                    for (int r = 0; r < kRB; ++r)
-                        acc[r][i] = fmaf(u == 0 ? pr[r].x : u == 1 ? pr[r].y : u == 2 ? pr[r].z : pr[r].w, v, acc[r][i]);
+                for (int r = 0; r < kRB; ++r) {
+                    const uint4 qv = *reinterpret_cast<const uint4*>(&q_s[r][8 * (i0 + u)]);
+                    sc[r] = tail_dot2<BF>(kraw[u].x, qv.x, sc[r]);
+                    sc[r] = tail_dot2<BF>(kraw[u].y, qv.y, sc[r]);
+                    sc[r] = tail_dot2<BF>(kraw[u].z, qv.z, sc[r]);
+                    sc[r] = tail_dot2<BF>(kraw[u].w, qv.w, sc[r]);
                 }
+        }
+        float alpha[kRB];
+#pragma unroll
+        for (int r = 0; r < kRB; ++r) {
+            const float sv = t0 + lane < len_r[r] ? sc[r] * p.qscale : -INFINITY;
+            const float m_new = fmaxf(m_run[r], wave_max(sv));
+            // a row that has seen no token yet keeps m = -inf: nothing to rescale, every weight 0
+            alpha[r] = m_new == -INFINITY ? 1.0f : exp2f(m_run[r] - m_new);
+            const float pr = m_new == -INFINITY ? 0.0f : exp2f(sv - m_new);
+            l_run[r] = l_run[r] * alpha[r] + wave_sum(pr);
+            m_run[r] = m_new;
+            p_s[lane][r] = pr;
+        }
+        __syncthreads();
+        // ---- P.V, lane = (token slot, 8 coordinates)
+#pragma unroll
+        for (int r = 0; r < kRB; ++r)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[r][c] *= alpha[r];
+#pragma unroll
+        for (int b0 = 0; b0 < NLD; b0 += 8) {   // eight wave loads at a time
+            uint4 vraw[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int t = min((b0 + u) * TPL + slot, cnt - 1);   // past the end: a re-read with weight 0
+                vraw[u] = *reinterpret_cast<const uint4*>(Vt + (size_t)(t0 + t) * D + 8 * piece);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int t = (b0 + u) * TPL + slot;
+                const float4 pr4 = *reinterpret_cast<const float4*>(&p_s[t][0]);
+                const float pr[4] = {pr4.x, pr4.y, pr4.z, pr4.w};
+                const uint32_t w[4] = {vraw[u].x, vraw[u].y, vraw[u].z, vraw[u].w};
+#pragma unroll
+                for (int c2 = 0; c2 < 4; ++c2) {
+                    const float2 f = pair16_to_float2(w[c2], BF);
+#pragma unroll
+                    for (int r = 0; r < kRB; ++r) {
+                        acc[r][2 * c2] = fmaf(pr[r], f.x, acc[r][2 * c2]);
+                        acc[r][2 * c2 + 1] = fmaf(pr[r], f.y, acc[r][2 * c2 + 1]);
+                    }
+                }
+            }
         }
         __syncthreads();
     }
+    // ---- the token slots' shares are added (lanes piece + LPR * slot), slot 0 stores
+#pragma unroll
+    for (int r = 0; r < kRB; ++r)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            float v = acc[r][c];
+#pragma unroll
+            for (int m = LPR; m < 64; m <<= 1) v += __shfl_xor(v, m, 64);
+            acc[r][c] = v;
+        }
 #pragma unroll
     for (int r = 0; r < kRB; ++r) {
         if (r0 + r >= r_end) break;
         const size_t prow = (size_t)usel * p.R + r0 + r;
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) tail_o[prow * D + lane * EPL + i] = acc[r][i];
+        if (slot == 0) {
+            float4* dst = reinterpret_cast<float4*>(tail_o + prow * D + 8 * piece);
+            dst[0] = make_float4(acc[r][0], acc[r][1], acc[r][2], acc[r][3]);
+            dst[1] = make_float4(acc[r][4], acc[r][5], acc[r][6], acc[r][7]);
+        }
         if (lane == 0) {
             tail_ml[prow * 2] = m_run[r];
             tail_ml[prow * 2 + 1] = l_run[r];
@@ -512,12 +553,12 @@ hipError_t launch_attend(const polykv_pool* pool, const AttendPlan& plan, const 
     }
     if (plan.has_tails) {
         dim3 grid(plan.A, units, (plan.nq * plan.G + kRB - 1) / kRB);
-        if (plan.D == 128)
-            attend_tail_kernel<128><<<grid, 64, 0, s>>>((const __half*)Q, *tails, tail_ml, tail_o, plan);
-        else if (plan.D == 64)
-            attend_tail_kernel<64><<<grid, 64, 0, s>>>((const __half*)Q, *tails, tail_ml, tail_o, plan);
-        else
-            attend_tail_kernel<256><<<grid, 64, 0, s>>>((const __half*)Q, *tails, tail_ml, tail_o, plan);
+        using TailKern = decltype(&attend_tail_kernel<128, false>);
+        static const TailKern tail_table[3][2] = {{attend_tail_kernel<64, false>, attend_tail_kernel<64, true>},
+                                                  {attend_tail_kernel<128, false>, attend_tail_kernel<128, true>},
+                                                  {attend_tail_kernel<256, false>, attend_tail_kernel<256, true>}};
+        tail_table[plan.D == 64 ? 0 : plan.D == 128 ? 1 : 2][plan.io_bf16 ? 1 : 0]<<<grid, 64, 0, s>>>(
+            (const __half*)Q, *tails, tail_ml, tail_o, plan);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     const long nrows = (long)units * plan.R;
