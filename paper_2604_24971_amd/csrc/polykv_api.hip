@@ -155,13 +155,28 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
         // tiles per wave -- below that the per-workgroup prologue, epilogue and the partials written for
         // the merge kernel cost more than the idle CUs (measured on one-layer calls of the Llama shape:
         // 16 splits of 8 tiles 16.8 us, 32 splits of 4 tiles 19.3 us).
-        const int block_rows = matrix_kernel_block_rows(p.D, p.vcodec);
-        const long groups = (long)units * ((p.R + block_rows - 1) / block_rows);
-        long want = (256 + groups - 1) / groups;
-        if (want > cap_tiles / 8) want = cap_tiles / 8;
-        if (prm->splits > 0) want = prm->splits;
-        if (want > (cap_tiles + 3) / 4) want = (cap_tiles + 3) / 4;
-        if (want < 1) want = 1;
+        // Rows per workgroup: 64 where the kernel has such a form, but 32 when 64-row blocks, split as far as
+        // the two-tiles-per-wave rule allows, would leave CUs without a workgroup (one-layer calls: 8 KV heads x
+        // 16 splits = 128 workgroups of 64 rows, or 256 of 32 rows that each do half the matrix work).
+        auto splits_for = [&](int block_rows, long* n_groups) {
+            const long groups = (long)units * ((p.R + block_rows - 1) / block_rows);
+            long want = (256 + groups - 1) / groups;
+            if (want > cap_tiles / 8) want = cap_tiles / 8;
+            if (prm->splits > 0) want = prm->splits;
+            if (want > (cap_tiles + 3) / 4) want = (cap_tiles + 3) / 4;
+            if (want < 1) want = 1;
+            *n_groups = groups;
+            return want;
+        };
+        int block_rows = matrix_kernel_block_rows(p.D, p.vcodec);
+        long groups = 0;
+        long want = splits_for(block_rows, &groups);
+        if (block_rows == 64 && p.R > 32 && groups * want < 256) {
+            long g32 = 0;
+            const long w32 = splits_for(32, &g32);
+            if (g32 * w32 > groups * want) block_rows = 32, want = w32;
+        }
+        p.block_rows = block_rows;
         nsplit = (int)want;
     }
     p.nsplit = nsplit;

@@ -760,7 +760,7 @@ static hipError_t launch_dv(const polykv_pool* pool, const AttendPlan& plan, con
     const int direct = matrix_kernel_direct(plan) ? 1 : 0;
     constexpr bool two_tiles_fit = D == 64 || (D == 128 && VC != 2 && VC != 6);   // matrix_kernel_block_rows()
     if constexpr (two_tiles_fit) {
-        if (plan.R > 32)
+        if (plan.R > 32 && plan.block_rows == 64)
             return launch_one<D, 2, VC, KC, K16>(dim3(plan.nsplit, units, (plan.R + 63) / 64), storage, plan, Q, ws_ml, ws_o,
                                                  out, direct, s);
     }

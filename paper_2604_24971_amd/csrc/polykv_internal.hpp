@@ -42,6 +42,7 @@ struct AttendPlan {
     float qscale;                // softmax scale * log2(e): scores are kept in base-2 units
     int kernel;                  // POLYKV_KERNEL_VECTOR / _MATRIX (resolved)
     int nsplit;                  // token-range splits per KV head
+    int block_rows;              // matrix-core kernel: query rows per workgroup, 64 or 32
     int has_tails, tail_capacity, tail_causal;
     int io_bf16;                 // 1: Q and the tails are bfloat16, 0: fp16
     int key_fp16;                // 1: scores over the dequantized keys rounded to fp16 (POLYKV_KEY_PRECISION_FP16)
