@@ -277,7 +277,7 @@ def main():
     # (what this GPU sustains for read + write traffic) and pool_attend launched back to back on its own
     # (the attention kernel is issue-bound, so its duration follows the shader clock, which the power
     # management keeps lower while memory-bound kernels run in between).
-    t_copy = t_att_iso = k_att_iso = append_rate = None
+    t_copy = t_att_iso = k_att_iso = k_att_zero = append_rate = None
     other = None
     if args.extras:
         def timed(fn, n):
@@ -290,6 +290,18 @@ def main():
             return float(np.median([a.elapsed_time(b) for a, b in evs])) * 1e-3
         t_copy = timed(lambda: Kd.copy_(K), 10)
         t_att_iso, k_att_iso = attend_back_to_back(pk, pools, Q, out, ws, tails, kprec, args.steps)
+        # The same launches over all-zero contents (zero K, V and Q: the same kernel, instruction stream and
+        # bytes).  The power management lowers the shader clock by how much the operands make the matrix cores
+        # and vector ALUs switch; with nothing switching the kernel shows what its instruction stream alone
+        # takes at the full clock.
+        if tails is None and not args.per_layer:
+            zK, zV, zQ = torch.zeros_like(K), torch.zeros_like(V), torch.zeros_like(Q)
+            for p in pools:
+                p.encode(zK, zV)
+            k_att_zero = attend_back_to_back(pk, pools, zQ, out, ws, None, kprec, args.steps)[1]
+            del zK, zV, zQ
+            for p in pools:
+                p.encode(K, V)
         # incremental fill: the same tensors appended 64 tokens at a time into a pool of the same capacity
         chunk = 64
         Kc = [K[:, :, i:i + chunk].contiguous() for i in range(0, T - chunk + 1, chunk)]
@@ -381,6 +393,12 @@ def main():
         "attend_back_to_back_note": "pool_attend launched back to back over the rotated pools, outside the timed "
                                     "region: kernel duration from the kernel's own events; call_ms = stream events "
                                     "around each call (kernel + launch gap)",
+        "attend_zero_data_back_to_back_ms": k_att_zero and k_att_zero * 1e3,
+        "attend_zero_data_frac_of_hbm_peak": k_att_zero and att_bytes / k_att_zero / 1e9 / HBM_PEAK_GBPS,
+        "attend_zero_data_note": "the same back-to-back launches with K = V = Q = 0 (same kernel, same bytes): the "
+                                 "duration of the instruction stream at the full shader clock; with random data the "
+                                 "power management lowers the clock (2.4 -> about 1.4 GHz), which is the gap to the "
+                                 "figure above",
         "other_configs": other,
         "device_copy_GB_per_s": t_copy and 2 * K.numel() * 2 / t_copy / 1e9,
         "append_64_tokens_per_s": append_rate,
