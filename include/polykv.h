@@ -217,7 +217,9 @@ size_t pool_attend_workspace(const polykv_pool* pool, const polykv_attend_params
 
 /* Q_dev: fp16 (or bfloat16, see io_dtype) [layer_end-layer_begin, agents, q_per_agent, q_heads, head_dim];
  * out_dev: fp32, same shape.  Reads the pool only; concurrent calls on different streams are
- * safe if they use different workspaces. */
+ * safe if they use different workspaces.  POLYKV_ESHAPE for shapes beyond the launch limits: more than 2^20 query
+ * rows (agents * q_per_agent * q_heads / kv_heads) per KV head; more than 262,140 with POLYKV_KERNEL_VECTOR; with
+ * tails, q_per_agent * q_heads / kv_heads above 262,140.  POLYKV_EINVAL for a negative or non-finite scale. */
 int pool_attend(const polykv_pool* pool, const void* Q_dev, void* out_dev,
                 const polykv_attend_params* params, void* stream);
 

@@ -132,6 +132,15 @@ static int make_plan(const polykv_pool* pool, const polykv_attend_params* prm, A
         return POLYKV_ESHAPE;
     }
     p.kernel = prm->kernel == POLYKV_KERNEL_AUTO ? (mat_ok ? POLYKV_KERNEL_MATRIX : POLYKV_KERNEL_VECTOR) : prm->kernel;
+    // Launch limits: the vector kernel and the tail kernel put their 4-row blocks on grid.z (at most 65,535).
+    if (p.kernel == POLYKV_KERNEL_VECTOR && (p.R + 3) / 4 > 65535) {
+        set_error("pool_attend: the vector kernel supports at most 262,140 query rows per KV head (got %d)", p.R);
+        return POLYKV_ESHAPE;
+    }
+    if (tails && ((long)p.nq * p.G + 3) / 4 > 65535) {
+        set_error("pool_attend: with tails, q_per_agent * (q_heads / kv_heads) = %ld exceeds 262,140", (long)p.nq * p.G);
+        return POLYKV_ESHAPE;
+    }
     p.key_fp16 = (prm->key_precision == POLYKV_KEY_PRECISION_FP16 && p.kernel == POLYKV_KERNEL_MATRIX &&
                   p.kcodec == POLYKV_KEYS_Q8_BLOCK32 && p.vcodec == POLYKV_VALUES_TQ3 && p.D != 256)
                      ? 1

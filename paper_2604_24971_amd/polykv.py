@@ -192,7 +192,7 @@ class Pool:
             _check(lib.pool_set_sign_seed(self._h, sign_seed))
         self.nbytes = lib.pool_bytes(self._h)
         self.storage = None
-        self._workspace = None
+        self._workspaces = {}   # stream handle -> cached attend workspace
 
     def bind(self, storage: torch.Tensor | None = None):
         if storage is None:
@@ -315,9 +315,12 @@ class Pool:
         if need == 0:
             _check(lib.pool_attend(self._h, None, None, C.byref(p), None))  # surfaces the shape error
         if workspace is None:
-            if self._workspace is None or self._workspace.numel() < need:
-                self._workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
-            workspace = self._workspace
+            # one cached workspace per stream: calls on different streams may overlap and must not share one
+            key = _stream_ptr(stream).value
+            ws = self._workspaces.get(key)
+            if ws is None or ws.numel() < need:
+                ws = self._workspaces[key] = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+            workspace = ws
         p.workspace_dev = _dev_ptr(workspace, torch.uint8, "workspace")
         p.workspace_bytes = workspace.numel()
         if out is None:

@@ -182,6 +182,21 @@ def test_attend_plan_validation_and_workspace_size():
     assert lib.pool_attend_workspace(h, C.byref(q)) == 0
     q.tail_capacity = 8
     assert lib.pool_attend_workspace(h, C.byref(q)) > need
+    # launch limits: 4-row blocks of the vector and tail kernels sit on grid.z (65,535 at most)
+    big = pk.AttendParams.from_buffer_copy(p)
+    big.agents, big.q_per_agent = 1, 65536                       # 262,144 rows per KV head
+    assert lib.pool_attend_workspace(h, C.byref(big)) > 0        # fine for the matrix kernel
+    big.kernel = pk.KERNEL_VECTOR
+    assert lib.pool_attend_workspace(h, C.byref(big)) == 0
+    assert b"262,140" in lib.polykv_last_error()
+    q.q_per_agent = 65536
+    assert lib.pool_attend_workspace(h, C.byref(q)) == 0
+    big.kernel, big.q_per_agent = pk.KERNEL_AUTO, (1 << 18) + 1   # more than 2^20 rows
+    assert lib.pool_attend_workspace(h, C.byref(big)) == 0
+    for bad in (-1.0, float("nan"), float("inf")):
+        q = pk.AttendParams.from_buffer_copy(p)
+        q.scale = bad
+        assert lib.pool_attend_workspace(h, C.byref(q)) == 0, bad
     lib.pool_destroy(h)
 
 
