@@ -62,23 +62,41 @@ def cpu_baseline(cfg, W, layers=None):
     }
 
 
-def attend_back_to_back(pk, pools, Q, out, ws, tails, kprec, n):
-    """pool_attend n times in a row over the rotated pools.  Returns (median stream-level time per call, median
+def attend_back_to_back(pk, pools, Q, out, ws, tails, kprec, n=None):
+    """pool_attend in a row over the rotated pools, in steady state: the launches run for about 60 ms before the
+    timed ones start (the shader clock takes tens of milliseconds to settle after a burst begins) and n launches
+    (default: about 100 ms worth, at least 20) are timed.  Returns (median stream-level time per call, median
     duration of the call's main kernel), seconds."""
     import torch
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n + 3)]
+
+    def launch(i):
+        pools[i % len(pools)].attend(Q, out, workspace=ws, tails=tails, key_precision=kprec)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(3):
+        launch(i)
+    a.record()
+    for i in range(5):
+        launch(i)
+    b.record()
+    torch.cuda.synchronize()
+    est = max(a.elapsed_time(b) * 1e-3 / 5, 1e-6)             # seconds per call, roughly
+    warm = int(min(max(0.06 / est, 3), 5000))
+    n = int(min(max(0.1 / est, 20), 3000)) if n is None else n
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n)]
     for e in evs:
         for x in e:
             x.record()
     torch.cuda.synchronize()
+    for i in range(warm):
+        launch(i)
     for i, e in enumerate(evs):
         e[0].record()
         pk.time_next_kernel(e[2], e[3])
-        pools[i % len(pools)].attend(Q, out, workspace=ws, tails=tails, key_precision=kprec)
+        launch(warm + i)
         e[1].record()
     torch.cuda.synchronize()
-    call = float(np.median([e[0].elapsed_time(e[1]) for e in evs[3:]])) * 1e-3
-    kern = float(np.median([e[2].elapsed_time(e[3]) for e in evs[3:]])) * 1e-3
+    call = float(np.median([e[0].elapsed_time(e[1]) for e in evs])) * 1e-3
+    kern = float(np.median([e[2].elapsed_time(e[3]) for e in evs])) * 1e-3
     return call, kern
 
 
@@ -114,7 +132,7 @@ def other_config(pk, W, n, kprec):
                          [tail_len] * cfg.agents)
     del K, V
     ws = torch.empty(max(pools[0].attend_workspace_bytes(Q, tails=tails), 256), dtype=torch.uint8, device="cuda")
-    call, kern = attend_back_to_back(pk, pools, Q, out, ws, tails, kprec, 10)
+    call, kern = attend_back_to_back(pk, pools, Q, out, ws, tails, kprec)
     tail_bytes = cfg.agents * tail_len * units * 4 * d
     nbytes = packed + Q.numel() * 2 + out.numel() * 4 + tail_bytes
     R = cfg.rows_per_kv_head
@@ -143,8 +161,10 @@ VALUE_CODECS = {"tq3": (0, 3, False), "tq3-scaled": (1, 3, True), "int8": (2, 8,
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    # The defaults measure the steady state: after a burst of work begins the shader clock needs tens of
+    # milliseconds to settle (the first steps run up to 25 % slower), so 100 steps (~35 ms) warm up and 500 are timed.
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", type=int, default=3, help="workload configuration (default: Llama-3-8B shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pools", type=int, default=3, help="distinct pool copies rotated between steps")
@@ -289,7 +309,7 @@ def main():
             torch.cuda.synchronize()
             return float(np.median([a.elapsed_time(b) for a, b in evs])) * 1e-3
         t_copy = timed(lambda: Kd.copy_(K), 10)
-        t_att_iso, k_att_iso = attend_back_to_back(pk, pools, Q, out, ws, tails, kprec, args.steps)
+        t_att_iso, k_att_iso = attend_back_to_back(pk, pools, Q, out, ws, tails, kprec)
         # The same launches over all-zero contents (zero K, V and Q: the same kernel, instruction stream and
         # bytes).  The power management lowers the shader clock by how much the operands make the matrix cores
         # and vector ALUs switch; with nothing switching the kernel shows what its instruction stream alone
@@ -298,7 +318,7 @@ def main():
             zK, zV, zQ = torch.zeros_like(K), torch.zeros_like(V), torch.zeros_like(Q)
             for p in pools:
                 p.encode(zK, zV)
-            k_att_zero = attend_back_to_back(pk, pools, zQ, out, ws, None, kprec, args.steps)[1]
+            k_att_zero = attend_back_to_back(pk, pools, zQ, out, ws, None, kprec)[1]
             del zK, zV, zQ
             for p in pools:
                 p.encode(K, V)
@@ -356,7 +376,7 @@ def main():
            "stream), median over the timed steps; traffic = the stored rocprofv3 FETCH_SIZE + WRITE_SIZE figure of "
            "profiles/ (copy-scaled), not measured in this run")
     vc = codec                                                          # the kernels' value-codec template argument
-    nt = 1 if (cfg.rows_per_kv_head <= 32 or d == 256 or (vc in (2, 6) and d == 128)) else 2
+    nt = 1 if (cfg.rows_per_kv_head <= 32 or d == 256 or (vc in (1, 2, 6) and d == 128)) else 2
     kc = 1 if args.key_codec == "tensor" else 0
     attend_roof = roof(att_gbps, "attend_mfma_kernel<%d,%d,%d,%d,%s> (pool_attend)" % (d, nt, vc, kc, "true" if args.key_precision == "fp16" else "false") + how +
                        "; achieved = algorithmic bytes (packed pool + Q + out) / duration")

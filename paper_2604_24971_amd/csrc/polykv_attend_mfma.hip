@@ -12,8 +12,9 @@
 //            code*s has up to 18 significant bits, so it is split exactly into two fp16 terms
 //            hi = fp16(code*s), lo = code*s - hi (one packed fma), each fed to the two K=16 MFMAs of a
 //            q8_0 block with fp32 accumulation: key dequantization stays exact.
-//   softmax  online, per row, in base-2 units; the reference maximum is only raised when a row
-//            exceeds it by more than 2^8, so the accumulator rescale is rare; p <= 256 fits fp16.
+//   softmax  online, per row, in base-2 units; a row's reference only moves when the row's probabilities
+//            of one tile sum to more than 2^15 in a lane, so the accumulator rescale is rare, p fits
+//            fp16, and the common case takes no maximum over the scores at all.
 //   PV       O^T[v, r] += sum_t c[code[t, v]] * p[t, r]   with the score tile's accumulator layout
 //            feeding the B operand directly (the value codes are stored in that k-order), centroids
 //            looked up with byte permutes.  The softmax denominator is summed from the very same
@@ -170,8 +171,26 @@ __device__ __forceinline__ void key_split(const RawK<D>& rk, int j, int s, half8
     lo = __builtin_elementwise_fma(a.h, sv, -hi);  // exact remainder of the product
 }
 
+// Constants the main loop keeps in scalar registers.  As 32-bit literals they would double the size of every
+// instruction that uses them, and a lone wave's instruction fetch is what bounds the loop.
+struct LoopConsts {
+    uint32_t m7, m3, m4;   // byte masks 0x07070707, 0x03030303, 0x04040404 (value-code selectors)
+    half2v one2;           // (1, 1): the packed dot product that sums a pair of probabilities
+};
+__device__ __forceinline__ LoopConsts make_loop_consts() {
+    uint32_t m7 = 0x07070707u, m3 = 0x03030303u, m4 = 0x04040404u, one = 0x3c003c00u;
+    asm volatile("" : "+s"(m7), "+s"(m3), "+s"(m4), "+s"(one));   // opaque: the compiler would fold them back
+    union {
+        uint32_t u;
+        half2v h;
+    } o;
+    o.u = one;
+    return LoopConsts{m7, m3, m4, o.h};
+}
+
 // Value group G of a lane: eight 3-bit codes -> fp16 centroids, the A operand of one P.V product.
-template <int D, int VC> __device__ __forceinline__ void value_group(const RawV<D, VC>& rv, int G, H8& va) {
+template <int D, int VC>
+__device__ __forceinline__ void value_group(const RawV<D, VC>& rv, int G, H8& va, const LoopConsts& lc) {
     if (vc_bits(VC) == 4) {
         group8_b4(rv.n[G], va.u);
         return;
@@ -189,7 +208,7 @@ template <int D, int VC> __device__ __forceinline__ void value_group(const RawV<
         return;
     }
     uint32_t sel_a, sel_b;
-    vcode_selectors(rv.w[G >> 2][0], rv.w[G >> 2][1], rv.w[G >> 2][2], G & 3, sel_a, sel_b);
+    vcode_selectors(rv.w[G >> 2][0], rv.w[G >> 2][1], rv.w[G >> 2][2], G & 3, lc.m7, lc.m3, lc.m4, sel_a, sel_b);
     lookup4(sel_a, va.u[0], va.u[1]);
     lookup4(sel_b, va.u[2], va.u[3]);
 }
@@ -201,13 +220,12 @@ __device__ __forceinline__ float max16(const float16v& a) {
     return fmaxf(m, a[15]);
 }
 
-// Four scores of a row -> fp16 probabilities (packed pairs) and their sum into the denominator.  With
+// Four scores of a row -> fp16 probabilities (packed pairs) and their sum into lsum (the tile's sum).  With
 // value scales (g != nullptr: the lane's RawV::g) the P.V operand is p * scale of its token (formed in fp32,
 // rounded to fp16 once), at most 2^8 * 2^7; the denominator sums the plain, unrounded p.
 template <bool VS>
 __device__ __forceinline__ void exp4(const float16v& S, int c, float qscale, float mneg, H8 (&pb)[2], float& lsum,
-                                     const uint32_t* g) {
-    const half2v one2 = {(_Float16)1.0f, (_Float16)1.0f};
+                                     const uint32_t* g, half2v one2) {
 #pragma unroll
     for (int pr = 0; pr < 2; ++pr) {
         const int i = 4 * c + 2 * pr;
@@ -236,10 +254,10 @@ __device__ __forceinline__ void exp4(const float16v& S, int c, float qscale, flo
 // The pool's last tile when it crosses the end of the pool, read straight from memory: scores, softmax
 // and PV one after the other, tokens >= T masked out.  Runs at most once per KV head.
 template <int D, int NT, int VC, int KC, bool K16>
-__device__ __forceinline__ void process_ragged_tile(TileRsrc rs, uint32_t lt, int tile, int T, float qscale, float raise_thr,
+__device__ __forceinline__ void process_ragged_tile(TileRsrc rs, uint32_t lt, int tile, int T, float qscale,
                                                  int lane, const half8 (&qb)[NT][D / 32][2], float16v (&O)[D / 32][NT],
-                                                 float (&Lsum)[NT], float (&m_ref)[NT], float (&m_thr)[NT],
-                                                 float (&mneg)[NT]) {
+                                                 float (&Lsum)[NT], float (&m_ref)[NT], float (&mneg)[NT],
+                                                 const LoopConsts& lc) {
     constexpr int NB = D / 32, NG = D / 16;
     const int h = lane >> 5;
     RawK<D> rk;
@@ -276,18 +294,17 @@ __device__ __forceinline__ void process_ragged_tile(TileRsrc rs, uint32_t lt, in
         const float m_new = fmaxf(m_ref[nt], xor32_max(max16(S[nt])));
         const float alpha = __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
         m_ref[nt] = m_new;
-        m_thr[nt] = m_new + raise_thr;
         mneg[nt] = -m_new * qscale;
         Lsum[nt] *= alpha;
 #pragma unroll
         for (int g = 0; g < D / 32; ++g) O[g][nt] *= alpha;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) exp4<vc_has_scale(VC)>(S[nt], c, qscale, mneg[nt], pb[nt], Lsum[nt], rv.g);
+        for (int c = 0; c < 4; ++c) exp4<vc_has_scale(VC)>(S[nt], c, qscale, mneg[nt], pb[nt], Lsum[nt], rv.g, lc.one2);
     }
 #pragma unroll
     for (int G = 0; G < NG; ++G) {
         H8 va;
-        value_group<D, VC>(rv, G, va);
+        value_group<D, VC>(rv, G, va, lc);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) O[G >> 1][nt] = mfma32(va.h, pb[nt][G & 1].h, O[G >> 1][nt]);
     }
@@ -302,46 +319,31 @@ __device__ __forceinline__ void process_ragged_tile(TileRsrc rs, uint32_t lt, in
 //   rv, rk     tile A's value codes and tile B's key codes / scales, in registers
 //   rvN, rkN   the same for the next step, requested here from nextV (the tile after A) and nextK (the
 //              tile after B); the caller alternates the two register sets, so nothing is copied
-//   Sa         scores of tile A on entry, of tile B on exit; mloc / raise: per-lane row maxima of the
-//              same tile and whether some row outgrew the reference
+//   Sa         scores of tile A on entry, of tile B on exit
 // Only full tiles go through here; a ragged last tile is handled by process_ragged_tile.
+//
+// Softmax bookkeeping: the reference m_ref (raw score units) of a row only moves when the row's probabilities
+// of a tile, taken against the old reference, sum to more than raise_sum() in one of the row's two lanes.  Every
+// probability that reaches a P.V product is therefore at most raise_sum(): 2^15 for the plain codecs (fp16
+// holds it; what matters for the result is the relative precision of a probability, which does not depend on its
+// magnitude, and a probability 2^-29 below the row's largest may flush to zero), 2^8 with value scales (the
+// operand is probability times a scale of up to 2^7).  The common case takes no maximum over the scores, and on
+// keys with outlier channels, where a row's maximum keeps creeping up, the expensive rescale of the accumulators
+// stays rare: with 2^8 it was a tenth of the kernel's time on the Llama-shaped workload.
+constexpr float raise_sum(bool value_scales) { return value_scales ? 256.0f : 32768.0f; }
+
 template <int D, int NT, int VC, int KC, bool K16, bool HAS_A, bool HAS_B>
 __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<D>& rk, RawV<D, VC>& rvN, RawK<D>& rkN,
-                                              TileRsrc rs, uint32_t nextK, uint32_t nextV, float qscale,
-                                              float raise_thr, int lane, const half8 (&qb)[NT][D / 32][2],
-                                              float16v (&O)[D / 32][NT], float (&Lsum)[NT], float (&m_ref)[NT],
-                                              float (&m_thr)[NT], float (&mneg)[NT], float16v (&Sa)[NT],
-                                              float (&mloc)[NT], bool& raise) {
+                                              TileRsrc rs, uint32_t nextK, uint32_t nextV, float qscale, int lane,
+                                              const half8 (&qb)[NT][D / 32][2], float16v (&O)[D / 32][NT],
+                                              float (&Lsum)[NT], float (&m_ref)[NT], float (&mneg)[NT],
+                                              float16v (&Sa)[NT], const LoopConsts& lc) {
     constexpr int NB = D / 32, NG = D / 16, MG = D / 32;
     const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     float16v Sb[NT];
-
-    if (HAS_A && __builtin_expect(__any(raise), 0)) {
-        // Rare: a row of tile A outgrew the softmax reference by more than 2^8.  The accumulators live
-        // in accumulation registers that vector instructions cannot read; an MFMA with zero operands
-        // (D = 0*0 + C) carries them to vector registers and back, so the hot path never copies them.
+    float lt[NT];   // this tile's probability sums, per lane
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            // Only the rows that outgrew their reference move it: a row's result then depends on that
-            // row's scores alone, whatever other agents' rows share the wave.
-            const float row_max = xor32_max(mloc[nt]);
-            const float m_new = row_max > m_thr[nt] ? fmaxf(m_ref[nt], row_max) : m_ref[nt];
-            const float alpha = m_new == m_ref[nt] ? 1.0f : __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
-            const bool first = __all(m_ref[nt] == -INFINITY);  // nothing accumulated yet: nothing to rescale
-            m_ref[nt] = m_new;
-            m_thr[nt] = m_new + raise_thr;
-            mneg[nt] = -m_new * qscale;
-            if (!first) {
-                Lsum[nt] *= alpha;
-#pragma unroll
-                for (int g = 0; g < MG; ++g) {
-                    float16v y = mfma32(zero8, zero8, O[g][nt]);
-                    y *= alpha;
-                    O[g][nt] = mfma32(zero8, zero8, y);
-                }
-            }
-        }
-    }
+    for (int nt = 0; nt < NT; ++nt) lt[nt] = 0.0f;
 
     // The step is written as a sequence of slices.  Each slice pairs a batch of MFMAs whose operands
     // are ready with the vector work that prepares the operands of the NEXT batch, and is closed by a
@@ -376,7 +378,7 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
     H8 pb[NT][2];      // probabilities of tile A: B operands of the P.V products, [row tile][k slice]
     half8 khi[2], klo[2];
     H8 va[2];
-    auto exp_chunk = [&](int c) { exp4<vc_has_scale(VC)>(Sa[c >> 2], c & 3, qscale, mneg[c >> 2], pb[c >> 2], Lsum[c >> 2], rv.g); };
+    auto exp_chunk = [&](int c) { exp4<vc_has_scale(VC)>(Sa[c >> 2], c & 3, qscale, mneg[c >> 2], pb[c >> 2], lt[c >> 2], rv.g, lc.one2); };
     auto kdeq = [&](int k) { key_split<D, KC>(rk, k >> 1, k & 1, khi[k & 1], klo[k & 1]); };
     auto qk = [&](int k) {
         const int j = k >> 1, s = k & 1;
@@ -387,7 +389,7 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
             for (int nt = 0; nt < NT; ++nt) Sb[nt] = mfma32(klo[k & 1], qb[nt][j][s], Sb[nt]);
         }
     };
-    auto vdeq = [&](int G) { value_group<D, VC>(rv, G, va[G & 1]); };
+    auto vdeq = [&](int G) { value_group<D, VC>(rv, G, va[G & 1], lc); };
     auto pv = [&](int G) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) O[G >> 1][nt] = mfma32(va[G & 1].h, pb[nt][G & 1].h, O[G >> 1][nt]);
@@ -412,54 +414,69 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
                 const int c0 = lead + (k * (NCH - lead)) / NQK, c1 = lead + ((k + 1) * (NCH - lead)) / NQK;
 #pragma unroll
                 for (int c = c0; c < c1; ++c) exp_chunk(c);
-                if (k + 1 == NQK) vdeq(0);
             }
             slice_end(integral_constant<int, (KC == 0 && !K16 ? 2 : 1) * NT>{}, integral_constant<int, (HAS_A ? 28 : 16)>{});
         }
     } else if (HAS_A) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) exp_chunk(c);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    if (HAS_A) {
+        // Does a row have to move its reference?  Rare after a row's first tiles (always at its very first tile,
+        // where the reference is -inf and every probability comes out as +inf).  The probabilities of the rows
+        // that move are then recomputed against the new reference; those of the other rows come out as they
+        // were.  Only the rows that outgrew their reference move it: a row's result depends on that row's
+        // scores alone, whatever other agents' rows share the wave.
+        bool raise = false;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) raise |= !(lt[nt] <= raise_sum(vc_has_scale(VC)));
+        if (__builtin_expect(__any(raise), 0)) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const bool row_raise = !(xor32_max(lt[nt]) <= raise_sum(vc_has_scale(VC)));   // (+inf stays +inf through the max)
+                const float row_max = xor32_max(max16(Sa[nt]));
+                const float m_new = row_raise ? fmaxf(m_ref[nt], row_max) : m_ref[nt];
+                const float alpha = m_new == m_ref[nt] ? 1.0f : __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
+                const bool first = __all(m_ref[nt] == -INFINITY);  // nothing accumulated yet: nothing to rescale
+                m_ref[nt] = m_new;
+                mneg[nt] = -m_new * qscale;
+                if (!first) {
+                    // The accumulators live in accumulation registers that vector instructions cannot read; an
+                    // MFMA with zero operands (D = 0*0 + C) carries them to vector registers and back, so the
+                    // hot path never copies them.
+                    Lsum[nt] *= alpha;
+#pragma unroll
+                    for (int g = 0; g < MG; ++g) {
+                        float16v y = mfma32(zero8, zero8, O[g][nt]);
+                        y *= alpha;
+                        O[g][nt] = mfma32(zero8, zero8, y);
+                    }
+                }
+                lt[nt] = 0.0f;
+#pragma unroll
+                for (int c = 4 * nt; c < 4 * nt + 4; ++c) exp_chunk(c);
+            }
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) Lsum[nt] += lt[nt];
         vdeq(0);
         __builtin_amdgcn_sched_barrier(0);
     }
 
-    // The per-lane row maxima of tile B (for the next step's vote; no cross-lane reduction is needed for the
-    // vote) are taken while the P.V products of tile A run: that phase is bound by the matrix cores, so the
-    // accumulator reads and the maxima ride along for free.
-    constexpr bool kMaxInPV = HAS_A && HAS_B && NG >= 4;
-    constexpr int SPS = kMaxInPV ? 16 * NT / NG : 0;  // scores per P.V slice: 16 NT scores over NG slices
-    static_assert(!kMaxInPV || (SPS >= 1 && SPS * NG == 16 * NT), "");
-    if (kMaxInPV) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) mloc[nt] = -INFINITY;
-    }
     if (HAS_A) {
 #pragma unroll
         for (int G = 0; G < NG; ++G) {
             pv(G);
             if (G + 1 < NG) vdeq(G + 1);
-            if (kMaxInPV) {
-#pragma unroll
-                for (int x = G * SPS; x < (G + 1) * SPS; x += 2) {
-                    const int nt = x / 16, i = x % 16;
-                    if (x + 1 < (G + 1) * SPS)
-                        mloc[nt] = fmaxf(fmaxf(mloc[nt], Sb[nt][i]), Sb[nt][i + 1]);
-                    else  // an odd count (one score per slice at head_dim 256)
-                        mloc[nt] = fmaxf(mloc[nt], Sb[nt][i]);
-                }
-            }
-            slice_end(integral_constant<int, NT>{}, integral_constant<int, (kMaxInPV ? 12 + (3 * SPS + 1) / 2 : 12)>{});
+            slice_end(integral_constant<int, NT>{}, integral_constant<int, 12>{});
         }
     }
 
     if (HAS_B) {
-        raise = false;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            if (!kMaxInPV) mloc[nt] = max16(Sb[nt]);
-            raise |= mloc[nt] > m_thr[nt];  // also true while the reference is -inf
-            Sa[nt] = Sb[nt];
-        }
+        for (int nt = 0; nt < NT; ++nt) Sa[nt] = Sb[nt];
     }
 }
 
@@ -581,17 +598,14 @@ __global__ __launch_bounds__(256, kernel_waves_per_simd(D, NT, VC)) void attend_
                 for (int s = 0; s < 2; ++s) asm volatile("" : "+a"(qb[nt][j][s]));
     }
 
-    float Lsum[NT], m_ref[NT], m_thr[NT], mneg[NT], mloc[NT];
+    float Lsum[NT], m_ref[NT], mneg[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         m_ref[nt] = -INFINITY;
-        m_thr[nt] = -INFINITY;
-        mneg[nt] = 0.0f;
-        mloc[nt] = -INFINITY;
+        mneg[nt] = INFINITY;   // no reference yet: the first tile's probabilities come out as +inf and set one
         Lsum[nt] = 0.0f;
     }
-    const float raise_thr = 8.0f / qscale;  // raise the reference only when a row exceeds it by 2^8
-    bool raise = false;
+    const LoopConsts lc = make_loop_consts();
     float16v S[NT];  // scores of the tile whose softmax comes next
 
     // Local tile k is "B" in step k-1 (scores) and "A" in step k (softmax, PV).  Only the pool's very
@@ -603,28 +617,21 @@ __global__ __launch_bounds__(256, kernel_waves_per_simd(D, NT, VC)) void attend_
         RawK<D> rk2;
         RawV<D, VC> rv2;
         // prologue: scores of tile 0 from rk; requests K of tile 1 and (again) V of tile 0 into set 2
-        pipeline_step<D, NT, VC, KC, K16, false, true>(rv, rk, rv2, rk2, rs, tile_ptr(1), tile_ptr(0), qscale, raise_thr, lane, qb, O, Lsum,
-                                          m_ref, m_thr, mneg, S, mloc, raise);
+        pipeline_step<D, NT, VC, KC, K16, false, true>(rv, rk, rv2, rk2, rs, tile_ptr(1), tile_ptr(0), qscale, lane, qb, O, Lsum, m_ref, mneg, S, lc);
         int s = 0;
         for (; s + 1 < full_count - 1; s += 2) {  // two steps per trip: the sets swap roles without copies
-            pipeline_step<D, NT, VC, KC, K16, true, true>(rv2, rk2, rv, rk, rs, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
-                                             O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
-            pipeline_step<D, NT, VC, KC, K16, true, true>(rv, rk, rv2, rk2, rs, tile_ptr(s + 3), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
-                                             O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
+            pipeline_step<D, NT, VC, KC, K16, true, true>(rv2, rk2, rv, rk, rs, tile_ptr(s + 2), tile_ptr(s + 1), qscale, lane, qb, O, Lsum, m_ref, mneg, S, lc);
+            pipeline_step<D, NT, VC, KC, K16, true, true>(rv, rk, rv2, rk2, rs, tile_ptr(s + 3), tile_ptr(s + 2), qscale, lane, qb, O, Lsum, m_ref, mneg, S, lc);
         }
         if (s < full_count - 1) {  // one step with a B tile left: current = set 2
-            pipeline_step<D, NT, VC, KC, K16, true, true>(rv2, rk2, rv, rk, rs, tile_ptr(s + 2), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
-                                             O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
-            pipeline_step<D, NT, VC, KC, K16, true, false>(rv, rk, rv2, rk2, rs, tile_ptr(s + 2), tile_ptr(s + 2), qscale, raise_thr, lane, qb,
-                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
+            pipeline_step<D, NT, VC, KC, K16, true, true>(rv2, rk2, rv, rk, rs, tile_ptr(s + 2), tile_ptr(s + 1), qscale, lane, qb, O, Lsum, m_ref, mneg, S, lc);
+            pipeline_step<D, NT, VC, KC, K16, true, false>(rv, rk, rv2, rk2, rs, tile_ptr(s + 2), tile_ptr(s + 2), qscale, lane, qb, O, Lsum, m_ref, mneg, S, lc);
         } else {
-            pipeline_step<D, NT, VC, KC, K16, true, false>(rv2, rk2, rv, rk, rs, tile_ptr(s + 1), tile_ptr(s + 1), qscale, raise_thr, lane, qb,
-                                              O, Lsum, m_ref, m_thr, mneg, S, mloc, raise);
+            pipeline_step<D, NT, VC, KC, K16, true, false>(rv2, rk2, rv, rk, rs, tile_ptr(s + 1), tile_ptr(s + 1), qscale, lane, qb, O, Lsum, m_ref, mneg, S, lc);
         }
     }
     if (last_ragged)
-        process_ragged_tile<D, NT, VC, KC, K16>(rs, tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, raise_thr, lane, qb, O,
-                                   Lsum, m_ref, m_thr, mneg);
+        process_ragged_tile<D, NT, VC, KC, K16>(rs, tile_ptr(my_count - 1), my_first + 4 * (my_count - 1), p.T, qscale, lane, qb, O, Lsum, m_ref, mneg, lc);
 
     // ---- merge the four waves through LDS: every wave stores its row maxima, denominators and accumulators
     // as they are into buffers of its own; the final pass rescales them to the common row maximum and adds
@@ -724,11 +731,13 @@ bool matrix_kernel_supports(int head_dim, int rows_per_kv_head, int value_codec)
 }
 
 // Query rows per workgroup: 64 where the accumulators, the parked queries, two tiles of scores and two staged
-// tiles fit the 512 registers of a wave; 32 at head_dim 256 and, at head_dim 128, for the two codecs with the
-// most staged value bytes per tile (int8, and 4-bit codes with a scale).
+// tiles fit the 512 registers of a wave; 32 at head_dim 256 and, at head_dim 128, for the three codecs with the
+// most staged value bytes per tile (int8, and 3- or 4-bit codes with a scale).
 int matrix_kernel_block_rows(int head_dim, int value_codec) {
     if (head_dim == 256) return 32;
-    if (head_dim == 128 && (value_codec == POLYKV_VALUES_INT8 || value_codec == POLYKV_VALUES_TQ4_SCALED)) return 32;
+    if (head_dim == 128 && (value_codec == POLYKV_VALUES_INT8 || value_codec == POLYKV_VALUES_TQ4_SCALED ||
+                            value_codec == POLYKV_VALUES_TQ3_SCALED))
+        return 32;
     return 64;
 }
 
@@ -758,7 +767,7 @@ static hipError_t launch_dv(const polykv_pool* pool, const AttendPlan& plan, con
     const uint8_t* storage = reinterpret_cast<const uint8_t*>(pool->storage);
     const int units = plan.layers * plan.H;
     const int direct = matrix_kernel_direct(plan) ? 1 : 0;
-    constexpr bool two_tiles_fit = D == 64 || (D == 128 && VC != 2 && VC != 6);   // matrix_kernel_block_rows()
+    constexpr bool two_tiles_fit = D == 64 || (D == 128 && VC != 1 && VC != 2 && VC != 6);   // matrix_kernel_block_rows()
     if constexpr (two_tiles_fit) {
         if (plan.R > 32 && plan.block_rows == 64)
             return launch_one<D, 2, VC, KC, K16>(dim3(plan.nsplit, units, (plan.R + 63) / 64), storage, plan, Q, ws_ml, ws_o,

@@ -272,17 +272,23 @@ __device__ __forceinline__ int vcode_extract_b2(const uint32_t* v, int D, int t,
 }
 
 // Value-code selectors of one lane's triplet (w0, w1, w2): group gi (0..3) -> the codes of its eight
-// tokens, e = 0..3 in the bytes of sel_a and e = 4..7 in the bytes of sel_b.
-__device__ __forceinline__ void vcode_selectors(uint32_t w0, uint32_t w1, uint32_t w2, int gi, uint32_t& sel_a,
-                                                uint32_t& sel_b) {
+// tokens, e = 0..3 in the bytes of sel_a and e = 4..7 in the bytes of sel_b.  m7, m3, m4 are the byte masks
+// 0x07070707, 0x03030303 and 0x04040404: a caller whose loop is bound by instruction fetch keeps them in
+// registers (as literals they would double the size of the instructions that use them).
+__device__ __forceinline__ void vcode_selectors(uint32_t w0, uint32_t w1, uint32_t w2, int gi, uint32_t m7, uint32_t m3,
+                                                uint32_t m4, uint32_t& sel_a, uint32_t& sel_b) {
     if (gi < 3) {
         const uint32_t w = gi == 0 ? w0 : gi == 1 ? w1 : w2;
-        sel_a = w & 0x07070707u;
-        sel_b = (w >> 3) & 0x07070707u;
+        sel_a = w & m7;
+        sel_b = (w >> 3) & m7;
     } else {
-        sel_a = ((w0 >> 6) & 0x03030303u) | ((w1 >> 4) & 0x04040404u);
-        sel_b = ((w2 >> 6) & 0x03030303u) | ((w1 >> 5) & 0x04040404u);
+        sel_a = ((w0 >> 6) & m3) | ((w1 >> 4) & m4);
+        sel_b = ((w2 >> 6) & m3) | ((w1 >> 5) & m4);
     }
+}
+__device__ __forceinline__ void vcode_selectors(uint32_t w0, uint32_t w1, uint32_t w2, int gi, uint32_t& sel_a,
+                                                uint32_t& sel_b) {
+    vcode_selectors(w0, w1, w2, gi, 0x07070707u, 0x03030303u, 0x04040404u, sel_a, sel_b);
 }
 
 // ---- Walsh-Hadamard stages across the 8 lanes that share a token in the codec kernels ----------

@@ -447,18 +447,19 @@ def test_one_long_head_and_very_many_short_units():
 
 @pytest.mark.parametrize("d", [64, 128, 256])
 def test_attend_scores_that_keep_climbing_raise_the_softmax_reference_again_and_again(d):
-    # Along the pool the scores of some rows grow by more than 2^8 from tile to tile, so the matrix kernel has
-    # to move its softmax reference (and rescale what it has accumulated) in nearly every step, for those rows
-    # only; other rows of the same wave stay flat or fall.
+    # Along the pool the scores of some rows grow by more than 2^15 from tile to tile (17 to 18 binary orders:
+    # within a tile the probabilities against the old reference overflow fp16), so the matrix kernel has to move
+    # its softmax reference (and rescale what it has accumulated) in every step, for those rows only; others rise
+    # gently (a move every other tile), stay flat or fall.
     rng = np.random.default_rng(31 + d)
     T, A, qh = 330, 3, 4
     qdir = rng.standard_normal(d)
     qdir /= np.linalg.norm(qdir)
-    ramp = np.linspace(0.0, 9.0, T)[:, None]                          # key length along qdir
+    ramp = np.linspace(0.0, 14.0, T)[:, None]                         # key length along qdir
     K = (ramp * qdir[None, :] + 0.02 * rng.standard_normal((T, d))).astype(np.float16)[None, None]
     V = rng.standard_normal((1, 1, T, d)).astype(np.float16)
     case = Case(W.PoolConfig(0, "climb", 1, 1, qh, d, T, A, 1), K, V)
-    # rows: steeply rising (80 nats over the pool: 8 per tile), gently rising, flat, falling
+    # rows: steeply rising (126 nats over the pool: 12 per tile), gently rising, flat, falling
     lengths = np.array([9.0, 4.0, 0.0, -6.0, 9.0, 1.0, -9.0, 0.5, 2.0, 9.0, -1.0, 6.0])
     Q = (lengths[:, None] * qdir[None, :]).astype(np.float16).reshape(1, A, 1, qh, d)
     case.attend_check(Q, scale=1.0, splits=1)
