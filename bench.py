@@ -193,10 +193,12 @@ def main():
     ap.add_argument("--key-precision", choices=("exact", "fp16"), default="exact",
                     help="exact = scores over code * scale exactly (headline); fp16 = over the dequantized keys rounded "
                     "to fp16, the precision of the dense cache the paper's read path attends over")
-    ap.add_argument("--phases", default="eda", help="subset of e(ncode) d(ecode) a(ttend) to run per step; "
-                    "anything but the default is for profiling one kernel and is marked partial")
+    ap.add_argument("--phases", default="eda", help="the phases of a step, in the order given: e(ncode) d(ecode) "
+                    "a(ttend); a subset is for profiling one kernel and is marked partial")
     args = ap.parse_args()
-    args.extras = not args.no_extras and args.phases == "eda" and not args.per_layer
+    if not args.phases or len(set(args.phases)) != len(args.phases) or not set(args.phases) <= set("eda"):
+        ap.error("--phases takes each of e, d, a at most once")
+    args.extras = not args.no_extras and len(args.phases) == 3 and not args.per_layer
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the pool path shards by layer / KV head "
               "with no exchange between GPUs", file=sys.stderr)
@@ -239,39 +241,37 @@ def main():
         ws = torch.empty(max(pools[0].attend_workspace_bytes(Ql[0], tails=tails, layer_begin=0, layer_end=1), 256),
                          dtype=torch.uint8, device="cuda")
 
-    if args.phases != "eda":
+    if args.phases[0] != "e":
         for p in pools:
             p.encode(K, V)
 
     def step(i, ev=None, kev=None):
-        # ev: four events recorded on the stream between the calls (stream-level phase times, launch gaps
-        # included); kev: three (start, stop) pairs stamped by the runtime at the begin / end of each call's
-        # main kernel (kernel durations, what rocprofv3 --kernel-trace reports)
+        # The phases run in the order --phases names them.  ev: per phase a (before, after) pair of events
+        # recorded on the stream around the call (stream-level phase times, launch gaps included); kev: three
+        # (start, stop) pairs stamped by the runtime at the begin / end of each call's main kernel (kernel
+        # durations, what rocprofv3 --kernel-trace reports).  Index 0 = encode, 1 = decode, 2 = attend.
         p = pools[i % len(pools)]
-        if ev:
-            ev[0].record()
-        if "e" in args.phases:
-            if kev:
-                pk.time_next_kernel(*kev[0])
-            p.encode(K, V)
-        if ev:
-            ev[1].record()
-        if "d" in args.phases:
-            if kev:
-                pk.time_next_kernel(*kev[1])
-            p.decode(io_dtype, Kd, Vd)
-        if ev:
-            ev[2].record()
-        if "a" in args.phases:
-            if args.per_layer:
+        for ph in args.phases:
+            idx = "eda".index(ph)
+            if ev:
+                ev[2 * idx].record()
+            if ph == "e":
+                if kev:
+                    pk.time_next_kernel(*kev[0])
+                p.encode(K, V)
+            elif ph == "d":
+                if kev:
+                    pk.time_next_kernel(*kev[1])
+                p.decode(io_dtype, Kd, Vd)
+            elif args.per_layer:
                 for l in range(L):
                     p.attend(Ql[l], outl[l], layer_begin=l, layer_end=l + 1, workspace=ws, tails=tails, key_precision=kprec)
             else:
                 if kev:
                     pk.time_next_kernel(*kev[2])
                 p.attend(Q, out, workspace=ws, tails=tails, key_precision=kprec)
-        if ev:
-            ev[3].record()
+            if ev:
+                ev[2 * idx + 1].record()
 
     if args.calibrate_copy:      # elementwise copy kernel: reads and writes K.numel()*2 bytes
         for _ in range(3):
@@ -279,7 +279,10 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    for e in events:                 # (a phase that is left out keeps its pair: recorded here, zero apart)
+        for x in e:
+            x.record()
     kevents = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(3)]
                for _ in range(args.steps)]
     for trio in kevents:             # torch creates an event's handle at its first record()
@@ -343,8 +346,8 @@ def main():
             other = [other_config(pk, W, n, kprec) for n in (2, 4, 5)]
 
     enc = np.array([e[0].elapsed_time(e[1]) for e in events]) * 1e-3
-    dec = np.array([e[1].elapsed_time(e[2]) for e in events]) * 1e-3
-    att = np.array([e[2].elapsed_time(e[3]) for e in events]) * 1e-3
+    dec = np.array([e[2].elapsed_time(e[3]) for e in events]) * 1e-3
+    att = np.array([e[4].elapsed_time(e[5]) for e in events]) * 1e-3
     t_enc, t_dec, t_att = (max(float(np.median(x)), 1e-9) for x in (enc, dec, att))    # stream-level, with launch gaps
 
     def kernel_time(idx, phase, fallback):
@@ -376,7 +379,7 @@ def main():
            "stream), median over the timed steps; traffic = the stored rocprofv3 FETCH_SIZE + WRITE_SIZE figure of "
            "profiles/ (copy-scaled), not measured in this run")
     vc = codec                                                          # the kernels' value-codec template argument
-    nt = 1 if (cfg.rows_per_kv_head <= 32 or d == 256 or (vc in (1, 2, 6) and d == 128)) else 2
+    nt = 1 if (cfg.rows_per_kv_head <= 32 or d == 256 or (vc in (2, 6) and d == 128)) else 2
     kc = 1 if args.key_codec == "tensor" else 0
     attend_roof = roof(att_gbps, "attend_mfma_kernel<%d,%d,%d,%d,%s> (pool_attend)" % (d, nt, vc, kc, "true" if args.key_precision == "fp16" else "false") + how +
                        "; achieved = algorithmic bytes (packed pool + Q + out) / duration")
@@ -398,7 +401,7 @@ def main():
                    "value_codec": args.value_codec, "key_codec": args.key_codec, "key_precision": args.key_precision, "dense_dtype": "bf16" if args.bf16 else "f16",
                    "tail_len": args.tail_len, "tail_bytes": tail_bytes,
                    "attend_calls_per_step": L if args.per_layer else 1},
-        "step": "pool_encode -> pool_decode(fp16) -> pool_attend, all layers",
+        "step": " -> ".join({"e": "pool_encode", "d": "pool_decode(fp16)", "a": "pool_attend"}[ph] for ph in args.phases) + ", all layers",
         "encode_tokens_per_s": T / k_enc, "encode_GB_per_s": enc_bytes / k_enc / 1e9,
         "decode_GB_per_s": dec_bytes / k_dec / 1e9,
         "kernel_ms": {"attend": k_att * 1e3, "encode": k_enc * 1e3, "decode": k_dec * 1e3},
@@ -429,7 +432,7 @@ def main():
     for key, name in (("roofline_encode", "encode_hbm_bytes_per_launch"), ("roofline_decode", "decode_hbm_bytes_per_launch")):
         if name in vals:
             result[key]["traffic"] = float(vals[name])
-    if args.phases != "eda":
+    if len(args.phases) != 3:
         result["partial"] = "phases=%s: not a full step" % args.phases
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, W)

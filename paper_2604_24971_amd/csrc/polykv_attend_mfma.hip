@@ -256,7 +256,7 @@ __device__ __forceinline__ void exp4(const float16v& S, int c, float qscale, flo
 template <int D, int NT, int VC, int KC, bool K16>
 __device__ __forceinline__ void process_ragged_tile(TileRsrc rs, uint32_t lt, int tile, int T, float qscale,
                                                  int lane, const half8 (&qb)[NT][D / 32][2], float16v (&O)[D / 32][NT],
-                                                 float (&Lsum)[NT], float (&m_ref)[NT], float (&mneg)[NT],
+                                                 float (&Lsum)[NT], float* m_ref, float (&mneg)[NT],
                                                  const LoopConsts& lc) {
     constexpr int NB = D / 32, NG = D / 16;
     const int h = lane >> 5;
@@ -291,9 +291,10 @@ __device__ __forceinline__ void process_ragged_tile(TileRsrc rs, uint32_t lt, in
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         // this path always re-references: cheap here, and it needs no vote
-        const float m_new = fmaxf(m_ref[nt], xor32_max(max16(S[nt])));
-        const float alpha = __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
-        m_ref[nt] = m_new;
+        const float m_old = m_ref[32 * nt];
+        const float m_new = fmaxf(m_old, xor32_max(max16(S[nt])));
+        const float alpha = __builtin_amdgcn_exp2f((m_old - m_new) * qscale);
+        m_ref[32 * nt] = m_new;
         mneg[nt] = -m_new * qscale;
         Lsum[nt] *= alpha;
 #pragma unroll
@@ -336,7 +337,7 @@ template <int D, int NT, int VC, int KC, bool K16, bool HAS_A, bool HAS_B>
 __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<D>& rk, RawV<D, VC>& rvN, RawK<D>& rkN,
                                               TileRsrc rs, uint32_t nextK, uint32_t nextV, float qscale, int lane,
                                               const half8 (&qb)[NT][D / 32][2], float16v (&O)[D / 32][NT],
-                                              float (&Lsum)[NT], float (&m_ref)[NT], float (&mneg)[NT],
+                                              float (&Lsum)[NT], float* m_ref, float (&mneg)[NT],
                                               float16v (&Sa)[NT], const LoopConsts& lc) {
     constexpr int NB = D / 32, NG = D / 16, MG = D / 32;
     const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -437,10 +438,11 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
             for (int nt = 0; nt < NT; ++nt) {
                 const bool row_raise = !(xor32_max(lt[nt]) <= raise_sum(vc_has_scale(VC)));   // (+inf stays +inf through the max)
                 const float row_max = xor32_max(max16(Sa[nt]));
-                const float m_new = row_raise ? fmaxf(m_ref[nt], row_max) : m_ref[nt];
-                const float alpha = m_new == m_ref[nt] ? 1.0f : __builtin_amdgcn_exp2f((m_ref[nt] - m_new) * qscale);
-                const bool first = __all(m_ref[nt] == -INFINITY);  // nothing accumulated yet: nothing to rescale
-                m_ref[nt] = m_new;
+                const float m_old = m_ref[32 * nt];
+                const float m_new = row_raise ? fmaxf(m_old, row_max) : m_old;
+                const float alpha = m_new == m_old ? 1.0f : __builtin_amdgcn_exp2f((m_old - m_new) * qscale);
+                const bool first = __all(m_old == -INFINITY);  // nothing accumulated yet: nothing to rescale
+                m_ref[32 * nt] = m_new;
                 mneg[nt] = -m_new * qscale;
                 if (!first) {
                     // The accumulators live in accumulation registers that vector instructions cannot read; an
@@ -598,10 +600,14 @@ __global__ __launch_bounds__(256, kernel_waves_per_simd(D, NT, VC)) void attend_
                 for (int s = 0; s < 2; ++s) asm volatile("" : "+a"(qb[nt][j][s]));
     }
 
-    float Lsum[NT], m_ref[NT], mneg[NT];
+    // The references themselves are only read where a row moves its reference and at the merge: they live in the
+    // wave's row of m_s (LDS), not in registers.  Both lanes of a row hold the same value and write the same value;
+    // a wave's LDS accesses complete in order, so a wave reading back what it wrote needs no barrier.
+    float* const m_ref = &m_s[wave][n];   // row 32 nt + n at m_ref[32 * nt]
+    float Lsum[NT], mneg[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        m_ref[nt] = -INFINITY;
+        m_ref[32 * nt] = -INFINITY;
         mneg[nt] = INFINITY;   // no reference yet: the first tile's probabilities come out as +inf and set one
         Lsum[nt] = 0.0f;
     }
@@ -643,7 +649,6 @@ __global__ __launch_bounds__(256, kernel_waves_per_simd(D, NT, VC)) void attend_
             const int r = 32 * nt + n;
             const float l = xor32_sum(Lsum[nt]);  // the lane pair (n, h) shares a row
             if (h == 0) {
-                m_s[wave][r] = m_ref[nt];
                 l_s[wave * ROWS + r] = l;
             }
 #pragma unroll
@@ -731,13 +736,11 @@ bool matrix_kernel_supports(int head_dim, int rows_per_kv_head, int value_codec)
 }
 
 // Query rows per workgroup: 64 where the accumulators, the parked queries, two tiles of scores and two staged
-// tiles fit the 512 registers of a wave; 32 at head_dim 256 and, at head_dim 128, for the three codecs with the
-// most staged value bytes per tile (int8, and 3- or 4-bit codes with a scale).
+// tiles fit the 512 registers of a wave; 32 at head_dim 256 and, at head_dim 128, for the two codecs with the
+// most staged value bytes per tile (int8, and 4-bit codes with a scale).
 int matrix_kernel_block_rows(int head_dim, int value_codec) {
     if (head_dim == 256) return 32;
-    if (head_dim == 128 && (value_codec == POLYKV_VALUES_INT8 || value_codec == POLYKV_VALUES_TQ4_SCALED ||
-                            value_codec == POLYKV_VALUES_TQ3_SCALED))
-        return 32;
+    if (head_dim == 128 && (value_codec == POLYKV_VALUES_INT8 || value_codec == POLYKV_VALUES_TQ4_SCALED)) return 32;
     return 64;
 }
 
@@ -767,7 +770,7 @@ static hipError_t launch_dv(const polykv_pool* pool, const AttendPlan& plan, con
     const uint8_t* storage = reinterpret_cast<const uint8_t*>(pool->storage);
     const int units = plan.layers * plan.H;
     const int direct = matrix_kernel_direct(plan) ? 1 : 0;
-    constexpr bool two_tiles_fit = D == 64 || (D == 128 && VC != 1 && VC != 2 && VC != 6);   // matrix_kernel_block_rows()
+    constexpr bool two_tiles_fit = D == 64 || (D == 128 && VC != 2 && VC != 6);   // matrix_kernel_block_rows()
     if constexpr (two_tiles_fit) {
         if (plan.R > 32 && plan.block_rows == 64)
             return launch_one<D, 2, VC, KC, K16>(dim3(plan.nsplit, units, (plan.R + 63) / 64), storage, plan, Q, ws_ml, ws_o,
