@@ -225,7 +225,7 @@ __device__ __forceinline__ float max16(const float16v& a) {
 // rounded to fp16 once), at most 2^8 * 2^7; the denominator sums the plain, unrounded p.
 template <bool VS>
 __device__ __forceinline__ void exp4(const float16v& S, int c, float qscale, float mneg, H8 (&pb)[2], float& lsum,
-                                     const uint32_t* g, half2v one2) {
+                                     const uint32_t* g, half2v one2, float* gmax = nullptr) {
 #pragma unroll
     for (int pr = 0; pr < 2; ++pr) {
         const int i = 4 * c + 2 * pr;
@@ -244,8 +244,10 @@ __device__ __forceinline__ void exp4(const float16v& S, int c, float qscale, flo
                 _Float16 h[2];
             } g2;
             g2.u = g[i >> 1];
-            p2[0] = (_Float16)(e0 * (float)g2.h[0]);
-            p2[1] = (_Float16)(e1 * (float)g2.h[1]);
+            const float g0 = (float)g2.h[0], g1 = (float)g2.h[1];
+            p2[0] = (_Float16)(e0 * g0);
+            p2[1] = (_Float16)(e1 * g1);
+            if (gmax != nullptr) *gmax = fmaxf(fmaxf(*gmax, g0), g1);   // the largest scale among the lane's tokens
         }
         pb[i >> 3].p[(i & 7) >> 1] = p2;
     }
@@ -324,14 +326,15 @@ __device__ __forceinline__ void process_ragged_tile(TileRsrc rs, uint32_t lt, in
 // Only full tiles go through here; a ragged last tile is handled by process_ragged_tile.
 //
 // Softmax bookkeeping: the reference m_ref (raw score units) of a row only moves when the row's probabilities
-// of a tile, taken against the old reference, sum to more than raise_sum() in one of the row's two lanes.  Every
-// probability that reaches a P.V product is therefore at most raise_sum(): 2^15 for the plain codecs (fp16
-// holds it; what matters for the result is the relative precision of a probability, which does not depend on its
-// magnitude, and a probability 2^-29 below the row's largest may flush to zero), 2^8 with value scales (the
-// operand is probability times a scale of up to 2^7).  The common case takes no maximum over the scores, and on
-// keys with outlier channels, where a row's maximum keeps creeping up, the expensive rescale of the accumulators
-// stays rare: with 2^8 it was a tenth of the kernel's time on the Llama-shaped workload.
-constexpr float raise_sum(bool value_scales) { return value_scales ? 256.0f : 32768.0f; }
+// of a tile, taken against the old reference, sum to more than kRaiseSum = 2^15 in one of the row's two lanes --
+// with value scales: when that sum times the largest scale among the lane's tokens of the tile does.  Every operand
+// that reaches a P.V product (a probability, or a probability times its token's scale) is therefore at most 2^15:
+// fp16 holds it; what matters for the result is the relative precision of a probability, which does not depend on
+// its magnitude, and a probability 2^-29 below the row's largest may flush to zero.  The common case takes no
+// maximum over the scores, and on keys with outlier channels, where a row's maximum keeps creeping up, the expensive
+// rescale of the accumulators stays rare: with a threshold of 2^8 it was a tenth of the kernel's time on the
+// Llama-shaped workload.
+constexpr float kRaiseSum = 32768.0f;
 
 template <int D, int NT, int VC, int KC, bool K16, bool HAS_A, bool HAS_B>
 __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<D>& rk, RawV<D, VC>& rvN, RawK<D>& rkN,
@@ -379,7 +382,11 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
     H8 pb[NT][2];      // probabilities of tile A: B operands of the P.V products, [row tile][k slice]
     half8 khi[2], klo[2];
     H8 va[2];
-    auto exp_chunk = [&](int c) { exp4<vc_has_scale(VC)>(Sa[c >> 2], c & 3, qscale, mneg[c >> 2], pb[c >> 2], lt[c >> 2], rv.g, lc.one2); };
+    float gmax = vc_has_scale(VC) ? 5.9604645e-8f : 1.0f;   // (not 0: an infinite sum times it must still say "move")
+    auto exp_chunk = [&](int c) {
+        exp4<vc_has_scale(VC)>(Sa[c >> 2], c & 3, qscale, mneg[c >> 2], pb[c >> 2], lt[c >> 2], rv.g, lc.one2,
+                               vc_has_scale(VC) && c < 4 ? &gmax : nullptr);
+    };
     auto kdeq = [&](int k) { key_split<D, KC>(rk, k >> 1, k & 1, khi[k & 1], klo[k & 1]); };
     auto qk = [&](int k) {
         const int j = k >> 1, s = k & 1;
@@ -430,13 +437,16 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
         // that move are then recomputed against the new reference; those of the other rows come out as they
         // were.  Only the rows that outgrew their reference move it: a row's result depends on that row's
         // scores alone, whatever other agents' rows share the wave.
+        // gmax: the largest value scale among the lane's 16 tokens of this tile (1 without value scales), collected
+        // by the chunks of row tile 0; the products probability x scale stay below kRaiseSum if the tile's sum of
+        // probabilities times gmax does
         bool raise = false;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) raise |= !(lt[nt] <= raise_sum(vc_has_scale(VC)));
+        for (int nt = 0; nt < NT; ++nt) raise |= !(lt[nt] * gmax <= kRaiseSum);   // (inf and NaN say yes)
         if (__builtin_expect(__any(raise), 0)) {
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const bool row_raise = !(xor32_max(lt[nt]) <= raise_sum(vc_has_scale(VC)));   // (+inf stays +inf through the max)
+                const bool row_raise = !(xor32_max(lt[nt] * gmax) <= kRaiseSum);   // (+inf stays +inf through the max)
                 const float row_max = xor32_max(max16(Sa[nt]));
                 const float m_old = m_ref[32 * nt];
                 const float m_new = row_raise ? fmaxf(m_old, row_max) : m_old;
