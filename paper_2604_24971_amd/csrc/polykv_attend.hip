@@ -532,10 +532,25 @@ hipError_t launch_attend(const polykv_pool* pool, const AttendPlan& plan, const 
     const int units = plan.layers * plan.H;
     hipError_t err;
 
+    // The private tails go first: their partials are independent of the pool's, and where the matrix-core kernel
+    // writes the final output itself it takes them in (through its ws_ml / ws_o arguments, which it does not
+    // otherwise use then) instead of leaving them to the merge kernel.
+    if (plan.has_tails) {
+        dim3 grid(plan.A, units, (plan.nq * plan.G + kRB - 1) / kRB);
+        using TailKern = decltype(&attend_tail_kernel<128, false>);
+        static const TailKern tail_table[3][2] = {{attend_tail_kernel<64, false>, attend_tail_kernel<64, true>},
+                                                  {attend_tail_kernel<128, false>, attend_tail_kernel<128, true>},
+                                                  {attend_tail_kernel<256, false>, attend_tail_kernel<256, true>}};
+        tail_table[plan.D == 64 ? 0 : plan.D == 128 ? 1 : 2][plan.io_bf16 ? 1 : 0]<<<grid, 64, 0, s>>>(
+            (const __half*)Q, *tails, tail_ml, tail_o, plan);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
     if (plan.kernel == POLYKV_KERNEL_MATRIX) {
-        err = launch_attend_matrix(pool, plan, Q, ws_ml, ws_o, (float*)out, s);
+        const bool direct = matrix_kernel_direct(plan);
+        err = launch_attend_matrix(pool, plan, Q, direct && plan.has_tails ? tail_ml : ws_ml,
+                                   direct && plan.has_tails ? tail_o : ws_o, (float*)out, s);
         if (err != hipSuccess) return err;
-        if (matrix_kernel_direct(plan)) return hipSuccess;
+        if (direct) return hipSuccess;
     } else {
         dim3 grid(plan.nsplit / 4, units, (plan.R + kRB - 1) / kRB);
         using Kern = decltype(&attend_vector_kernel<128, 0, 0>);
@@ -549,16 +564,6 @@ hipError_t launch_attend(const polykv_pool* pool, const AttendPlan& plan, const 
 #undef POLYKV_VEC_ROW
         auto kern = table[plan.kcodec][plan.D == 64 ? 0 : plan.D == 128 ? 1 : 2][plan.vcodec];
         launch_main_kernel(kern, grid, dim3(256), 0, s, storage, (const __half*)Q, ws_ml, ws_o, plan);
-        if ((err = hipGetLastError()) != hipSuccess) return err;
-    }
-    if (plan.has_tails) {
-        dim3 grid(plan.A, units, (plan.nq * plan.G + kRB - 1) / kRB);
-        using TailKern = decltype(&attend_tail_kernel<128, false>);
-        static const TailKern tail_table[3][2] = {{attend_tail_kernel<64, false>, attend_tail_kernel<64, true>},
-                                                  {attend_tail_kernel<128, false>, attend_tail_kernel<128, true>},
-                                                  {attend_tail_kernel<256, false>, attend_tail_kernel<256, true>}};
-        tail_table[plan.D == 64 ? 0 : plan.D == 128 ? 1 : 2][plan.io_bf16 ? 1 : 0]<<<grid, 64, 0, s>>>(
-            (const __half*)Q, *tails, tail_ml, tail_o, plan);
         if ((err = hipGetLastError()) != hipSuccess) return err;
     }
     const long nrows = (long)units * plan.R;

@@ -497,6 +497,8 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
 // so that one workgroup's query fetch, pipeline ramp and merge overlap the others' main loops).
 constexpr int kernel_waves_per_simd(int D, int NT, int VC) { return (D == 64 && NT == 1 && vc_bits(VC) == 3 && !vc_has_scale(VC)) ? 3 : 1; }
 
+// ws_ml / ws_o: where the kernel leaves its split's partial (direct == 0); with direct == 1 and private tails,
+// the tail kernel's partials (row maxima and denominators / unnormalized sums), read in the final pass.
 template <int D, int NT, int VC, int KC, bool K16>
 __global__ __launch_bounds__(256, kernel_waves_per_simd(D, NT, VC)) void attend_mfma_kernel(const uint8_t* __restrict__ pool,
                                                           const __half* __restrict__ Q,
@@ -687,12 +689,29 @@ __global__ __launch_bounds__(256, kernel_waves_per_simd(D, NT, VC)) void attend_
         for (int w = 0; w < 4; ++w)
             fw[w] = m_s[w][rr] == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f((m_s[w][rr] - Mr) * qscale);
         const float l = (l_s[rr] * fw[0] + l_s[ROWS + rr] * fw[1]) + (l_s[2 * ROWS + rr] * fw[2] + l_s[3 * ROWS + rr] * fw[3]);
+        // Direct output with private tails: the row's tail partial (maximum in base-2 units, denominator and
+        // unnormalized sum in the original value domain; written by the tail kernel, which ran before this one
+        // and whose buffers arrive in ws_ml / ws_o) joins by log-sum-exp weights: the pool part gets wa / den
+        // instead of 1 / l, the tail part wb / den once the pool part has been rotated back.
+        float inv_l = __builtin_amdgcn_rcpf(l), tail_w = 0.0f;
+        size_t tail_row = 0;
+        if (direct && p.has_tails) {
+            tail_row = (size_t)usel * p.R + min(r, p.R - 1);
+            const float tm = ws_ml[tail_row * 2], tl = ws_ml[tail_row * 2 + 1];
+            if (tl > 0.0f) {
+                const float Mp = Mr * qscale, M2 = fmaxf(Mp, tm);
+                const float wa = __builtin_amdgcn_exp2f(Mp - M2), wb = __builtin_amdgcn_exp2f(tm - M2);
+                const float inv = 1.0f / (wa * l + wb * tl);
+                inv_l = wa * inv;
+                tail_w = wb * inv;
+            }
+        }
         // direct: 1/l, the centroid scale, 1/sqrt(D) and the entry sign of the DPP stages in one factor
         // int8 values are accumulated unrotated and unscaled: 1/l is all that is left to do
         constexpr float kCS = inv_centroid_scale<vc_bits(VC)>();
-        const float f = VC == 2 ? (direct ? __builtin_amdgcn_rcpf(l) : 1.0f)
+        const float f = VC == 2 ? (direct ? inv_l : 1.0f)
                         : direct ? quad_entry_sign(lane) * (kCS * (D == 64 ? 0.125f : D == 128 ? 0.08838834764831845f : 0.0625f)) *
-                                       __builtin_amdgcn_rcpf(l)
+                                       inv_l
                                  : kCS;
 #pragma unroll
         for (int w = 0; w < 4; ++w) fw[w] *= f;
@@ -718,6 +737,17 @@ __global__ __launch_bounds__(256, kernel_waves_per_simd(D, NT, VC)) void attend_
                         float(&x4)[4] = *reinterpret_cast<float(*)[4]>(&x[4 * i]);
                         flip_signs<4>(x4, sign_word(p.signs, i >> 1) >> (16 * (i & 1) + 4 * qd));
                     }
+                }
+            }
+            if (tail_w != 0.0f) {
+                const float4* t4 = reinterpret_cast<const float4*>(ws_o + tail_row * D) + qd;
+#pragma unroll
+                for (int i = 0; i < CPL / 4; ++i) {
+                    const float4 t = t4[4 * i];
+                    x[4 * i] = fmaf(tail_w, t.x, x[4 * i]);
+                    x[4 * i + 1] = fmaf(tail_w, t.y, x[4 * i + 1]);
+                    x[4 * i + 2] = fmaf(tail_w, t.z, x[4 * i + 2]);
+                    x[4 * i + 3] = fmaf(tail_w, t.w, x[4 * i + 3]);
                 }
             }
             if (r < p.R) {
@@ -754,7 +784,7 @@ int matrix_kernel_block_rows(int head_dim, int value_codec) {
     return 64;
 }
 
-bool matrix_kernel_direct(const AttendPlan& plan) { return plan.nsplit == 1 && !plan.has_tails; }
+bool matrix_kernel_direct(const AttendPlan& plan) { return plan.nsplit == 1; }
 
 template <int D, int NT, int VC, int KC, bool K16>
 static hipError_t launch_one(dim3 grid, const uint8_t* storage, const AttendPlan& plan, const void* Q, float* ws_ml,
