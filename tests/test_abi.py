@@ -228,3 +228,14 @@ def test_header_is_valid_c99(tmp_path):
     r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
                         "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
+
+
+def test_bench_command_line_refuses_more_than_one_gpu_and_malformed_phases():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    bench = os.path.join(root, "bench.py")
+    r = subprocess.run([sys.executable, bench, "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
+    r = subprocess.run([sys.executable, bench, "--phases", "ee"], capture_output=True, text=True)
+    assert r.returncode != 0 and "--phases" in r.stderr
