@@ -22,6 +22,18 @@
 
 namespace polykv {
 
+// The dense output of pool_decode is written once and read by some later kernel, 537 MB of it at the Llama shape:
+// it is stored with the non-temporal hint, so that it streams to memory instead of sitting in the last-level
+// cache as dirty lines whose write-back the NEXT kernels would pay for (measured: whatever followed pool_decode
+// ran 9-10 us longer; decode itself takes 2-3 us more this way).  Every store instruction of a wave covers whole
+// cache lines (see decode_kernel), which is what makes streaming stores cheap here.  The packed pool that
+// pool_encode writes keeps ordinary stores: it is what the next kernels read, and streaming it cost 3 us.
+typedef uint32_t StreamQuad __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void stream_store16(void* dst, uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    const StreamQuad q = {a, b, c, d};
+    __builtin_nontemporal_store(q, reinterpret_cast<StreamQuad*>(dst));
+}
+
 template <int D> __device__ __forceinline__ constexpr float inv_sqrt_d() {
     return D == 64 ? 0.125f : D == 128 ? 0.08838834764831845f : 0.0625f;
 }
@@ -540,8 +552,7 @@ template <int N> struct RowStore<__half, N> {
     static __device__ __forceinline__ void store(__half* dst, const float (&x)[N]) {
 #pragma unroll
         for (int i = 0; i < N / 8; ++i) {
-            uint4 o;
-            uint32_t* w = reinterpret_cast<uint32_t*>(&o);
+            uint32_t w[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 Half2Bits b;
@@ -549,7 +560,7 @@ template <int N> struct RowStore<__half, N> {
                 b.h[1] = (_Float16)x[8 * i + 2 * k + 1];
                 w[k] = b.u;
             }
-            reinterpret_cast<uint4*>(dst)[i] = o;
+            stream_store16(reinterpret_cast<uint4*>(dst) + i, w[0], w[1], w[2], w[3]);
         }
     }
 };
@@ -565,12 +576,11 @@ template <int N> struct RowStore<Bf16Out, N> {
     static __device__ __forceinline__ void store(Bf16Out* dst, const float (&x)[N]) {
 #pragma unroll
         for (int i = 0; i < N / 8; ++i) {
-            uint4 o;
-            uint32_t* w = reinterpret_cast<uint32_t*>(&o);
+            uint32_t w[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k)  // high halves of the two rounded words
                 w[k] = __builtin_amdgcn_perm(rne(x[8 * i + 2 * k + 1]), rne(x[8 * i + 2 * k]), 0x07060302u);
-            reinterpret_cast<uint4*>(dst)[i] = o;
+            stream_store16(reinterpret_cast<uint4*>(dst) + i, w[0], w[1], w[2], w[3]);
         }
     }
 };
@@ -578,7 +588,8 @@ template <int N> struct RowStore<float, N> {
     static __device__ __forceinline__ void store(float* dst, const float (&x)[N]) {
 #pragma unroll
         for (int i = 0; i < N / 4; ++i)
-            reinterpret_cast<float4*>(dst)[i] = make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
+            stream_store16(reinterpret_cast<float4*>(dst) + i, __float_as_uint(x[4 * i]), __float_as_uint(x[4 * i + 1]),
+                           __float_as_uint(x[4 * i + 2]), __float_as_uint(x[4 * i + 3]));
     }
 };
 
