@@ -240,8 +240,11 @@ __global__ __launch_bounds__(256) void attend_vector_kernel(const uint8_t* __res
 // ------------------------------------------------------------------------------ tail kernel ---
 // Dense 16-bit attention of one agent's rows over its private, uncompressed continuation.
 // One wave per (selected layer, kv head, agent, block of kRB rows); emits (m, l, o) in the original domain.
-// Written for many waves per SIMD (under 128 registers): the tails are small and scattered, so what hides
-// the memory latency is other waves, not a deep pipeline inside one.  Per block of 64 tokens:
+// The loops over a block's loads and pieces are unrolled in full: the compiler then keeps a block's key row and
+// the query pieces in registers (all 256 at head_dim 128, one wave per SIMD plus what the 19 KB of LDS allow) and
+// has every load of a block in flight at once.  Held under 128 registers for more waves per SIMD the kernel is
+// 2 % faster on 64-token tails of all layers and 4 % slower on one layer's 32-token tails (measured); the
+// unrolled form stays.  Per block of 64 tokens:
 //   scores  the 64 key rows are fetched with coalesced loads and staged in LDS; lane = token then walks its
 //           row in 16-byte pieces; the products with the raw 16-bit queries (LDS broadcast) are packed dot
 //           products with fp32 accumulation, the softmax scale is applied to the sum;
