@@ -450,6 +450,7 @@ __device__ __forceinline__ void pipeline_step(const RawV<D, VC>& rv, const RawK<
                 const float row_max = xor32_max(max16(Sa[nt]));
                 const float m_old = m_ref[32 * nt];
                 const float m_new = row_raise ? fmaxf(m_old, row_max) : m_old;
+                if (!__any(m_new != m_old)) continue;   // no row of this row tile moves: it keeps what it has
                 const float alpha = m_new == m_old ? 1.0f : __builtin_amdgcn_exp2f((m_old - m_new) * qscale);
                 const bool first = __all(m_old == -INFINITY);  // nothing accumulated yet: nothing to rescale
                 m_ref[32 * nt] = m_new;
