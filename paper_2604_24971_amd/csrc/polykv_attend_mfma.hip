@@ -637,6 +637,14 @@ __global__ __launch_bounds__(256, kernel_waves_per_simd(D, NT, VC)) void attend_
         RawV<D, VC> rv2;
         // prologue: scores of tile 0 from rk; requests K of tile 1 and (again) V of tile 0 into set 2
         pipeline_step<D, NT, VC, KC, K16, false, true>(rv, rk, rv2, rk2, rs, tile_ptr(1), tile_ptr(0), qscale, lane, qb, O, Lsum, m_ref, mneg, S, lc);
+        // the rows' first references: the maxima of this first tile, taken here once instead of letting the first
+        // step find out through infinite probabilities and compute its tile's probabilities twice
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const float m0 = xor32_max(max16(S[nt]));
+            m_ref[32 * nt] = m0;
+            mneg[nt] = -m0 * qscale;
+        }
         int s = 0;
         for (; s + 1 < full_count - 1; s += 2) {  // two steps per trip: the sets swap roles without copies
             pipeline_step<D, NT, VC, KC, K16, true, true>(rv2, rk2, rv, rk, rs, tile_ptr(s + 2), tile_ptr(s + 1), qscale, lane, qb, O, Lsum, m_ref, mneg, S, lc);
