@@ -266,7 +266,7 @@ template <bool BF> __device__ __forceinline__ float tail_dot2(uint32_t a, uint32
 }
 
 template <int D, bool BF>
-__global__ __launch_bounds__(64, 4) void attend_tail_kernel(const __half* __restrict__ Q, TailPtrs tails,
+__global__ __launch_bounds__(64) void attend_tail_kernel(const __half* __restrict__ Q, TailPtrs tails,
                                                             float* __restrict__ tail_ml,
                                                             float* __restrict__ tail_o, AttendPlan p) {
     constexpr int LPR = D / 8;       // lanes per value row
